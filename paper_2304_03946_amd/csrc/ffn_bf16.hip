@@ -1,0 +1,488 @@
+// bf16 expert FFN (paper Eq. 2) per vExpert bucket, forward and backward, as grouped GEMMs on
+// the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation).
+//
+// Two kernel families share one 256x256x64 workgroup tile (4 wavefronts, 2x2, each owning a
+// 128x128 accumulator block = 16 MFMA tiles; operands staged through LDS, double buffered,
+// one barrier per K step):
+//
+//  * rows_gemm: C[rows of bucket v, :] = In[rows of v, :] . W_owner(v)    (fwd GEMM1/GEMM2,
+//    bwd dH and dXp).  The row dimension is cut per bucket: a device-side lookup maps the flat
+//    row-tile index to (vExpert, tile inside it), so highly skewed bucket sizes need no host
+//    synchronisation.  A ragged last tile of a bucket only runs the 32-row MFMA blocks that
+//    hold rows; row blocks are dealt to the two wave rows alternately so both stay busy.
+//  * wgrad_gemm: dW_e = sum over the vExperts v of e of L_v^T . R_v  -- the contraction runs
+//    over the tokens of every bucket of e in ascending vExpert id inside one accumulator, which
+//    is the single-GPU image of the paper's replica gradient synchronisation.  Output tiles are
+//    issued hottest expert first so the long contractions start early.
+//
+// Operand layouts: an operand whose contraction index is contiguous in memory is copied to LDS
+// as is; otherwise 8x8 blocks are transposed in registers on the way.  LDS tiles are
+// [row][64 k] with the 16-byte chunk index XOR-swizzled by (row ^ row>>3) & 7, which keeps the
+// MFMA fragment reads and both kinds of tile writes free of bank conflicts.
+// The MFMA is issued as (weights-fragment, activations-fragment) so that a lane ends up with 4
+// consecutive output columns of one output row: 8-byte stores.
+#include "common.h"
+
+namespace flexmoe {
+
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int kGemmThreads = 256;
+constexpr int MB = 4, NB = 4;                       // 32x32 MFMA tiles per wave: 4 x 4
+constexpr int kTileElems = BM * BK;                 // one operand tile in LDS (elements)
+constexpr size_t kGemmLds = 2 * 2 * kTileElems * sizeof(bf16_t);   // 2 stages x (A + B) = 128 KB
+
+enum { EPI_FWD1 = 0, EPI_PLAIN = 1, EPI_DH = 2 };
+
+union Frag8 {
+  uint4 u;
+  bf16x8 v;
+};
+
+__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
+__device__ __forceinline__ int lds_off(int row, int chunk) { return row * BK + ((chunk ^ swz(row)) << 3); }
+
+// ---- global -> registers ----------------------------------------------------------------
+// Operand stored [rows, K] with K contiguous.  Thread t owns chunk t&7 of rows (t>>3) + 32*i.
+// Rows >= rows_valid are not loaded (their 32-row block is skipped by the MFMA loop or their
+// results are dropped); chunks at k >= kmax read as zero.
+__device__ __forceinline__ void gload_kcontig(uint4 (&r)[8], const bf16_t* __restrict__ base, size_t ld, int rows_valid,
+                                              int k0, int kmax) {
+  const int c = threadIdx.x & 7, rr = threadIdx.x >> 3;
+  const bool kok = k0 + c * 8 < kmax;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int row = rr + 32 * i;
+    r[i] = make_uint4(0, 0, 0, 0);
+    if (kok && row < rows_valid) r[i] = *(const uint4*)(base + (size_t)row * ld + k0 + c * 8);
+  }
+}
+__device__ __forceinline__ void sstore_kcontig(bf16_t* tile, const uint4 (&r)[8]) {
+  const int c = threadIdx.x & 7, rr = threadIdx.x >> 3;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) *(uint4*)(tile + lds_off(rr + 32 * i, c)) = r[i];
+}
+
+// Operand stored [K, cols] with cols contiguous.  Thread t owns the 8x8 block at
+// k = 8*(t>>5).., col = 8*(t&31)..; rows k >= k_valid and columns >= cols_valid read as zero.
+__device__ __forceinline__ void gload_kstrided(uint4 (&r)[8], const bf16_t* __restrict__ base, size_t ld, int k_valid,
+                                               int cols_valid) {
+  const int nc = threadIdx.x & 31, kc = threadIdx.x >> 5;
+  const bool cok = nc * 8 < cols_valid;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int kk = kc * 8 + j;
+    r[j] = make_uint4(0, 0, 0, 0);
+    if (cok && kk < k_valid) r[j] = *(const uint4*)(base + (size_t)kk * ld + nc * 8);
+  }
+}
+__device__ __forceinline__ uint32_t lo16(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
+__device__ __forceinline__ uint32_t hi16(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
+__device__ __forceinline__ void sstore_kstrided(bf16_t* tile, const uint4 (&r)[8]) {
+  const int nc = threadIdx.x & 31, kc = threadIdx.x >> 5;
+  // r[j] holds columns 0..7 of k-row j; emit, per column n, the 8 k-values as one 16-byte chunk
+  uint4 o;
+#define FLEXMOE_TR(n, comp, pick)                                                          \
+  o = make_uint4(pick(r[0].comp, r[1].comp), pick(r[2].comp, r[3].comp), pick(r[4].comp, r[5].comp), \
+                 pick(r[6].comp, r[7].comp));                                                \
+  *(uint4*)(tile + lds_off(nc * 8 + n, kc)) = o;
+  FLEXMOE_TR(0, x, lo16) FLEXMOE_TR(1, x, hi16) FLEXMOE_TR(2, y, lo16) FLEXMOE_TR(3, y, hi16)
+  FLEXMOE_TR(4, z, lo16) FLEXMOE_TR(5, z, hi16) FLEXMOE_TR(6, w, lo16) FLEXMOE_TR(7, w, hi16)
+#undef FLEXMOE_TR
+}
+
+// ---- LDS -> MFMA ---------------------------------------------------------------------------
+// acc[i][j]: output rows (wm + 2*i)*32 + lane%32, columns (wn*NB + j)*32 + 8*(q/4) + 4*(lane/32) + q%4.
+template <bool FULL>
+__device__ __forceinline__ void mma_tile(const bf16_t* __restrict__ As, const bf16_t* __restrict__ Bs,
+                                         f32x16 (&acc)[MB][NB], int wm, int wn, int nblk_rows) {
+  const int lane = threadIdx.x & 63;
+  const int r = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int s = 0; s < BK / 16; ++s) {
+    Frag8 af[MB], bfr[NB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+      if (FULL || wm + 2 * i < nblk_rows) af[i].u = *(const uint4*)(As + lds_off((wm + 2 * i) * 32 + r, 2 * s + h));
+#pragma unroll
+    for (int j = 0; j < NB; ++j) bfr[j].u = *(const uint4*)(Bs + lds_off((wn * NB + j) * 32 + r, 2 * s + h));
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+      if (FULL || wm + 2 * i < nblk_rows) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j].v, af[i].v, acc[i][j], 0, 0, 0);
+      }
+  }
+}
+
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[MB][NB]) {
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+}
+
+__device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
+  return make_uint2(pack_bf16x2(a, b), pack_bf16x2(c, d));
+}
+
+// K loop of rows_gemm: register prefetch of tile kt+1 while tile kt is multiplied out of LDS.
+template <bool WT, bool FULL>
+__device__ __forceinline__ void rows_mainloop(bf16_t* smem, f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ a_base,
+                                              const bf16_t* __restrict__ w_e, int K, int NC, int n0, int rows_valid,
+                                              int cols_valid, int wm, int wn, int nblk_rows) {
+  const int KT = (K + BK - 1) / BK;
+  uint4 ra[8], rb[8];
+  gload_kcontig(ra, a_base, K, rows_valid, 0, K);
+  if (WT) gload_kcontig(rb, w_e + (size_t)n0 * K, K, cols_valid, 0, K);
+  else gload_kstrided(rb, w_e + n0, NC, K, cols_valid);
+  sstore_kcontig(smem, ra);
+  if (WT) sstore_kcontig(smem + kTileElems, rb); else sstore_kstrided(smem + kTileElems, rb);
+  __syncthreads();
+
+  for (int kt = 0; kt < KT; ++kt) {
+    bf16_t* cur = smem + (kt & 1) * 2 * kTileElems;
+    bf16_t* nxt = smem + ((kt & 1) ^ 1) * 2 * kTileElems;
+    const bool more = kt + 1 < KT;
+    if (more) {
+      const int k0 = (kt + 1) * BK;
+      gload_kcontig(ra, a_base, K, rows_valid, k0, K);
+      if (WT) gload_kcontig(rb, w_e + (size_t)n0 * K, K, cols_valid, k0, K);
+      else gload_kstrided(rb, w_e + (size_t)k0 * NC + n0, NC, K - k0, cols_valid);
+    }
+    mma_tile<FULL>(cur, cur + kTileElems, acc, wm, wn, nblk_rows);
+    if (more) {
+      sstore_kcontig(nxt, ra);
+      if (WT) sstore_kcontig(nxt + kTileElems, rb); else sstore_kstrided(nxt + kTileElems, rb);
+    }
+    __syncthreads();
+  }
+}
+
+// =============================================================================================
+// rows_gemm: C[p, n] = sum_k In[p, k] * W_e[k, n] (WT=false, W_e [K,NC]) or W_e[n, k] (WT=true)
+// =============================================================================================
+template <bool WT, int EPI, int ACT>
+__global__ __launch_bounds__(kGemmThreads) void rows_gemm_bf16(
+    const bf16_t* __restrict__ in, const bf16_t* __restrict__ w, const bf16_t* __restrict__ bias,
+    const int32_t* __restrict__ voff, const int32_t* __restrict__ owner, int V, int K, int NC, int col_tiles,
+    const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0, bf16_t* __restrict__ out1) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t* smem = (bf16_t*)smem_raw;
+  __shared__ int s_tile[3];
+
+  // flat row-tile index -> (vExpert, tile inside it): one wave scans the buckets' tile counts
+  const int rt = blockIdx.x / col_tiles, ct = blockIdx.x % col_tiles;
+  if (threadIdx.x < kWave) {
+    const int lane = threadIdx.x;
+    if (lane == 0) s_tile[0] = -1;
+    const int per = (V + kWave - 1) / kWave;     // <= 8 buckets per lane
+    int cnt[FLEXMOE_MAX_VEXPERTS / kWave];
+    int sum = 0;
+#pragma unroll
+    for (int q = 0; q < FLEXMOE_MAX_VEXPERTS / kWave; ++q) {
+      const int v = lane * per + q;
+      cnt[q] = 0;
+      if (q < per && v < V) cnt[q] = (voff[v + 1] - voff[v] + BM - 1) / BM;
+      sum += cnt[q];
+    }
+    int incl = sum;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const int up = __shfl_up(incl, o);
+      if (lane >= o) incl += up;
+    }
+    int start = incl - sum;
+#pragma unroll
+    for (int q = 0; q < FLEXMOE_MAX_VEXPERTS / kWave; ++q) {
+      if (rt >= start && rt < start + cnt[q]) {
+        s_tile[0] = lane * per + q;
+        s_tile[1] = rt - start;
+      }
+      start += cnt[q];
+    }
+  }
+  __syncthreads();
+  const int v = s_tile[0];
+  if (v < 0) return;                                  // beyond the last tile (uniform)
+  const int row0 = voff[v] + s_tile[1] * BM;
+  const int rows_valid = min(BM, voff[v + 1] - row0);
+  const int e = owner[v];
+  const int n0 = ct * BN;
+  const int cols_valid = min(BN, NC - n0);
+  const int nblk_rows = (rows_valid + 31) >> 5;
+
+  const bf16_t* a_base = in + (size_t)row0 * K;
+  const bf16_t* w_e = w + (size_t)e * K * NC;
+
+  const int wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  f32x16 acc[MB][NB];
+  zero_acc(acc);
+
+  if (nblk_rows == 2 * MB)
+    rows_mainloop<WT, true>(smem, acc, a_base, w_e, K, NC, n0, rows_valid, cols_valid, wm, wn, nblk_rows);
+  else
+    rows_mainloop<WT, false>(smem, acc, a_base, w_e, K, NC, n0, rows_valid, cols_valid, wm, wn, nblk_rows);
+
+  // epilogue: lane owns row (lane%32) of each of its row blocks and 4-column groups
+  const int lane = threadIdx.x & 63;
+  const int r = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < MB; ++i) {
+    const int lrow = (wm + 2 * i) * 32 + r;
+    const bool row_ok = lrow < rows_valid;
+    const size_t grow = (size_t)(row0 + lrow);
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int lcol = (wn * NB + j) * 32 + 8 * g + 4 * h;
+        if (row_ok && lcol < cols_valid) {
+          const int col = n0 + lcol;
+          float c0 = acc[i][j][4 * g + 0], c1 = acc[i][j][4 * g + 1], c2 = acc[i][j][4 * g + 2], c3 = acc[i][j][4 * g + 3];
+          if (bias) {
+            const uint2 bb = *(const uint2*)(bias + (size_t)e * NC + col);
+            c0 += __uint_as_float(bb.x << 16); c1 += __uint_as_float(bb.x & 0xffff0000u);
+            c2 += __uint_as_float(bb.y << 16); c3 += __uint_as_float(bb.y & 0xffff0000u);
+          }
+          const size_t o = grow * NC + col;
+          if (EPI == EPI_PLAIN) {
+            *(uint2*)(out0 + o) = pack4(c0, c1, c2, c3);
+          } else if (EPI == EPI_FWD1) {
+            // keep the pre-activation; the activation is taken of the value as stored
+            const uint2 pre = pack4(c0, c1, c2, c3);
+            *(uint2*)(out0 + o) = pre;
+            *(uint2*)(out1 + o) = pack4(act_fast<ACT>(__uint_as_float(pre.x << 16)), act_fast<ACT>(__uint_as_float(pre.x & 0xffff0000u)),
+                                        act_fast<ACT>(__uint_as_float(pre.y << 16)), act_fast<ACT>(__uint_as_float(pre.y & 0xffff0000u)));
+          } else {
+            const uint2 pre = *(const uint2*)(hpre_in + o);
+            float a0, a1, a2, a3, d0, d1, d2, d3;
+            act_both<ACT>(__uint_as_float(pre.x << 16), &a0, &d0);
+            act_both<ACT>(__uint_as_float(pre.x & 0xffff0000u), &a1, &d1);
+            act_both<ACT>(__uint_as_float(pre.y << 16), &a2, &d2);
+            act_both<ACT>(__uint_as_float(pre.y & 0xffff0000u), &a3, &d3);
+            *(uint2*)(out0 + o) = pack4(c0 * d0, c1 * d1, c2 * d2, c3 * d3);
+            *(uint2*)(out1 + o) = pack4(a0, a1, a2, a3);
+          }
+        }
+      }
+    }
+  }
+}
+
+// =============================================================================================
+// wgrad_gemm: dW_e[m, n] = sum_{v owned by e, ascending v} sum_{p in bucket v} L[p, m] * R[p, n]
+// =============================================================================================
+__global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_bf16(const bf16_t* __restrict__ L,
+                                                                const bf16_t* __restrict__ R,
+                                                                const int32_t* __restrict__ voff,
+                                                                const int32_t* __restrict__ owner, int E, int V, int M,
+                                                                int NC, int m_tiles, int n_tiles,
+                                                                bf16_t* __restrict__ dw) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t* smem = (bf16_t*)smem_raw;
+  __shared__ int s_cnt[FLEXMOE_MAX_VEXPERTS], s_own[FLEXMOE_MAX_VEXPERTS];
+  __shared__ int s_load[FLEXMOE_MAX_EXPERTS];
+  __shared__ int s_e;
+  __shared__ int s_nb;
+  __shared__ int s_bstart[FLEXMOE_MAX_VEXPERTS], s_brows[FLEXMOE_MAX_VEXPERTS];
+
+  const int tiles_per_e = m_tiles * n_tiles;
+  const int want_rank = blockIdx.x / tiles_per_e;
+  const int tile = blockIdx.x % tiles_per_e;
+  const int mt = tile / n_tiles, nt = tile % n_tiles;
+
+  for (int v = threadIdx.x; v < V; v += kGemmThreads) {
+    s_cnt[v] = voff[v + 1] - voff[v];
+    s_own[v] = owner[v];
+  }
+  for (int e = threadIdx.x; e < E; e += kGemmThreads) s_load[e] = 0;
+  __syncthreads();
+  for (int v = threadIdx.x; v < V; v += kGemmThreads) atomicAdd(&s_load[s_own[v]], s_cnt[v]);
+  __syncthreads();
+  // the expert whose load has rank `want_rank` (descending load, ties by ascending id)
+  for (int e = threadIdx.x; e < E; e += kGemmThreads) {
+    const int l = s_load[e];
+    int rank = 0;
+    for (int o = 0; o < E; ++o) {
+      const int lo = s_load[o];
+      rank += (lo > l || (lo == l && o < e)) ? 1 : 0;
+    }
+    if (rank == want_rank) s_e = e;
+  }
+  __syncthreads();
+  const int e = s_e;
+  if (threadIdx.x < kWave) {                   // its non-empty buckets, ascending vExpert id
+    const int lane = threadIdx.x;
+    const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    int nbw = 0;
+    for (int vb = 0; vb < V; vb += kWave) {
+      const int v = vb + lane;
+      const bool hit = v < V && s_own[v] == e && s_cnt[v] > 0;
+      const unsigned long long mask = __ballot(hit);
+      if (hit) {
+        const int pos = nbw + __popcll(mask & lt);
+        s_bstart[pos] = voff[v];
+        s_brows[pos] = s_cnt[v];
+      }
+      nbw += __popcll(mask);
+    }
+    if (lane == 0) s_nb = nbw;
+  }
+  __syncthreads();
+  const int nb = s_nb;
+
+  const int m0 = mt * BM, n0 = nt * BN;
+  const int mvalid = min(BM, M - m0), nvalid = min(BN, NC - n0);
+  const int wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  f32x16 acc[MB][NB];
+  zero_acc(acc);
+
+  if (nb > 0) {
+    uint4 ra[8], rb[8];
+    int bi = 0, koff = 0;
+    {
+      const size_t p0 = (size_t)s_bstart[0];
+      gload_kstrided(ra, L + p0 * M + m0, M, s_brows[0], mvalid);
+      gload_kstrided(rb, R + p0 * NC + n0, NC, s_brows[0], nvalid);
+    }
+    sstore_kstrided(smem, ra);
+    sstore_kstrided(smem + kTileElems, rb);
+    __syncthreads();
+    int it = 0;
+    while (true) {
+      // advance to the next K tile (next 64 tokens of this bucket, else the next bucket)
+      int nbi = bi, nkoff = koff + BK;
+      if (nkoff >= s_brows[bi]) {
+        nbi = bi + 1;
+        nkoff = 0;
+      }
+      const bool more = nbi < nb;
+      bf16_t* cur = smem + (it & 1) * 2 * kTileElems;
+      bf16_t* nxt = smem + ((it & 1) ^ 1) * 2 * kTileElems;
+      if (more) {
+        const size_t p0 = (size_t)s_bstart[nbi] + nkoff;
+        const int kv = s_brows[nbi] - nkoff;
+        gload_kstrided(ra, L + p0 * M + m0, M, kv, mvalid);
+        gload_kstrided(rb, R + p0 * NC + n0, NC, kv, nvalid);
+      }
+      mma_tile<true>(cur, cur + kTileElems, acc, wm, wn, MB * 2);
+      if (more) {
+        sstore_kstrided(nxt, ra);
+        sstore_kstrided(nxt + kTileElems, rb);
+      }
+      __syncthreads();
+      if (!more) break;
+      bi = nbi;
+      koff = nkoff;
+      ++it;
+    }
+  }
+
+  const int lane = threadIdx.x & 63;
+  const int r = lane & 31, h = lane >> 5;
+  bf16_t* out = dw + (size_t)e * M * NC;
+#pragma unroll
+  for (int i = 0; i < MB; ++i) {
+    const int lrow = (wm + 2 * i) * 32 + r;
+    const bool row_ok = lrow < mvalid;
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int lcol = (wn * NB + j) * 32 + 8 * g + 4 * h;
+        if (row_ok && lcol < nvalid)
+          *(uint2*)(out + (size_t)(m0 + lrow) * NC + n0 + lcol) =
+              pack4(acc[i][j][4 * g + 0], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+      }
+  }
+}
+
+// =============================================================================================
+// host side
+// =============================================================================================
+size_t ffn_ws_bytes(int A, int f, int dtype) {
+  const size_t s = dtype == FLEXMOE_BF16 ? 2 : 4;
+  return align_up((size_t)A * f * s, 256) * 2;      // dHpre (or H in forward) + H
+}
+
+template <typename Kern> static hipError_t allow_big_lds(Kern kern) {
+  return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLds);
+}
+
+static int max_row_tiles(int A, int V) { return A / BM + V; }
+
+template <bool WT, int EPI, int ACT>
+static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w, const void* bias, int K, int NC,
+                                const void* hpre_in, void* out0, void* out1, hipStream_t s) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t err = allow_big_lds(rows_gemm_bf16<WT, EPI, ACT>);
+    if (err != hipSuccess) return err;
+    attr_done = true;
+  }
+  const int col_tiles = (NC + BN - 1) / BN;
+  const unsigned grid = (unsigned)max_row_tiles(a.A, a.V) * col_tiles;
+  hipLaunchKernelGGL((rows_gemm_bf16<WT, EPI, ACT>), dim3(grid), dim3(kGemmThreads), kGemmLds, s, (const bf16_t*)in,
+                     (const bf16_t*)w, (const bf16_t*)bias, a.voff, a.owner, a.V, K, NC, col_tiles,
+                     (const bf16_t*)hpre_in, (bf16_t*)out0, (bf16_t*)out1);
+  return hipGetLastError();
+}
+
+template <bool WT, int EPI>
+static hipError_t launch_rows(const FfnArgs& a, const void* in, const void* w, const void* bias, int K, int NC,
+                              const void* hpre_in, void* out0, void* out1, hipStream_t s) {
+  if (EPI == EPI_PLAIN) return launch_rows_t<WT, EPI, FLEXMOE_RELU>(a, in, w, bias, K, NC, hpre_in, out0, out1, s);
+  switch (a.act) {
+    case FLEXMOE_RELU: return launch_rows_t<WT, EPI, FLEXMOE_RELU>(a, in, w, bias, K, NC, hpre_in, out0, out1, s);
+    case FLEXMOE_GELU_ERF: return launch_rows_t<WT, EPI, FLEXMOE_GELU_ERF>(a, in, w, bias, K, NC, hpre_in, out0, out1, s);
+    default: return launch_rows_t<WT, EPI, FLEXMOE_GELU_TANH>(a, in, w, bias, K, NC, hpre_in, out0, out1, s);
+  }
+}
+
+static hipError_t launch_wgrad(const FfnArgs& a, const void* L, const void* R, int M, int NC, void* dw, hipStream_t s) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t err = allow_big_lds(wgrad_gemm_bf16);
+    if (err != hipSuccess) return err;
+    attr_done = true;
+  }
+  const int m_tiles = (M + BM - 1) / BM, n_tiles = (NC + BN - 1) / BN;
+  hipLaunchKernelGGL(wgrad_gemm_bf16, dim3((unsigned)a.E * m_tiles * n_tiles), dim3(kGemmThreads), kGemmLds, s,
+                     (const bf16_t*)L, (const bf16_t*)R, a.voff, a.owner, a.E, a.V, M, NC, m_tiles, n_tiles,
+                     (bf16_t*)dw);
+  return hipGetLastError();
+}
+
+hipError_t launch_ffn_fwd_bf16(const FfnArgs& a, const void* xp, const void* w1, const void* b1, const void* w2,
+                               const void* b2, void* hpre, void* yp, void* ws, hipStream_t s) {
+  if (a.A == 0) return hipSuccess;
+  void* h = ws;
+  hipError_t err = launch_rows<false, EPI_FWD1>(a, xp, w1, b1, a.d, a.f, nullptr, hpre, h, s);
+  if (err != hipSuccess) return err;
+  return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, yp, nullptr, s);
+}
+
+hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp, const void* hpre, const void* w1,
+                               const void* w2, void* dxp, void* dw1, void* dw2, void* ws, hipStream_t s) {
+  bf16_t* dhpre = (bf16_t*)ws;
+  bf16_t* h = (bf16_t*)((char*)ws + align_up((size_t)a.A * a.f * sizeof(bf16_t), 256));
+  hipError_t err;
+  if (a.A > 0) {
+    // dH = dYp . W2^T fused with act'(Hpre); W2_e is [f, d], contraction index d contiguous
+    err = launch_rows<true, EPI_DH>(a, dyp, w2, nullptr, a.d, a.f, hpre, dhpre, h, s);
+    if (err != hipSuccess) return err;
+    // dXp = dHpre . W1^T; W1_e is [d, f], contraction index f contiguous
+    err = launch_rows<true, EPI_PLAIN>(a, dhpre, w1, nullptr, a.f, a.d, nullptr, dxp, nullptr, s);
+    if (err != hipSuccess) return err;
+  }
+  err = launch_wgrad(a, h, dyp, a.f, a.d, dw2, s);
+  if (err != hipSuccess) return err;
+  return launch_wgrad(a, xp, dhpre, a.d, a.f, dw1, s);
+}
+
+}  // namespace flexmoe

@@ -1,0 +1,93 @@
+"""One MoE layer on one GPU: buffers owned here, every step done by libflexmoe.
+
+Forward (paper Section 3.1 workflow on a single GPU):
+    gate_topk -> route(placement table) -> permute -> expert_ffn_fwd -> combine
+Backward of the expert path for an upstream gradient dY (gate output held constant):
+    permute(dY, row_scale = gate weights) -> expert_ffn_bwd -> combine(weights = None)
+
+This class only allocates device memory once and sequences the C-ABI calls; it
+does no arithmetic of its own.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+from . import workloads as W
+
+
+def to_device(t, device="cuda"):
+    """Upload a stored tensor (Bf16Tensor bit patterns or float32 ndarray) unchanged."""
+    if t is None:
+        return None
+    if isinstance(t, W.Bf16Tensor):
+        return torch.from_numpy(t.bits.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(t, dtype=np.float32)).to(device)
+
+
+def to_host_f32(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy()
+
+
+class MoELayer:
+    def __init__(self, N, d, f, E, k, V, dtype, act, backward=False, device="cuda"):
+        self.N, self.d, self.f, self.E, self.k, self.V = N, d, f, E, k, V
+        self.A = N * k
+        self.act = act
+        self.dtype_code = dtype
+        tdt = torch.bfloat16 if dtype == B.BF16 else torch.float32
+        dev = device
+        i32 = dict(dtype=torch.int32, device=dev)
+        A = self.A
+        self.topk_idx = torch.empty((N, k), **i32)
+        self.topk_w = torch.empty((N, k), dtype=torch.float32, device=dev)
+        self.expert_count = torch.empty(E, **i32)
+        self.vexpert_count = torch.empty(V, **i32)
+        self.vexpert_off = torch.empty(V + 1, **i32)
+        self.vexpert_owner = torch.empty(V, **i32)
+        self.dest = torch.empty(A, **i32)
+        self.src = torch.empty(A, **i32)
+        self.xp = torch.empty((A, d), dtype=tdt, device=dev)
+        self.hpre = torch.empty((A, f), dtype=tdt, device=dev)
+        self.yp = torch.empty((A, d), dtype=tdt, device=dev)
+        self.y = torch.empty((N, d), dtype=tdt, device=dev)
+        ws_bytes = B.flexmoe_workspace_bytes(N, d, f, E, k, V, dtype)
+        if ws_bytes == 0:
+            raise ValueError("unsupported layer shape")
+        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self.has_backward = backward
+        if backward:
+            self.dyp = torch.empty((A, d), dtype=tdt, device=dev)
+            self.dxp = torch.empty((A, d), dtype=tdt, device=dev)
+            self.dx = torch.empty((N, d), dtype=tdt, device=dev)
+            self.dw1 = torch.empty((E, d, f), dtype=tdt, device=dev)
+            self.dw2 = torch.empty((E, f, d), dtype=tdt, device=dev)
+
+    @classmethod
+    def for_config(cls, cfg: W.LayerConfig, device="cuda"):
+        return cls(cfg.N, cfg.d, cfg.f, cfg.E, cfg.k, cfg.V, cfg.dtype, cfg.act, cfg.backward, device)
+
+    # -- individual stages ------------------------------------------------
+    def gate(self, x, wg):
+        B.flexmoe_gate_topk(x, wg, self.k, self.topk_idx, self.topk_w, self.ws)
+
+    def route(self, rep_off, rep_ids):
+        B.flexmoe_route(self.topk_idx, self.E, rep_off, rep_ids, self.expert_count, self.vexpert_count,
+                        self.vexpert_off, self.vexpert_owner, self.dest, self.src, self.ws)
+
+    def forward(self, x, wg, w1, w2, rep_off, rep_ids, b1=None, b2=None):
+        self.gate(x, wg)
+        self.route(rep_off, rep_ids)
+        B.flexmoe_permute(x, self.src, None, self.k, self.xp)
+        B.flexmoe_expert_ffn_fwd(self.xp, self.vexpert_off, self.vexpert_owner, w1, b1, w2, b2, self.act,
+                                 self.hpre, self.yp, self.ws)
+        B.flexmoe_combine(self.yp, self.dest, self.topk_w, self.k, self.y)
+        return self.y
+
+    def backward(self, dy, w1, w2):
+        B.flexmoe_permute(dy, self.src, self.topk_w, self.k, self.dyp)
+        B.flexmoe_expert_ffn_bwd(self.dyp, self.xp, self.hpre, w1, w2, self.vexpert_off, self.vexpert_owner,
+                                 self.act, self.dxp, self.dw1, self.dw2, self.ws)
+        B.flexmoe_combine(self.dxp, self.dest, None, self.k, self.dx)
+        return self.dx, self.dw1, self.dw2

@@ -1,0 +1,329 @@
+"""GPU parity: every stage of the HIP path (called through the C ABI) against the CPU oracle.
+
+Integer artefacts (routing counts, offsets, permutation) must match bit for bit; the
+permuted copy must match bit for bit; floating-point outputs must satisfy
+    max|gpu - ref| / max|ref| <= 2e-2   (bf16 operands, fp32 accumulation)
+                              <= 1e-5   (fp32)
+per output tensor.  Top-k indices must be identical on every token whose logit
+margin exceeds the worst-case fp32 accumulation error of the gate; on the few
+tokens below it the GPU's choice must be a valid top-k within that error.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import flexmoe_oracle as O
+from paper_2304_03946_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = {W.DT_BF16: 2e-2, W.DT_F32: 1e-5}
+
+
+@pytest.fixture(scope="module")
+def api():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a visible MI355X")
+    from paper_2304_03946_amd import binding, layer
+    binding.load_library()          # fails loudly when the HIP library is not built
+    return binding, layer
+
+
+def rel_err(gpu, ref):
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    scale = np.abs(ref).max()
+    if scale == 0:
+        return float(np.abs(gpu).max())
+    return float(np.abs(gpu - ref).max() / scale)
+
+
+def host(t):
+    return t.detach().float().cpu().numpy() if t.dtype != torch.int32 else t.cpu().numpy()
+
+
+def gate_error_bound(x, wg, dtype):
+    """Worst-case |fp32 accumulated logit - exact logit| per token: (d+1) u sum_i |x_i w_i|
+    maximised over experts (u = 2^-24; bf16 products are exact in fp32, fp32 products add one
+    more rounding, covered by the +1 and the factor 2)."""
+    ax = np.abs(np.asarray(x, dtype=np.float64))
+    aw = np.abs(np.asarray(wg, dtype=np.float64))
+    s = (ax @ aw).max(axis=1)
+    return 2.0 * (x.shape[1] + 1) * 2.0 ** -24 * s
+
+
+def check_gate(idx_gpu, w_gpu, x, wg, k, dtype, tokens=None):
+    """Returns the boolean mask of tokens whose selection is pinned (margin above the bound)."""
+    xs = W.decode(x) if tokens is None else W.decode(x)[tokens]
+    wgd = W.decode(wg)
+    idx_ref, w_ref, logits = O.gate_topk(xs, wgd, k)
+    bound = gate_error_bound(xs, wgd, dtype)
+    pinned = O.topk_margin(logits, k) > 2.0 * bound
+    assert pinned.mean() > 0.9, f"too many near-tie tokens: {1 - pinned.mean():.4f}"
+    assert np.array_equal(idx_gpu[pinned], idx_ref[pinned]), "top-k indices differ on pinned tokens"
+    # near-tie tokens: the selection must be a set of distinct experts whose exact logits are
+    # within the error bound of the exact top-k values, slot by slot
+    for t in np.nonzero(~pinned)[0]:
+        sel = idx_gpu[t]
+        assert len(set(sel.tolist())) == k and sel.min() >= 0 and sel.max() < logits.shape[1]
+        ref_sorted = np.sort(logits[t])[::-1][:k]
+        assert np.all(np.abs(logits[t, sel] - ref_sorted) <= 2.0 * bound[t] + 1e-30)
+    # gate weights: softmax of the kept logits; an error e in each logit moves a weight by < 2e
+    same = np.all(idx_gpu == idx_ref, axis=1)
+    assert np.all(np.abs(w_gpu[same] - w_ref[same]) <= 4.0 * bound[same, None] + 2e-6)
+    np.testing.assert_allclose(w_gpu.sum(axis=1), 1.0, atol=1e-5)
+    return same
+
+
+def upload(layer_mod, inp):
+    up = layer_mod.to_device
+    return dict(x=up(inp.x), wg=up(inp.wg), w1=up(inp.w1), w2=up(inp.w2), dy=up(inp.dy))
+
+
+def run_stagewise(api, cfg, inp, rep_off, rep_ids, b1=None, b2=None):
+    """Run the layer on the GPU and compare stage by stage, each oracle stage fed with the
+    GPU's own upstream results (so only that stage's arithmetic is under test), then end to end."""
+    binding, layer_mod = api
+    tol = TOL[cfg.dtype]
+    dev = upload(layer_mod, inp)
+    L = layer_mod.MoELayer.for_config(cfg)
+    db1 = layer_mod.to_device(b1)
+    db2 = layer_mod.to_device(b2)
+    L.forward(dev["x"], dev["wg"], dev["w1"], dev["w2"], rep_off, rep_ids, db1, db2)
+    torch.cuda.synchronize()
+    k, E = cfg.k, cfg.E
+    x, wg, w1, w2 = inp.x, inp.wg, inp.w1, inp.w2
+
+    # a1 gate
+    idx_gpu, w_gpu = host(L.topk_idx), host(L.topk_w)
+    same = check_gate(idx_gpu, w_gpu, x, wg, k, cfg.dtype)
+
+    # a2 route, on the GPU's own top-k: bit exact
+    r = O.route(idx_gpu, E, rep_off, rep_ids)
+    for name in ("expert_count", "vexpert_count", "vexpert_off", "vexpert_owner", "dest", "src"):
+        assert np.array_equal(host(getattr(L, name)), r[name]), name
+
+    # a3 permute: exact copy
+    xd = W.decode(x)
+    xp_ref = O.permute(xd, r["src"], k)
+    xp_gpu = host(L.xp)
+    assert np.array_equal(xp_gpu.astype(np.float64), xp_ref), "permute is not an exact copy"
+
+    # a4 expert FFN forward
+    b1d = None if b1 is None else W.decode(b1)
+    b2d = None if b2 is None else W.decode(b2)
+    hpre_ref, yp_ref = O.expert_ffn_fwd(xp_ref, r["vexpert_off"], r["vexpert_owner"], w1, b1d, w2, b2d, cfg.act)
+    assert rel_err(host(L.hpre), hpre_ref) <= tol, "hpre"
+    assert rel_err(host(L.yp), yp_ref) <= tol, "yp"
+
+    # a6 combine, fed with the GPU's yp and gate weights
+    y_stage = O.combine(host(L.yp), r["dest"], w_gpu, k)
+    assert rel_err(host(L.y), y_stage) <= (tol if cfg.dtype == W.DT_F32 else 2.0 ** -8), "combine"
+
+    # end to end against the definition (Eq. 2-4), on the tokens whose selection is pinned
+    y_def = O.moe_layer_forward(xd, W.decode(wg), w1, b1d, w2, b2d, k, cfg.act)
+    assert rel_err(host(L.y)[same], y_def[same]) <= tol, "layer output"
+
+    out = dict(layer=L, route=r, idx=idx_gpu, w=w_gpu, same=same)
+    if not cfg.backward:
+        return out
+
+    L.backward(dev["dy"], dev["w1"], dev["w2"])
+    torch.cuda.synchronize()
+    dyd = W.decode(inp.dy)
+    # backward permute with the gate weights as row scale
+    dyp_ref = O.permute(dyd, r["src"], k, row_scale=w_gpu.reshape(-1))
+    assert rel_err(host(L.dyp), dyp_ref) <= (tol if cfg.dtype == W.DT_F32 else 2.0 ** -8), "dyp"
+    # a5 FFN backward, fed with the GPU's dyp and hpre
+    dxp_ref, dw1_ref, dw2_ref = O.expert_ffn_bwd(host(L.dyp), xp_ref, host(L.hpre), w1, w2, r["vexpert_off"],
+                                                 r["vexpert_owner"], E, cfg.act)
+    assert rel_err(host(L.dxp), dxp_ref) <= tol, "dxp"
+    assert rel_err(host(L.dw1), dw1_ref) <= tol, "dw1"
+    assert rel_err(host(L.dw2), dw2_ref) <= tol, "dw2"
+    dx_stage = O.combine(host(L.dxp), r["dest"], None, k)
+    assert rel_err(host(L.dx), dx_stage) <= (tol if cfg.dtype == W.DT_F32 else 2.0 ** -8), "dx combine"
+    # end to end gradients against the definition with the GPU's selection and the exact gate weights
+    # (exact softmax over the kept logits, in the order the GPU reported them)
+    kept = np.take_along_axis(O.gate_logits(xd, W.decode(wg)), idx_gpu.astype(np.int64), axis=1)
+    ex = np.exp(kept - kept.max(axis=1, keepdims=True))
+    w_sel = ex / ex.sum(axis=1, keepdims=True)
+    dx_def, dw1_def, dw2_def = O.moe_layer_backward(xd, W.decode(wg), w1, None, w2, k, cfg.act, dyd,
+                                                    topk=(idx_gpu, w_sel))
+    assert rel_err(host(L.dx), dx_def) <= tol, "dx"
+    assert rel_err(host(L.dw1), dw1_def) <= tol, "dw1 end to end"
+    assert rel_err(host(L.dw2), dw2_def) <= tol, "dw2 end to end"
+    empty = np.nonzero(r["expert_count"] == 0)[0]
+    for e in empty:
+        assert not host(L.dw1[e]).any() and not host(L.dw2[e]).any(), "empty expert must get zero gradient"
+    return out
+
+
+# ---------------------------------------------------------------------------------- cases
+def test_tiny_fp32_full_config(api):
+    cfg = W.CONFIGS["tiny"]
+    inp = W.make_layer_inputs(cfg)
+    run_stagewise(api, cfg, inp, *W.config_placement(cfg))
+
+
+def test_tiny_fp32_backward_and_bias(api):
+    cfg = W.scaled(W.CONFIGS["tiny"], N=301, E=5, V=8, k=2, backward=True, max_rep=3)
+    inp = W.make_layer_inputs(cfg, seed=77)
+    rng = np.random.default_rng(0)
+    b1 = (rng.standard_normal((cfg.E, cfg.f)) * 0.05).astype(np.float32)
+    b2 = (rng.standard_normal((cfg.E, cfg.d)) * 0.05).astype(np.float32)
+    binding, layer_mod = api
+    # biases only enter the forward pass (bias gradients are not part of the path)
+    cfg_f = W.scaled(cfg, backward=False)
+    run_stagewise(api, cfg_f, inp, *W.placement_from_loads([5, 4, 3, 2, 1], cfg.V, 3, shuffle_seed=3), b1=b1, b2=b2)
+    run_stagewise(api, cfg, inp, *W.placement_from_loads([5, 4, 3, 2, 1], cfg.V, 3, shuffle_seed=3))
+
+
+SMALL = {
+    # several 256-row tiles per bucket, ragged bucket tails, K and column tails (d, f multiples of 8 only)
+    "bert_small": W.scaled(W.CONFIGS["bert"], N=1500, d=328, f=776, E=6, V=9, max_rep=2),
+    "gpt_small": W.scaled(W.CONFIGS["gpt_m"], N=2100, d=264, f=520, E=8, V=14, max_rep=4),
+    "swin_small": W.scaled(W.CONFIGS["swin"], N=3000, d=256, f=512, E=8, V=11, max_rep=4),
+    "xl_small": W.scaled(W.CONFIGS["gpt_xl"], N=2600, d=192, f=384, E=64, V=96, max_rep=8),
+}
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_reduced_configs_elementwise(api, name):
+    cfg = SMALL[name]
+    inp = W.make_layer_inputs(cfg)
+    rep_off, rep_ids = W.placement_from_loads(W.prior_loads(cfg), cfg.V, cfg.max_rep, shuffle_seed=11)
+    out = run_stagewise(api, cfg, inp, rep_off, rep_ids)
+    r = out["route"]
+    # replica shares differ by at most one token
+    for e in range(cfg.E):
+        shares = r["vexpert_count"][rep_ids[rep_off[e]:rep_off[e + 1]]]
+        assert shares.max() - shares.min() <= 1 and shares.sum() == r["expert_count"][e]
+
+
+def test_bf16_bias_forward(api):
+    cfg = W.scaled(SMALL["bert_small"], N=700)
+    inp = W.make_layer_inputs(cfg, seed=5)
+    rng = np.random.default_rng(1)
+    b1 = W.Bf16Tensor.from_f32((rng.standard_normal((cfg.E, cfg.f)) * 0.3).astype(np.float32))
+    b2 = W.Bf16Tensor.from_f32((rng.standard_normal((cfg.E, cfg.d)) * 0.3).astype(np.float32))
+    run_stagewise(api, cfg, inp, *W.placement_from_loads(W.prior_loads(cfg), cfg.V, 2), b1=b1, b2=b2)
+
+
+@pytest.mark.parametrize("act", [W.ACT_RELU, W.ACT_GELU_TANH])
+def test_other_activations(api, act):
+    cfg = W.scaled(SMALL["gpt_small"], N=900, act=act)
+    inp = W.make_layer_inputs(cfg, seed=9)
+    run_stagewise(api, cfg, inp, *W.placement_from_loads(W.prior_loads(cfg), cfg.V, 4))
+
+
+def test_exact_ties_pick_lower_expert(api):
+    """Small-integer inputs make every fp32 sum exact, so ties are real ties on both sides."""
+    binding, layer_mod = api
+    rng = np.random.default_rng(4)
+    N, d, E, k = 257, 64, 12, 3
+    x = rng.integers(-2, 3, size=(N, d)).astype(np.float32)
+    wg = rng.integers(-1, 2, size=(d, E)).astype(np.float32)
+    wg[:, 5] = wg[:, 2]                       # two identical experts: always tied
+    idx_ref, w_ref, logits = O.gate_topk(x, wg, k)
+    for dtype, store in ((binding.F32, lambda a: a), (binding.BF16, W.Bf16Tensor.from_f32)):
+        xd, wd = layer_mod.to_device(store(x)), layer_mod.to_device(store(wg))
+        idx = torch.empty((N, k), dtype=torch.int32, device="cuda")
+        w = torch.empty((N, k), dtype=torch.float32, device="cuda")
+        ws = torch.empty(binding.flexmoe_workspace_bytes(N, d, 64, E, k, E, dtype), dtype=torch.uint8, device="cuda")
+        binding.flexmoe_gate_topk(xd, wd, k, idx, w, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(idx.cpu().numpy(), idx_ref)
+        np.testing.assert_allclose(w.cpu().numpy(), w_ref, atol=2e-6)
+
+
+def _route_only(api, idx_np, E, rep_off, rep_ids):
+    binding, layer_mod = api
+    N, k = idx_np.shape
+    V = len(rep_ids)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    idx = torch.from_numpy(np.ascontiguousarray(idx_np, dtype=np.int32)).cuda()
+    out = dict(expert_count=torch.full((E,), -7, **i32), vexpert_count=torch.full((V,), -7, **i32),
+               vexpert_off=torch.full((V + 1,), -7, **i32), vexpert_owner=torch.full((V,), -7, **i32),
+               dest=torch.full((max(N * k, 1),), -7, **i32), src=torch.full((max(N * k, 1),), -7, **i32))
+    ws = torch.empty(binding.flexmoe_workspace_bytes(max(N, 1), 8, 8, E, k, V, binding.F32), dtype=torch.uint8, device="cuda")
+    binding.flexmoe_route(idx, E, rep_off, rep_ids, out["expert_count"], out["vexpert_count"], out["vexpert_off"],
+                          out["vexpert_owner"], out["dest"], out["src"], ws)
+    torch.cuda.synchronize()
+    return {n: t.cpu().numpy() for n, t in out.items()}
+
+
+@pytest.mark.parametrize("case", ["one_expert", "fewer_tokens_than_replicas", "k_equals_E", "ragged_unit", "max_sizes"])
+def test_route_adversarial(api, case):
+    rng = np.random.default_rng(12)
+    if case == "one_expert":                # every token to expert 3, which has 5 replicas
+        E, V, N, k = 8, 12, 4099, 1
+        idx = np.full((N, 1), 3, dtype=np.int32)
+        rep_off, rep_ids = W.placement_from_loads([0, 0, 0, 100, 0, 0, 0, 0], V, 5, shuffle_seed=2)
+    elif case == "fewer_tokens_than_replicas":
+        E, V, N, k = 4, 16, 3, 2
+        idx = np.array([[0, 1], [0, 2], [1, 0]], dtype=np.int32)
+        rep_off, rep_ids = W.placement_from_loads([9, 1, 1, 1], V, 13)
+    elif case == "k_equals_E":
+        E, V, N, k = 4, 6, 777, 4
+        idx = np.stack([rng.permutation(E) for _ in range(N)]).astype(np.int32)
+        rep_off, rep_ids = W.placement_from_loads([1, 1, 1, 1], V, 3, shuffle_seed=1)
+    elif case == "ragged_unit":             # A not a multiple of the 64-lane rounds nor of the unit length
+        E, V, N, k = 37, 53, 12345, 2
+        cfg = W.scaled(W.CONFIGS["gpt_xl"], N=N, E=E, V=V, k=k)
+        idx = W.sample_topk_idx(cfg, 3, log_p=1.5 * np.log(1.0 / (np.arange(E) + 1.0)))
+        rep_off, rep_ids = W.placement_from_loads(np.bincount(idx.reshape(-1), minlength=E), V, 8, shuffle_seed=5)
+    else:                                    # the library's limits: E = 256, V = 512, k = 8
+        E, V, N, k = 256, 512, 20000, 8
+        cfg = W.scaled(W.CONFIGS["gpt_xl"], N=N, E=E, V=V, k=k)
+        idx = W.sample_topk_idx(cfg, 4, log_p=1.2 * np.log(1.0 / (np.arange(E) + 1.0)))
+        rep_off, rep_ids = W.placement_from_loads(np.bincount(idx.reshape(-1), minlength=E), V, 8, shuffle_seed=6)
+    got = _route_only(api, idx, E, rep_off, rep_ids)
+    ref = O.route(idx, E, rep_off, rep_ids)
+    for name, arr in ref.items():
+        assert np.array_equal(got[name][:arr.shape[0]], arr), (case, name)
+
+
+def test_route_empty_batch(api):
+    got = _route_only(api, np.zeros((0, 2), dtype=np.int32), 3, [0, 1, 2, 4], [0, 1, 2, 3])
+    assert got["expert_count"].tolist() == [0, 0, 0] and got["vexpert_off"].tolist() == [0, 0, 0, 0, 0]
+    assert got["vexpert_owner"].tolist() == [0, 1, 2, 2]
+
+
+def test_errors_are_reported_before_any_launch(api):
+    binding, layer_mod = api
+    idx = np.zeros((4, 1), dtype=np.int32)
+    for off, ids in (([0, 1, 1], [0]), ([0, 1, 3], [0, 1, 1]), ([0, 2, 3], [0, 1, 3])):
+        with pytest.raises(binding.FlexMoEError) as ei:
+            _route_only(api, idx, 2, off, ids + [0] * 0)
+        assert ei.value.status in (binding.BAD_PLACEMENT, binding.INVALID_ARG)
+    x = torch.zeros((4, 12), dtype=torch.bfloat16, device="cuda")     # d not a multiple of 8
+    with pytest.raises(binding.FlexMoEError) as ei:
+        binding.flexmoe_permute(x, torch.zeros(4, dtype=torch.int32, device="cuda"), None, 1, torch.empty_like(x))
+    assert ei.value.status == binding.INVALID_ARG
+    # workspace too small
+    L = layer_mod.MoELayer(64, 64, 64, 4, 1, 4, binding.BF16, binding.RELU)
+    xp = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros((4, 64, 64), dtype=torch.bfloat16, device="cuda")
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(binding.FlexMoEError) as ei:
+        binding.flexmoe_expert_ffn_fwd(xp, L.vexpert_off, L.vexpert_owner, w, None, w, None, binding.RELU, L.hpre, L.yp, small)
+    assert ei.value.status == binding.WORKSPACE_TOO_SMALL
+    torch.cuda.synchronize()
+
+
+def test_two_runs_are_bit_identical(api):
+    binding, layer_mod = api
+    cfg = SMALL["gpt_small"]
+    inp = W.make_layer_inputs(cfg)
+    rep = W.placement_from_loads(W.prior_loads(cfg), cfg.V, cfg.max_rep, shuffle_seed=11)
+    dev = upload(layer_mod, inp)
+    outs = []
+    for _ in range(2):
+        L = layer_mod.MoELayer.for_config(cfg)
+        L.forward(dev["x"], dev["wg"], dev["w1"], dev["w2"], *rep)
+        L.backward(dev["dy"], dev["w1"], dev["w2"])
+        torch.cuda.synchronize()
+        outs.append([t.clone() for t in (L.dest, L.src, L.vexpert_off, L.y, L.dx, L.dw1, L.dw2)])
+    for a, b in zip(*outs):
+        assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a,
+                           b.view(torch.int16) if b.dtype == torch.bfloat16 else b)
