@@ -41,78 +41,135 @@ union Frag8 {
 __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 __device__ __forceinline__ int lds_off(int row, int chunk) { return row * BK + ((chunk ^ swz(row)) << 3); }
 
-// ---- global -> registers ----------------------------------------------------------------
-// Operand stored [rows, K] with K contiguous.  Thread t owns chunk t&7 of rows (t>>3) + 32*i.
-// Rows >= rows_valid are not loaded (their 32-row block is skipped by the MFMA loop or their
-// results are dropped); chunks at k >= kmax read as zero.
-__device__ __forceinline__ void gload_kcontig(uint4 (&r)[8], const bf16_t* __restrict__ base, size_t ld, int rows_valid,
-                                              int k0, int kmax) {
-  const int c = threadIdx.x & 7, rr = threadIdx.x >> 3;
-  const bool kok = k0 + c * 8 < kmax;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int row = rr + 32 * i;
-    r[i] = make_uint4(0, 0, 0, 0);
-    if (kok && row < rows_valid) r[i] = *(const uint4*)(base + (size_t)row * ld + k0 + c * 8);
-  }
+// ---- workgroup id -> tile, XCD aware ---------------------------------------------------------
+// Workgroups are dealt round-robin to the 8 XCDs (id % 8), each with its own L2.  The tile grid
+// (rows x cols) is cut into patches of kPatchH x pw tiles (32 tiles, one per CU of an XCD) and
+// the j-th workgroup of XCD x gets tile j%32 of patch (j/32)*8 + x, so the workgroups that run
+// together on one XCD share kPatchH row operands and pw column operands in that L2 instead of
+// 32 different ones.
+constexpr int kXcds = 8, kPatch = 32;
+__host__ __device__ inline int patch_width(int cols) { return cols >= 7 ? 8 : (cols >= 3 ? 4 : (cols == 2 ? 2 : 1)); }
+__host__ __device__ inline unsigned patched_grid(int rows, int cols) {
+  const int pw = patch_width(cols), ph = kPatch / pw;
+  const int np = ((rows + ph - 1) / ph) * ((cols + pw - 1) / pw);
+  return (unsigned)((np + kXcds - 1) / kXcds * kXcds) * kPatch;
 }
-__device__ __forceinline__ void sstore_kcontig(bf16_t* tile, const uint4 (&r)[8]) {
-  const int c = threadIdx.x & 7, rr = threadIdx.x >> 3;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) *(uint4*)(tile + lds_off(rr + 32 * i, c)) = r[i];
+// returns false when the workgroup falls into the padding of the patch grid
+__device__ __forceinline__ bool patched_tile(unsigned b, int rows, int cols, int* r, int* c) {
+  const int pw = patch_width(cols), ph = kPatch / pw;
+  const int npc = (cols + pw - 1) / pw;
+  const unsigned x = b % kXcds, j = b / kXcds;
+  const unsigned P = (j / kPatch) * kXcds + x, q = j % kPatch;
+  *r = (int)(P / npc) * ph + (int)(q / pw);
+  *c = (int)(P % npc) * pw + (int)(q % pw);
+  return *r < rows && *c < cols;
 }
 
-// Operand stored [K, cols] with cols contiguous.  Thread t owns the 8x8 block at
-// k = 8*(t>>5).., col = 8*(t&31)..; rows k >= k_valid and columns >= cols_valid read as zero.
-__device__ __forceinline__ void gload_kstrided(uint4 (&r)[8], const bf16_t* __restrict__ base, size_t ld, int k_valid,
-                                               int cols_valid) {
-  const int nc = threadIdx.x & 31, kc = threadIdx.x >> 5;
-  const bool cok = nc * 8 < cols_valid;
+// ---- global -> registers -> LDS -------------------------------------------------------------
+// Workgroup barrier that orders LDS traffic only: global loads issued for a later tile stay in
+// flight across it (a full __syncthreads would wait for them).
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Operand stored [rows, ld] with the contraction index contiguous.  Thread t owns 16-byte chunk
+// t&7 of rows (t>>3) + 32*i.  Rows past rows_valid are clamped to the last valid row (their
+// products are never stored), so full-K tiles load without predication; a ragged last K tile
+// reads chunks past K as zero.
+struct KContigSrc {
+  const bf16_t* base;
+  uint32_t off[8];
+  int K;
+  __device__ __forceinline__ void init(const bf16_t* b, size_t ld, int rows_valid, int K_) {
+    base = b;
+    K = K_;
+    const int c = threadIdx.x & 7, rr = threadIdx.x >> 3;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int kk = kc * 8 + j;
-    r[j] = make_uint4(0, 0, 0, 0);
-    if (cok && kk < k_valid) r[j] = *(const uint4*)(base + (size_t)kk * ld + nc * 8);
+    for (int i = 0; i < 8; ++i) off[i] = (uint32_t)(min(rr + 32 * i, rows_valid - 1) * ld + c * 8);
   }
-}
-__device__ __forceinline__ uint32_t lo16(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
-__device__ __forceinline__ uint32_t hi16(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
-__device__ __forceinline__ void sstore_kstrided(bf16_t* tile, const uint4 (&r)[8]) {
-  const int nc = threadIdx.x & 31, kc = threadIdx.x >> 5;
-  // r[j] holds columns 0..7 of k-row j; emit, per column n, the 8 k-values as one 16-byte chunk
-  uint4 o;
-#define FLEXMOE_TR(n, comp, pick)                                                          \
+  __device__ __forceinline__ void load(uint4 (&r)[8], int k0) const {
+    if (k0 + BK <= K) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) r[i] = *(const uint4*)(base + k0 + off[i]);
+    } else {
+      const bool kok = k0 + (int)(threadIdx.x & 7) * 8 < K;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        r[i] = make_uint4(0, 0, 0, 0);
+        if (kok) r[i] = *(const uint4*)(base + k0 + off[i]);
+      }
+    }
+  }
+  static __device__ __forceinline__ void store(bf16_t* tile, const uint4 (&r)[8]) {
+    const int c = threadIdx.x & 7, rr = threadIdx.x >> 3;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) *(uint4*)(tile + lds_off(rr + 32 * i, c)) = r[i];
+  }
+};
+
+// Operand stored [K, ld] with the output index contiguous.  Thread t owns the 8x8 block at
+// k = 8*(t>>5).., column 8*(t&31)..; columns past cols_valid are clamped to the last valid
+// 8-column group; contraction rows >= k_valid read as zero (they would add to the sums).
+struct KStridedSrc {
+  uint32_t off[8];
+  __device__ __forceinline__ void init(size_t ld, int cols_valid) {
+    const int nc = min((int)(threadIdx.x & 31), cols_valid / 8 - 1), kc = threadIdx.x >> 5;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) off[j] = (uint32_t)((kc * 8 + j) * ld + nc * 8);
+  }
+  // `p` points at contraction row 0 of this tile, first column of the tile
+  __device__ __forceinline__ void load(uint4 (&r)[8], const bf16_t* __restrict__ p, int k_valid) const {
+    if (k_valid >= BK) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) r[j] = *(const uint4*)(p + off[j]);
+    } else {
+      const int kc = threadIdx.x >> 5;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        r[j] = make_uint4(0, 0, 0, 0);
+        if (kc * 8 + j < k_valid) r[j] = *(const uint4*)(p + off[j]);
+      }
+    }
+  }
+  static __device__ __forceinline__ uint32_t lo16(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
+  static __device__ __forceinline__ uint32_t hi16(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
+  // r[j] holds columns 0..7 of k-row j; emit, per column n, its 8 k-values as one 16-byte chunk
+  static __device__ __forceinline__ void store(bf16_t* tile, const uint4 (&r)[8]) {
+    const int nc = threadIdx.x & 31, kc = threadIdx.x >> 5;
+    uint4 o;
+#define FLEXMOE_TR(n, comp, pick)                                                                    \
   o = make_uint4(pick(r[0].comp, r[1].comp), pick(r[2].comp, r[3].comp), pick(r[4].comp, r[5].comp), \
-                 pick(r[6].comp, r[7].comp));                                                \
+                 pick(r[6].comp, r[7].comp));                                                        \
   *(uint4*)(tile + lds_off(nc * 8 + n, kc)) = o;
-  FLEXMOE_TR(0, x, lo16) FLEXMOE_TR(1, x, hi16) FLEXMOE_TR(2, y, lo16) FLEXMOE_TR(3, y, hi16)
-  FLEXMOE_TR(4, z, lo16) FLEXMOE_TR(5, z, hi16) FLEXMOE_TR(6, w, lo16) FLEXMOE_TR(7, w, hi16)
+    FLEXMOE_TR(0, x, lo16) FLEXMOE_TR(1, x, hi16) FLEXMOE_TR(2, y, lo16) FLEXMOE_TR(3, y, hi16)
+    FLEXMOE_TR(4, z, lo16) FLEXMOE_TR(5, z, hi16) FLEXMOE_TR(6, w, lo16) FLEXMOE_TR(7, w, hi16)
 #undef FLEXMOE_TR
-}
+  }
+};
 
 // ---- LDS -> MFMA ---------------------------------------------------------------------------
+// One 16-wide k step of the wave's 128x128 block.
 // acc[i][j]: output rows (wm + 2*i)*32 + lane%32, columns (wn*NB + j)*32 + 8*(q/4) + 4*(lane/32) + q%4.
 template <bool FULL>
-__device__ __forceinline__ void mma_tile(const bf16_t* __restrict__ As, const bf16_t* __restrict__ Bs,
-                                         f32x16 (&acc)[MB][NB], int wm, int wn, int nblk_rows) {
+__device__ __forceinline__ void mma_kstep(const bf16_t* __restrict__ As, const bf16_t* __restrict__ Bs, int s,
+                                          f32x16 (&acc)[MB][NB], int wm, int wn, int nblk_rows) {
   const int lane = threadIdx.x & 63;
   const int r = lane & 31, h = lane >> 5;
+  Frag8 af[MB], bfr[NB];
 #pragma unroll
-  for (int s = 0; s < BK / 16; ++s) {
-    Frag8 af[MB], bfr[NB];
+  for (int i = 0; i < MB; ++i)
+    if (FULL || wm + 2 * i < nblk_rows) af[i].u = *(const uint4*)(As + lds_off((wm + 2 * i) * 32 + r, 2 * s + h));
 #pragma unroll
-    for (int i = 0; i < MB; ++i)
-      if (FULL || wm + 2 * i < nblk_rows) af[i].u = *(const uint4*)(As + lds_off((wm + 2 * i) * 32 + r, 2 * s + h));
+  for (int j = 0; j < NB; ++j) bfr[j].u = *(const uint4*)(Bs + lds_off((wn * NB + j) * 32 + r, 2 * s + h));
 #pragma unroll
-    for (int j = 0; j < NB; ++j) bfr[j].u = *(const uint4*)(Bs + lds_off((wn * NB + j) * 32 + r, 2 * s + h));
+  for (int i = 0; i < MB; ++i)
+    if (FULL || wm + 2 * i < nblk_rows) {
 #pragma unroll
-    for (int i = 0; i < MB; ++i)
-      if (FULL || wm + 2 * i < nblk_rows) {
-#pragma unroll
-        for (int j = 0; j < NB; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j].v, af[i].v, acc[i][j], 0, 0, 0);
-      }
-  }
+      for (int j = 0; j < NB; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j].v, af[i].v, acc[i][j], 0, 0, 0);
+    }
 }
 
 __device__ __forceinline__ void zero_acc(f32x16 (&acc)[MB][NB]) {
@@ -128,104 +185,107 @@ __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
   return make_uint2(pack_bf16x2(a, b), pack_bf16x2(c, d));
 }
 
-// K loop of rows_gemm: register prefetch of tile kt+1 while tile kt is multiplied out of LDS.
+// One K tile of the software pipeline.  On entry LDS stage `cur` holds tile t and the registers
+// ra/rb hold tile t+1 (loaded during the previous step).  The tile is multiplied in four k
+// steps; early in the step each register set is written to stage `nxt` and immediately reused
+// for the loads of tile t+2, which then have most of a step of MFMA work to land.
+template <bool FULL, bool STORE, bool LOAD, typename StoreA, typename StoreB, typename LoadA, typename LoadB>
+__device__ __forceinline__ void pipe_step(bf16_t* cur, bf16_t* nxt, f32x16 (&acc)[MB][NB], uint4 (&ra)[8],
+                                          uint4 (&rb)[8], StoreA store_a, StoreB store_b, LoadA& load_a, LoadB& load_b,
+                                          int wm, int wn, int nblk_rows) {
+  mma_kstep<FULL>(cur, cur + kTileElems, 0, acc, wm, wn, nblk_rows);
+  if (STORE) store_a(nxt, ra);
+  if (LOAD) load_a(ra);
+  mma_kstep<FULL>(cur, cur + kTileElems, 1, acc, wm, wn, nblk_rows);
+  if (STORE) store_b(nxt + kTileElems, rb);
+  if (LOAD) load_b(rb);
+  mma_kstep<FULL>(cur, cur + kTileElems, 2, acc, wm, wn, nblk_rows);
+  mma_kstep<FULL>(cur, cur + kTileElems, 3, acc, wm, wn, nblk_rows);
+  lds_barrier();
+}
+
+// Drives T tiles through the pipeline.  load_a(ra) / load_b(rb) fetch the next tile in sequence.
+template <bool FULL, typename StoreA, typename StoreB, typename LoadA, typename LoadB>
+__device__ __forceinline__ void run_pipeline(bf16_t* smem, f32x16 (&acc)[MB][NB], int T, StoreA store_a,
+                                             StoreB store_b, LoadA& load_a, LoadB& load_b, int wm, int wn,
+                                             int nblk_rows) {
+  uint4 ra[8], rb[8];
+  load_a(ra);
+  load_b(rb);
+  store_a(smem, ra);
+  store_b(smem + kTileElems, rb);
+  if (T > 1) {
+    load_a(ra);
+    load_b(rb);
+  }
+  lds_barrier();
+  int t = 0;
+  for (; t + 2 < T; ++t) {
+    bf16_t* cur = smem + (t & 1) * 2 * kTileElems;
+    bf16_t* nxt = smem + ((t & 1) ^ 1) * 2 * kTileElems;
+    pipe_step<FULL, true, true>(cur, nxt, acc, ra, rb, store_a, store_b, load_a, load_b, wm, wn, nblk_rows);
+  }
+  if (t + 1 < T) {
+    bf16_t* cur = smem + (t & 1) * 2 * kTileElems;
+    bf16_t* nxt = smem + ((t & 1) ^ 1) * 2 * kTileElems;
+    pipe_step<FULL, true, false>(cur, nxt, acc, ra, rb, store_a, store_b, load_a, load_b, wm, wn, nblk_rows);
+    ++t;
+  }
+  {
+    bf16_t* cur = smem + (t & 1) * 2 * kTileElems;
+    pipe_step<FULL, false, false>(cur, cur, acc, ra, rb, store_a, store_b, load_a, load_b, wm, wn, nblk_rows);
+  }
+}
+
+// K loop of rows_gemm.
 template <bool WT, bool FULL>
 __device__ __forceinline__ void rows_mainloop(bf16_t* smem, f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ a_base,
                                               const bf16_t* __restrict__ w_e, int K, int NC, int n0, int rows_valid,
                                               int cols_valid, int wm, int wn, int nblk_rows) {
   const int KT = (K + BK - 1) / BK;
-  uint4 ra[8], rb[8];
-  gload_kcontig(ra, a_base, K, rows_valid, 0, K);
-  if (WT) gload_kcontig(rb, w_e + (size_t)n0 * K, K, cols_valid, 0, K);
-  else gload_kstrided(rb, w_e + n0, NC, K, cols_valid);
-  sstore_kcontig(smem, ra);
-  if (WT) sstore_kcontig(smem + kTileElems, rb); else sstore_kstrided(smem + kTileElems, rb);
-  __syncthreads();
-
-  for (int kt = 0; kt < KT; ++kt) {
-    bf16_t* cur = smem + (kt & 1) * 2 * kTileElems;
-    bf16_t* nxt = smem + ((kt & 1) ^ 1) * 2 * kTileElems;
-    const bool more = kt + 1 < KT;
-    if (more) {
-      const int k0 = (kt + 1) * BK;
-      gload_kcontig(ra, a_base, K, rows_valid, k0, K);
-      if (WT) gload_kcontig(rb, w_e + (size_t)n0 * K, K, cols_valid, k0, K);
-      else gload_kstrided(rb, w_e + (size_t)k0 * NC + n0, NC, K - k0, cols_valid);
-    }
-    mma_tile<FULL>(cur, cur + kTileElems, acc, wm, wn, nblk_rows);
-    if (more) {
-      sstore_kcontig(nxt, ra);
-      if (WT) sstore_kcontig(nxt + kTileElems, rb); else sstore_kstrided(nxt + kTileElems, rb);
-    }
-    __syncthreads();
+  KContigSrc a_src;
+  a_src.init(a_base, K, rows_valid, K);
+  int ka = 0, kb = 0;
+  auto load_a = [&](uint4 (&ra)[8]) {
+    a_src.load(ra, ka);
+    ka += BK;
+  };
+  if (WT) {
+    KContigSrc w_src;
+    w_src.init(w_e + (size_t)n0 * K, K, cols_valid, K);
+    auto load_b = [&](uint4 (&rb)[8]) {
+      w_src.load(rb, kb);
+      kb += BK;
+    };
+    run_pipeline<FULL>(smem, acc, KT, KContigSrc::store, KContigSrc::store, load_a, load_b, wm, wn, nblk_rows);
+  } else {
+    KStridedSrc w_src;
+    w_src.init(NC, cols_valid);
+    const bf16_t* wp = w_e + n0;
+    auto load_b = [&](uint4 (&rb)[8]) {
+      w_src.load(rb, wp + (size_t)kb * NC, K - kb);
+      kb += BK;
+    };
+    run_pipeline<FULL>(smem, acc, KT, KContigSrc::store, KStridedSrc::store, load_a, load_b, wm, wn, nblk_rows);
   }
 }
 
-// =============================================================================================
-// rows_gemm: C[p, n] = sum_k In[p, k] * W_e[k, n] (WT=false, W_e [K,NC]) or W_e[n, k] (WT=true)
-// =============================================================================================
-template <bool WT, int EPI, int ACT>
-__global__ __launch_bounds__(kGemmThreads) void rows_gemm_bf16(
-    const bf16_t* __restrict__ in, const bf16_t* __restrict__ w, const bf16_t* __restrict__ bias,
-    const int32_t* __restrict__ voff, const int32_t* __restrict__ owner, int V, int K, int NC, int col_tiles,
-    const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0, bf16_t* __restrict__ out1) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16_t* smem = (bf16_t*)smem_raw;
-  __shared__ int s_tile[3];
-
-  // flat row-tile index -> (vExpert, tile inside it): one wave scans the buckets' tile counts
-  const int rt = blockIdx.x / col_tiles, ct = blockIdx.x % col_tiles;
-  if (threadIdx.x < kWave) {
-    const int lane = threadIdx.x;
-    if (lane == 0) s_tile[0] = -1;
-    const int per = (V + kWave - 1) / kWave;     // <= 8 buckets per lane
-    int cnt[FLEXMOE_MAX_VEXPERTS / kWave];
-    int sum = 0;
-#pragma unroll
-    for (int q = 0; q < FLEXMOE_MAX_VEXPERTS / kWave; ++q) {
-      const int v = lane * per + q;
-      cnt[q] = 0;
-      if (q < per && v < V) cnt[q] = (voff[v + 1] - voff[v] + BM - 1) / BM;
-      sum += cnt[q];
-    }
-    int incl = sum;
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-      const int up = __shfl_up(incl, o);
-      if (lane >= o) incl += up;
-    }
-    int start = incl - sum;
-#pragma unroll
-    for (int q = 0; q < FLEXMOE_MAX_VEXPERTS / kWave; ++q) {
-      if (rt >= start && rt < start + cnt[q]) {
-        s_tile[0] = lane * per + q;
-        s_tile[1] = rt - start;
-      }
-      start += cnt[q];
-    }
-  }
-  __syncthreads();
-  const int v = s_tile[0];
-  if (v < 0) return;                                  // beyond the last tile (uniform)
-  const int row0 = voff[v] + s_tile[1] * BM;
-  const int rows_valid = min(BM, voff[v + 1] - row0);
-  const int e = owner[v];
-  const int n0 = ct * BN;
-  const int cols_valid = min(BN, NC - n0);
+// One output tile of rows_gemm: main loop and epilogue.  FULL = all eight 32-row blocks hold rows.
+// (Kept as two separate instantiations with their own accumulators: merging the accumulators of
+// a full-tile and a ragged-tile path costs hundreds of register copies.)
+template <bool WT, int EPI, int ACT, bool FULL>
+__device__ __forceinline__ void rows_tile(bf16_t* smem, const bf16_t* __restrict__ in, const bf16_t* __restrict__ w,
+                                          const bf16_t* __restrict__ bias, int K, int NC, int row0, int rows_valid,
+                                          int e, int n0, int cols_valid, const bf16_t* __restrict__ hpre_in,
+                                          bf16_t* __restrict__ out0, bf16_t* __restrict__ out1) {
   const int nblk_rows = (rows_valid + 31) >> 5;
-
   const bf16_t* a_base = in + (size_t)row0 * K;
   const bf16_t* w_e = w + (size_t)e * K * NC;
-
   const int wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   f32x16 acc[MB][NB];
   zero_acc(acc);
-
-  if (nblk_rows == 2 * MB)
-    rows_mainloop<WT, true>(smem, acc, a_base, w_e, K, NC, n0, rows_valid, cols_valid, wm, wn, nblk_rows);
-  else
-    rows_mainloop<WT, false>(smem, acc, a_base, w_e, K, NC, n0, rows_valid, cols_valid, wm, wn, nblk_rows);
+  rows_mainloop<WT, FULL>(smem, acc, a_base, w_e, K, NC, n0, rows_valid, cols_valid, wm, wn, nblk_rows);
 
   // epilogue: lane owns row (lane%32) of each of its row blocks and 4-column groups
   const int lane = threadIdx.x & 63;
@@ -273,6 +333,64 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_bf16(
   }
 }
 
+
+template <bool WT, int EPI, int ACT>
+__global__ __launch_bounds__(kGemmThreads) void rows_gemm_bf16(
+    const bf16_t* __restrict__ in, const bf16_t* __restrict__ w, const bf16_t* __restrict__ bias,
+    const int32_t* __restrict__ voff, const int32_t* __restrict__ owner, int V, int K, int NC, int row_tiles_max,
+    int col_tiles, const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0, bf16_t* __restrict__ out1) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t* smem = (bf16_t*)smem_raw;
+  __shared__ int s_tile[3];
+
+  // flat row-tile index -> (vExpert, tile inside it): one wave scans the buckets' tile counts
+  int rt, ct;
+  const bool in_grid = patched_tile(blockIdx.x, row_tiles_max, col_tiles, &rt, &ct);
+  if (threadIdx.x < kWave) {
+    const int lane = threadIdx.x;
+    if (lane == 0) s_tile[0] = -1;
+    if (!in_grid) rt = -1;
+    const int per = (V + kWave - 1) / kWave;     // <= 8 buckets per lane
+    int cnt[FLEXMOE_MAX_VEXPERTS / kWave];
+    int sum = 0;
+#pragma unroll
+    for (int q = 0; q < FLEXMOE_MAX_VEXPERTS / kWave; ++q) {
+      const int v = lane * per + q;
+      cnt[q] = 0;
+      if (q < per && v < V) cnt[q] = (voff[v + 1] - voff[v] + BM - 1) / BM;
+      sum += cnt[q];
+    }
+    int incl = sum;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const int up = __shfl_up(incl, o);
+      if (lane >= o) incl += up;
+    }
+    int start = incl - sum;
+#pragma unroll
+    for (int q = 0; q < FLEXMOE_MAX_VEXPERTS / kWave; ++q) {
+      if (rt >= start && rt < start + cnt[q]) {
+        s_tile[0] = lane * per + q;
+        s_tile[1] = rt - start;
+      }
+      start += cnt[q];
+    }
+  }
+  __syncthreads();
+  const int v = s_tile[0];
+  if (v < 0) return;                                  // beyond the last tile (uniform)
+  const int row0 = voff[v] + s_tile[1] * BM;
+  const int rows_valid = min(BM, voff[v + 1] - row0);
+  const int e = owner[v];
+  const int n0 = ct * BN;
+  const int cols_valid = min(BN, NC - n0);
+  const int nblk_rows = (rows_valid + 31) >> 5;
+  // Ragged tiles run the full-tile code (rows past the bucket are clamped on load and dropped
+  // on store): skipping their empty 32-row MFMA blocks needs conditional MFMA groups, which the
+  // register allocator only handles by spilling the accumulators.
+  rows_tile<WT, EPI, ACT, true>(smem, in, w, bias, K, NC, row0, rows_valid, e, n0, cols_valid, hpre_in, out0, out1);
+}
+
 // =============================================================================================
 // wgrad_gemm: dW_e[m, n] = sum_{v owned by e, ascending v} sum_{p in bucket v} L[p, m] * R[p, n]
 // =============================================================================================
@@ -290,10 +408,10 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_bf16(const bf16_t* __
   __shared__ int s_nb;
   __shared__ int s_bstart[FLEXMOE_MAX_VEXPERTS], s_brows[FLEXMOE_MAX_VEXPERTS];
 
-  const int tiles_per_e = m_tiles * n_tiles;
-  const int want_rank = blockIdx.x / tiles_per_e;
-  const int tile = blockIdx.x % tiles_per_e;
-  const int mt = tile / n_tiles, nt = tile % n_tiles;
+  // tile grid: rows = (expert by descending load, m tile), cols = n tile
+  int grow, nt;
+  if (!patched_tile(blockIdx.x, E * m_tiles, n_tiles, &grow, &nt)) return;
+  const int want_rank = grow / m_tiles, mt = grow % m_tiles;
 
   for (int v = threadIdx.x; v < V; v += kGemmThreads) {
     s_cnt[v] = voff[v + 1] - voff[v];
@@ -343,44 +461,31 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_bf16(const bf16_t* __
   zero_acc(acc);
 
   if (nb > 0) {
-    uint4 ra[8], rb[8];
-    int bi = 0, koff = 0;
-    {
-      const size_t p0 = (size_t)s_bstart[0];
-      gload_kstrided(ra, L + p0 * M + m0, M, s_brows[0], mvalid);
-      gload_kstrided(rb, R + p0 * NC + n0, NC, s_brows[0], nvalid);
-    }
-    sstore_kstrided(smem, ra);
-    sstore_kstrided(smem + kTileElems, rb);
-    __syncthreads();
-    int it = 0;
-    while (true) {
-      // advance to the next K tile (next 64 tokens of this bucket, else the next bucket)
-      int nbi = bi, nkoff = koff + BK;
-      if (nkoff >= s_brows[bi]) {
-        nbi = bi + 1;
-        nkoff = 0;
+    int T = 0;
+    for (int b = 0; b < nb; ++b) T += (s_brows[b] + BK - 1) / BK;
+    KStridedSrc l_src, r_src;
+    l_src.init(M, mvalid);
+    r_src.init(NC, nvalid);
+    // next K tile of each operand: 64 tokens of bucket bi starting at koff
+    struct Cursor {
+      int bi, koff;
+    } ca{0, 0}, cb{0, 0};
+    auto advance = [&](Cursor& c) {
+      c.koff += BK;
+      if (c.koff >= s_brows[c.bi]) {
+        c.koff = 0;
+        c.bi = min(c.bi + 1, nb - 1);
       }
-      const bool more = nbi < nb;
-      bf16_t* cur = smem + (it & 1) * 2 * kTileElems;
-      bf16_t* nxt = smem + ((it & 1) ^ 1) * 2 * kTileElems;
-      if (more) {
-        const size_t p0 = (size_t)s_bstart[nbi] + nkoff;
-        const int kv = s_brows[nbi] - nkoff;
-        gload_kstrided(ra, L + p0 * M + m0, M, kv, mvalid);
-        gload_kstrided(rb, R + p0 * NC + n0, NC, kv, nvalid);
-      }
-      mma_tile<true>(cur, cur + kTileElems, acc, wm, wn, MB * 2);
-      if (more) {
-        sstore_kstrided(nxt, ra);
-        sstore_kstrided(nxt + kTileElems, rb);
-      }
-      __syncthreads();
-      if (!more) break;
-      bi = nbi;
-      koff = nkoff;
-      ++it;
-    }
+    };
+    auto load_a = [&](uint4 (&ra)[8]) {
+      l_src.load(ra, L + ((size_t)s_bstart[ca.bi] + ca.koff) * M + m0, s_brows[ca.bi] - ca.koff);
+      advance(ca);
+    };
+    auto load_b = [&](uint4 (&rb)[8]) {
+      r_src.load(rb, R + ((size_t)s_bstart[cb.bi] + cb.koff) * NC + n0, s_brows[cb.bi] - cb.koff);
+      advance(cb);
+    };
+    run_pipeline<true>(smem, acc, T, KStridedSrc::store, KStridedSrc::store, load_a, load_b, wm, wn, MB * 2);
   }
 
   const int lane = threadIdx.x & 63;
@@ -426,9 +531,10 @@ static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w,
     attr_done = true;
   }
   const int col_tiles = (NC + BN - 1) / BN;
-  const unsigned grid = (unsigned)max_row_tiles(a.A, a.V) * col_tiles;
+  const int row_tiles = max_row_tiles(a.A, a.V);
+  const unsigned grid = patched_grid(row_tiles, col_tiles);
   hipLaunchKernelGGL((rows_gemm_bf16<WT, EPI, ACT>), dim3(grid), dim3(kGemmThreads), kGemmLds, s, (const bf16_t*)in,
-                     (const bf16_t*)w, (const bf16_t*)bias, a.voff, a.owner, a.V, K, NC, col_tiles,
+                     (const bf16_t*)w, (const bf16_t*)bias, a.voff, a.owner, a.V, K, NC, row_tiles, col_tiles,
                      (const bf16_t*)hpre_in, (bf16_t*)out0, (bf16_t*)out1);
   return hipGetLastError();
 }
@@ -452,7 +558,7 @@ static hipError_t launch_wgrad(const FfnArgs& a, const void* L, const void* R, i
     attr_done = true;
   }
   const int m_tiles = (M + BM - 1) / BM, n_tiles = (NC + BN - 1) / BN;
-  hipLaunchKernelGGL(wgrad_gemm_bf16, dim3((unsigned)a.E * m_tiles * n_tiles), dim3(kGemmThreads), kGemmLds, s,
+  hipLaunchKernelGGL(wgrad_gemm_bf16, dim3(patched_grid(a.E * m_tiles, n_tiles)), dim3(kGemmThreads), kGemmLds, s,
                      (const bf16_t*)L, (const bf16_t*)R, a.voff, a.owner, a.E, a.V, M, NC, m_tiles, n_tiles,
                      (bf16_t*)dw);
   return hipGetLastError();
