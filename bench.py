@@ -26,6 +26,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per call of flexmoe_expert_ffn_fwd from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the
+# same counters' reading of a plain 1 GiB copy (summary and commands: profiles/*_hbm_traffic.txt).
+MEASURED_FFN_FWD_TRAFFIC_BYTES = {"bert": 736.9e6}
+
 WORKLOAD_TEXT = {
     "tiny": "configs[0] tiny fp32 MoE layer, forward",
     "bert": "configs[1] BERT-base-like MoE layer bf16, forward, 8192 tokens, d=768, f=3072, E=16, k=2, V=18",
@@ -90,8 +94,9 @@ class Runner:
         L, cfg = self.L, self.cfg
         from paper_2304_03946_amd import binding as B
         j = self.iter // 10 if self.drifting else 0
-        if self.drifting and self.iter % 10 == 0 and self.iter > 0:
-            # the hot set moved: new table from the loads of the previous step (inside the timed region)
+        if self.drifting and self.iter % 10 == 1 and self.iter > 1:
+            # the hot set moved on the previous step: new table from the loads that step observed
+            # (the read-back and the table build are inside the timed region)
             self.rep = self.W.placement_from_loads(L.expert_count.cpu().numpy(), cfg.V, cfg.max_rep)
         wg = self.wg_by_drift[j]
         rec = timers.record if timers else (lambda name: None)
@@ -209,6 +214,8 @@ def main():
     ap.add_argument("--workload", default="bert", choices=list(WORKLOAD_TEXT))
     ap.add_argument("--all-workloads", action="store_true", help="also time the other configurations (extra JSON field)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run a plain 1 GiB device copy (calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs the MoE-layer hot path on ONE GPU; --gpus N with N > 1 is not supported "
@@ -222,6 +229,13 @@ def main():
     steps = args.steps if args.steps is not None else (20 if big else 200)
     warmup = args.warmup if args.warmup is not None else (3 if big else 20)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     r, res = run_workload(name, steps, warmup)
     cfg = r.cfg
     ffn = res["stages"]["ffn_fwd"]
@@ -245,7 +259,7 @@ def main():
         "roofline": {"kernel": "flexmoe_expert_ffn_fwd (two grouped-GEMM launches: rows_gemm_bf16 x2)",
                      "bound": ffn["bound"], "achieved": ffn["achieved"],
                      "peak": MFMA_BF16_PEAK_TFLOPS if cfg.dtype == W.DT_BF16 else FP32_VECTOR_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": ffn["frac"], "traffic": None,
+                     "unit": "TFLOP/s", "frac": ffn["frac"], "traffic": MEASURED_FFN_FWD_TRAFFIC_BYTES.get(name),
                      "launch_ms": dom_ms, "algorithmic_flops": 4 * cfg.A * cfg.d * cfg.f,
                      "stages": res["stages"]},
     }

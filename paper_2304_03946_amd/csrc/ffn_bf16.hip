@@ -3,13 +3,12 @@
 //
 // Two kernel families share one 256x256x64 workgroup tile (4 wavefronts, 2x2, each owning a
 // 128x128 accumulator block = 16 MFMA tiles; operands staged through LDS, double buffered,
-// one barrier per K step):
+// one LDS-only barrier per K step, the next-but-one K tile in flight in registers):
 //
 //  * rows_gemm: C[rows of bucket v, :] = In[rows of v, :] . W_owner(v)    (fwd GEMM1/GEMM2,
 //    bwd dH and dXp).  The row dimension is cut per bucket: a device-side lookup maps the flat
 //    row-tile index to (vExpert, tile inside it), so highly skewed bucket sizes need no host
-//    synchronisation.  A ragged last tile of a bucket only runs the 32-row MFMA blocks that
-//    hold rows; row blocks are dealt to the two wave rows alternately so both stay busy.
+//    synchronisation.  Rows of a ragged last tile are clamped on load and dropped on store.
 //  * wgrad_gemm: dW_e = sum over the vExperts v of e of L_v^T . R_v  -- the contraction runs
 //    over the tokens of every bucket of e in ascending vExpert id inside one accumulator, which
 //    is the single-GPU image of the paper's replica gradient synchronisation.  Output tiles are
