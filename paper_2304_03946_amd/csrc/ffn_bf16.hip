@@ -19,7 +19,8 @@
 // [row][64 k] with the 16-byte chunk index XOR-swizzled by (row ^ row>>3) & 7, which keeps the
 // MFMA fragment reads and both kinds of tile writes free of bank conflicts.
 // The MFMA is issued as (weights-fragment, activations-fragment) so that a lane ends up with 4
-// consecutive output columns of one output row: 8-byte stores.
+// consecutive output columns of one output row; the epilogue passes the accumulators through a
+// wave-private LDS patch so that global stores fill whole 128-byte lines.
 #include "common.h"
 
 namespace flexmoe {
@@ -183,6 +184,48 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[MB][NB]) {
 __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
   return make_uint2(pack_bf16x2(a, b), pack_bf16x2(c, d));
 }
+__device__ __forceinline__ void unpack4(uint2 u, float* v) {
+  v[0] = __uint_as_float(u.x << 16);
+  v[1] = __uint_as_float(u.x & 0xffff0000u);
+  v[2] = __uint_as_float(u.y << 16);
+  v[3] = __uint_as_float(u.y & 0xffff0000u);
+}
+
+// ---- epilogue ---------------------------------------------------------------------------------
+// A lane's accumulators hold 4-column pieces of 32 different rows, which would make every global
+// store touch 32 cache lines.  Instead the wave's 128x128 fp32 block goes out in eight rounds of
+// 32 rows x 64 columns: accumulator registers -> wave-private 8 KB LDS patch (16-byte chunks,
+// chunk index XORed with row & 15: conflict free both ways) -> read back so that 16 lanes cover
+// 64 consecutive columns of one row -> per-element epilogue in fp32 -> bf16 -> 8-byte stores that
+// fill whole 128-byte lines.  The K loop ends with a barrier, so the LDS tiles are free.
+// emit(row in the wave's block (0..127), column in the wave's block (multiple of 4), float4)
+template <typename Emit>
+__device__ __forceinline__ void epilogue_rounds(float* patch, const f32x16 (&acc)[MB][NB], Emit emit) {
+  const int lane = threadIdx.x & 63;
+  const int r = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < MB; ++i) {
+#pragma unroll
+    for (int jh = 0; jh < NB / 2; ++jh) {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int c = jj * 8 + 2 * g + h;
+          const f32x16& a = acc[i][jh * 2 + jj];
+          *(float4*)(patch + r * 64 + ((c ^ (r & 15)) << 2)) = make_float4(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]);
+        }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront", "local");
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int row = it * 4 + (lane >> 4), c = lane & 15;
+        const float4 v = *(const float4*)(patch + row * 64 + ((c ^ (row & 15)) << 2));
+        emit(i * 32 + row, jh * 64 + c * 4, v);
+      }
+    }
+  }
+}
 
 // One K tile of the software pipeline.  On entry LDS stage `cur` holds tile t and the registers
 // ra/rb hold tile t+1 (loaded during the previous step).  The tile is multiplied in four k
@@ -286,52 +329,39 @@ __device__ __forceinline__ void rows_tile(bf16_t* smem, const bf16_t* __restrict
   zero_acc(acc);
   rows_mainloop<WT, FULL>(smem, acc, a_base, w_e, K, NC, n0, rows_valid, cols_valid, wm, wn, nblk_rows);
 
-  // epilogue: lane owns row (lane%32) of each of its row blocks and 4-column groups
-  const int lane = threadIdx.x & 63;
-  const int r = lane & 31, h = lane >> 5;
+  // epilogue through the wave-private LDS patch
+  float* patch = (float*)smem + (threadIdx.x >> 6) * (32 * 64);
+  const int col_base = n0 + wn * (NB * 32);
+  epilogue_rounds(patch, acc, [&](int row_w, int col_w, float4 c) {
+    const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
+    const int col = col_base + col_w;
+    if (lrow < rows_valid && col < NC) {
+      if (bias) {
+        float b[4];
+        unpack4(*(const uint2*)(bias + (size_t)e * NC + col), b);
+        c.x += b[0]; c.y += b[1]; c.z += b[2]; c.w += b[3];
+      }
+      const size_t o = (size_t)(row0 + lrow) * NC + col;
+      if (EPI == EPI_PLAIN) {
+        *(uint2*)(out0 + o) = pack4(c.x, c.y, c.z, c.w);
+      } else if (EPI == EPI_FWD1) {
+        // keep the pre-activation; the activation is taken of the value as stored
+        const uint2 pre = pack4(c.x, c.y, c.z, c.w);
+        *(uint2*)(out0 + o) = pre;
+        float z[4];
+        unpack4(pre, z);
+        *(uint2*)(out1 + o) = pack4(act_fast<ACT>(z[0]), act_fast<ACT>(z[1]), act_fast<ACT>(z[2]), act_fast<ACT>(z[3]));
+      } else {
+        float z[4], a[4], d[4];
+        unpack4(*(const uint2*)(hpre_in + o), z);
 #pragma unroll
-  for (int i = 0; i < MB; ++i) {
-    const int lrow = (wm + 2 * i) * 32 + r;
-    const bool row_ok = lrow < rows_valid;
-    const size_t grow = (size_t)(row0 + lrow);
-#pragma unroll
-    for (int j = 0; j < NB; ++j) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int lcol = (wn * NB + j) * 32 + 8 * g + 4 * h;
-        if (row_ok && lcol < cols_valid) {
-          const int col = n0 + lcol;
-          float c0 = acc[i][j][4 * g + 0], c1 = acc[i][j][4 * g + 1], c2 = acc[i][j][4 * g + 2], c3 = acc[i][j][4 * g + 3];
-          if (bias) {
-            const uint2 bb = *(const uint2*)(bias + (size_t)e * NC + col);
-            c0 += __uint_as_float(bb.x << 16); c1 += __uint_as_float(bb.x & 0xffff0000u);
-            c2 += __uint_as_float(bb.y << 16); c3 += __uint_as_float(bb.y & 0xffff0000u);
-          }
-          const size_t o = grow * NC + col;
-          if (EPI == EPI_PLAIN) {
-            *(uint2*)(out0 + o) = pack4(c0, c1, c2, c3);
-          } else if (EPI == EPI_FWD1) {
-            // keep the pre-activation; the activation is taken of the value as stored
-            const uint2 pre = pack4(c0, c1, c2, c3);
-            *(uint2*)(out0 + o) = pre;
-            *(uint2*)(out1 + o) = pack4(act_fast<ACT>(__uint_as_float(pre.x << 16)), act_fast<ACT>(__uint_as_float(pre.x & 0xffff0000u)),
-                                        act_fast<ACT>(__uint_as_float(pre.y << 16)), act_fast<ACT>(__uint_as_float(pre.y & 0xffff0000u)));
-          } else {
-            const uint2 pre = *(const uint2*)(hpre_in + o);
-            float a0, a1, a2, a3, d0, d1, d2, d3;
-            act_both<ACT>(__uint_as_float(pre.x << 16), &a0, &d0);
-            act_both<ACT>(__uint_as_float(pre.x & 0xffff0000u), &a1, &d1);
-            act_both<ACT>(__uint_as_float(pre.y << 16), &a2, &d2);
-            act_both<ACT>(__uint_as_float(pre.y & 0xffff0000u), &a3, &d3);
-            *(uint2*)(out0 + o) = pack4(c0 * d0, c1 * d1, c2 * d2, c3 * d3);
-            *(uint2*)(out1 + o) = pack4(a0, a1, a2, a3);
-          }
-        }
+        for (int q = 0; q < 4; ++q) act_both<ACT>(z[q], &a[q], &d[q]);
+        *(uint2*)(out0 + o) = pack4(c.x * d[0], c.y * d[1], c.z * d[2], c.w * d[3]);
+        *(uint2*)(out1 + o) = pack4(a[0], a[1], a[2], a[3]);
       }
     }
-  }
+  });
 }
-
 
 template <bool WT, int EPI, int ACT>
 __global__ __launch_bounds__(kGemmThreads) void rows_gemm_bf16(
@@ -487,23 +517,14 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_bf16(const bf16_t* __
     run_pipeline<true>(smem, acc, T, KStridedSrc::store, KStridedSrc::store, load_a, load_b, wm, wn, MB * 2);
   }
 
-  const int lane = threadIdx.x & 63;
-  const int r = lane & 31, h = lane >> 5;
+  float* patch = (float*)smem + wave * (32 * 64);
   bf16_t* out = dw + (size_t)e * M * NC;
-#pragma unroll
-  for (int i = 0; i < MB; ++i) {
-    const int lrow = (wm + 2 * i) * 32 + r;
-    const bool row_ok = lrow < mvalid;
-#pragma unroll
-    for (int j = 0; j < NB; ++j)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int lcol = (wn * NB + j) * 32 + 8 * g + 4 * h;
-        if (row_ok && lcol < nvalid)
-          *(uint2*)(out + (size_t)(m0 + lrow) * NC + n0 + lcol) =
-              pack4(acc[i][j][4 * g + 0], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-      }
-  }
+  const int col_base = n0 + wn * (NB * 32);
+  epilogue_rounds(patch, acc, [&](int row_w, int col_w, float4 c) {
+    const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
+    const int col = col_base + col_w;
+    if (lrow < mvalid && col < NC) *(uint2*)(out + (size_t)(m0 + lrow) * NC + col) = pack4(c.x, c.y, c.z, c.w);
+  });
 }
 
 // =============================================================================================
