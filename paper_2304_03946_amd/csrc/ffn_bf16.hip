@@ -312,25 +312,15 @@ __device__ __forceinline__ void rows_mainloop(bf16_t* smem, f32x16 (&acc)[MB][NB
   }
 }
 
-// One output tile of rows_gemm: main loop and epilogue.  FULL = all eight 32-row blocks hold rows.
-// (Kept as two separate instantiations with their own accumulators: merging the accumulators of
-// a full-tile and a ragged-tile path costs hundreds of register copies.)
-template <bool WT, int EPI, int ACT, bool FULL>
-__device__ __forceinline__ void rows_tile(bf16_t* smem, const bf16_t* __restrict__ in, const bf16_t* __restrict__ w,
-                                          const bf16_t* __restrict__ bias, int K, int NC, int row0, int rows_valid,
-                                          int e, int n0, int cols_valid, const bf16_t* __restrict__ hpre_in,
-                                          bf16_t* __restrict__ out0, bf16_t* __restrict__ out1) {
-  const int nblk_rows = (rows_valid + 31) >> 5;
-  const bf16_t* a_base = in + (size_t)row0 * K;
-  const bf16_t* w_e = w + (size_t)e * K * NC;
+// Epilogue of the rows kernels: bias, then plain store / pre-activation + activation / dH*act' + H.
+template <int EPI, int ACT>
+__device__ __forceinline__ void rows_epilogue(float* lds, const f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ bias,
+                                              int NC, int row0, int rows_valid, int e, int n0,
+                                              const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
+                                              bf16_t* __restrict__ out1) {
   const int wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  f32x16 acc[MB][NB];
-  zero_acc(acc);
-  rows_mainloop<WT, FULL>(smem, acc, a_base, w_e, K, NC, n0, rows_valid, cols_valid, wm, wn, nblk_rows);
-
-  // epilogue through the wave-private LDS patch
-  float* patch = (float*)smem + (threadIdx.x >> 6) * (32 * 64);
+  float* patch = lds + wave * (32 * 64);
   const int col_base = n0 + wn * (NB * 32);
   epilogue_rounds(patch, acc, [&](int row_w, int col_w, float4 c) {
     const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
@@ -363,16 +353,34 @@ __device__ __forceinline__ void rows_tile(bf16_t* smem, const bf16_t* __restrict
   });
 }
 
-template <bool WT, int EPI, int ACT>
-__global__ __launch_bounds__(kGemmThreads) void rows_gemm_bf16(
-    const bf16_t* __restrict__ in, const bf16_t* __restrict__ w, const bf16_t* __restrict__ bias,
-    const int32_t* __restrict__ voff, const int32_t* __restrict__ owner, int V, int K, int NC, int row_tiles_max,
-    int col_tiles, const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0, bf16_t* __restrict__ out1) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16_t* smem = (bf16_t*)smem_raw;
-  __shared__ int s_tile[3];
+// One output tile of rows_gemm: main loop and epilogue.  FULL = all eight 32-row blocks hold rows.
+// (Kept as two separate instantiations with their own accumulators: merging the accumulators of
+// a full-tile and a ragged-tile path costs hundreds of register copies.)
+template <bool WT, int EPI, int ACT, bool FULL>
+__device__ __forceinline__ void rows_tile(bf16_t* smem, const bf16_t* __restrict__ in, const bf16_t* __restrict__ w,
+                                          const bf16_t* __restrict__ bias, int K, int NC, int row0, int rows_valid,
+                                          int e, int n0, int cols_valid, const bf16_t* __restrict__ hpre_in,
+                                          bf16_t* __restrict__ out0, bf16_t* __restrict__ out1) {
+  const int nblk_rows = (rows_valid + 31) >> 5;
+  const bf16_t* a_base = in + (size_t)row0 * K;
+  const bf16_t* w_e = w + (size_t)e * K * NC;
+  const int wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  f32x16 acc[MB][NB];
+  zero_acc(acc);
+  rows_mainloop<WT, FULL>(smem, acc, a_base, w_e, K, NC, n0, rows_valid, cols_valid, wm, wn, nblk_rows);
 
-  // flat row-tile index -> (vExpert, tile inside it): one wave scans the buckets' tile counts
+  rows_epilogue<EPI, ACT>((float*)smem, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1);
+}
+
+// flat row-tile index -> (vExpert, tile inside it): one wave scans the buckets' tile counts.
+// Returns false (for the whole workgroup) when the workgroup has no tile.
+struct RowTile {
+  int row0, rows_valid, e, n0, cols_valid;
+};
+__device__ __forceinline__ bool lookup_row_tile(const int32_t* __restrict__ voff, const int32_t* __restrict__ owner,
+                                                int V, int NC, int row_tiles_max, int col_tiles, int* s_tile,
+                                                RowTile* out) {
   int rt, ct;
   const bool in_grid = patched_tile(blockIdx.x, row_tiles_max, col_tiles, &rt, &ct);
   if (threadIdx.x < kWave) {
@@ -407,17 +415,176 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_bf16(
   }
   __syncthreads();
   const int v = s_tile[0];
-  if (v < 0) return;                                  // beyond the last tile (uniform)
-  const int row0 = voff[v] + s_tile[1] * BM;
-  const int rows_valid = min(BM, voff[v + 1] - row0);
-  const int e = owner[v];
-  const int n0 = ct * BN;
-  const int cols_valid = min(BN, NC - n0);
-  const int nblk_rows = (rows_valid + 31) >> 5;
+  if (v < 0) return false;                            // beyond the last tile (uniform)
+  out->row0 = voff[v] + s_tile[1] * BM;
+  out->rows_valid = min(BM, voff[v + 1] - out->row0);
+  out->e = owner[v];
+  out->n0 = ct * BN;
+  out->cols_valid = min(BN, NC - out->n0);
+  return true;
+}
+
+template <bool WT, int EPI, int ACT>
+__global__ __launch_bounds__(kGemmThreads) void rows_gemm_bf16(
+    const bf16_t* __restrict__ in, const bf16_t* __restrict__ w, const bf16_t* __restrict__ bias,
+    const int32_t* __restrict__ voff, const int32_t* __restrict__ owner, int V, int K, int NC, int row_tiles_max,
+    int col_tiles, const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0, bf16_t* __restrict__ out1) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t* smem = (bf16_t*)smem_raw;
+  __shared__ int s_tile[2];
+  RowTile t;
+  if (!lookup_row_tile(voff, owner, V, NC, row_tiles_max, col_tiles, s_tile, &t)) return;
   // Ragged tiles run the full-tile code (rows past the bucket are clamped on load and dropped
   // on store): skipping their empty 32-row MFMA blocks needs conditional MFMA groups, which the
   // register allocator only handles by spilling the accumulators.
-  rows_tile<WT, EPI, ACT, true>(smem, in, w, bias, K, NC, row0, rows_valid, e, n0, cols_valid, hpre_in, out0, out1);
+  rows_tile<WT, EPI, ACT, true>(smem, in, w, bias, K, NC, t.row0, t.rows_valid, t.e, t.n0, t.cols_valid, hpre_in,
+                                out0, out1);
+}
+
+// =============================================================================================
+// rows_gemm_dma: the same product for operands that are both contraction-contiguous
+// (In [rows, K], W_e [NC, K]) and K a multiple of 128, with global -> LDS direct loads
+// (global_load_lds, 16 bytes per lane, no register staging, no LDS store instructions).
+// Four LDS stages of a 32-wide K tile (2 x 16 KB each): while tile t is multiplied, tiles
+// t+1..t+3 are landed or in flight and tile t+4 is issued half-way through the step.  A direct load writes lane i's 16 bytes at
+// the wave's LDS base + 16*i, so one instruction fills 16 rows x 64 bytes; the bank swizzle
+// (16-byte chunk index XOR (row>>2)&3) is applied by choosing which global chunk a lane fetches.
+// =============================================================================================
+constexpr int DK = 32;
+constexpr int kDmaStages = 4;
+constexpr int kDmaTileBytes = 256 * DK * 2;            // one operand tile: 16 KB
+constexpr int kDmaStageBytes = 2 * kDmaTileBytes;      // A + B
+typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+
+__device__ __forceinline__ int dma_off(int row, int c) { return row * (DK * 2) + ((c ^ ((row >> 2) & 3)) << 4); }
+
+struct DmaSrc {
+  const bf16_t* base;
+  uint32_t off[4];
+  __device__ __forceinline__ void init(const bf16_t* b, size_t ld, int rows_valid) {
+    base = b;
+    const int w = threadIdx.x >> 6, i = threadIdx.x & 63;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int row = (w * 4 + q) * 16 + (i >> 2);
+      const int c = (i & 3) ^ ((row >> 2) & 3);
+      off[q] = (uint32_t)(min(row, rows_valid - 1) * ld + c * 8);
+    }
+  }
+  // Fills the 16 KB LDS tile at `tile` with K columns k0..k0+31 of the operand's 256 rows.
+  // The direct load is issued from inline assembly (M0 = LDS byte address of the wave's 1 KB
+  // slice, lane i lands at M0 + 16*i): the compiler's wait-count insertion cannot tell which LDS
+  // stage a direct load writes and would wait for every outstanding load before any LDS read;
+  // here the waits are placed by hand (wait_vmcnt_le) before the barrier that publishes a stage.
+  __device__ __forceinline__ void issue(lds_byte_t* tile, int k0) const {
+    const unsigned w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)tile) + w * 4096;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const bf16_t* g = base + k0 + off[q];
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds0 + q * 1024) : "memory");
+    }
+  }
+};
+
+// s_waitcnt vmcnt(8 * tiles) only (expcnt / lgkmcnt fields left at "no wait"): returns once at
+// most `tiles` of the most recently issued K tiles (8 direct loads per wave each) are in flight.
+__device__ __forceinline__ void wait_tiles_in_flight(int tiles) {
+  if (tiles >= 3) __builtin_amdgcn_s_waitcnt(0x4F78);        // vmcnt(24)
+  else if (tiles == 2) __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16)
+  else if (tiles == 1) __builtin_amdgcn_s_waitcnt(0x0F78);   // vmcnt(8)
+  else __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0)
+}
+
+struct DmaFrags {
+  Frag8 a[MB], b[NB];
+};
+__device__ __forceinline__ void dma_read_frags(DmaFrags& f, const lds_byte_t* stage, int ks, int wm, int wn) {
+  const int lane = threadIdx.x & 63;
+  const int r = lane & 31, h = lane >> 5;
+  const lds_byte_t* As = stage;
+  const lds_byte_t* Bs = stage + kDmaTileBytes;
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+    f.a[i].v = *(const __attribute__((address_space(3))) bf16x8*)(As + dma_off((wm + 2 * i) * 32 + r, 2 * ks + h));
+#pragma unroll
+  for (int j = 0; j < NB; ++j)
+    f.b[j].v = *(const __attribute__((address_space(3))) bf16x8*)(Bs + dma_off((wn * NB + j) * 32 + r, 2 * ks + h));
+}
+__device__ __forceinline__ void dma_mma(f32x16 (&acc)[MB][NB], const DmaFrags& f) {
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j].v, f.a[i].v, acc[i][j], 0, 0, 0);
+}
+
+// One K tile (two 16-wide k steps).  On entry f0 holds the fragments of (tile kt, k step 0).
+// The barrier sits between the two k steps: before it the wave has fetched everything it needs
+// from `cur`, so after it `cur` is free for tile kt+4; and tile kt+1 is published, so its first
+// fragments can be fetched while the second k step's MFMAs run -- no LDS latency after the barrier.
+__device__ __forceinline__ void dma_step(lds_byte_t* cur, const lds_byte_t* nxt, f32x16 (&acc)[MB][NB], DmaFrags& f0,
+                                         DmaFrags& f1, const DmaSrc& a_src, const DmaSrc& w_src, int kt, int KT,
+                                         int wm, int wn) {
+  dma_read_frags(f1, cur, 1, wm, wn);
+  dma_mma(acc, f0);
+  if (kt + 1 < KT) wait_tiles_in_flight(min(2, KT - 2 - kt));    // my part of tile kt+1 has landed
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  if (kt + 4 < KT) {
+    a_src.issue(cur, (kt + 4) * DK);
+    w_src.issue(cur + kDmaTileBytes, (kt + 4) * DK);
+  }
+  if (kt + 1 < KT) dma_read_frags(f0, nxt, 0, wm, wn);
+  dma_mma(acc, f1);
+}
+
+template <int EPI, int ACT>
+__global__ __launch_bounds__(kGemmThreads) void rows_gemm_dma_bf16(
+    const bf16_t* __restrict__ in, const bf16_t* __restrict__ w, const bf16_t* __restrict__ bias,
+    const int32_t* __restrict__ voff, const int32_t* __restrict__ owner, int V, int K, int NC, int row_tiles_max,
+    int col_tiles, const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0, bf16_t* __restrict__ out1) {
+  __shared__ __align__(1024) unsigned char stage0[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage1[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage3[kDmaStageBytes];
+  __shared__ int s_tile[2];
+  RowTile t;
+  if (!lookup_row_tile(voff, owner, V, NC, row_tiles_max, col_tiles, s_tile, &t)) return;
+  lds_byte_t* s0 = (lds_byte_t*)stage0;
+  lds_byte_t* s1 = (lds_byte_t*)stage1;
+  lds_byte_t* s2 = (lds_byte_t*)stage2;
+  lds_byte_t* s3 = (lds_byte_t*)stage3;
+  const int wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  DmaSrc a_src, w_src;
+  a_src.init(in + (size_t)t.row0 * K, K, t.rows_valid);
+  w_src.init(w + (size_t)t.e * K * NC + (size_t)t.n0 * K, K, t.cols_valid);
+  f32x16 acc[MB][NB];
+  zero_acc(acc);
+  const int KT = K / DK;                               // a multiple of 4 (host checks K % 128 == 0)
+  a_src.issue(s0, 0);
+  w_src.issue(s0 + kDmaTileBytes, 0);
+  a_src.issue(s1, DK);
+  w_src.issue(s1 + kDmaTileBytes, DK);
+  a_src.issue(s2, 2 * DK);
+  w_src.issue(s2 + kDmaTileBytes, 2 * DK);
+  a_src.issue(s3, 3 * DK);
+  w_src.issue(s3 + kDmaTileBytes, 3 * DK);
+  wait_tiles_in_flight(3);
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  DmaFrags f0, f1;
+  dma_read_frags(f0, s0, 0, wm, wn);
+  for (int kt = 0; kt < KT; kt += 4) {
+    dma_step(s0, s1, acc, f0, f1, a_src, w_src, kt, KT, wm, wn);
+    dma_step(s1, s2, acc, f0, f1, a_src, w_src, kt + 1, KT, wm, wn);
+    dma_step(s2, s3, acc, f0, f1, a_src, w_src, kt + 2, KT, wm, wn);
+    dma_step(s3, s0, acc, f0, f1, a_src, w_src, kt + 3, KT, wm, wn);
+  }
+  __syncthreads();                                     // all waves done with the last tile: LDS is free
+  rows_epilogue<EPI, ACT>((float*)stage0, acc, bias, NC, t.row0, t.rows_valid, t.e, t.n0, hpre_in, out0, out1);
 }
 
 // =============================================================================================
@@ -553,6 +720,13 @@ static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w,
   const int col_tiles = (NC + BN - 1) / BN;
   const int row_tiles = max_row_tiles(a.A, a.V);
   const unsigned grid = patched_grid(row_tiles, col_tiles);
+  if (WT && K % 128 == 0) {
+    // both operands contraction-contiguous and K a whole number of pipeline rounds: direct-to-LDS path
+    hipLaunchKernelGGL((rows_gemm_dma_bf16<EPI, ACT>), dim3(grid), dim3(kGemmThreads), 0, s, (const bf16_t*)in,
+                       (const bf16_t*)w, (const bf16_t*)bias, a.voff, a.owner, a.V, K, NC, row_tiles, col_tiles,
+                       (const bf16_t*)hpre_in, (bf16_t*)out0, (bf16_t*)out1);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL((rows_gemm_bf16<WT, EPI, ACT>), dim3(grid), dim3(kGemmThreads), kGemmLds, s, (const bf16_t*)in,
                      (const bf16_t*)w, (const bf16_t*)bias, a.voff, a.owner, a.V, K, NC, row_tiles, col_tiles,
                      (const bf16_t*)hpre_in, (bf16_t*)out0, (bf16_t*)out1);

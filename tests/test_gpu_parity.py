@@ -184,6 +184,8 @@ SMALL = {
     "gpt_small": W.scaled(W.CONFIGS["gpt_m"], N=2100, d=264, f=520, E=8, V=14, max_rep=4),
     "swin_small": W.scaled(W.CONFIGS["swin"], N=3000, d=256, f=512, E=8, V=11, max_rep=4),
     "xl_small": W.scaled(W.CONFIGS["gpt_xl"], N=2600, d=192, f=384, E=64, V=96, max_rep=8),
+    # d and f multiples of 128 with ragged column tiles: the backward GEMMs take the direct-to-LDS path
+    "gpt_dma": W.scaled(W.CONFIGS["gpt_m"], N=1900, d=384, f=640, E=8, V=13, max_rep=4),
 }
 
 
