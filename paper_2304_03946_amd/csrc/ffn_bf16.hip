@@ -42,24 +42,31 @@ __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 __device__ __forceinline__ int lds_off(int row, int chunk) { return row * BK + ((chunk ^ swz(row)) << 3); }
 
 // ---- workgroup id -> tile, XCD aware ---------------------------------------------------------
-// Workgroups are dealt round-robin to the 8 XCDs (id % 8), each with its own L2.  The tile grid
-// (rows x cols) is cut into patches of kPatchH x pw tiles (32 tiles, one per CU of an XCD) and
-// the j-th workgroup of XCD x gets tile j%32 of patch (j/32)*8 + x, so the workgroups that run
-// together on one XCD share kPatchH row operands and pw column operands in that L2 instead of
-// 32 different ones.
+// Workgroups are dealt round-robin to the 8 XCDs (id % 8), each with its own L2, and an XCD runs
+// its workgroups in ascending id.  The rows x cols tile grid is cut into patches of ph x pw tiles
+// (about 32 = one per CU of an XCD; pw divides cols whenever a divisor in 5..8 exists, so patches
+// are full and every XCD gets the same work); the j-th workgroup of XCD x gets tile j % (ph*pw) of
+// patch (j / (ph*pw)) * 8 + x.  The workgroups that run together on one XCD then share ph row
+// operands and pw column operands in its L2, and the 8 patches in flight on the 8 XCDs are
+// neighbours in the grid, so what they share is fetched from HBM once.
 constexpr int kXcds = 8, kPatch = 32;
-__host__ __device__ inline int patch_width(int cols) { return cols >= 7 ? 8 : (cols >= 3 ? 4 : (cols == 2 ? 2 : 1)); }
+__host__ __device__ inline int patch_width(int cols) {
+  if (cols <= 8) return cols;
+  for (int pw = 8; pw >= 5; --pw)
+    if (cols % pw == 0) return pw;
+  return 8;
+}
 __host__ __device__ inline unsigned patched_grid(int rows, int cols) {
   const int pw = patch_width(cols), ph = kPatch / pw;
   const int np = ((rows + ph - 1) / ph) * ((cols + pw - 1) / pw);
-  return (unsigned)((np + kXcds - 1) / kXcds * kXcds) * kPatch;
+  return (unsigned)((np + kXcds - 1) / kXcds * kXcds) * (ph * pw);
 }
 // returns false when the workgroup falls into the padding of the patch grid
 __device__ __forceinline__ bool patched_tile(unsigned b, int rows, int cols, int* r, int* c) {
-  const int pw = patch_width(cols), ph = kPatch / pw;
+  const int pw = patch_width(cols), ph = kPatch / pw, psize = ph * pw;
   const int npc = (cols + pw - 1) / pw;
   const unsigned x = b % kXcds, j = b / kXcds;
-  const unsigned P = (j / kPatch) * kXcds + x, q = j % kPatch;
+  const unsigned P = (j / psize) * kXcds + x, q = j % psize;
   *r = (int)(P / npc) * ph + (int)(q / pw);
   *c = (int)(P % npc) * pw + (int)(q % pw);
   return *r < rows && *c < cols;
@@ -381,12 +388,9 @@ struct RowTile {
 __device__ __forceinline__ bool lookup_row_tile(const int32_t* __restrict__ voff, const int32_t* __restrict__ owner,
                                                 int V, int NC, int row_tiles_max, int col_tiles, int* s_tile,
                                                 RowTile* out) {
-  int rt, ct;
-  const bool in_grid = patched_tile(blockIdx.x, row_tiles_max, col_tiles, &rt, &ct);
   if (threadIdx.x < kWave) {
     const int lane = threadIdx.x;
     if (lane == 0) s_tile[0] = -1;
-    if (!in_grid) rt = -1;
     const int per = (V + kWave - 1) / kWave;     // <= 8 buckets per lane
     int cnt[FLEXMOE_MAX_VEXPERTS / kWave];
     int sum = 0;
@@ -403,12 +407,15 @@ __device__ __forceinline__ bool lookup_row_tile(const int32_t* __restrict__ voff
       const int up = __shfl_up(incl, o);
       if (lane >= o) incl += up;
     }
+    int rt = -1, ct = 0;
+    if (!patched_tile(blockIdx.x, row_tiles_max, col_tiles, &rt, &ct)) rt = -1;
     int start = incl - sum;
 #pragma unroll
     for (int q = 0; q < FLEXMOE_MAX_VEXPERTS / kWave; ++q) {
       if (rt >= start && rt < start + cnt[q]) {
         s_tile[0] = lane * per + q;
         s_tile[1] = rt - start;
+        s_tile[2] = ct;
       }
       start += cnt[q];
     }
@@ -419,7 +426,7 @@ __device__ __forceinline__ bool lookup_row_tile(const int32_t* __restrict__ voff
   out->row0 = voff[v] + s_tile[1] * BM;
   out->rows_valid = min(BM, voff[v + 1] - out->row0);
   out->e = owner[v];
-  out->n0 = ct * BN;
+  out->n0 = s_tile[2] * BN;
   out->cols_valid = min(BN, NC - out->n0);
   return true;
 }
@@ -431,7 +438,7 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_bf16(
     int col_tiles, const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0, bf16_t* __restrict__ out1) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t* smem = (bf16_t*)smem_raw;
-  __shared__ int s_tile[2];
+  __shared__ int s_tile[3];
   RowTile t;
   if (!lookup_row_tile(voff, owner, V, NC, row_tiles_max, col_tiles, s_tile, &t)) return;
   // Ragged tiles run the full-tile code (rows past the bucket are clamped on load and dropped
@@ -549,7 +556,7 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_dma_bf16(
   __shared__ __align__(1024) unsigned char stage1[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char stage3[kDmaStageBytes];
-  __shared__ int s_tile[2];
+  __shared__ int s_tile[3];
   RowTile t;
   if (!lookup_row_tile(voff, owner, V, NC, row_tiles_max, col_tiles, s_tile, &t)) return;
   lds_byte_t* s0 = (lds_byte_t*)stage0;
