@@ -206,29 +206,44 @@ __device__ __forceinline__ void unpack4(uint2 u, float* v) {
 // 64 consecutive columns of one row -> per-element epilogue in fp32 -> bf16 -> 8-byte stores that
 // fill whole 128-byte lines.  The K loop ends with a barrier, so the LDS tiles are free.
 // emit(row in the wave's block (0..127), column in the wave's block (multiple of 4), float4)
-template <typename Emit>
-__device__ __forceinline__ void epilogue_rounds(float* patch, const f32x16 (&acc)[MB][NB], Emit emit) {
+// fetch(row, col) -> uint2: an optional per-element side input (the saved pre-activations of the
+// backward epilogue); the fetches of round n+1 are issued before round n is processed so that
+// their latency hides behind it.  emit(row, col, float4 accumulators, uint2 fetched).
+template <bool FETCH, typename Fetch, typename Emit>
+__device__ __forceinline__ void epilogue_rounds(float* patch, const f32x16 (&acc)[MB][NB], Fetch fetch, Emit emit) {
   const int lane = threadIdx.x & 63;
   const int r = lane & 31, h = lane >> 5;
+  const int rsub = lane >> 4, c = lane & 15;
+  uint2 side[2][8];
+  if (FETCH) {
+#pragma unroll
+    for (int it = 0; it < 8; ++it) side[0][it] = fetch(it * 4 + rsub, c * 4);
+  }
 #pragma unroll
   for (int i = 0; i < MB; ++i) {
 #pragma unroll
     for (int jh = 0; jh < NB / 2; ++jh) {
+      const int round = i * (NB / 2) + jh;
+      if (FETCH && round + 1 < MB * (NB / 2)) {
+        const int ni = (round + 1) / (NB / 2), njh = (round + 1) % (NB / 2);
+#pragma unroll
+        for (int it = 0; it < 8; ++it) side[(round + 1) & 1][it] = fetch(ni * 32 + it * 4 + rsub, njh * 64 + c * 4);
+      }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int c = jj * 8 + 2 * g + h;
+          const int cc = jj * 8 + 2 * g + h;
           const f32x16& a = acc[i][jh * 2 + jj];
-          *(float4*)(patch + r * 64 + ((c ^ (r & 15)) << 2)) = make_float4(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]);
+          *(float4*)(patch + r * 64 + ((cc ^ (r & 15)) << 2)) = make_float4(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]);
         }
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront", "local");
 #pragma unroll
       for (int it = 0; it < 8; ++it) {
-        const int row = it * 4 + (lane >> 4), c = lane & 15;
+        const int row = it * 4 + rsub;
         const float4 v = *(const float4*)(patch + row * 64 + ((c ^ (row & 15)) << 2));
-        emit(i * 32 + row, jh * 64 + c * 4, v);
+        emit(i * 32 + row, jh * 64 + c * 4, v, FETCH ? side[round & 1][it] : make_uint2(0, 0));
       }
     }
   }
@@ -329,7 +344,13 @@ __device__ __forceinline__ void rows_epilogue(float* lds, const f32x16 (&acc)[MB
   const int wm = wave >> 1, wn = wave & 1;
   float* patch = lds + wave * (32 * 64);
   const int col_base = n0 + wn * (NB * 32);
-  epilogue_rounds(patch, acc, [&](int row_w, int col_w, float4 c) {
+  auto fetch = [&](int row_w, int col_w) -> uint2 {
+    const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
+    const int col = col_base + col_w;
+    if (lrow < rows_valid && col < NC) return *(const uint2*)(hpre_in + (size_t)(row0 + lrow) * NC + col);
+    return make_uint2(0, 0);
+  };
+  epilogue_rounds<EPI == EPI_DH>(patch, acc, fetch, [&](int row_w, int col_w, float4 c, uint2 pre_in) {
     const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
     const int col = col_base + col_w;
     if (lrow < rows_valid && col < NC) {
@@ -350,7 +371,7 @@ __device__ __forceinline__ void rows_epilogue(float* lds, const f32x16 (&acc)[MB
         *(uint2*)(out1 + o) = pack4(act_fast<ACT>(z[0]), act_fast<ACT>(z[1]), act_fast<ACT>(z[2]), act_fast<ACT>(z[3]));
       } else {
         float z[4], a[4], d[4];
-        unpack4(*(const uint2*)(hpre_in + o), z);
+        unpack4(pre_in, z);
 #pragma unroll
         for (int q = 0; q < 4; ++q) act_both<ACT>(z[q], &a[q], &d[q]);
         *(uint2*)(out0 + o) = pack4(c.x * d[0], c.y * d[1], c.z * d[2], c.w * d[3]);
@@ -694,7 +715,7 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_bf16(const bf16_t* __
   float* patch = (float*)smem + wave * (32 * 64);
   bf16_t* out = dw + (size_t)e * M * NC;
   const int col_base = n0 + wn * (NB * 32);
-  epilogue_rounds(patch, acc, [&](int row_w, int col_w, float4 c) {
+  epilogue_rounds<false>(patch, acc, [](int, int) { return make_uint2(0, 0); }, [&](int row_w, int col_w, float4 c, uint2) {
     const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
     const int col = col_base + col_w;
     if (lrow < mvalid && col < NC) *(uint2*)(out + (size_t)(m0 + lrow) * NC + col) = pack4(c.x, c.y, c.z, c.w);
