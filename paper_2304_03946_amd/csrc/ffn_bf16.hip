@@ -515,6 +515,61 @@ struct DmaSrc {
   }
 };
 
+// Operand stored [K, ld] with the output index contiguous (the forward weights W_e [K, NC]): the
+// 32 x 256 tile is copied to LDS as it lies in memory, one k-row = 512 bytes = 32 chunks, two
+// k-rows per direct-load instruction, and transposed on the way out of LDS by ds_read_tr16_b64.
+// Chunk index XOR (k & 3) << 2 keeps those transposing reads free of bank conflicts.  Columns
+// past cols_valid are clamped to the last valid 8-column chunk.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ int dmat_chunk(int krow, int c) { return c ^ ((krow & 3) << 2); }
+
+struct DmaSrcT {
+  const bf16_t* base;     // first contraction row, first column of the tile
+  uint32_t off[4];
+  size_t ld;
+  __device__ __forceinline__ void init(const bf16_t* b, size_t ld_, int cols_valid) {
+    base = b;
+    ld = ld_;
+    const int w = threadIdx.x >> 6, i = threadIdx.x & 63;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int krow = (w * 4 + q) * 2 + (i >> 5);
+      const int c = min(dmat_chunk(krow, i & 31), cols_valid / 8 - 1);
+      off[q] = (uint32_t)(krow * ld + c * 8);
+    }
+  }
+  __device__ __forceinline__ void issue(lds_byte_t* tile, int k0) const {
+    const unsigned w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)tile) + w * 4096;
+    const bf16_t* rowp = base + (size_t)k0 * ld;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const bf16_t* g = rowp + off[q];
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds0 + q * 1024) : "memory");
+    }
+  }
+};
+
+// MFMA fragment (8 consecutive k of output column nb0 + lane%32, k = 16*ks + 8*(lane/32) ..) from
+// a [32 k][256 n] tile.  ds_read_tr16_b64 works on groups of 16 lanes: lanes 4m..4m+3 of a group
+// address 16 consecutive elements of row m (4 each) and lane i of the group receives column i of
+// those four rows.  So lane L (group g = L/16, i = L%16) points at row k' + i/4, columns
+// nb0 + 16*(g%2) + 4*(i%4), with k' = 16*ks + 8*(g/2) (+4 for the second read).
+__device__ __forceinline__ bf16x8 dmat_read_frag(const lds_byte_t* tile, int nb0, int ks) {
+  const int L = threadIdx.x & 63;
+  const int g = L >> 4, i = L & 15;
+  const int col = nb0 + 16 * (g & 1) + 4 * (i & 3);
+  const int k_lo = 16 * ks + 8 * (g >> 1) + (i >> 2);
+  const int k_hi = k_lo + 4;
+  const int a_lo = k_lo * 512 + (dmat_chunk(k_lo, col >> 3) << 4) + ((col & 7) << 1);
+  const int a_hi = k_hi * 512 + (dmat_chunk(k_hi, col >> 3) << 4) + ((col & 7) << 1);
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(tile + a_lo));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(tile + a_hi));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
 // s_waitcnt vmcnt(8 * tiles) only (expcnt / lgkmcnt fields left at "no wait"): returns once at
 // most `tiles` of the most recently issued K tiles (8 direct loads per wave each) are in flight.
 __device__ __forceinline__ void wait_tiles_in_flight(int tiles) {
@@ -527,6 +582,7 @@ __device__ __forceinline__ void wait_tiles_in_flight(int tiles) {
 struct DmaFrags {
   Frag8 a[MB], b[NB];
 };
+template <bool WT>
 __device__ __forceinline__ void dma_read_frags(DmaFrags& f, const lds_byte_t* stage, int ks, int wm, int wn) {
   const int lane = threadIdx.x & 63;
   const int r = lane & 31, h = lane >> 5;
@@ -536,8 +592,10 @@ __device__ __forceinline__ void dma_read_frags(DmaFrags& f, const lds_byte_t* st
   for (int i = 0; i < MB; ++i)
     f.a[i].v = *(const __attribute__((address_space(3))) bf16x8*)(As + dma_off((wm + 2 * i) * 32 + r, 2 * ks + h));
 #pragma unroll
-  for (int j = 0; j < NB; ++j)
-    f.b[j].v = *(const __attribute__((address_space(3))) bf16x8*)(Bs + dma_off((wn * NB + j) * 32 + r, 2 * ks + h));
+  for (int j = 0; j < NB; ++j) {
+    if (WT) f.b[j].v = *(const __attribute__((address_space(3))) bf16x8*)(Bs + dma_off((wn * NB + j) * 32 + r, 2 * ks + h));
+    else f.b[j].v = dmat_read_frag(Bs, (wn * NB + j) * 32, ks);
+  }
 }
 __device__ __forceinline__ void dma_mma(f32x16 (&acc)[MB][NB], const DmaFrags& f) {
 #pragma unroll
@@ -551,10 +609,11 @@ __device__ __forceinline__ void dma_mma(f32x16 (&acc)[MB][NB], const DmaFrags& f
 // The barrier sits between the two k steps: before it the wave has fetched everything it needs
 // from `cur`, so after it `cur` is free for tile kt+4; and tile kt+1 is published, so its first
 // fragments can be fetched while the second k step's MFMAs run -- no LDS latency after the barrier.
+template <bool WT, typename WSrc>
 __device__ __forceinline__ void dma_step(lds_byte_t* cur, const lds_byte_t* nxt, f32x16 (&acc)[MB][NB], DmaFrags& f0,
-                                         DmaFrags& f1, const DmaSrc& a_src, const DmaSrc& w_src, int kt, int KT,
+                                         DmaFrags& f1, const DmaSrc& a_src, const WSrc& w_src, int kt, int KT,
                                          int wm, int wn) {
-  dma_read_frags(f1, cur, 1, wm, wn);
+  dma_read_frags<WT>(f1, cur, 1, wm, wn);
   dma_mma(acc, f0);
   if (kt + 1 < KT) wait_tiles_in_flight(min(2, KT - 2 - kt));    // my part of tile kt+1 has landed
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -564,31 +623,20 @@ __device__ __forceinline__ void dma_step(lds_byte_t* cur, const lds_byte_t* nxt,
     a_src.issue(cur, (kt + 4) * DK);
     w_src.issue(cur + kDmaTileBytes, (kt + 4) * DK);
   }
-  if (kt + 1 < KT) dma_read_frags(f0, nxt, 0, wm, wn);
+  if (kt + 1 < KT) dma_read_frags<WT>(f0, nxt, 0, wm, wn);
   dma_mma(acc, f1);
 }
 
-template <int EPI, int ACT>
-__global__ __launch_bounds__(kGemmThreads) void rows_gemm_dma_bf16(
-    const bf16_t* __restrict__ in, const bf16_t* __restrict__ w, const bf16_t* __restrict__ bias,
-    const int32_t* __restrict__ voff, const int32_t* __restrict__ owner, int V, int K, int NC, int row_tiles_max,
-    int col_tiles, const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0, bf16_t* __restrict__ out1) {
-  __shared__ __align__(1024) unsigned char stage0[kDmaStageBytes];
-  __shared__ __align__(1024) unsigned char stage1[kDmaStageBytes];
-  __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
-  __shared__ __align__(1024) unsigned char stage3[kDmaStageBytes];
-  __shared__ int s_tile[3];
-  RowTile t;
-  if (!lookup_row_tile(voff, owner, V, NC, row_tiles_max, col_tiles, s_tile, &t)) return;
-  lds_byte_t* s0 = (lds_byte_t*)stage0;
-  lds_byte_t* s1 = (lds_byte_t*)stage1;
-  lds_byte_t* s2 = (lds_byte_t*)stage2;
-  lds_byte_t* s3 = (lds_byte_t*)stage3;
+template <bool WT, typename WSrc, int EPI, int ACT>
+__device__ __forceinline__ void rows_dma_body(lds_byte_t* s0, lds_byte_t* s1, lds_byte_t* s2, lds_byte_t* s3,
+                                              const RowTile& t, const bf16_t* __restrict__ in, const WSrc& w_src,
+                                              const bf16_t* __restrict__ bias, int K, int NC,
+                                              const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
+                                              bf16_t* __restrict__ out1) {
   const int wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  DmaSrc a_src, w_src;
+  DmaSrc a_src;
   a_src.init(in + (size_t)t.row0 * K, K, t.rows_valid);
-  w_src.init(w + (size_t)t.e * K * NC + (size_t)t.n0 * K, K, t.cols_valid);
   f32x16 acc[MB][NB];
   zero_acc(acc);
   const int KT = K / DK;                               // a multiple of 4 (host checks K % 128 == 0)
@@ -604,15 +652,43 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_dma_bf16(
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
   DmaFrags f0, f1;
-  dma_read_frags(f0, s0, 0, wm, wn);
+  dma_read_frags<WT>(f0, s0, 0, wm, wn);
   for (int kt = 0; kt < KT; kt += 4) {
-    dma_step(s0, s1, acc, f0, f1, a_src, w_src, kt, KT, wm, wn);
-    dma_step(s1, s2, acc, f0, f1, a_src, w_src, kt + 1, KT, wm, wn);
-    dma_step(s2, s3, acc, f0, f1, a_src, w_src, kt + 2, KT, wm, wn);
-    dma_step(s3, s0, acc, f0, f1, a_src, w_src, kt + 3, KT, wm, wn);
+    dma_step<WT>(s0, s1, acc, f0, f1, a_src, w_src, kt, KT, wm, wn);
+    dma_step<WT>(s1, s2, acc, f0, f1, a_src, w_src, kt + 1, KT, wm, wn);
+    dma_step<WT>(s2, s3, acc, f0, f1, a_src, w_src, kt + 2, KT, wm, wn);
+    dma_step<WT>(s3, s0, acc, f0, f1, a_src, w_src, kt + 3, KT, wm, wn);
   }
   __syncthreads();                                     // all waves done with the last tile: LDS is free
-  rows_epilogue<EPI, ACT>((float*)stage0, acc, bias, NC, t.row0, t.rows_valid, t.e, t.n0, hpre_in, out0, out1);
+  rows_epilogue<EPI, ACT>((float*)s0, acc, bias, NC, t.row0, t.rows_valid, t.e, t.n0, hpre_in, out0, out1);
+}
+
+template <bool WT, int EPI, int ACT>
+__global__ __launch_bounds__(kGemmThreads) void rows_gemm_dma_bf16(
+    const bf16_t* __restrict__ in, const bf16_t* __restrict__ w, const bf16_t* __restrict__ bias,
+    const int32_t* __restrict__ voff, const int32_t* __restrict__ owner, int V, int K, int NC, int row_tiles_max,
+    int col_tiles, const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0, bf16_t* __restrict__ out1) {
+  __shared__ __align__(1024) unsigned char stage0[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage1[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage3[kDmaStageBytes];
+  __shared__ int s_tile[3];
+  RowTile t;
+  if (!lookup_row_tile(voff, owner, V, NC, row_tiles_max, col_tiles, s_tile, &t)) return;
+  lds_byte_t* s0 = (lds_byte_t*)stage0;
+  lds_byte_t* s1 = (lds_byte_t*)stage1;
+  lds_byte_t* s2 = (lds_byte_t*)stage2;
+  lds_byte_t* s3 = (lds_byte_t*)stage3;
+  const bf16_t* w_e = w + (size_t)t.e * K * NC;
+  if (WT) {
+    DmaSrc w_src;
+    w_src.init(w_e + (size_t)t.n0 * K, K, t.cols_valid);
+    rows_dma_body<true, DmaSrc, EPI, ACT>(s0, s1, s2, s3, t, in, w_src, bias, K, NC, hpre_in, out0, out1);
+  } else {
+    DmaSrcT w_src;
+    w_src.init(w_e + t.n0, NC, t.cols_valid);
+    rows_dma_body<false, DmaSrcT, EPI, ACT>(s0, s1, s2, s3, t, in, w_src, bias, K, NC, hpre_in, out0, out1);
+  }
 }
 
 // =============================================================================================
@@ -748,9 +824,9 @@ static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w,
   const int col_tiles = (NC + BN - 1) / BN;
   const int row_tiles = max_row_tiles(a.A, a.V);
   const unsigned grid = patched_grid(row_tiles, col_tiles);
-  if (WT && K % 128 == 0) {
-    // both operands contraction-contiguous and K a whole number of pipeline rounds: direct-to-LDS path
-    hipLaunchKernelGGL((rows_gemm_dma_bf16<EPI, ACT>), dim3(grid), dim3(kGemmThreads), 0, s, (const bf16_t*)in,
+  if (K % 128 == 0) {
+    // K is a whole number of pipeline rounds: direct-to-LDS path
+    hipLaunchKernelGGL((rows_gemm_dma_bf16<WT, EPI, ACT>), dim3(grid), dim3(kGemmThreads), 0, s, (const bf16_t*)in,
                        (const bf16_t*)w, (const bf16_t*)bias, a.voff, a.owner, a.V, K, NC, row_tiles, col_tiles,
                        (const bf16_t*)hpre_in, (bf16_t*)out0, (bf16_t*)out1);
     return hipGetLastError();
