@@ -32,6 +32,9 @@ constexpr int kTileElems = BM * BK;                 // one operand tile in LDS (
 constexpr size_t kGemmLds = 2 * 2 * kTileElems * sizeof(bf16_t);   // 2 stages x (A + B) = 128 KB
 
 enum { EPI_FWD1 = 0, EPI_PLAIN = 1, EPI_DH = 2 };
+#ifndef FLEXMOE_WGRAD_DMA
+#define FLEXMOE_WGRAD_DMA 1
+#endif
 
 union Frag8 {
   uint4 u;
@@ -582,19 +585,22 @@ __device__ __forceinline__ void wait_tiles_in_flight(int tiles) {
 struct DmaFrags {
   Frag8 a[MB], b[NB];
 };
-template <bool WT>
+// TRA / TRB: the operand's LDS tile is [k][256] (transposing reads) instead of [256][k].
+template <bool TRA, bool TRB>
 __device__ __forceinline__ void dma_read_frags(DmaFrags& f, const lds_byte_t* stage, int ks, int wm, int wn) {
   const int lane = threadIdx.x & 63;
   const int r = lane & 31, h = lane >> 5;
   const lds_byte_t* As = stage;
   const lds_byte_t* Bs = stage + kDmaTileBytes;
 #pragma unroll
-  for (int i = 0; i < MB; ++i)
-    f.a[i].v = *(const __attribute__((address_space(3))) bf16x8*)(As + dma_off((wm + 2 * i) * 32 + r, 2 * ks + h));
+  for (int i = 0; i < MB; ++i) {
+    if (TRA) f.a[i].v = dmat_read_frag(As, (wm + 2 * i) * 32, ks);
+    else f.a[i].v = *(const __attribute__((address_space(3))) bf16x8*)(As + dma_off((wm + 2 * i) * 32 + r, 2 * ks + h));
+  }
 #pragma unroll
   for (int j = 0; j < NB; ++j) {
-    if (WT) f.b[j].v = *(const __attribute__((address_space(3))) bf16x8*)(Bs + dma_off((wn * NB + j) * 32 + r, 2 * ks + h));
-    else f.b[j].v = dmat_read_frag(Bs, (wn * NB + j) * 32, ks);
+    if (TRB) f.b[j].v = dmat_read_frag(Bs, (wn * NB + j) * 32, ks);
+    else f.b[j].v = *(const __attribute__((address_space(3))) bf16x8*)(Bs + dma_off((wn * NB + j) * 32 + r, 2 * ks + h));
   }
 }
 __device__ __forceinline__ void dma_mma(f32x16 (&acc)[MB][NB], const DmaFrags& f) {
@@ -609,22 +615,41 @@ __device__ __forceinline__ void dma_mma(f32x16 (&acc)[MB][NB], const DmaFrags& f
 // The barrier sits between the two k steps: before it the wave has fetched everything it needs
 // from `cur`, so after it `cur` is free for tile kt+4; and tile kt+1 is published, so its first
 // fragments can be fetched while the second k step's MFMAs run -- no LDS latency after the barrier.
-template <bool WT, typename WSrc>
+// issue(stage) starts the direct loads of the next K tile in sequence into `stage`.
+template <bool TRA, bool TRB, typename Issue>
 __device__ __forceinline__ void dma_step(lds_byte_t* cur, const lds_byte_t* nxt, f32x16 (&acc)[MB][NB], DmaFrags& f0,
-                                         DmaFrags& f1, const DmaSrc& a_src, const WSrc& w_src, int kt, int KT,
-                                         int wm, int wn) {
-  dma_read_frags<WT>(f1, cur, 1, wm, wn);
+                                         DmaFrags& f1, Issue& issue, int kt, int KT, int wm, int wn) {
+  dma_read_frags<TRA, TRB>(f1, cur, 1, wm, wn);
   dma_mma(acc, f0);
   if (kt + 1 < KT) wait_tiles_in_flight(min(2, KT - 2 - kt));    // my part of tile kt+1 has landed
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-  if (kt + 4 < KT) {
-    a_src.issue(cur, (kt + 4) * DK);
-    w_src.issue(cur + kDmaTileBytes, (kt + 4) * DK);
-  }
-  if (kt + 1 < KT) dma_read_frags<WT>(f0, nxt, 0, wm, wn);
+  if (kt + 4 < KT) issue(cur);
+  if (kt + 1 < KT) dma_read_frags<TRA, TRB>(f0, nxt, 0, wm, wn);
   dma_mma(acc, f1);
+}
+
+// The whole K loop: KT tiles (a multiple of 4) through the four stages.
+template <bool TRA, bool TRB, typename Issue>
+__device__ __forceinline__ void dma_pipeline(lds_byte_t* s0, lds_byte_t* s1, lds_byte_t* s2, lds_byte_t* s3,
+                                             f32x16 (&acc)[MB][NB], Issue& issue, int KT, int wm, int wn) {
+  issue(s0);
+  issue(s1);
+  issue(s2);
+  issue(s3);
+  wait_tiles_in_flight(3);
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  DmaFrags f0, f1;
+  dma_read_frags<TRA, TRB>(f0, s0, 0, wm, wn);
+  for (int kt = 0; kt < KT; kt += 4) {
+    dma_step<TRA, TRB>(s0, s1, acc, f0, f1, issue, kt, KT, wm, wn);
+    dma_step<TRA, TRB>(s1, s2, acc, f0, f1, issue, kt + 1, KT, wm, wn);
+    dma_step<TRA, TRB>(s2, s3, acc, f0, f1, issue, kt + 2, KT, wm, wn);
+    dma_step<TRA, TRB>(s3, s0, acc, f0, f1, issue, kt + 3, KT, wm, wn);
+  }
+  __syncthreads();                                     // all waves done with the last tile: LDS is free
 }
 
 template <bool WT, typename WSrc, int EPI, int ACT>
@@ -639,27 +664,13 @@ __device__ __forceinline__ void rows_dma_body(lds_byte_t* s0, lds_byte_t* s1, ld
   a_src.init(in + (size_t)t.row0 * K, K, t.rows_valid);
   f32x16 acc[MB][NB];
   zero_acc(acc);
-  const int KT = K / DK;                               // a multiple of 4 (host checks K % 128 == 0)
-  a_src.issue(s0, 0);
-  w_src.issue(s0 + kDmaTileBytes, 0);
-  a_src.issue(s1, DK);
-  w_src.issue(s1 + kDmaTileBytes, DK);
-  a_src.issue(s2, 2 * DK);
-  w_src.issue(s2 + kDmaTileBytes, 2 * DK);
-  a_src.issue(s3, 3 * DK);
-  w_src.issue(s3 + kDmaTileBytes, 3 * DK);
-  wait_tiles_in_flight(3);
-  __builtin_amdgcn_s_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-  DmaFrags f0, f1;
-  dma_read_frags<WT>(f0, s0, 0, wm, wn);
-  for (int kt = 0; kt < KT; kt += 4) {
-    dma_step<WT>(s0, s1, acc, f0, f1, a_src, w_src, kt, KT, wm, wn);
-    dma_step<WT>(s1, s2, acc, f0, f1, a_src, w_src, kt + 1, KT, wm, wn);
-    dma_step<WT>(s2, s3, acc, f0, f1, a_src, w_src, kt + 2, KT, wm, wn);
-    dma_step<WT>(s3, s0, acc, f0, f1, a_src, w_src, kt + 3, KT, wm, wn);
-  }
-  __syncthreads();                                     // all waves done with the last tile: LDS is free
+  int k_next = 0;
+  auto issue = [&](lds_byte_t* stage) {
+    a_src.issue(stage, k_next);
+    w_src.issue(stage + kDmaTileBytes, k_next);
+    k_next += DK;
+  };
+  dma_pipeline<false, !WT>(s0, s1, s2, s3, acc, issue, K / DK, wm, wn);   // K % 128 == 0 (host check)
   rows_epilogue<EPI, ACT>((float*)s0, acc, bias, NC, t.row0, t.rows_valid, t.e, t.n0, hpre_in, out0, out1);
 }
 
@@ -691,6 +702,53 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_dma_bf16(
   }
 }
 
+// Shared prologue of the weight-gradient kernels: per-expert loads from the bucket sizes, the
+// expert whose load has rank `want_rank` (descending load, ties by ascending id: hot experts'
+// tiles are issued first), and the list of its non-empty buckets in ascending vExpert id.
+__device__ __forceinline__ int wgrad_pick_expert(const int32_t* __restrict__ voff, const int32_t* __restrict__ owner,
+                                                 int E, int V, int want_rank, int* s_cnt, int* s_own, int* s_load,
+                                                 int* s_e_p, int* s_nb_p, int* s_bstart, int* s_brows) {
+  for (int v = threadIdx.x; v < V; v += kGemmThreads) {
+    s_cnt[v] = voff[v + 1] - voff[v];
+    s_own[v] = owner[v];
+  }
+  for (int e = threadIdx.x; e < E; e += kGemmThreads) s_load[e] = 0;
+  __syncthreads();
+  for (int v = threadIdx.x; v < V; v += kGemmThreads) atomicAdd(&s_load[s_own[v]], s_cnt[v]);
+  __syncthreads();
+  // the expert whose load has rank `want_rank` (descending load, ties by ascending id)
+  for (int e = threadIdx.x; e < E; e += kGemmThreads) {
+    const int l = s_load[e];
+    int rank = 0;
+    for (int o = 0; o < E; ++o) {
+      const int lo = s_load[o];
+      rank += (lo > l || (lo == l && o < e)) ? 1 : 0;
+    }
+    if (rank == want_rank) *s_e_p = e;
+  }
+  __syncthreads();
+  const int e = *s_e_p;
+  if (threadIdx.x < kWave) {                   // its non-empty buckets, ascending vExpert id
+    const int lane = threadIdx.x;
+    const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    int nbw = 0;
+    for (int vb = 0; vb < V; vb += kWave) {
+      const int v = vb + lane;
+      const bool hit = v < V && s_own[v] == e && s_cnt[v] > 0;
+      const unsigned long long mask = __ballot(hit);
+      if (hit) {
+        const int pos = nbw + __popcll(mask & lt);
+        s_bstart[pos] = voff[v];
+        s_brows[pos] = s_cnt[v];
+      }
+      nbw += __popcll(mask);
+    }
+    if (lane == 0) *s_nb_p = nbw;
+  }
+  __syncthreads();
+  return e;
+}
+
 // =============================================================================================
 // wgrad_gemm: dW_e[m, n] = sum_{v owned by e, ascending v} sum_{p in bucket v} L[p, m] * R[p, n]
 // =============================================================================================
@@ -713,44 +771,7 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_bf16(const bf16_t* __
   if (!patched_tile(blockIdx.x, E * m_tiles, n_tiles, &grow, &nt)) return;
   const int want_rank = grow / m_tiles, mt = grow % m_tiles;
 
-  for (int v = threadIdx.x; v < V; v += kGemmThreads) {
-    s_cnt[v] = voff[v + 1] - voff[v];
-    s_own[v] = owner[v];
-  }
-  for (int e = threadIdx.x; e < E; e += kGemmThreads) s_load[e] = 0;
-  __syncthreads();
-  for (int v = threadIdx.x; v < V; v += kGemmThreads) atomicAdd(&s_load[s_own[v]], s_cnt[v]);
-  __syncthreads();
-  // the expert whose load has rank `want_rank` (descending load, ties by ascending id)
-  for (int e = threadIdx.x; e < E; e += kGemmThreads) {
-    const int l = s_load[e];
-    int rank = 0;
-    for (int o = 0; o < E; ++o) {
-      const int lo = s_load[o];
-      rank += (lo > l || (lo == l && o < e)) ? 1 : 0;
-    }
-    if (rank == want_rank) s_e = e;
-  }
-  __syncthreads();
-  const int e = s_e;
-  if (threadIdx.x < kWave) {                   // its non-empty buckets, ascending vExpert id
-    const int lane = threadIdx.x;
-    const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    int nbw = 0;
-    for (int vb = 0; vb < V; vb += kWave) {
-      const int v = vb + lane;
-      const bool hit = v < V && s_own[v] == e && s_cnt[v] > 0;
-      const unsigned long long mask = __ballot(hit);
-      if (hit) {
-        const int pos = nbw + __popcll(mask & lt);
-        s_bstart[pos] = voff[v];
-        s_brows[pos] = s_cnt[v];
-      }
-      nbw += __popcll(mask);
-    }
-    if (lane == 0) s_nb = nbw;
-  }
-  __syncthreads();
+  const int e = wgrad_pick_expert(voff, owner, E, V, want_rank, s_cnt, s_own, s_load, &s_e, &s_nb, s_bstart, s_brows);
   const int nb = s_nb;
 
   const int m0 = mt * BM, n0 = nt * BN;
@@ -789,6 +810,110 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_bf16(const bf16_t* __
   }
 
   float* patch = (float*)smem + wave * (32 * 64);
+  bf16_t* out = dw + (size_t)e * M * NC;
+  const int col_base = n0 + wn * (NB * 32);
+  epilogue_rounds<false>(patch, acc, [](int, int) { return make_uint2(0, 0); }, [&](int row_w, int col_w, float4 c, uint2) {
+    const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
+    const int col = col_base + col_w;
+    if (lrow < mvalid && col < NC) *(uint2*)(out + (size_t)(m0 + lrow) * NC + col) = pack4(c.x, c.y, c.z, c.w);
+  });
+}
+
+// =============================================================================================
+// wgrad_gemm_dma: the same weight-gradient product on the direct-to-LDS pipeline.  Both operands
+// are token-major ([tokens, M] and [tokens, NC]), i.e. contraction-strided: their 32-token K tiles
+// are copied to LDS as stored and transposed by the LDS reads.  Tokens past the end of a bucket
+// (the ragged last K tile of each vExpert, and the padding that rounds the tile count up to the
+// pipeline's multiple of 4) are fetched from a row of zeros instead, since direct loads cannot
+// be predicated to zero.
+// =============================================================================================
+__device__ const uint4 kZeroRow[32] = {};
+
+struct DmaSrcTok {
+  uint32_t off[4];
+  int krow[4];
+  size_t ld;
+  __device__ __forceinline__ void init(size_t ld_, int cols_valid) {
+    ld = ld_;
+    const int w = threadIdx.x >> 6, i = threadIdx.x & 63;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      krow[q] = (w * 4 + q) * 2 + (i >> 5);
+      const int c = min(dmat_chunk(krow[q], i & 31), cols_valid / 8 - 1);
+      off[q] = (uint32_t)(krow[q] * ld + c * 8);
+    }
+  }
+  // `p`: token row 0 of this K tile, first column of the tile; rows >= k_valid come from kZeroRow
+  __device__ __forceinline__ void issue(lds_byte_t* tile, const bf16_t* __restrict__ p, int k_valid) const {
+    const unsigned w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)tile) + w * 4096;
+    const bf16_t* z = (const bf16_t*)kZeroRow + (threadIdx.x & 31) * 8;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const bf16_t* g = (k_valid >= DK || krow[q] < k_valid) ? p + off[q] : z;
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds0 + q * 1024) : "memory");
+    }
+  }
+};
+
+__global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_dma_bf16(const bf16_t* __restrict__ L,
+                                                                    const bf16_t* __restrict__ R,
+                                                                    const int32_t* __restrict__ voff,
+                                                                    const int32_t* __restrict__ owner, int E, int V,
+                                                                    int M, int NC, int m_tiles, int n_tiles,
+                                                                    bf16_t* __restrict__ dw) {
+  __shared__ __align__(1024) unsigned char stage0[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage1[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage3[kDmaStageBytes];
+  __shared__ int s_cnt[FLEXMOE_MAX_VEXPERTS];
+  __shared__ int s_own[FLEXMOE_MAX_VEXPERTS];
+  __shared__ int s_load[FLEXMOE_MAX_EXPERTS];
+  __shared__ int s_e, s_nb;
+  __shared__ int s_bstart[FLEXMOE_MAX_VEXPERTS], s_brows[FLEXMOE_MAX_VEXPERTS];
+
+  // tile grid: rows = (expert by descending load, m tile), cols = n tile
+  int grow, nt;
+  if (!patched_tile(blockIdx.x, E * m_tiles, n_tiles, &grow, &nt)) return;
+  const int want_rank = grow / m_tiles, mt = grow % m_tiles;
+  const int e = wgrad_pick_expert(voff, owner, E, V, want_rank, s_cnt, s_own, s_load, &s_e, &s_nb, s_bstart, s_brows);
+  const int nb = s_nb;
+
+  const int m0 = mt * BM, n0 = nt * BN;
+  const int mvalid = min(BM, M - m0), nvalid = min(BN, NC - n0);
+  const int wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  f32x16 acc[MB][NB];
+  zero_acc(acc);
+  lds_byte_t* s0 = (lds_byte_t*)stage0;
+
+  if (nb > 0) {
+    int T = 0;
+    for (int b = 0; b < nb; ++b) T += (s_brows[b] + DK - 1) / DK;
+    const int KT = (T + 3) & ~3;                 // padded with all-zero tiles
+    DmaSrcTok l_src, r_src;
+    l_src.init(M, mvalid);
+    r_src.init(NC, nvalid);
+    int bi = 0, koff = 0, issued = 0;            // next K tile: 32 tokens of bucket bi from koff
+    auto issue = [&](lds_byte_t* stage) {
+      const bool real = issued < T;
+      const size_t p0 = (size_t)s_bstart[bi] + koff;
+      const int kv = real ? s_brows[bi] - koff : 0;
+      l_src.issue(stage, L + p0 * M + m0, kv);
+      r_src.issue(stage + kDmaTileBytes, R + p0 * NC + n0, kv);
+      ++issued;
+      if (real) {
+        koff += DK;
+        if (koff >= s_brows[bi]) {
+          koff = 0;
+          bi = min(bi + 1, nb - 1);
+        }
+      }
+    };
+    dma_pipeline<true, true>(s0, (lds_byte_t*)stage1, (lds_byte_t*)stage2, (lds_byte_t*)stage3, acc, issue, KT, wm, wn);
+  }
+
+  float* patch = (float*)stage0 + wave * (32 * 64);
   bf16_t* out = dw + (size_t)e * M * NC;
   const int col_base = n0 + wn * (NB * 32);
   epilogue_rounds<false>(patch, acc, [](int, int) { return make_uint2(0, 0); }, [&](int row_w, int col_w, float4 c, uint2) {
@@ -856,6 +981,12 @@ static hipError_t launch_wgrad(const FfnArgs& a, const void* L, const void* R, i
     attr_done = true;
   }
   const int m_tiles = (M + BM - 1) / BM, n_tiles = (NC + BN - 1) / BN;
+  if (FLEXMOE_WGRAD_DMA) {
+    hipLaunchKernelGGL(wgrad_gemm_dma_bf16, dim3(patched_grid(a.E * m_tiles, n_tiles)), dim3(kGemmThreads), 0, s,
+                       (const bf16_t*)L, (const bf16_t*)R, a.voff, a.owner, a.E, a.V, M, NC, m_tiles, n_tiles,
+                       (bf16_t*)dw);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(wgrad_gemm_bf16, dim3(patched_grid(a.E * m_tiles, n_tiles)), dim3(kGemmThreads), kGemmLds, s,
                      (const bf16_t*)L, (const bf16_t*)R, a.voff, a.owner, a.E, a.V, M, NC, m_tiles, n_tiles,
                      (bf16_t*)dw);
