@@ -1,23 +1,29 @@
 // bf16 expert FFN (paper Eq. 2) per vExpert bucket, forward and backward, as grouped GEMMs on
 // the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation).
 //
-// Two kernel families share one 256x256x64 workgroup tile (4 wavefronts, 2x2, each owning a
-// 128x128 accumulator block = 16 MFMA tiles; operands staged through LDS, double buffered,
-// one LDS-only barrier per K step, the next-but-one K tile in flight in registers):
+// All kernels share one 256x256 workgroup tile: 4 wavefronts (2x2), each owning a 128x128
+// accumulator block = 16 MFMA tiles = 256 accumulator registers, one workgroup per compute unit.
 //
-//  * rows_gemm: C[rows of bucket v, :] = In[rows of v, :] . W_owner(v)    (fwd GEMM1/GEMM2,
+//  * rows GEMMs: C[rows of bucket v, :] = In[rows of v, :] . W_owner(v)    (fwd GEMM1/GEMM2,
 //    bwd dH and dXp).  The row dimension is cut per bucket: a device-side lookup maps the flat
 //    row-tile index to (vExpert, tile inside it), so highly skewed bucket sizes need no host
 //    synchronisation.  Rows of a ragged last tile are clamped on load and dropped on store.
-//  * wgrad_gemm: dW_e = sum over the vExperts v of e of L_v^T . R_v  -- the contraction runs
-//    over the tokens of every bucket of e in ascending vExpert id inside one accumulator, which
-//    is the single-GPU image of the paper's replica gradient synchronisation.  Output tiles are
-//    issued hottest expert first so the long contractions start early.
+//  * weight-gradient GEMMs: dW_e = sum over the vExperts v of e of L_v^T . R_v -- the contraction
+//    runs over the tokens of every bucket of e in ascending vExpert id inside one accumulator,
+//    which is the single-GPU image of the paper's replica gradient synchronisation.  Output tiles
+//    are issued hottest expert first so the long contractions start early.
 //
-// Operand layouts: an operand whose contraction index is contiguous in memory is copied to LDS
-// as is; otherwise 8x8 blocks are transposed in registers on the way.  LDS tiles are
-// [row][64 k] with the 16-byte chunk index XOR-swizzled by (row ^ row>>3) & 7, which keeps the
-// MFMA fragment reads and both kinds of tile writes free of bank conflicts.
+// Two operand pipelines:
+//  * direct-to-LDS (rows_gemm_dma_bf16, wgrad_gemm_dma_bf16; used whenever K is a multiple of
+//    128, i.e. for every benchmark shape): global_load_lds_dwordx4 copies 32-wide K tiles
+//    straight into one of four LDS stages (no register staging, no LDS store instructions); an
+//    operand whose contraction index is strided in memory is copied as stored and transposed on
+//    the way out of LDS by ds_read_tr16_b64.  The kernels are bound by L2 -> LDS bandwidth.
+//  * register-staged (rows_gemm_bf16, wgrad_gemm_bf16; any K that is a multiple of 8): 64-wide K
+//    tiles through registers into two LDS stages, strided operands transposed 8x8 in registers.
+//
+// LDS tiles are XOR-swizzled at 16-byte chunk granularity so that fragment reads and tile
+// writes are free of bank conflicts (measured: SQ_LDS_BANK_CONFLICT = 0).
 // The MFMA is issued as (weights-fragment, activations-fragment) so that a lane ends up with 4
 // consecutive output columns of one output row; the epilogue passes the accumulators through a
 // wave-private LDS patch so that global stores fill whole 128-byte lines.
