@@ -56,24 +56,27 @@ __device__ __forceinline__ float act_deriv(float z, int act) {
 }
 
 // Fast forms for the bf16 GEMM epilogues, where results are rounded to bf16 (relative 2^-9).
-// erf by the rational-exponential formula 7.1.26 of Abramowitz & Stegun (|error| <= 1.5e-7)
-// with the hardware reciprocal and exp2; it also returns exp(-x^2), which the GELU derivative
-// needs (the normal density at z is exp(-(z/sqrt 2)^2)/sqrt(2 pi)).
-__device__ __forceinline__ float fast_erf(float x, float* exp_neg_x2) {
-  const float ax = fabsf(x);
-  const float t = __frcp_rn(fmaf(0.3275911f, ax, 1.f));
-  float p = fmaf(1.061405429f, t, -1.453152027f);
-  p = fmaf(p, t, 1.421413741f);
-  p = fmaf(p, t, -0.284496736f);
-  p = fmaf(p, t, 0.254829592f);
+// The normal CDF comes from the complementary error function by the rational-exponential
+// formula 7.1.26 of Abramowitz & Stegun (erfc(x) = (a1 t + ... + a5 t^5) e^{-x^2}, t = 1/(1+px),
+// x >= 0, |error| <= 1.5e-7) with the hardware reciprocal (v_rcp_f32, 1 ulp) and exp2:
+// Phi(-|z|) = erfc(|z|/sqrt 2)/2, Phi(|z|) = 1 - Phi(-|z|).  The same exponential e^{-z^2/2}
+// gives the normal density that the GELU derivative needs.
+__device__ __forceinline__ float fast_norm_cdf(float z, float* exp_neg_half_z2) {
+  const float ax = fabsf(z) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.f));
+  float p = fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);     // half the polynomial: Phi, not erfc
+  p = fmaf(p, t, 0.5f * 1.421413741f);
+  p = fmaf(p, t, 0.5f * -0.284496736f);
+  p = fmaf(p, t, 0.5f * 0.254829592f);
   p *= t;
   const float ex = __builtin_amdgcn_exp2f(ax * ax * -1.44269504088896341f);
-  *exp_neg_x2 = ex;
-  return copysignf(fmaf(-p, ex, 1.f), x);
+  *exp_neg_half_z2 = ex;
+  const float q = p * ex;                                            // Phi(-|z|)
+  return z > 0.f ? 1.f - q : q;
 }
 __device__ __forceinline__ float fast_tanh(float u) {   // 1 - 2/(1+e^{2u}), saturates cleanly
   const float e2 = __builtin_amdgcn_exp2f(fminf(u, 15.f) * 2.88539008177792681f);
-  return 1.f - 2.f * __frcp_rn(e2 + 1.f);
+  return 1.f - 2.f * __builtin_amdgcn_rcpf(e2 + 1.f);
 }
 template <int ACT> __device__ __forceinline__ void act_both(float z, float* a, float* da) {
   if (ACT == FLEXMOE_RELU) {
@@ -81,7 +84,7 @@ template <int ACT> __device__ __forceinline__ void act_both(float z, float* a, f
     *da = z > 0.f ? 1.f : 0.f;
   } else if (ACT == FLEXMOE_GELU_ERF) {
     float ex;
-    const float cdf = fmaf(0.5f, fast_erf(z * 0.70710678118654752f, &ex), 0.5f);
+    const float cdf = fast_norm_cdf(z, &ex);
     *a = z * cdf;
     *da = fmaf(z * 0.39894228040143268f, ex, cdf);
   } else {

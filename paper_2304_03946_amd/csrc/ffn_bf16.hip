@@ -349,42 +349,48 @@ __device__ __forceinline__ void rows_epilogue(float* lds, const f32x16 (&acc)[MB
                                               int NC, int row0, int rows_valid, int e, int n0,
                                               const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
                                               bf16_t* __restrict__ out1) {
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   float* patch = lds + wave * (32 * 64);
   const int col_base = n0 + wn * (NB * 32);
+  // tile-relative 32-bit offsets on top of uniform per-tile base pointers (scalar base + vector
+  // offset addressing instead of 64-bit vector address arithmetic per store)
+  const size_t tile_base = (size_t)row0 * NC + col_base;
+  const bf16_t* hpre_t = hpre_in ? hpre_in + tile_base : nullptr;
+  bf16_t* out0_t = out0 + tile_base;
+  bf16_t* out1_t = out1 ? out1 + tile_base : nullptr;
+  const bf16_t* bias_t = bias ? bias + (size_t)e * NC + col_base : nullptr;
+  const int cols_left = NC - col_base;
   auto fetch = [&](int row_w, int col_w) -> uint2 {
     const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
-    const int col = col_base + col_w;
-    if (lrow < rows_valid && col < NC) return *(const uint2*)(hpre_in + (size_t)(row0 + lrow) * NC + col);
+    if (lrow < rows_valid && col_w < cols_left) return *(const uint2*)(hpre_t + (uint32_t)(lrow * NC + col_w));
     return make_uint2(0, 0);
   };
   epilogue_rounds<EPI == EPI_DH>(patch, acc, fetch, [&](int row_w, int col_w, float4 c, uint2 pre_in) {
     const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
-    const int col = col_base + col_w;
-    if (lrow < rows_valid && col < NC) {
-      if (bias) {
+    if (lrow < rows_valid && col_w < cols_left) {
+      if (bias_t) {
         float b[4];
-        unpack4(*(const uint2*)(bias + (size_t)e * NC + col), b);
+        unpack4(*(const uint2*)(bias_t + col_w), b);
         c.x += b[0]; c.y += b[1]; c.z += b[2]; c.w += b[3];
       }
-      const size_t o = (size_t)(row0 + lrow) * NC + col;
+      const uint32_t o = (uint32_t)(lrow * NC + col_w);
       if (EPI == EPI_PLAIN) {
-        *(uint2*)(out0 + o) = pack4(c.x, c.y, c.z, c.w);
+        *(uint2*)(out0_t + o) = pack4(c.x, c.y, c.z, c.w);
       } else if (EPI == EPI_FWD1) {
         // keep the pre-activation; the activation is taken of the value as stored
         const uint2 pre = pack4(c.x, c.y, c.z, c.w);
-        *(uint2*)(out0 + o) = pre;
+        *(uint2*)(out0_t + o) = pre;
         float z[4];
         unpack4(pre, z);
-        *(uint2*)(out1 + o) = pack4(act_fast<ACT>(z[0]), act_fast<ACT>(z[1]), act_fast<ACT>(z[2]), act_fast<ACT>(z[3]));
+        *(uint2*)(out1_t + o) = pack4(act_fast<ACT>(z[0]), act_fast<ACT>(z[1]), act_fast<ACT>(z[2]), act_fast<ACT>(z[3]));
       } else {
         float z[4], a[4], d[4];
         unpack4(pre_in, z);
 #pragma unroll
         for (int q = 0; q < 4; ++q) act_both<ACT>(z[q], &a[q], &d[q]);
-        *(uint2*)(out0 + o) = pack4(c.x * d[0], c.y * d[1], c.z * d[2], c.w * d[3]);
-        *(uint2*)(out1 + o) = pack4(a[0], a[1], a[2], a[3]);
+        *(uint2*)(out0_t + o) = pack4(c.x * d[0], c.y * d[1], c.z * d[2], c.w * d[3]);
+        *(uint2*)(out1_t + o) = pack4(a[0], a[1], a[2], a[3]);
       }
     }
   });
@@ -453,10 +459,12 @@ __device__ __forceinline__ bool lookup_row_tile(const int32_t* __restrict__ voff
   __syncthreads();
   const int v = s_tile[0];
   if (v < 0) return false;                            // beyond the last tile (uniform)
-  out->row0 = voff[v] + s_tile[1] * BM;
-  out->rows_valid = min(BM, voff[v + 1] - out->row0);
-  out->e = owner[v];
-  out->n0 = s_tile[2] * BN;
+  // workgroup-uniform values: keep them in scalar registers (scalar base addresses, scalar compares)
+  const int row0 = __builtin_amdgcn_readfirstlane(voff[v] + s_tile[1] * BM);
+  out->row0 = row0;
+  out->rows_valid = __builtin_amdgcn_readfirstlane(min(BM, voff[v + 1] - row0));
+  out->e = __builtin_amdgcn_readfirstlane(owner[v]);
+  out->n0 = __builtin_amdgcn_readfirstlane(s_tile[2] * BN);
   out->cols_valid = min(BN, NC - out->n0);
   return true;
 }

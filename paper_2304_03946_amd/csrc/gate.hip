@@ -1,7 +1,9 @@
 // Top-k gate (paper Eq. 3): logits l = x . W_g, keep the k largest per token, softmax over them.
 //
-// bf16 path: HBM-bound streaming of x.  The logits come from MFMA so that the 2*d*E flops per
-// token do not cap the kernel below the memory roofline: the gate weights act as the MFMA
+// bf16 path: HBM-bound streaming of x (one workgroup per 32 or 64 tokens, the contraction split
+// over its four wavefronts, partial logits summed in a fixed order through LDS).  The logits
+// come from MFMA so that the 2*d*E flops per token do not cap the kernel below the memory
+// roofline: the gate weights act as the MFMA
 // row operand (32 experts per tile) and 32 tokens as the column operand, hence after the
 // K loop every lane holds half of one token's logits and its partner lane (lane ^ 32) the
 // other half -- the top-k selection is a register scan plus one cross-lane exchange per pick.
@@ -40,62 +42,12 @@ union Frag {
   bf16x8 v;
 };
 
-template <int NT>   // NT tiles of 32 experts
-__global__ __launch_bounds__(kGateThreads) void gate_bf16_kernel(const bf16_t* __restrict__ x,
-                                                                 const bf16_t* __restrict__ wgt, int N, int d,
-                                                                 int E, int k, int32_t* __restrict__ topk_idx,
-                                                                 float* __restrict__ topk_w) {
-  const int lane = threadIdx.x % kWave;
-  const int j = lane & 31, h = lane >> 5;
-  const int group = blockIdx.x * (kGateThreads / kWave) + threadIdx.x / kWave;
-  const int t0 = group * 32;
-  if (t0 >= N) return;                       // wave-uniform
-  const int t = t0 + j;
-  const int tl = min(t, N - 1);              // clamp loads of the ragged last group
-
-  f32x16 acc[NT];
-#pragma unroll
-  for (int r = 0; r < NT; ++r)
-#pragma unroll
-    for (int n = 0; n < 16; ++n) acc[r][n] = 0.f;
-
-  const bf16_t* xrow = x + (size_t)tl * d + 32 * h;
-  const bf16_t* wrow = wgt + (size_t)j * d + 32 * h;
-  const int full = d / 64;
-  for (int c = 0; c < full; ++c) {
-    Frag xb[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) xb[s].u = *(const uint4*)(xrow + c * 64 + s * 8);
-#pragma unroll
-    for (int r = 0; r < NT; ++r) {
-      Frag wa[4];
-#pragma unroll
-      for (int s = 0; s < 4; ++s) wa[s].u = *(const uint4*)(wrow + (size_t)r * 32 * d + c * 64 + s * 8);
-#pragma unroll
-      for (int s = 0; s < 4; ++s) acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[s].v, xb[s].v, acc[r], 0, 0, 0);
-    }
-  }
-  if (full * 64 < d) {                        // ragged K tail, 8-element pieces past d read as zero
-    const int c = full;
-    Frag xb[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const bool ok = c * 64 + 32 * h + s * 8 < d;
-      xb[s].u = ok ? *(const uint4*)(xrow + c * 64 + s * 8) : make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int r = 0; r < NT; ++r) {
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const bool ok = c * 64 + 32 * h + s * 8 < d;
-        Frag wa;
-        wa.u = ok ? *(const uint4*)(wrow + (size_t)r * 32 * d + c * 64 + s * 8) : make_uint4(0, 0, 0, 0);
-        acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa.v, xb[s].v, acc[r], 0, 0, 0);
-      }
-    }
-  }
-
-  // lane holds, for token t, the logits of experts r*32 + 8*(n/4) + 4*h + n%4
+// Top-k selection and softmax for one tile of 32 tokens whose logits sit in MFMA layout:
+// lane (j = lane%32, h = lane/32) holds, for token j, experts r*32 + 8*(n/4) + 4*h + n%4.
+template <int NT>
+__device__ __forceinline__ void gate_select_store(f32x16 (&acc)[NT], int t, int N, int E, int k,
+                                                  int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
+  const int h = (threadIdx.x % kWave) >> 5;
 #pragma unroll
   for (int r = 0; r < NT; ++r)
 #pragma unroll
@@ -150,6 +102,113 @@ __global__ __launch_bounds__(kGateThreads) void gate_bf16_kernel(const bf16_t* _
         topk_idx[(size_t)t * k + p] = sel_e[p];
         topk_w[(size_t)t * k + p] = ex[p] * inv;
       }
+  }
+}
+
+// One workgroup = 32*CT tokens.  The contraction is split over the four wavefronts (wave w takes
+// the 64-wide K chunks w, w+4, ...), so even a small batch puts four waves on every compute
+// unit and each wave keeps two chunks of loads in flight; the partial logits are then added in
+// a fixed order (3, 2, 1, 0) through LDS, so results do not depend on timing, and wave 0 selects.
+template <int NT, int CT>   // NT tiles of 32 experts, CT tiles of 32 tokens
+__global__ __launch_bounds__(kGateThreads) void gate_bf16_kernel(const bf16_t* __restrict__ x,
+                                                                 const bf16_t* __restrict__ wgt, int N, int d,
+                                                                 int E, int k, int32_t* __restrict__ topk_idx,
+                                                                 float* __restrict__ topk_w) {
+  __shared__ float4 partial[NT * CT * 4 * kWave];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int j = lane & 31, h = lane >> 5;
+  const int t0 = blockIdx.x * (32 * CT);
+
+  f32x16 acc[CT][NT];
+#pragma unroll
+  for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+    for (int r = 0; r < NT; ++r)
+#pragma unroll
+      for (int n = 0; n < 16; ++n) acc[ct][r][n] = 0.f;
+
+  const bf16_t* xrow[CT];
+#pragma unroll
+  for (int ct = 0; ct < CT; ++ct) xrow[ct] = x + (size_t)min(t0 + ct * 32 + j, N - 1) * d + 32 * h;   // clamp the ragged last tile
+  const bf16_t* wrow = wgt + (size_t)j * d + 32 * h;
+  const int nchunks = (d + 63) / 64;
+
+  // lane reads k = 64c + 32h + 8s .. +8 of its row for s = 0..3 (64 contiguous bytes); pieces past d are zero
+  auto load_chunk = [&](int c, Frag (&xb)[CT][4], Frag (&wa)[NT][4]) {
+    if (c * 64 + 64 <= d) {
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) xb[ct][s].u = *(const uint4*)(xrow[ct] + c * 64 + s * 8);
+#pragma unroll
+      for (int r = 0; r < NT; ++r)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) wa[r][s].u = *(const uint4*)(wrow + (size_t)r * 32 * d + c * 64 + s * 8);
+    } else {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const bool ok = c * 64 + 32 * h + s * 8 < d;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) xb[ct][s].u = ok ? *(const uint4*)(xrow[ct] + c * 64 + s * 8) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < NT; ++r) wa[r][s].u = ok ? *(const uint4*)(wrow + (size_t)r * 32 * d + c * 64 + s * 8) : make_uint4(0, 0, 0, 0);
+      }
+    }
+  };
+  auto mma_chunk = [&](const Frag (&xb)[CT][4], const Frag (&wa)[NT][4]) {
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+      for (int r = 0; r < NT; ++r)
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          acc[ct][r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[r][s].v, xb[ct][s].v, acc[ct][r], 0, 0, 0);
+  };
+
+  Frag xb0[CT][4], wa0[NT][4], xb1[CT][4], wa1[NT][4];
+  int c = wave;
+  if (c < nchunks) load_chunk(c, xb0, wa0);
+  for (; c < nchunks; c += 8) {              // two chunks per trip: the register sets alternate
+    if (c + 4 < nchunks) load_chunk(c + 4, xb1, wa1);
+    mma_chunk(xb0, wa0);
+    if (c + 4 < nchunks) {
+      if (c + 8 < nchunks) load_chunk(c + 8, xb0, wa0);
+      mma_chunk(xb1, wa1);
+    }
+  }
+
+  // fixed-order sum of the four partial results: wave 3 writes, waves 2 and 1 add, wave 0 finishes
+#pragma unroll
+  for (int turn = 3; turn >= 1; --turn) {
+    if (wave == turn) {
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int r = 0; r < NT; ++r)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            float4* slot = &partial[((ct * NT + r) * 4 + q) * kWave + lane];
+            float4 v = make_float4(acc[ct][r][4 * q], acc[ct][r][4 * q + 1], acc[ct][r][4 * q + 2], acc[ct][r][4 * q + 3]);
+            if (turn != 3) {
+              const float4 o = *slot;
+              v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+            }
+            *slot = v;
+          }
+    }
+    __syncthreads();
+  }
+  if (wave != 0) return;
+#pragma unroll
+  for (int ct = 0; ct < CT; ++ct) {
+#pragma unroll
+    for (int r = 0; r < NT; ++r)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 o = partial[((ct * NT + r) * 4 + q) * kWave + lane];
+        acc[ct][r][4 * q] += o.x; acc[ct][r][4 * q + 1] += o.y; acc[ct][r][4 * q + 2] += o.z; acc[ct][r][4 * q + 3] += o.w;
+      }
+    if (t0 + ct * 32 < N) gate_select_store<NT>(acc[ct], t0 + ct * 32 + j, N, E, k, topk_idx, topk_w);
   }
 }
 
@@ -242,14 +301,22 @@ hipError_t launch_gate(const void* x, const void* wg, int N, int d, int E, int k
   bf16_t* wgt = (bf16_t*)ws;
   hipLaunchKernelGGL(gate_transpose_wg_kernel, dim3((d + 255) / 256, epad), dim3(256), 0, s, (const bf16_t*)wg, d, E,
                      epad, wgt);
-  const int groups = (N + 31) / 32;
-  const dim3 grid((groups + wpb - 1) / wpb), block(kGateThreads);
   const bf16_t* xb = (const bf16_t*)x;
-  switch (nt) {
-    case 1: hipLaunchKernelGGL(gate_bf16_kernel<1>, grid, block, 0, s, xb, wgt, N, d, E, k, idx, w); break;
-    case 2: hipLaunchKernelGGL(gate_bf16_kernel<2>, grid, block, 0, s, xb, wgt, N, d, E, k, idx, w); break;
-    case 4: hipLaunchKernelGGL(gate_bf16_kernel<4>, grid, block, 0, s, xb, wgt, N, d, E, k, idx, w); break;
-    default: hipLaunchKernelGGL(gate_bf16_kernel<8>, grid, block, 0, s, xb, wgt, N, d, E, k, idx, w); break;
+  const dim3 block(kGateThreads);
+  // 64 tokens per workgroup halves the gate-weight traffic from L2; 32 keeps small batches spread
+  // over all compute units
+  const bool wide = nt <= 2 && N >= 64 * 512;
+  const dim3 grid(wide ? (N + 63) / 64 : (N + 31) / 32);
+  if (wide) {
+    if (nt == 1) hipLaunchKernelGGL((gate_bf16_kernel<1, 2>), grid, block, 0, s, xb, wgt, N, d, E, k, idx, w);
+    else hipLaunchKernelGGL((gate_bf16_kernel<2, 2>), grid, block, 0, s, xb, wgt, N, d, E, k, idx, w);
+  } else {
+    switch (nt) {
+      case 1: hipLaunchKernelGGL((gate_bf16_kernel<1, 1>), grid, block, 0, s, xb, wgt, N, d, E, k, idx, w); break;
+      case 2: hipLaunchKernelGGL((gate_bf16_kernel<2, 1>), grid, block, 0, s, xb, wgt, N, d, E, k, idx, w); break;
+      case 4: hipLaunchKernelGGL((gate_bf16_kernel<4, 1>), grid, block, 0, s, xb, wgt, N, d, E, k, idx, w); break;
+      default: hipLaunchKernelGGL((gate_bf16_kernel<8, 1>), grid, block, 0, s, xb, wgt, N, d, E, k, idx, w); break;
+    }
   }
   return hipGetLastError();
 }
