@@ -27,6 +27,8 @@
 // The MFMA is issued as (weights-fragment, activations-fragment) so that a lane ends up with 4
 // consecutive output columns of one output row; the epilogue passes the accumulators through a
 // wave-private LDS patch so that global stores fill whole 128-byte lines.
+#include <mutex>
+
 #include "common.h"
 
 namespace flexmoe {
@@ -207,6 +209,59 @@ __device__ __forceinline__ void unpack4(uint2 u, float* v) {
   v[3] = __uint_as_float(u.y & 0xffff0000u);
 }
 
+// ---- activation tables -------------------------------------------------------------------------
+// The GELU epilogues act on pre-activations already rounded to bf16, so the activation has only
+// 2^16 possible arguments.  Both GELU forms are z*F(z) with F(z) + F(-z) = 1, which makes
+//   GELU(z)  = max(z, 0) + r(|z|),          r(a) = GELU(a) - a   (= GELU(-a), even in z)
+//   GELU'(z) = [z >= 0] + sign(z) * q(|z|),  q(a) = GELU'(a) - 1
+// so one table over the bf16 magnitudes serves both signs.  r and q vanish (below 1e-13) from
+// |z| = 8 on and r(a) -> -a/2, q -> -1/2 as a -> 0: magnitudes are clamped to [2^-24, 8], which
+// costs an absolute error below 2^-25.  Entries are computed in double precision on the device,
+// once per device, and held as {r, q} fp32 pairs: 3457 entries, padded to 28 KB so that the GEMM
+// kernels can pull the table into LDS with whole 1 KB direct loads.
+constexpr int kLutLo = 103 << 7;                    // bf16 bits of 2^-24
+constexpr int kLutHi = 130 << 7;                    // bf16 bits of 8.0
+constexpr int kLutBytes = 28 * 1024;
+constexpr int kLutEntries = kLutBytes / 8;
+static_assert(kLutHi - kLutLo + 1 <= kLutEntries, "table does not fit its padding");
+__device__ __align__(1024) float2 g_act_lut[2][kLutEntries];    // [0] erf form, [1] tanh form
+
+__global__ void act_lut_init_kernel() {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= kLutEntries) return;
+  const int m = min(kLutLo + i, kLutHi);
+  const double a = (double)__uint_as_float((uint32_t)m << 16);
+  double Fneg, dF;                                   // F(-a) and F'(a)
+  if (blockIdx.y == 0) {
+    Fneg = 0.5 * erfc(a * 0.70710678118654752440);
+    dF = 0.39894228040143267794 * exp(-0.5 * a * a);
+  } else {
+    const double c = 0.79788456080286535588, u = c * (a + 0.044715 * a * a * a);
+    const double th = tanh(u);
+    Fneg = 0.5 * (1.0 - th);
+    dF = 0.5 * (1.0 - th * th) * c * (1.0 + 3.0 * 0.044715 * a * a);
+  }
+  // r = -a F(-a);  GELU'(a) = F(a) + a F'(a) = 1 - F(-a) + a F'(a)
+  g_act_lut[blockIdx.y][i] = make_float2((float)(-a * Fneg), (float)(a * dF - Fneg));
+}
+
+// Table entry for the bf16 value whose fp32 bit pattern is zu (LDS copy of one table).
+typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+__device__ __forceinline__ uint32_t lut_offset(uint32_t zu) {
+  const uint32_t m = (zu >> 16) & 0x7fffu;
+  return (min(max(m, (uint32_t)kLutLo), (uint32_t)kLutHi) - kLutLo) << 3;
+}
+__device__ __forceinline__ float lut_act(const lds_byte_t* lut, uint32_t zu) {
+  const float r = *(const __attribute__((address_space(3))) float*)(lut + lut_offset(zu));
+  return fmaxf(__uint_as_float(zu), 0.f) + r;
+}
+__device__ __forceinline__ void lut_act_both(const lds_byte_t* lut, uint32_t zu, float* a, float* da) {
+  const f32x2_t rq = *(const __attribute__((address_space(3))) f32x2_t*)(lut + lut_offset(zu));
+  *a = fmaxf(__uint_as_float(zu), 0.f) + rq[0];
+  *da = (int32_t)zu < 0 ? -rq[1] : 1.f + rq[1];
+}
+template <int EPI, int ACT> constexpr bool epilogue_uses_lut() { return EPI != EPI_PLAIN && ACT != FLEXMOE_RELU; }
+
 // ---- epilogue ---------------------------------------------------------------------------------
 // A lane's accumulators hold 4-column pieces of 32 different rows, which would make every global
 // store touch 32 cache lines.  Instead the wave's 128x128 fp32 block goes out in eight rounds of
@@ -214,12 +269,19 @@ __device__ __forceinline__ void unpack4(uint2 u, float* v) {
 // chunk index XORed with row & 15: conflict free both ways) -> read back so that 16 lanes cover
 // 64 consecutive columns of one row -> per-element epilogue in fp32 -> bf16 -> 8-byte stores that
 // fill whole 128-byte lines.  The K loop ends with a barrier, so the LDS tiles are free.
-// emit(row in the wave's block (0..127), column in the wave's block (multiple of 4), float4)
+// Per round, all eight 4-element pieces are first computed (compute(row in the wave's block
+// (0..127), column in the wave's block (multiple of 4), float4 accumulators, uint2 side input)
+// -> EpiOut, unconditional: straight-line code the scheduler can interleave) and then stored
+// (store(row, col, EpiOut), where the ragged-edge predicates live).
 // fetch(row, col) -> uint2: an optional per-element side input (the saved pre-activations of the
 // backward epilogue); the fetches of round n+1 are issued before round n is processed so that
-// their latency hides behind it.  emit(row, col, float4 accumulators, uint2 fetched).
-template <bool FETCH, typename Fetch, typename Emit>
-__device__ __forceinline__ void epilogue_rounds(float* patch, const f32x16 (&acc)[MB][NB], Fetch fetch, Emit emit) {
+// their latency hides behind it.
+struct EpiOut {
+  uint2 a, b;
+};
+template <bool FETCH, typename Fetch, typename Compute, typename Store>
+__device__ __forceinline__ void epilogue_rounds(float* patch, const f32x16 (&acc)[MB][NB], Fetch fetch, Compute compute,
+                                                Store store) {
   const int lane = threadIdx.x & 63;
   const int r = lane & 31, h = lane >> 5;
   const int rsub = lane >> 4, c = lane & 15;
@@ -248,12 +310,15 @@ __device__ __forceinline__ void epilogue_rounds(float* patch, const f32x16 (&acc
           *(float4*)(patch + r * 64 + ((cc ^ (r & 15)) << 2)) = make_float4(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]);
         }
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront", "local");
+      EpiOut o[8];
 #pragma unroll
       for (int it = 0; it < 8; ++it) {
         const int row = it * 4 + rsub;
         const float4 v = *(const float4*)(patch + row * 64 + ((c ^ (row & 15)) << 2));
-        emit(i * 32 + row, jh * 64 + c * 4, v, FETCH ? side[round & 1][it] : make_uint2(0, 0));
+        o[it] = compute(i * 32 + row, jh * 64 + c * 4, v, FETCH ? side[round & 1][it] : make_uint2(0, 0));
       }
+#pragma unroll
+      for (int it = 0; it < 8; ++it) store(i * 32 + it * 4 + rsub, jh * 64 + c * 4, o[it]);
     }
   }
 }
@@ -344,11 +409,13 @@ __device__ __forceinline__ void rows_mainloop(bf16_t* smem, f32x16 (&acc)[MB][NB
 }
 
 // Epilogue of the rows kernels: bias, then plain store / pre-activation + activation / dH*act' + H.
-template <int EPI, int ACT>
-__device__ __forceinline__ void rows_epilogue(float* lds, const f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ bias,
-                                              int NC, int row0, int rows_valid, int e, int n0,
-                                              const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
-                                              bf16_t* __restrict__ out1) {
+// LUT: the activation comes from the LDS copy `lut` of the activation table ({r, q} pairs, see
+// above); otherwise it is evaluated arithmetically.
+template <int EPI, int ACT, bool LUT, bool BIAS>
+__device__ __forceinline__ void rows_epilogue_t(float* lds, const f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ bias,
+                                                int NC, int row0, int rows_valid, int e, int n0,
+                                                const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
+                                                bf16_t* __restrict__ out1, const lds_byte_t* lut) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   float* patch = lds + wave * (32 * 64);
@@ -356,44 +423,66 @@ __device__ __forceinline__ void rows_epilogue(float* lds, const f32x16 (&acc)[MB
   // tile-relative 32-bit offsets on top of uniform per-tile base pointers (scalar base + vector
   // offset addressing instead of 64-bit vector address arithmetic per store)
   const size_t tile_base = (size_t)row0 * NC + col_base;
-  const bf16_t* hpre_t = hpre_in ? hpre_in + tile_base : nullptr;
+  const bf16_t* hpre_t = hpre_in + tile_base;
   bf16_t* out0_t = out0 + tile_base;
-  bf16_t* out1_t = out1 ? out1 + tile_base : nullptr;
-  const bf16_t* bias_t = bias ? bias + (size_t)e * NC + col_base : nullptr;
+  bf16_t* out1_t = out1 + tile_base;
+  const bf16_t* bias_t = bias + (size_t)e * NC + col_base;
   const int cols_left = NC - col_base;
+  auto tile_row = [&](int row_w) { return (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31); };
   auto fetch = [&](int row_w, int col_w) -> uint2 {
-    const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
+    const int lrow = tile_row(row_w);
     if (lrow < rows_valid && col_w < cols_left) return *(const uint2*)(hpre_t + (uint32_t)(lrow * NC + col_w));
     return make_uint2(0, 0);
   };
-  epilogue_rounds<EPI == EPI_DH>(patch, acc, fetch, [&](int row_w, int col_w, float4 c, uint2 pre_in) {
-    const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
-    if (lrow < rows_valid && col_w < cols_left) {
-      if (bias_t) {
-        float b[4];
-        unpack4(*(const uint2*)(bias_t + col_w), b);
-        c.x += b[0]; c.y += b[1]; c.z += b[2]; c.w += b[3];
-      }
-      const uint32_t o = (uint32_t)(lrow * NC + col_w);
-      if (EPI == EPI_PLAIN) {
-        *(uint2*)(out0_t + o) = pack4(c.x, c.y, c.z, c.w);
-      } else if (EPI == EPI_FWD1) {
-        // keep the pre-activation; the activation is taken of the value as stored
-        const uint2 pre = pack4(c.x, c.y, c.z, c.w);
-        *(uint2*)(out0_t + o) = pre;
-        float z[4];
-        unpack4(pre, z);
-        *(uint2*)(out1_t + o) = pack4(act_fast<ACT>(z[0]), act_fast<ACT>(z[1]), act_fast<ACT>(z[2]), act_fast<ACT>(z[3]));
-      } else {
-        float z[4], a[4], d[4];
-        unpack4(pre_in, z);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) act_both<ACT>(z[q], &a[q], &d[q]);
-        *(uint2*)(out0_t + o) = pack4(c.x * d[0], c.y * d[1], c.z * d[2], c.w * d[3]);
-        *(uint2*)(out1_t + o) = pack4(a[0], a[1], a[2], a[3]);
-      }
+  auto compute = [&](int row_w, int col_w, float4 c, uint2 pre_in) -> EpiOut {
+    EpiOut o;
+    if (BIAS) {
+      float b[4];
+      unpack4(*(const uint2*)(bias_t + min(col_w, cols_left - 4)), b);
+      c.x += b[0]; c.y += b[1]; c.z += b[2]; c.w += b[3];
     }
-  });
+    if (EPI == EPI_PLAIN) {
+      o.a = pack4(c.x, c.y, c.z, c.w);
+      o.b = make_uint2(0, 0);
+    } else if (EPI == EPI_FWD1) {
+      // keep the pre-activation; the activation is taken of the value as stored
+      o.a = pack4(c.x, c.y, c.z, c.w);
+      float z[4], a[4];
+      unpack4(o.a, z);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) a[q] = LUT ? lut_act(lut, __float_as_uint(z[q])) : act_fast<ACT>(z[q]);
+      o.b = pack4(a[0], a[1], a[2], a[3]);
+    } else {
+      float z[4], a[4], d[4];
+      unpack4(pre_in, z);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (LUT) lut_act_both(lut, __float_as_uint(z[q]), &a[q], &d[q]);
+        else act_both<ACT>(z[q], &a[q], &d[q]);
+      }
+      o.a = pack4(c.x * d[0], c.y * d[1], c.z * d[2], c.w * d[3]);
+      o.b = pack4(a[0], a[1], a[2], a[3]);
+    }
+    return o;
+  };
+  auto store = [&](int row_w, int col_w, const EpiOut& o) {
+    const int lrow = tile_row(row_w);
+    if (lrow < rows_valid && col_w < cols_left) {
+      const uint32_t off = (uint32_t)(lrow * NC + col_w);
+      *(uint2*)(out0_t + off) = o.a;
+      if (EPI != EPI_PLAIN) *(uint2*)(out1_t + off) = o.b;
+    }
+  };
+  epilogue_rounds<EPI == EPI_DH>(patch, acc, fetch, compute, store);
+}
+
+template <int EPI, int ACT, bool LUT = false>
+__device__ __forceinline__ void rows_epilogue(float* lds, const f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ bias,
+                                              int NC, int row0, int rows_valid, int e, int n0,
+                                              const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
+                                              bf16_t* __restrict__ out1, const lds_byte_t* lut = nullptr) {
+  if (bias) rows_epilogue_t<EPI, ACT, LUT, true>(lds, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1, lut);
+  else rows_epilogue_t<EPI, ACT, LUT, false>(lds, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1, lut);
 }
 
 // One output tile of rows_gemm: main loop and epilogue.  FULL = all eight 32-row blocks hold rows.
@@ -499,7 +588,6 @@ constexpr int DK = 32;
 constexpr int kDmaStages = 4;
 constexpr int kDmaTileBytes = 256 * DK * 2;            // one operand tile: 16 KB
 constexpr int kDmaStageBytes = 2 * kDmaTileBytes;      // A + B
-typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
 
 __device__ __forceinline__ int dma_off(int row, int c) { return row * (DK * 2) + ((c ^ ((row >> 2) & 3)) << 4); }
 
@@ -671,7 +759,7 @@ __device__ __forceinline__ void rows_dma_body(lds_byte_t* s0, lds_byte_t* s1, ld
                                               const RowTile& t, const bf16_t* __restrict__ in, const WSrc& w_src,
                                               const bf16_t* __restrict__ bias, int K, int NC,
                                               const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
-                                              bf16_t* __restrict__ out1) {
+                                              bf16_t* __restrict__ out1, const lds_byte_t* lut) {
   const int wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   DmaSrc a_src;
@@ -685,7 +773,8 @@ __device__ __forceinline__ void rows_dma_body(lds_byte_t* s0, lds_byte_t* s1, ld
     k_next += DK;
   };
   dma_pipeline<false, !WT>(s0, s1, s2, s3, acc, issue, K / DK, wm, wn);   // K % 128 == 0 (host check)
-  rows_epilogue<EPI, ACT>((float*)s0, acc, bias, NC, t.row0, t.rows_valid, t.e, t.n0, hpre_in, out0, out1);
+  rows_epilogue<EPI, ACT, epilogue_uses_lut<EPI, ACT>()>((float*)s0, acc, bias, NC, t.row0, t.rows_valid, t.e, t.n0, hpre_in, out0,
+                                                          out1, lut);
 }
 
 template <bool WT, int EPI, int ACT>
@@ -697,9 +786,26 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_dma_bf16(
   __shared__ __align__(1024) unsigned char stage1[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char stage3[kDmaStageBytes];
+  constexpr bool kLut = epilogue_uses_lut<EPI, ACT>();
+  __shared__ __align__(1024) unsigned char lut_lds[kLut ? kLutBytes : 16];
   __shared__ int s_tile[3];
   RowTile t;
   if (!lookup_row_tile(voff, owner, V, NC, row_tiles_max, col_tiles, s_tile, &t)) return;
+  const lds_byte_t* lut = nullptr;
+  if (kLut) {
+    // the table rides in front of the operand tiles: its direct loads are the oldest in every
+    // wave's queue, so the first wait of the K loop covers them and its barrier publishes them
+    lut = (const lds_byte_t*)lut_lds;
+    const unsigned w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)lut) + w * (kLutBytes / 4);
+    const unsigned char* g = (const unsigned char*)g_act_lut[ACT == FLEXMOE_GELU_ERF ? 0 : 1] + w * (kLutBytes / 4) +
+                             (threadIdx.x & 63) * 16;
+#pragma unroll
+    for (int q = 0; q < kLutBytes / 4 / 1024; ++q) {
+      const unsigned char* gq = g + q * 1024;
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gq), "s"(lds0 + q * 1024) : "memory");
+    }
+  }
   lds_byte_t* s0 = (lds_byte_t*)stage0;
   lds_byte_t* s1 = (lds_byte_t*)stage1;
   lds_byte_t* s2 = (lds_byte_t*)stage2;
@@ -708,11 +814,11 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_dma_bf16(
   if (WT) {
     DmaSrc w_src;
     w_src.init(w_e + (size_t)t.n0 * K, K, t.cols_valid);
-    rows_dma_body<true, DmaSrc, EPI, ACT>(s0, s1, s2, s3, t, in, w_src, bias, K, NC, hpre_in, out0, out1);
+    rows_dma_body<true, DmaSrc, EPI, ACT>(s0, s1, s2, s3, t, in, w_src, bias, K, NC, hpre_in, out0, out1, lut);
   } else {
     DmaSrcT w_src;
     w_src.init(w_e + t.n0, NC, t.cols_valid);
-    rows_dma_body<false, DmaSrcT, EPI, ACT>(s0, s1, s2, s3, t, in, w_src, bias, K, NC, hpre_in, out0, out1);
+    rows_dma_body<false, DmaSrcT, EPI, ACT>(s0, s1, s2, s3, t, in, w_src, bias, K, NC, hpre_in, out0, out1, lut);
   }
 }
 
@@ -826,11 +932,14 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_bf16(const bf16_t* __
   float* patch = (float*)smem + wave * (32 * 64);
   bf16_t* out = dw + (size_t)e * M * NC;
   const int col_base = n0 + wn * (NB * 32);
-  epilogue_rounds<false>(patch, acc, [](int, int) { return make_uint2(0, 0); }, [&](int row_w, int col_w, float4 c, uint2) {
-    const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
-    const int col = col_base + col_w;
-    if (lrow < mvalid && col < NC) *(uint2*)(out + (size_t)(m0 + lrow) * NC + col) = pack4(c.x, c.y, c.z, c.w);
-  });
+  epilogue_rounds<false>(
+      patch, acc, [](int, int) { return make_uint2(0, 0); },
+      [](int, int, float4 c, uint2) { return EpiOut{pack4(c.x, c.y, c.z, c.w), make_uint2(0, 0)}; },
+      [&](int row_w, int col_w, const EpiOut& o) {
+        const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
+        const int col = col_base + col_w;
+        if (lrow < mvalid && col < NC) *(uint2*)(out + (size_t)(m0 + lrow) * NC + col) = o.a;
+      });
 }
 
 // =============================================================================================
@@ -930,11 +1039,14 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_dma_bf16(const bf16_t
   float* patch = (float*)stage0 + wave * (32 * 64);
   bf16_t* out = dw + (size_t)e * M * NC;
   const int col_base = n0 + wn * (NB * 32);
-  epilogue_rounds<false>(patch, acc, [](int, int) { return make_uint2(0, 0); }, [&](int row_w, int col_w, float4 c, uint2) {
-    const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
-    const int col = col_base + col_w;
-    if (lrow < mvalid && col < NC) *(uint2*)(out + (size_t)(m0 + lrow) * NC + col) = pack4(c.x, c.y, c.z, c.w);
-  });
+  epilogue_rounds<false>(
+      patch, acc, [](int, int) { return make_uint2(0, 0); },
+      [](int, int, float4 c, uint2) { return EpiOut{pack4(c.x, c.y, c.z, c.w), make_uint2(0, 0)}; },
+      [&](int row_w, int col_w, const EpiOut& o) {
+        const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
+        const int col = col_base + col_w;
+        if (lrow < mvalid && col < NC) *(uint2*)(out + (size_t)(m0 + lrow) * NC + col) = o.a;
+      });
 }
 
 // =============================================================================================
@@ -951,6 +1063,30 @@ template <typename Kern> static hipError_t allow_big_lds(Kern kern) {
 
 static int max_row_tiles(int A, int V) { return A / BM + V; }
 
+// Fills the activation tables of the current device the first time a kernel that reads them is
+// launched there.  The fill runs on the caller's stream and is waited for before the device is
+// marked ready (other streams may launch next); under stream capture nothing can be waited for,
+// so the fill is recorded into the capture and the device stays unmarked.
+static hipError_t ensure_act_lut(hipStream_t s) {
+  static std::mutex mu;
+  static bool ready[64] = {};
+  int dev = 0;
+  hipError_t err = hipGetDevice(&dev);
+  if (err != hipSuccess) return err;
+  std::lock_guard<std::mutex> lock(mu);
+  if (dev < 64 && ready[dev]) return hipSuccess;
+  hipLaunchKernelGGL(act_lut_init_kernel, dim3((kLutEntries + 255) / 256, 2), dim3(256), 0, s);
+  err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  err = hipStreamIsCapturing(s, &cap);
+  if (err != hipSuccess) return err;
+  if (cap != hipStreamCaptureStatusNone) return hipSuccess;
+  err = hipStreamSynchronize(s);
+  if (err == hipSuccess && dev < 64) ready[dev] = true;
+  return err;
+}
+
 template <bool WT, int EPI, int ACT>
 static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w, const void* bias, int K, int NC,
                                 const void* hpre_in, void* out0, void* out1, hipStream_t s) {
@@ -965,6 +1101,10 @@ static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w,
   const unsigned grid = patched_grid(row_tiles, col_tiles);
   if (K % 128 == 0) {
     // K is a whole number of pipeline rounds: direct-to-LDS path
+    if (epilogue_uses_lut<EPI, ACT>()) {
+      hipError_t err = ensure_act_lut(s);
+      if (err != hipSuccess) return err;
+    }
     hipLaunchKernelGGL((rows_gemm_dma_bf16<WT, EPI, ACT>), dim3(grid), dim3(kGemmThreads), 0, s, (const bf16_t*)in,
                        (const bf16_t*)w, (const bf16_t*)bias, a.voff, a.owner, a.V, K, NC, row_tiles, col_tiles,
                        (const bf16_t*)hpre_in, (bf16_t*)out0, (bf16_t*)out1);
