@@ -40,6 +40,9 @@ constexpr int kTileElems = BM * BK;                 // one operand tile in LDS (
 constexpr size_t kGemmLds = 2 * 2 * kTileElems * sizeof(bf16_t);   // 2 stages x (A + B) = 128 KB
 
 enum { EPI_FWD1 = 0, EPI_PLAIN = 1, EPI_DH = 2 };
+#ifndef FLEXMOE_DMA_CPOL
+#define FLEXMOE_DMA_CPOL ""      // cache-policy modifiers of the direct-to-LDS loads
+#endif
 #ifndef FLEXMOE_WGRAD_DMA
 #define FLEXMOE_WGRAD_DMA 1
 #endif
@@ -609,14 +612,12 @@ struct DmaSrc {
   // slice, lane i lands at M0 + 16*i): the compiler's wait-count insertion cannot tell which LDS
   // stage a direct load writes and would wait for every outstanding load before any LDS read;
   // here the waits are placed by hand (wait_vmcnt_le) before the barrier that publishes a stage.
-  __device__ __forceinline__ void issue(lds_byte_t* tile, int k0) const {
+  // q-th of the wave's four direct loads of one tile
+  __device__ __forceinline__ void part(lds_byte_t* tile, int k0, int q) const {
     const unsigned w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)tile) + w * 4096;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const bf16_t* g = base + k0 + off[q];
-      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds0 + q * 1024) : "memory");
-    }
+    const bf16_t* g = base + k0 + off[q];
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" FLEXMOE_DMA_CPOL ::"v"(g), "s"(lds0 + q * 1024) : "memory");
   }
 };
 
@@ -643,15 +644,11 @@ struct DmaSrcT {
       off[q] = (uint32_t)(krow * ld + c * 8);
     }
   }
-  __device__ __forceinline__ void issue(lds_byte_t* tile, int k0) const {
+  __device__ __forceinline__ void part(lds_byte_t* tile, int k0, int q) const {
     const unsigned w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)tile) + w * 4096;
-    const bf16_t* rowp = base + (size_t)k0 * ld;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const bf16_t* g = rowp + off[q];
-      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds0 + q * 1024) : "memory");
-    }
+    const bf16_t* g = base + (size_t)k0 * ld + off[q];
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" FLEXMOE_DMA_CPOL ::"v"(g), "s"(lds0 + q * 1024) : "memory");
   }
 };
 
@@ -717,42 +714,81 @@ __device__ __forceinline__ void dma_mma(f32x16 (&acc)[MB][NB], const DmaFrags& f
 // The barrier sits between the two k steps: before it the wave has fetched everything it needs
 // from `cur`, so after it `cur` is free for tile kt+4; and tile kt+1 is published, so its first
 // fragments can be fetched while the second k step's MFMAs run -- no LDS latency after the barrier.
-// issue(stage) starts the direct loads of the next K tile in sequence into `stage`.
-template <bool TRA, bool TRB, typename Issue>
+// The eight direct loads of tile kt+4 are spread between the second k step's MFMAs, one after
+// every two MFMAs (64 cycles of matrix-pipe work): the four waves share one address path, and a
+// wave that issues its loads back to back leaves its matrix pipe idle while it queues there.
+// Issue: begin() prepares the next tile in sequence, part(stage, q) starts its q-th direct load
+// (q = 0..7) into `stage`, end() moves on to the tile after it.
+// ISSUE: tile kt+4 exists.  NEXT: tile kt+1 exists; WAIT = how many younger tiles may still be in
+// flight once this wave's part of tile kt+1 has landed.
+template <bool TRA, bool TRB, bool ISSUE, int WAIT, bool NEXT, typename Issue>
 __device__ __forceinline__ void dma_step(lds_byte_t* cur, const lds_byte_t* nxt, f32x16 (&acc)[MB][NB], DmaFrags& f0,
-                                         DmaFrags& f1, Issue& issue, int kt, int KT, int wm, int wn) {
+                                         DmaFrags& f1, Issue& issue, int wm, int wn) {
   dma_read_frags<TRA, TRB>(f1, cur, 1, wm, wn);
+  if (ISSUE) issue.begin();
   dma_mma(acc, f0);
-  if (kt + 1 < KT) wait_tiles_in_flight(min(2, KT - 2 - kt));    // my part of tile kt+1 has landed
+  __builtin_amdgcn_sched_barrier(0);     // all of them queued before the wave goes to wait
+  if (NEXT) wait_tiles_in_flight(WAIT);
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-  if (kt + 4 < KT) issue(cur);
-  if (kt + 1 < KT) dma_read_frags<TRA, TRB>(f0, nxt, 0, wm, wn);
-  dma_mma(acc, f1);
+  if (NEXT) dma_read_frags<TRA, TRB>(f0, nxt, 0, wm, wn);
+#pragma unroll
+  for (int g = 0; g < 8; ++g) {
+    __builtin_amdgcn_sched_barrier(0);
+    const int i = g >> 1, j = (g & 1) * 2;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.b[j].v, f1.a[i].v, acc[i][j], 0, 0, 0);
+    acc[i][j + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.b[j + 1].v, f1.a[i].v, acc[i][j + 1], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (ISSUE) issue.part(cur, g);
+  }
+  if (ISSUE) issue.end();
 }
 
-// The whole K loop: KT tiles (a multiple of 4) through the four stages.
+// The whole K loop: KT tiles (a multiple of 4) through the four stages; the last four tiles,
+// which have nothing left to prefetch, run as a peeled tail so that the steady-state loop body is
+// branch-free.
 template <bool TRA, bool TRB, typename Issue>
 __device__ __forceinline__ void dma_pipeline(lds_byte_t* s0, lds_byte_t* s1, lds_byte_t* s2, lds_byte_t* s3,
                                              f32x16 (&acc)[MB][NB], Issue& issue, int KT, int wm, int wn) {
-  issue(s0);
-  issue(s1);
-  issue(s2);
-  issue(s3);
+  lds_byte_t* const stages[4] = {s0, s1, s2, s3};
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    issue.begin();
+#pragma unroll
+    for (int q = 0; q < 8; ++q) issue.part(stages[t], q);
+    issue.end();
+  }
   wait_tiles_in_flight(3);
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
   DmaFrags f0, f1;
   dma_read_frags<TRA, TRB>(f0, s0, 0, wm, wn);
-  for (int kt = 0; kt < KT; kt += 4) {
-    dma_step<TRA, TRB>(s0, s1, acc, f0, f1, issue, kt, KT, wm, wn);
-    dma_step<TRA, TRB>(s1, s2, acc, f0, f1, issue, kt + 1, KT, wm, wn);
-    dma_step<TRA, TRB>(s2, s3, acc, f0, f1, issue, kt + 2, KT, wm, wn);
-    dma_step<TRA, TRB>(s3, s0, acc, f0, f1, issue, kt + 3, KT, wm, wn);
+  for (int kt = 0; kt < KT - 4; kt += 4) {
+    dma_step<TRA, TRB, true, 2, true>(s0, s1, acc, f0, f1, issue, wm, wn);
+    dma_step<TRA, TRB, true, 2, true>(s1, s2, acc, f0, f1, issue, wm, wn);
+    dma_step<TRA, TRB, true, 2, true>(s2, s3, acc, f0, f1, issue, wm, wn);
+    dma_step<TRA, TRB, true, 2, true>(s3, s0, acc, f0, f1, issue, wm, wn);
   }
+  dma_step<TRA, TRB, false, 2, true>(s0, s1, acc, f0, f1, issue, wm, wn);
+  dma_step<TRA, TRB, false, 1, true>(s1, s2, acc, f0, f1, issue, wm, wn);
+  dma_step<TRA, TRB, false, 0, true>(s2, s3, acc, f0, f1, issue, wm, wn);
+  dma_step<TRA, TRB, false, 0, false>(s3, s0, acc, f0, f1, issue, wm, wn);
   __syncthreads();                                     // all waves done with the last tile: LDS is free
 }
+
+// Tile sequence of the rows kernels: K tile t of both operands starts at contraction index 32 t.
+template <typename WSrc> struct RowsIssue {
+  const DmaSrc& a_src;
+  const WSrc& w_src;
+  int k_next;
+  __device__ __forceinline__ void begin() {}
+  __device__ __forceinline__ void part(lds_byte_t* stage, int q) const {
+    if (q < 4) a_src.part(stage, k_next, q);
+    else w_src.part(stage + kDmaTileBytes, k_next, q - 4);
+  }
+  __device__ __forceinline__ void end() { k_next += DK; }
+};
 
 template <bool WT, typename WSrc, int EPI, int ACT>
 __device__ __forceinline__ void rows_dma_body(lds_byte_t* s0, lds_byte_t* s1, lds_byte_t* s2, lds_byte_t* s3,
@@ -766,12 +802,7 @@ __device__ __forceinline__ void rows_dma_body(lds_byte_t* s0, lds_byte_t* s1, ld
   a_src.init(in + (size_t)t.row0 * K, K, t.rows_valid);
   f32x16 acc[MB][NB];
   zero_acc(acc);
-  int k_next = 0;
-  auto issue = [&](lds_byte_t* stage) {
-    a_src.issue(stage, k_next);
-    w_src.issue(stage + kDmaTileBytes, k_next);
-    k_next += DK;
-  };
+  RowsIssue<WSrc> issue{a_src, w_src, 0};
   dma_pipeline<false, !WT>(s0, s1, s2, s3, acc, issue, K / DK, wm, wn);   // K % 128 == 0 (host check)
   rows_epilogue<EPI, ACT, epilogue_uses_lut<EPI, ACT>()>((float*)s0, acc, bias, NC, t.row0, t.rows_valid, t.e, t.n0, hpre_in, out0,
                                                           out1, lut);
@@ -803,7 +834,7 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_dma_bf16(
 #pragma unroll
     for (int q = 0; q < kLutBytes / 4 / 1024; ++q) {
       const unsigned char* gq = g + q * 1024;
-      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gq), "s"(lds0 + q * 1024) : "memory");
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" FLEXMOE_DMA_CPOL ::"v"(gq), "s"(lds0 + q * 1024) : "memory");
     }
   }
   lds_byte_t* s0 = (lds_byte_t*)stage0;
@@ -967,15 +998,48 @@ struct DmaSrcTok {
     }
   }
   // `p`: token row 0 of this K tile, first column of the tile; rows >= k_valid come from kZeroRow
-  __device__ __forceinline__ void issue(lds_byte_t* tile, const bf16_t* __restrict__ p, int k_valid) const {
+  __device__ __forceinline__ void part(lds_byte_t* tile, const bf16_t* __restrict__ p, int k_valid, int q) const {
     const unsigned w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)tile) + w * 4096;
     const bf16_t* z = (const bf16_t*)kZeroRow + (threadIdx.x & 31) * 8;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const bf16_t* g = (k_valid >= DK || krow[q] < k_valid) ? p + off[q] : z;
-      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds0 + q * 1024) : "memory");
+    const bf16_t* g = (k_valid >= DK || krow[q] < k_valid) ? p + off[q] : z;
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" FLEXMOE_DMA_CPOL ::"v"(g), "s"(lds0 + q * 1024) : "memory");
+  }
+};
+
+// Tile sequence of the weight-gradient kernel: 32-token K tiles of the expert's buckets in
+// ascending vExpert id, then all-zero tiles up to the padded count.
+struct WgradIssue {
+  const DmaSrcTok& l_src;
+  const DmaSrcTok& r_src;
+  const bf16_t* L;
+  const bf16_t* R;
+  const int* bstart;
+  const int* brows;
+  int M, NC, m0, n0, nb, T;
+  int bi, koff, issued;             // next K tile: 32 tokens of bucket bi from koff
+  const bf16_t* lp;
+  const bf16_t* rp;
+  int kv;
+  __device__ __forceinline__ void begin() {
+    const size_t p0 = (size_t)bstart[bi] + koff;
+    kv = issued < T ? brows[bi] - koff : 0;
+    lp = L + p0 * M + m0;
+    rp = R + p0 * NC + n0;
+  }
+  __device__ __forceinline__ void part(lds_byte_t* stage, int q) const {
+    if (q < 4) l_src.part(stage, lp, kv, q);
+    else r_src.part(stage + kDmaTileBytes, rp, kv, q - 4);
+  }
+  __device__ __forceinline__ void end() {
+    if (issued < T) {
+      koff += DK;
+      if (koff >= brows[bi]) {
+        koff = 0;
+        bi = min(bi + 1, nb - 1);
+      }
     }
+    ++issued;
   }
 };
 
@@ -1017,22 +1081,7 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_dma_bf16(const bf16_t
     DmaSrcTok l_src, r_src;
     l_src.init(M, mvalid);
     r_src.init(NC, nvalid);
-    int bi = 0, koff = 0, issued = 0;            // next K tile: 32 tokens of bucket bi from koff
-    auto issue = [&](lds_byte_t* stage) {
-      const bool real = issued < T;
-      const size_t p0 = (size_t)s_bstart[bi] + koff;
-      const int kv = real ? s_brows[bi] - koff : 0;
-      l_src.issue(stage, L + p0 * M + m0, kv);
-      r_src.issue(stage + kDmaTileBytes, R + p0 * NC + n0, kv);
-      ++issued;
-      if (real) {
-        koff += DK;
-        if (koff >= s_brows[bi]) {
-          koff = 0;
-          bi = min(bi + 1, nb - 1);
-        }
-      }
-    };
+    WgradIssue issue{l_src, r_src, L, R, s_bstart, s_brows, M, NC, m0, n0, nb, T, 0, 0, 0, nullptr, nullptr, 0};
     dma_pipeline<true, true>(s0, (lds_byte_t*)stage1, (lds_byte_t*)stage2, (lds_byte_t*)stage3, acc, issue, KT, wm, wn);
   }
 
