@@ -714,35 +714,47 @@ __device__ __forceinline__ void dma_mma(f32x16 (&acc)[MB][NB], const DmaFrags& f
 // The barrier sits between the two k steps: before it the wave has fetched everything it needs
 // from `cur`, so after it `cur` is free for tile kt+4; and tile kt+1 is published, so its first
 // fragments can be fetched while the second k step's MFMAs run -- no LDS latency after the barrier.
-// The eight direct loads of tile kt+4 are spread between the second k step's MFMAs, one after
-// every two MFMAs (64 cycles of matrix-pipe work): the four waves share one address path, and a
-// wave that issues its loads back to back leaves its matrix pipe idle while it queues there.
+// The direct loads are spread evenly between the MFMAs, one after every four (128 cycles of
+// matrix-pipe work): the four waves share one address path, and a wave that issues its loads back
+// to back leaves its matrix pipe idle while it queues there.  So a tile's eight loads per wave go
+// out in two halves: loads 0..3 of tile kt+4 after the barrier of step kt (into `cur`, just
+// freed), loads 4..7 before the barrier of step kt+1 (into that step's `prev`).
 // Issue: begin() prepares the next tile in sequence, part(stage, q) starts its q-th direct load
 // (q = 0..7) into `stage`, end() moves on to the tile after it.
-// ISSUE: tile kt+4 exists.  NEXT: tile kt+1 exists; WAIT = how many younger tiles may still be in
-// flight once this wave's part of tile kt+1 has landed.
-template <bool TRA, bool TRB, bool ISSUE, int WAIT, bool NEXT, typename Issue>
-__device__ __forceinline__ void dma_step(lds_byte_t* cur, const lds_byte_t* nxt, f32x16 (&acc)[MB][NB], DmaFrags& f0,
-                                         DmaFrags& f1, Issue& issue, int wm, int wn) {
+// PRE: tile kt+3 exists (its second half is issued here).  POST: tile kt+4 exists.
+// NEXT: tile kt+1 exists; WAIT = how many younger tiles may still be in flight once this wave's
+// part of tile kt+1 has landed.
+template <bool TRA, bool TRB, bool PRE, bool POST, int WAIT, bool NEXT, typename Issue>
+__device__ __forceinline__ void dma_step(lds_byte_t* prev, lds_byte_t* cur, const lds_byte_t* nxt,
+                                         f32x16 (&acc)[MB][NB], DmaFrags& f0, DmaFrags& f1, Issue& issue, int wm,
+                                         int wn) {
   dma_read_frags<TRA, TRB>(f1, cur, 1, wm, wn);
-  if (ISSUE) issue.begin();
-  dma_mma(acc, f0);
-  __builtin_amdgcn_sched_barrier(0);     // all of them queued before the wave goes to wait
+#pragma unroll
+  for (int i = 0; i < MB; ++i) {
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.b[j].v, f0.a[i].v, acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (PRE) issue.part(prev, 4 + i);
+  }
+  if (PRE) issue.end();
+  __builtin_amdgcn_sched_barrier(0);     // everything above is queued before the wave goes to wait
   if (NEXT) wait_tiles_in_flight(WAIT);
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
   if (NEXT) dma_read_frags<TRA, TRB>(f0, nxt, 0, wm, wn);
+  if (POST) issue.begin();
 #pragma unroll
-  for (int g = 0; g < 8; ++g) {
+  for (int i = 0; i < MB; ++i) {
     __builtin_amdgcn_sched_barrier(0);
-    const int i = g >> 1, j = (g & 1) * 2;
-    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.b[j].v, f1.a[i].v, acc[i][j], 0, 0, 0);
-    acc[i][j + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.b[j + 1].v, f1.a[i].v, acc[i][j + 1], 0, 0, 0);
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.b[j].v, f1.a[i].v, acc[i][j], 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
-    if (ISSUE) issue.part(cur, g);
+    if (POST) issue.part(cur, i);
   }
-  if (ISSUE) issue.end();
 }
 
 // The whole K loop: KT tiles (a multiple of 4) through the four stages; the last four tiles,
@@ -756,24 +768,24 @@ __device__ __forceinline__ void dma_pipeline(lds_byte_t* s0, lds_byte_t* s1, lds
   for (int t = 0; t < 4; ++t) {
     issue.begin();
 #pragma unroll
-    for (int q = 0; q < 8; ++q) issue.part(stages[t], q);
-    issue.end();
+    for (int q = 0; q < (t < 3 ? 8 : 4); ++q) issue.part(stages[t], q);   // tile 3: first half only
+    if (t < 3) issue.end();
   }
-  wait_tiles_in_flight(3);
+  __builtin_amdgcn_s_waitcnt(0x4F74);                  // vmcnt(20): tile 0 has landed
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
   DmaFrags f0, f1;
   dma_read_frags<TRA, TRB>(f0, s0, 0, wm, wn);
   for (int kt = 0; kt < KT - 4; kt += 4) {
-    dma_step<TRA, TRB, true, 2, true>(s0, s1, acc, f0, f1, issue, wm, wn);
-    dma_step<TRA, TRB, true, 2, true>(s1, s2, acc, f0, f1, issue, wm, wn);
-    dma_step<TRA, TRB, true, 2, true>(s2, s3, acc, f0, f1, issue, wm, wn);
-    dma_step<TRA, TRB, true, 2, true>(s3, s0, acc, f0, f1, issue, wm, wn);
+    dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f0, f1, issue, wm, wn);
+    dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f0, f1, issue, wm, wn);
+    dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f0, f1, issue, wm, wn);
+    dma_step<TRA, TRB, true, true, 2, true>(s2, s3, s0, acc, f0, f1, issue, wm, wn);
   }
-  dma_step<TRA, TRB, false, 2, true>(s0, s1, acc, f0, f1, issue, wm, wn);
-  dma_step<TRA, TRB, false, 1, true>(s1, s2, acc, f0, f1, issue, wm, wn);
-  dma_step<TRA, TRB, false, 0, true>(s2, s3, acc, f0, f1, issue, wm, wn);
-  dma_step<TRA, TRB, false, 0, false>(s3, s0, acc, f0, f1, issue, wm, wn);
+  dma_step<TRA, TRB, true, false, 2, true>(s3, s0, s1, acc, f0, f1, issue, wm, wn);
+  dma_step<TRA, TRB, false, false, 1, true>(s0, s1, s2, acc, f0, f1, issue, wm, wn);
+  dma_step<TRA, TRB, false, false, 0, true>(s1, s2, s3, acc, f0, f1, issue, wm, wn);
+  dma_step<TRA, TRB, false, false, 0, false>(s2, s3, s0, acc, f0, f1, issue, wm, wn);
   __syncthreads();                                     // all waves done with the last tile: LDS is free
 }
 
