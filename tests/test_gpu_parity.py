@@ -218,6 +218,48 @@ def test_other_activations(api, act):
     run_stagewise(api, cfg, inp, *W.placement_from_loads(W.prior_loads(cfg), cfg.V, 4))
 
 
+def _bf16_ulp(v):
+    """Spacing of bf16 numbers at |v| (8 significand bits; subnormals below 2^-126)."""
+    a = np.maximum(np.abs(np.asarray(v, dtype=np.float64)), 2.0 ** -126)
+    return 2.0 ** (np.floor(np.log2(a)) - 7)
+
+
+@pytest.mark.parametrize("act", [W.ACT_GELU_ERF, W.ACT_GELU_TANH])
+def test_activation_on_every_bf16_value(api, act):
+    """Every finite bf16 pre-activation once: with identity weights (one expert, d = f = 128, exact
+    sums) Hpre is Xp itself, Yp is act(Xp) and, for dY = 1, dXp is act'(Xp), each rounded once to
+    bf16.  Covers the tiny and huge magnitudes the random workloads never produce."""
+    B, layer = api
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    bits[(bits & 0x7F80) == 0x7F80] = 0                      # NaN/Inf patterns -> +0
+    bits[(bits & 0x7F80) == 0] &= 0x8000                     # subnormals -> +-0 (matrix cores may flush them)
+    A, d = 512, 128
+    xp = W.Bf16Tensor(bits.reshape(A, d))
+    z = W.decode(xp).astype(np.float64)
+    eye = W.Bf16Tensor.from_f32(np.eye(d, dtype=np.float32)[None])
+    ones = W.Bf16Tensor.from_f32(np.ones((A, d), dtype=np.float32))
+    up = layer.to_device
+    i32 = lambda a: torch.tensor(a, dtype=torch.int32, device="cuda")
+    voff, owner = i32([0, A]), i32([0])
+    hpre = torch.empty(A, d, dtype=torch.bfloat16, device="cuda")
+    yp, dxp = torch.empty_like(hpre), torch.empty_like(hpre)
+    dw1 = torch.empty(1, d, d, dtype=torch.bfloat16, device="cuda")
+    dw2 = torch.empty_like(dw1)
+    ws = torch.empty(B.flexmoe_workspace_bytes(A, d, d, 1, 1, 1, W.DT_BF16), dtype=torch.uint8, device="cuda")
+    xp_d, eye_d = up(xp), up(eye)
+    B.flexmoe_expert_ffn_fwd(xp_d, voff, owner, eye_d, None, eye_d, None, act, hpre, yp, ws)
+    B.flexmoe_expert_ffn_bwd(up(ones), xp_d, hpre, eye_d, eye_d, voff, owner, act, dxp, dw1, dw2, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(hpre).astype(np.float64), z)
+    # magnitudes below 2^-24 are evaluated at 2^-24: an absolute error below 2^-25
+    for got, ref in ((host(yp), O.act_fn(z, act)), (host(dxp), O.act_grad(z, act))):
+        err = np.abs(got.astype(np.float64) - ref)
+        allowed = np.maximum(_bf16_ulp(ref), 2.0 ** -24)
+        worst = int(np.argmax(err / allowed))
+        assert (err <= allowed).all(), (z.flat[worst], got.flat[worst], ref.flat[worst])
+        assert (err <= 0.5 * _bf16_ulp(ref) + 2.0 ** -24).mean() > 0.999        # correctly rounded almost everywhere
+
+
 def test_exact_ties_pick_lower_expert(api):
     """Small-integer inputs make every fp32 sum exact, so ties are real ties on both sides."""
     binding, layer_mod = api
