@@ -105,6 +105,8 @@ int flexmoe_permute(const void* x, const int32_t* src, const float* row_scale,
  *   vexpert_off [V+1], vexpert_owner [V] as written by flexmoe_route.
  *   -> hpre [A,f] dtype (pre-activation, kept for the backward pass), yp [A,d] dtype.
  * The activation is applied to hpre as stored (i.e. after rounding to dtype).
+ * The first bf16 GELU call on a device (forward or backward) fills that device's activation
+ * tables and waits once for `stream`; under stream capture the fill is recorded instead.
  */
 int flexmoe_expert_ffn_fwd(const void* xp, const int32_t* vexpert_off, const int32_t* vexpert_owner,
                            const void* w1, const void* b1, const void* w2, const void* b2,
