@@ -131,7 +131,15 @@ class StageTimers:
         self.last = ev
 
     def mean_ms(self):
-        return {n: sum(a.elapsed_time(b) for a, b in p) / len(p) for n, p in self.pairs.items()}
+        """Mean interval per stage over the steps.  Intervals above five times the stage's median are
+        left out: they are host stalls between two launches (the queue ran dry), not kernel time."""
+        out = {}
+        for n, p in self.pairs.items():
+            t = sorted(a.elapsed_time(b) for a, b in p)
+            med = 0.5 * (t[(len(t) - 1) // 2] + t[len(t) // 2])
+            kept = [v for v in t if v <= 5.0 * med]
+            out[n] = sum(kept) / len(kept)
+        return out
 
 
 def run_workload(name, steps, warmup, with_stages=True):

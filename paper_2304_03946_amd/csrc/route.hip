@@ -11,6 +11,9 @@
 // unit.  Kernel 1 writes hist[unit][e].  Kernel 2: every block re-derives, for its own four
 // units, the number of earlier assignments per expert (prefix over units), the replica
 // shares and bucket offsets, then places its assignments.
+// Up to 4096 assignments the whole router is one workgroup of sixteen waves instead
+// (route_fused_kernel): the same steps with the histograms kept in LDS and every wave's
+// assignments held in registers, one launch instead of two.
 #include "common.h"
 
 namespace flexmoe {
@@ -19,7 +22,7 @@ constexpr int kRouteThreads = 256;
 constexpr int kRouteWaves = kRouteThreads / kWave;
 
 int route_units(int A, int* unit_len) {
-  int len = 512;
+  int len = A <= 65536 ? 256 : 512;     // short units: the placement rounds of a unit run one after another
   if ((A + len - 1) / len > 1024) len = (int)align_up((size_t)(A + 1023) / 1024, 64);
   *unit_len = len;
   int u = (A + len - 1) / len;
@@ -29,6 +32,55 @@ int route_units(int A, int* unit_len) {
 size_t route_ws_bytes(int A, int E) {
   int len;
   return align_up((size_t)route_units(A, &len) * E * sizeof(int32_t), 256);
+}
+
+
+// Even split of expert e's `tot` assignments over its replicas (Section 3.2): floor share q, the
+// first m = tot mod n_e replicas in list order take one more.  Fills the per-vExpert share and
+// the rank (within the expert) at which each vExpert's chunk starts.
+__device__ __forceinline__ void split_expert(int e, int tot, const uint16_t* roff, const uint16_t* rids, int32_t* eq,
+                                             int32_t* em, int32_t* vcount, int32_t* vstart,
+                                             int32_t* __restrict__ vexpert_owner, bool write_owner) {
+  const int o = roff[e], n = roff[e + 1] - o;
+  const int q = tot / n, m = tot - q * n;
+  eq[e] = q;
+  em[e] = m;
+  for (int r = 0; r < n; ++r) {
+    const int v = rids[o + r];
+    vcount[v] = q + (r < m ? 1 : 0);
+    vstart[v] = r * q + min(r, m);
+    if (write_owner) vexpert_owner[v] = e;
+  }
+}
+
+// Places the 64 assignments base_a .. base_a+63 of one wave (lane's expert id e, -1 = none).
+// Stable rank = assignments of the same expert before this wave's unit (wbase_w[e], advanced as
+// the rounds go by) + same-expert lanes below this one (ballot match over the 9-bit key).
+__device__ __forceinline__ void place_round(int a, int e, int lane, int32_t* wbase_w, const int32_t* eq,
+                                            const int32_t* em, const uint16_t* roff, const uint16_t* rids,
+                                            const int32_t* voff, const int32_t* vstart, int32_t* __restrict__ dest,
+                                            int32_t* __restrict__ src) {
+  const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  const unsigned key = (e < 0) ? 0x100u : (unsigned)e;   // 9 bits
+  unsigned long long peers = ~0ull;
+#pragma unroll
+  for (int b = 0; b < 9; ++b) {
+    const bool bit = (key >> b) & 1u;
+    const unsigned long long bal = __ballot(bit);
+    peers &= bit ? bal : ~bal;
+  }
+  if (e >= 0) {
+    const int before = __popcll(peers & lt);
+    const int rank = wbase_w[e] + before;
+    if (before == 0) wbase_w[e] += __popcll(peers);   // the group's lowest lane advances the count
+    const int q = eq[e], m = em[e];
+    const int cut = m * (q + 1);
+    const int r = (rank < cut) ? rank / (q + 1) : m + (rank - cut) / q;
+    const int v = rids[roff[e] + r];
+    const int p = voff[v] + rank - vstart[v];
+    dest[a] = p;
+    src[p] = a;
+  }
 }
 
 __global__ __launch_bounds__(kRouteThreads) void route_hist_kernel(const int32_t* __restrict__ idx, int A, int E,
@@ -100,17 +152,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_assign_kernel(
       wbase[ww][e] = run;
       if (u0 + ww < units) run += hist[(size_t)(u0 + ww) * E + e];
     }
-    // even split over the n_e replicas: floor share q, the first m replicas take one more
-    const int o = roff[e], n = roff[e + 1] - o;
-    const int q = tot / n, m = tot - q * n;
-    eq[e] = q;
-    em[e] = m;
-    for (int r = 0; r < n; ++r) {
-      const int v = rids[o + r];
-      vcount[v] = q + (r < m ? 1 : 0);
-      vstart[v] = r * q + min(r, m);
-      if (blockIdx.x == 0) vexpert_owner[v] = e;
-    }
+    split_expert(e, tot, roff, rids, eq, em, vcount, vstart, vexpert_owner, blockIdx.x == 0);
     if (blockIdx.x == 0) expert_count[e] = tot;
   }
   __syncthreads();
@@ -146,40 +188,118 @@ __global__ __launch_bounds__(kRouteThreads) void route_assign_kernel(
   if (u >= units) return;
   const int lo = u * unit_len;
   const int hi = min(lo + unit_len, A);
-  const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  for (int base_a = lo; base_a < hi; base_a += kWave) {
+  // the expert id of the next round is fetched while the current round is placed
+  auto fetch = [&](int base_a) {
     const int a = base_a + lane;
     int e = -1;
     if (a < hi) {
       e = idx[a];
       if ((unsigned)e >= (unsigned)E) e = -1;
     }
-    const unsigned key = (e < 0) ? 0x100u : (unsigned)e;   // 9 bits
-    unsigned long long peers = ~0ull;
+    return e;
+  };
+  int e_next = fetch(lo);
+  for (int base_a = lo; base_a < hi; base_a += kWave) {
+    const int e = e_next;
+    e_next = fetch(base_a + kWave);
+    place_round(base_a + lane, e, lane, wbase[w], eq, em, roff, rids, voff, vstart, dest, src);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The whole router in one workgroup (A <= kFusedMaxA): wave w owns the assignments
+// [w*unit_len, (w+1)*unit_len), at most 4 per lane, loaded once into registers.
+// ---------------------------------------------------------------------------------------------
+constexpr int kFusedThreads = 1024;
+constexpr int kFusedWaves = kFusedThreads / kWave;
+constexpr int kFusedRounds = 4;
+constexpr int kFusedMaxA = kFusedWaves * kWave * kFusedRounds;
+
+__global__ __launch_bounds__(kFusedThreads) void route_fused_kernel(
+    const int32_t* __restrict__ idx, int A, int E, int V, PlacementArg tab, int32_t* __restrict__ expert_count,
+    int32_t* __restrict__ vexpert_count, int32_t* __restrict__ vexpert_off, int32_t* __restrict__ vexpert_owner,
+    int32_t* __restrict__ dest, int32_t* __restrict__ src) {
+  __shared__ int32_t wbase[kFusedWaves][FLEXMOE_MAX_EXPERTS];       // histograms, then prefixes over waves
+  __shared__ int32_t eq[FLEXMOE_MAX_EXPERTS], em[FLEXMOE_MAX_EXPERTS];
+  __shared__ uint16_t roff[FLEXMOE_MAX_EXPERTS + 1], rids[FLEXMOE_MAX_VEXPERTS];
+  __shared__ int32_t vcount[FLEXMOE_MAX_VEXPERTS], vstart[FLEXMOE_MAX_VEXPERTS], voff[FLEXMOE_MAX_VEXPERTS + 1];
+  __shared__ int32_t wave_tot[FLEXMOE_MAX_VEXPERTS / kWave];
+
+  const int tid = threadIdx.x;
+  const int w = tid / kWave, lane = tid % kWave;
+  const int unit_len = ((A + kFusedWaves - 1) / kFusedWaves + kWave - 1) / kWave * kWave;
+  const int rounds = unit_len / kWave;                               // <= kFusedRounds (host check)
+  const int lo = w * unit_len, hi = min(lo + unit_len, A);
+
+  int ev[kFusedRounds];
 #pragma unroll
-    for (int b = 0; b < 9; ++b) {
-      const bool bit = (key >> b) & 1u;
-      const unsigned long long bal = __ballot(bit);
-      peers &= bit ? bal : ~bal;
+  for (int r = 0; r < kFusedRounds; ++r) {
+    const int a = lo + r * kWave + lane;
+    ev[r] = -1;
+    if (r < rounds && a < hi) ev[r] = idx[a];
+  }
+  for (int i = tid; i <= E; i += kFusedThreads) roff[i] = tab.rep_off[i];
+  for (int i = tid; i < V; i += kFusedThreads) rids[i] = tab.rep_ids[i];
+  for (int i = tid; i < kFusedWaves * FLEXMOE_MAX_EXPERTS; i += kFusedThreads) (&wbase[0][0])[i] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < kFusedRounds; ++r) {
+    if ((unsigned)ev[r] >= (unsigned)E) ev[r] = -1;
+    if (r < rounds && ev[r] >= 0) atomicAdd(&wbase[w][ev[r]], 1);
+  }
+  __syncthreads();
+  if (tid < E) {
+    const int e = tid;
+    int run = 0;
+    for (int ww = 0; ww < kFusedWaves; ++ww) {
+      const int c = wbase[ww][e];
+      wbase[ww][e] = run;
+      run += c;
     }
-    if (e >= 0) {
-      const int before = __popcll(peers & lt);
-      const int rank = wbase[w][e] + before;
-      if (before == 0) wbase[w][e] += __popcll(peers);   // the group's lowest lane advances the count
-      const int q = eq[e], m = em[e];
-      const int cut = m * (q + 1);
-      const int r = (rank < cut) ? rank / (q + 1) : m + (rank - cut) / q;
-      const int v = rids[roff[e] + r];
-      const int p = voff[v] + rank - vstart[v];
-      dest[a] = p;
-      src[p] = a;
+    split_expert(e, run, roff, rids, eq, em, vcount, vstart, vexpert_owner, true);
+    expert_count[e] = run;
+  }
+  __syncthreads();
+  // exclusive prefix sum of vcount in ascending vExpert id: one entry per thread, wave scans + wave totals
+  {
+    const int c = (tid < V) ? vcount[tid] : 0;
+    int incl = c;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const int up = __shfl_up(incl, o);
+      if (lane >= o) incl += up;
+    }
+    if (tid < FLEXMOE_MAX_VEXPERTS && lane == kWave - 1) wave_tot[w] = incl;
+    __syncthreads();
+    if (tid < FLEXMOE_MAX_VEXPERTS) {
+      int before = 0;
+      for (int ww = 0; ww < w; ++ww) before += wave_tot[ww];
+      if (tid < V) {
+        voff[tid] = before + incl - c;
+        vexpert_count[tid] = c;
+        vexpert_off[tid] = before + incl - c;
+      }
+      if (tid == V - 1) {
+        voff[V] = before + incl;             // == A for valid input
+        vexpert_off[V] = before + incl;
+      }
     }
   }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < kFusedRounds; ++r)
+    if (r < rounds && lo + r * kWave < hi)
+      place_round(lo + r * kWave + lane, ev[r], lane, wbase[w], eq, em, roff, rids, voff, vstart, dest, src);
 }
 
 hipError_t launch_route(const int32_t* idx, int A, int E, int V, const PlacementArg& tab, int32_t* expert_count,
                         int32_t* vexpert_count, int32_t* vexpert_off, int32_t* vexpert_owner, int32_t* dest,
                         int32_t* src, void* ws, hipStream_t s) {
+  if (A <= kFusedMaxA) {
+    hipLaunchKernelGGL(route_fused_kernel, dim3(1), dim3(kFusedThreads), 0, s, idx, A, E, V, tab, expert_count,
+                       vexpert_count, vexpert_off, vexpert_owner, dest, src);
+    return hipGetLastError();
+  }
   int unit_len;
   const int units = route_units(A, &unit_len);
   const int blocks = (units + kRouteWaves - 1) / kRouteWaves;
