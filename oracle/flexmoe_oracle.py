@@ -28,7 +28,8 @@ Pins (tests/test_oracle_*.py): brute-force top-k and softmax against library
 routines, closed-form replica shares, numpy bincount/stable argsort for the
 identity placement, identity experts, independence of the placement table,
 a dense all-experts evaluation, finite differences and torch.autograd (CPU,
-fp64) for the gradients.  No function here is "parity unpinned".
+fp64) for the gradients (expert path, gate path and biases).  No function here is
+"parity unpinned".
 """
 from __future__ import annotations
 
@@ -314,6 +315,66 @@ def expert_ffn_bwd(dyp, xp, hpre, w1, w2, vexpert_off, vexpert_owner, E: int, ac
 
 
 # ---------------------------------------------------------------------------
+# the rest of a trainable layer: gradient through the gate (Eq. 3-4), bias gradients (Eq. 2)
+# ---------------------------------------------------------------------------
+def gate_value_grad(dy, yp, dest, k: int) -> np.ndarray:
+    """Eq. 4 is linear in the gate values: dL/dg[t,j] = <dY_t, Yp[dest[t*k+j]]>, where
+    Yp holds the experts' outputs (bias b2 included) in bucket order.  Returns [N,k]."""
+    dy, yp = _f64(dy), _f64(yp)
+    dest = np.asarray(dest)
+    N = dest.shape[0] // k
+    dg = np.zeros((N, k), dtype=np.float64)
+    for t in range(N):
+        for j in range(k):
+            dg[t, j] = float(np.dot(dy[t], yp[int(dest[t * k + j])]))
+    return dg
+
+
+def topk_softmax_bwd(topk_w, dg) -> np.ndarray:
+    """Gradient w.r.t. the k kept logits of Eq. 3 (the discarded logits get none: their gate
+    value is identically zero).  Softmax Jacobian: dl_j = g_j * (dg_j - sum_i g_i dg_i)."""
+    g, dg = _f64(topk_w), _f64(dg)
+    inner = (g * dg).sum(axis=1, keepdims=True)
+    return g * (dg - inner)
+
+
+def gate_bwd(x, wg, topk_idx, topk_w, dy, yp, dest):
+    """Backward of the gate path for an upstream dY.  The logits are l = x.W_g, so with dl
+    scattered to the selected experts' columns: dW_g = X^T.dl and dX_gate = dl.W_g^T.
+    Returns (dl [N,k], dwg [d,E], dx_gate [N,d]); dx_gate adds to the expert-path dX."""
+    x, wg = _f64(x), _f64(wg)
+    idx = np.asarray(topk_idx)
+    N, k = idx.shape
+    dl = topk_softmax_bwd(topk_w, gate_value_grad(dy, yp, dest, k))
+    dwg = np.zeros_like(wg)
+    dxg = np.zeros_like(x)
+    for t in range(N):
+        for j in range(k):
+            e = int(idx[t, j])
+            dwg[:, e] += dl[t, j] * x[t]
+            dxg[t] += dl[t, j] * wg[:, e]
+    return dl, dwg, dxg
+
+
+def expert_bias_grads(dyp, hpre, w2, vexpert_off, vexpert_owner, E: int, act: int):
+    """db2_e = sum of the rows of dYp in e's buckets; db1_e = sum of the rows of
+    dHpre = (dYp.W2_e^T) * act'(Hpre) there (b1 enters Hpre, b2 enters Yp, both with unit
+    coefficient).  Returns (db1 [E,f], db2 [E,d])."""
+    dyp, hpre = _f64(dyp), _f64(hpre)
+    db1 = np.zeros((E, hpre.shape[1]), dtype=np.float64)
+    db2 = np.zeros((E, dyp.shape[1]), dtype=np.float64)
+    for v in range(len(vexpert_owner)):
+        lo, hi = int(vexpert_off[v]), int(vexpert_off[v + 1])
+        if hi == lo:
+            continue
+        e = int(vexpert_owner[v])
+        dhpre = (dyp[lo:hi] @ _f64(w2[e]).T) * act_grad(hpre[lo:hi], act)
+        db1[e] += dhpre.sum(axis=0)
+        db2[e] += dyp[lo:hi].sum(axis=0)
+    return db1, db2
+
+
+# ---------------------------------------------------------------------------
 # the method end to end, step by step
 # ---------------------------------------------------------------------------
 def staged_forward(x, wg, w1, b1, w2, b2, k: int, act: int, rep_off, rep_ids, topk=None):
@@ -331,17 +392,23 @@ def staged_forward(x, wg, w1, b1, w2, b2, k: int, act: int, rep_off, rep_ids, to
     return dict(topk_idx=idx, topk_w=w, route=r, xp=xp, hpre=hpre, yp=yp, y=y)
 
 
-def staged_backward(fwd: dict, dy, w1, w2, k: int, act: int):
+def staged_backward(fwd: dict, dy, w1, w2, k: int, act: int, x=None, wg=None):
     """Backward of the expert path for an upstream gradient dY (gate weights held
     constant): dYp = permute(dY, scale = gate weights); FFN backward per bucket;
-    dX = combine(dXp, weights = 1)."""
+    dX = combine(dXp, weights = 1).  With x and W_g given, also the gate path and the bias
+    gradients: dl, dwg, dx_gate (dx_total = dx + dx_gate), db1, db2."""
     r = fwd["route"]
     E = r["expert_count"].shape[0]
     dyp = permute(dy, r["src"], k, row_scale=_f64(fwd["topk_w"]).reshape(-1))
     dxp, dw1, dw2 = expert_ffn_bwd(dyp, fwd["xp"], fwd["hpre"], w1, w2,
                                    r["vexpert_off"], r["vexpert_owner"], E, act)
     dx = combine(dxp, r["dest"], None, k)
-    return dict(dyp=dyp, dxp=dxp, dw1=dw1, dw2=dw2, dx=dx)
+    out = dict(dyp=dyp, dxp=dxp, dw1=dw1, dw2=dw2, dx=dx)
+    if x is not None:
+        dl, dwg, dxg = gate_bwd(x, wg, fwd["topk_idx"], fwd["topk_w"], dy, fwd["yp"], r["dest"])
+        db1, db2 = expert_bias_grads(dyp, fwd["hpre"], w2, r["vexpert_off"], r["vexpert_owner"], E, act)
+        out.update(dl=dl, dwg=dwg, dx_gate=dxg, dx_total=dx + dxg, db1=db1, db2=db2)
+    return out
 
 
 # ---------------------------------------------------------------------------

@@ -230,3 +230,85 @@ def test_gradient_columns_match_full_gradient():
         c1, r2 = O.expert_grad_columns(x, dy, idx, w, e, w1[e], w2[e], cols, O.ACT_GELU_ERF)
         np.testing.assert_allclose(c1, dw1[e][:, cols], rtol=1e-12, atol=1e-13)
         np.testing.assert_allclose(r2, dw2[e][cols, :], rtol=1e-12, atol=1e-13)
+
+
+# ------------------------------------------------------------------ gate path and biases
+def _staged_full(x, wg, w1, b1, w2, b2, k, act, dy, rep=None):
+    E = w1.shape[0]
+    rep_off, rep_ids = rep if rep is not None else W.identity_placement(E)
+    fwd = O.staged_forward(x, wg, w1, b1, w2, b2, k, act, rep_off, rep_ids)
+    return fwd, O.staged_backward(fwd, dy, w1, w2, k, act, x=x, wg=wg)
+
+
+@pytest.mark.parametrize("act", [O.ACT_RELU, O.ACT_GELU_ERF, O.ACT_GELU_TANH])
+@pytest.mark.parametrize("k", [1, 2, 3])
+def test_full_layer_gradients_match_autograd(act, k):
+    """Everything trainable at once: autograd through topk -> softmax -> dense experts with the
+    gate left attached gives dX (both paths), dW_g, dW1, dW2, db1, db2."""
+    x, wg, w1, b1, w2, b2 = _small_problem(60 + k, N=31, E=5, k=k)
+    dy = np.random.default_rng(3).standard_normal(x.shape)
+    rng = np.random.default_rng(4)
+    rep = _random_table(rng, 5, 8)
+    _, g = _staged_full(x, wg, w1, b1, w2, b2, k, act, dy, rep)
+    t = {n: torch.from_numpy(a).requires_grad_(True) for n, a in dict(x=x, wg=wg, w1=w1, b1=b1, w2=w2, b2=b2).items()}
+    logits = t["x"] @ t["wg"]
+    tv, ti = torch.topk(logits, k, dim=1)
+    gate = torch.zeros_like(logits).scatter(1, ti, torch.softmax(tv, dim=1))
+    y = torch.zeros_like(t["x"])
+    for e in range(5):
+        y = y + gate[:, e:e + 1] * (_torch_act(t["x"] @ t["w1"][e] + t["b1"][e], act) @ t["w2"][e] + t["b2"][e])
+    (y * torch.from_numpy(dy)).sum().backward()
+    for name, got in (("x", g["dx_total"]), ("wg", g["dwg"]), ("w1", g["dw1"]), ("w2", g["dw2"]),
+                      ("b1", g["db1"]), ("b2", g["db2"])):
+        np.testing.assert_allclose(got, t[name].grad.numpy(), rtol=1e-9, atol=1e-11, err_msg=name)
+    if k == 1:        # a single kept logit has gate value 1 whatever the logit: no gradient through the gate
+        assert np.abs(g["dwg"]).max() == 0.0 and np.abs(g["dx_gate"]).max() == 0.0
+
+
+def test_gate_weight_gradient_finite_differences():
+    """Central differences in W_g with the selection left to the gate itself (steps far smaller
+    than any logit margin of this problem, so the kept set does not change)."""
+    x, wg, w1, b1, w2, b2 = _small_problem(71, N=11, d=5, f=7, E=4, k=2)
+    dy = np.random.default_rng(5).standard_normal(x.shape)
+    act = O.ACT_GELU_ERF
+    assert O.topk_margin(O.gate_logits(x, wg), 2).min() > 1e-3
+    _, g = _staged_full(x, wg, w1, b1, w2, b2, 2, act, dy)
+    L = lambda wg_: float((dy * O.moe_layer_forward(x, wg_, w1, b1, w2, b2, 2, act)).sum())
+    h = 1e-6
+    for i in range(wg.shape[0]):
+        for e in range(wg.shape[1]):
+            up, dn = wg.copy(), wg.copy()
+            up[i, e] += h
+            dn[i, e] -= h
+            fd = (L(up) - L(dn)) / (2 * h)
+            assert abs(fd - g["dwg"][i, e]) <= 1e-6 * max(1.0, abs(g["dwg"][i, e])), (i, e)
+
+
+def test_softmax_jacobian_properties():
+    """The kept gate values sum to one, so their logit gradients sum to zero per token; a
+    gradient that is the same for all kept experts moves nothing; two experts: closed form."""
+    rng = np.random.default_rng(6)
+    g = rng.random((50, 3))
+    g /= g.sum(axis=1, keepdims=True)
+    dg = rng.standard_normal((50, 3))
+    dl = O.topk_softmax_bwd(g, dg)
+    np.testing.assert_allclose(dl.sum(axis=1), 0.0, atol=1e-15)
+    np.testing.assert_allclose(O.topk_softmax_bwd(g, np.ones_like(dg) * 2.5), 0.0, atol=1e-15)
+    g2, dg2 = g[:, :2] / g[:, :2].sum(axis=1, keepdims=True), dg[:, :2]
+    want0 = g2[:, 0] * g2[:, 1] * (dg2[:, 0] - dg2[:, 1])        # d sigmoid(l0 - l1) chain rule
+    np.testing.assert_allclose(O.topk_softmax_bwd(g2, dg2)[:, 0], want0, rtol=1e-12, atol=1e-15)
+
+
+def test_bias_gradients_are_bucket_column_sums_for_linear_experts():
+    """Hand case: W2 = 0 makes dHpre vanish (db1 = 0) and db2_e the gate-weighted sum of dY over
+    the tokens routed to e, whatever the placement."""
+    x, wg, w1, b1, w2, b2 = _small_problem(81, N=23, E=4, k=2)
+    dy = np.random.default_rng(7).standard_normal(x.shape)
+    fwd, g = _staged_full(x, wg, w1, b1, np.zeros_like(w2), b2, 2, O.ACT_GELU_ERF, dy,
+                          _random_table(np.random.default_rng(8), 4, 7))
+    assert np.abs(g["db1"]).max() == 0.0
+    want = np.zeros_like(b2)
+    for t in range(x.shape[0]):
+        for j in range(2):
+            want[fwd["topk_idx"][t, j]] += fwd["topk_w"][t, j] * dy[t]
+    np.testing.assert_allclose(g["db2"], want, rtol=1e-12, atol=1e-14)
