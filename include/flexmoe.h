@@ -137,6 +137,38 @@ int flexmoe_expert_ffn_bwd(const void* dyp, const void* xp, const void* hpre,
 int flexmoe_combine(const void* yp, const int32_t* dest, const float* topk_w,
                     int N, int k, int d, int dtype, void* y, void* stream);
 
+/*
+ * Backward of the gate path (Eq. 3-4; the logits are x . W_g, the top-k kept, softmax over the
+ * kept ones) for an upstream gradient dy of the layer output.  Completes a trainable layer
+ * together with flexmoe_expert_ffn_bwd, which treats the gate values as constants.
+ *   dg[t,j] = <dy[t,:], yp[dest[t*k+j],:]>        yp: the experts' outputs in bucket order (forward)
+ *   dl[t,j] = topk_w[t,j] * (dg[t,j] - sum_i topk_w[t,i] * dg[t,i])      -> dl [N,k] float
+ *   dx[t,:] += sum_j dl[t,j] * wg[:, topk_idx[t,j]]     dx [N,d] dtype, IN/OUT: holds the expert-path
+ *                                                       gradient on entry (flexmoe_combine of dxp)
+ *   dwg[:,e] = sum over the assignments a routed to e of dl[a] * x[a div k,:]   -> dwg [d,E] dtype,
+ *              overwritten; summed over xp (= flexmoe_permute of x) bucket by bucket in a fixed order
+ *   wg [d,E], dy [N,d], yp [A,d], xp [A,d] dtype; topk_idx/topk_w [N,k]; dest/src [A];
+ *   vexpert_off [V+1], vexpert_owner [V] as written by flexmoe_route.
+ * With k = 1 the single kept gate value is 1 whatever the logit: dl and dwg are zero, dx unchanged.
+ */
+int flexmoe_gate_bwd(const void* wg, const int32_t* topk_idx, const float* topk_w, const void* dy,
+                     const void* yp, const void* xp, const int32_t* dest, const int32_t* src,
+                     const int32_t* vexpert_off, const int32_t* vexpert_owner,
+                     int N, int d, int E, int k, int V, int dtype,
+                     float* dl, void* dx, void* dwg, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Bias gradients of Eq. 2: db1_e = sum of the rows of dHpre in e's buckets, db2_e = the same for
+ * dyp (the gate-scaled, permuted upstream gradient that flexmoe_expert_ffn_bwd consumed).
+ *   db1 [E,f], db2 [E,d] dtype, overwritten (zeros for experts without tokens); either may be NULL.
+ * `ws` must be the workspace of the preceding flexmoe_expert_ffn_bwd call of the same sizes,
+ * untouched since: dHpre is read from it, and the part behind dHpre is overwritten.
+ * Fixed summation order: reproducible bit for bit.
+ */
+int flexmoe_expert_bias_grads(const void* dyp, const int32_t* vexpert_off, const int32_t* vexpert_owner,
+                              int A, int d, int f, int E, int V, int dtype,
+                              void* db1, void* db2, void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

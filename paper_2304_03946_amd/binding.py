@@ -21,7 +21,8 @@ RELU, GELU_ERF, GELU_TANH = 0, 1, 2
 OK, INVALID_ARG, BAD_PLACEMENT, WORKSPACE_TOO_SMALL, UNSUPPORTED, DEVICE_ERROR = range(6)
 
 EXPORTS = ["flexmoe_status_str", "flexmoe_workspace_bytes", "flexmoe_gate_topk", "flexmoe_route",
-           "flexmoe_permute", "flexmoe_expert_ffn_fwd", "flexmoe_expert_ffn_bwd", "flexmoe_combine"]
+           "flexmoe_permute", "flexmoe_expert_ffn_fwd", "flexmoe_expert_ffn_bwd", "flexmoe_combine",
+           "flexmoe_gate_bwd", "flexmoe_expert_bias_grads"]
 
 _lib = None
 
@@ -59,6 +60,10 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.flexmoe_expert_ffn_fwd.argtypes = [c_vp] * 7 + [c_int] * 7 + [c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.flexmoe_expert_ffn_bwd.restype = c_int
     lib.flexmoe_expert_ffn_bwd.argtypes = [c_vp] * 7 + [c_int] * 7 + [c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    lib.flexmoe_gate_bwd.restype = c_int
+    lib.flexmoe_gate_bwd.argtypes = [c_vp] * 10 + [c_int] * 6 + [c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    lib.flexmoe_expert_bias_grads.restype = c_int
+    lib.flexmoe_expert_bias_grads.argtypes = [c_vp] * 3 + [c_int] * 6 + [c_vp, c_vp, c_vp, c_sz, c_vp]
     if path == LIB_PATH:
         _lib = lib
     return lib
@@ -156,3 +161,24 @@ def flexmoe_expert_ffn_bwd(dyp, xp, hpre, w1, w2, vexpert_off, vexpert_owner, ac
                                                _ptr(vexpert_owner), A, d, f, E, V, act, dtype_code(xp), _ptr(dxp),
                                                _ptr(dw1), _ptr(dw2), _ptr(ws), ws.numel() * ws.element_size(), _stream())
     _check(st, "flexmoe_expert_ffn_bwd")
+
+
+def flexmoe_gate_bwd(wg, topk_idx, topk_w, dy, yp, xp, dest, src, vexpert_off, vexpert_owner, dl, dx, dwg, ws):
+    N, d = dy.shape
+    E = wg.shape[1]
+    k = topk_idx.shape[1]
+    V = vexpert_owner.shape[0]
+    st = load_library().flexmoe_gate_bwd(_ptr(wg), _ptr(topk_idx), _ptr(topk_w), _ptr(dy), _ptr(yp), _ptr(xp),
+                                         _ptr(dest), _ptr(src), _ptr(vexpert_off), _ptr(vexpert_owner), N, d, E, k, V,
+                                         dtype_code(dy), _ptr(dl), _ptr(dx), _ptr(dwg), _ptr(ws),
+                                         ws.numel() * ws.element_size(), _stream())
+    _check(st, "flexmoe_gate_bwd")
+
+
+def flexmoe_expert_bias_grads(dyp, vexpert_off, vexpert_owner, f, E, db1, db2, ws):
+    A, d = dyp.shape
+    V = vexpert_owner.shape[0]
+    st = load_library().flexmoe_expert_bias_grads(_ptr(dyp), _ptr(vexpert_off), _ptr(vexpert_owner), A, d, f, E, V,
+                                                  dtype_code(dyp), _ptr(db1), _ptr(db2), _ptr(ws),
+                                                  ws.numel() * ws.element_size(), _stream())
+    _check(st, "flexmoe_expert_bias_grads")

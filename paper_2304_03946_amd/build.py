@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libflexmoe.so")
-SOURCES = ["api.hip", "gate.hip", "route.hip", "permute_combine.hip", "ffn_f32.hip", "ffn_bf16.hip"]
+SOURCES = ["api.hip", "gate.hip", "route.hip", "permute_combine.hip", "ffn_f32.hip", "ffn_bf16.hip", "gate_bwd.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",

@@ -42,8 +42,12 @@ size_t flexmoe_workspace_bytes(int N, int d, int f, int E, int k, int V, int dty
   size_t need = gate_ws_bytes(d, E, dtype);
   const size_t r = route_ws_bytes(A, E);
   const size_t g = ffn_ws_bytes(A, f, dtype);
+  const size_t gb = gate_bwd_ws_bytes(A, d, E, V, dtype);
+  const size_t bg = bias_grads_ws_bytes(A, d, f, V, dtype);
   if (r > need) need = r;
   if (g > need) need = g;
+  if (gb > need) need = gb;
+  if (bg > need) need = bg;
   return need < 256 ? 256 : need;
 }
 
@@ -148,6 +152,34 @@ int flexmoe_expert_ffn_bwd(const void* dyp, const void* xp, const void* hpre, co
   const hipStream_t s = (hipStream_t)stream;
   return dev_status(dtype == FLEXMOE_BF16 ? launch_ffn_bwd_bf16(a, dyp, xp, hpre, w1, w2, dxp, dw1, dw2, ws, s)
                                           : launch_ffn_bwd_f32(a, dyp, xp, hpre, w1, w2, dxp, dw1, dw2, ws, s));
+}
+
+int flexmoe_gate_bwd(const void* wg, const int32_t* topk_idx, const float* topk_w, const void* dy, const void* yp,
+                     const void* xp, const int32_t* dest, const int32_t* src, const int32_t* vexpert_off,
+                     const int32_t* vexpert_owner, int N, int d, int E, int k, int V, int dtype, float* dl, void* dx,
+                     void* dwg, void* ws, size_t ws_bytes, void* stream) {
+  if (!dtype_ok(dtype)) return FLEXMOE_UNSUPPORTED;
+  const int st = dims_status(N, d, 8, E, k, V);
+  if (st != FLEXMOE_OK) return st;
+  if (!wg || !dwg || !vexpert_off || !vexpert_owner || !ws || !aligned16(wg) || !aligned16(dwg) || !aligned16(ws))
+    return FLEXMOE_INVALID_ARG;
+  if (N > 0 && (!topk_idx || !topk_w || !dy || !yp || !xp || !dest || !src || !dl || !dx || !aligned16(dy) ||
+                !aligned16(yp) || !aligned16(xp) || !aligned16(dx)))
+    return FLEXMOE_INVALID_ARG;
+  if (ws_bytes < gate_bwd_ws_bytes(N * k, d, E, V, dtype)) return FLEXMOE_WORKSPACE_TOO_SMALL;
+  return dev_status(launch_gate_bwd(wg, topk_idx, topk_w, dy, yp, xp, dest, src, vexpert_off, vexpert_owner, N, d, E,
+                                    k, V, dtype, dl, dx, dwg, ws, (hipStream_t)stream));
+}
+
+int flexmoe_expert_bias_grads(const void* dyp, const int32_t* vexpert_off, const int32_t* vexpert_owner, int A, int d,
+                              int f, int E, int V, int dtype, void* db1, void* db2, void* ws, size_t ws_bytes,
+                              void* stream) {
+  const int st = ffn_common(A, d, f, E, V, FLEXMOE_RELU, dtype, vexpert_off, vexpert_owner, ws, ws_bytes);
+  if (st != FLEXMOE_OK) return st;
+  if (!aligned16(db1) || !aligned16(db2) || (A > 0 && (!dyp || !aligned16(dyp)))) return FLEXMOE_INVALID_ARG;
+  if (ws_bytes < bias_grads_ws_bytes(A, d, f, V, dtype)) return FLEXMOE_WORKSPACE_TOO_SMALL;
+  return dev_status(launch_bias_grads(dyp, vexpert_off, vexpert_owner, A, d, f, E, V, dtype, db1, db2, ws,
+                                      (hipStream_t)stream));
 }
 
 }  // extern "C"

@@ -37,6 +37,30 @@ template <> struct Elem<bf16_t> {
   static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 };
 
+// Sixteen bytes of a row as floats (4 x fp32 or 8 x bf16) and back.
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int n = 4;
+  static __device__ __forceinline__ void unpack(const uint4& u, float* v) {
+    v[0] = __uint_as_float(u.x); v[1] = __uint_as_float(u.y); v[2] = __uint_as_float(u.z); v[3] = __uint_as_float(u.w);
+  }
+  static __device__ __forceinline__ uint4 pack(const float* v) {
+    return make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
+  }
+};
+template <> struct Vec16<bf16_t> {
+  static constexpr int n = 8;
+  static __device__ __forceinline__ void unpack(const uint4& u, float* v) {
+    v[0] = __uint_as_float(u.x << 16); v[1] = __uint_as_float(u.x & 0xffff0000u);
+    v[2] = __uint_as_float(u.y << 16); v[3] = __uint_as_float(u.y & 0xffff0000u);
+    v[4] = __uint_as_float(u.z << 16); v[5] = __uint_as_float(u.z & 0xffff0000u);
+    v[6] = __uint_as_float(u.w << 16); v[7] = __uint_as_float(u.w & 0xffff0000u);
+  }
+  static __device__ __forceinline__ uint4 pack(const float* v) {
+    return make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+  }
+};
+
 // Activations of the expert FFN (Eq. 2 uses ReLU; GELU for the BERT/GPT/Swin-shaped layers).
 // Accurate forms (libm erff/tanhf), used by the fp32 path.
 __device__ __forceinline__ float act_apply(float z, int act) {
@@ -135,6 +159,15 @@ hipError_t launch_ffn_fwd_bf16(const FfnArgs& a, const void* xp, const void* w1,
 hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp, const void* hpre,
                                const void* w1, const void* w2, void* dxp, void* dw1, void* dw2,
                                void* ws, hipStream_t s);
+// gate-path backward and bias gradients (gate_bwd.hip)
+size_t gate_bwd_ws_bytes(int A, int d, int E, int V, int dtype);
+hipError_t launch_gate_bwd(const void* wg, const int32_t* idx, const float* w, const void* dy,
+                           const void* yp, const void* xp, const int32_t* dest, const int32_t* src,
+                           const int32_t* voff, const int32_t* owner, int N, int d, int E, int k, int V, int dtype,
+                           float* dl, void* dx, void* dwg, void* ws, hipStream_t s);
+size_t bias_grads_ws_bytes(int A, int d, int f, int V, int dtype);
+hipError_t launch_bias_grads(const void* dyp, const int32_t* voff, const int32_t* owner, int A, int d, int f, int E,
+                             int V, int dtype, void* db1, void* db2, void* ws, hipStream_t s);
 hipError_t launch_ffn_fwd_f32(const FfnArgs& a, const void* xp, const void* w1, const void* b1,
                               const void* w2, const void* b2, void* hpre, void* yp, void* ws, hipStream_t s);
 hipError_t launch_ffn_bwd_f32(const FfnArgs& a, const void* dyp, const void* xp, const void* hpre,

@@ -10,29 +10,6 @@ namespace flexmoe {
 constexpr int kRowThreads = 256;
 constexpr int kRowWaves = kRowThreads / kWave;
 
-template <typename T> struct Vec16;
-template <> struct Vec16<float> {
-  static constexpr int n = 4;
-  static __device__ __forceinline__ void unpack(const uint4& u, float* v) {
-    v[0] = __uint_as_float(u.x); v[1] = __uint_as_float(u.y); v[2] = __uint_as_float(u.z); v[3] = __uint_as_float(u.w);
-  }
-  static __device__ __forceinline__ uint4 pack(const float* v) {
-    return make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
-  }
-};
-template <> struct Vec16<bf16_t> {
-  static constexpr int n = 8;
-  static __device__ __forceinline__ void unpack(const uint4& u, float* v) {
-    v[0] = __uint_as_float(u.x << 16); v[1] = __uint_as_float(u.x & 0xffff0000u);
-    v[2] = __uint_as_float(u.y << 16); v[3] = __uint_as_float(u.y & 0xffff0000u);
-    v[4] = __uint_as_float(u.z << 16); v[5] = __uint_as_float(u.z & 0xffff0000u);
-    v[6] = __uint_as_float(u.w << 16); v[7] = __uint_as_float(u.w & 0xffff0000u);
-  }
-  static __device__ __forceinline__ uint4 pack(const float* v) {
-    return make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
-  }
-};
-
 // xp[p,:] = x[src[p]/k,:] * scale[src[p]]
 template <typename T, bool SCALE>
 __global__ __launch_bounds__(kRowThreads) void permute_kernel(const T* __restrict__ x, const int32_t* __restrict__ src,

@@ -91,3 +91,22 @@ class MoELayer:
                                  self.act, self.dxp, self.dw1, self.dw2, self.ws)
         B.flexmoe_combine(self.dxp, self.dest, None, self.k, self.dx)
         return self.dx, self.dw1, self.dw2
+
+    def backward_full(self, dy, wg, w1, w2):
+        """Backward of everything trainable: the expert path as in `backward`, plus the bias
+        gradients and the gate path (dW_g, and the gate's share of dX added to self.dx)."""
+        dev, tdt = self.dx.device, self.dx.dtype
+        if not hasattr(self, "dwg"):
+            self.db1 = torch.empty((self.E, self.f), dtype=tdt, device=dev)
+            self.db2 = torch.empty((self.E, self.d), dtype=tdt, device=dev)
+            self.dl = torch.empty((self.N, self.k), dtype=torch.float32, device=dev)
+            self.dwg = torch.empty((self.d, self.E), dtype=tdt, device=dev)
+        B.flexmoe_permute(dy, self.src, self.topk_w, self.k, self.dyp)
+        B.flexmoe_expert_ffn_bwd(self.dyp, self.xp, self.hpre, w1, w2, self.vexpert_off, self.vexpert_owner,
+                                 self.act, self.dxp, self.dw1, self.dw2, self.ws)
+        B.flexmoe_expert_bias_grads(self.dyp, self.vexpert_off, self.vexpert_owner, self.f, self.E, self.db1,
+                                    self.db2, self.ws)
+        B.flexmoe_combine(self.dxp, self.dest, None, self.k, self.dx)
+        B.flexmoe_gate_bwd(wg, self.topk_idx, self.topk_w, dy, self.yp, self.xp, self.dest, self.src,
+                           self.vexpert_off, self.vexpert_owner, self.dl, self.dx, self.dwg, self.ws)
+        return dict(dx=self.dx, dw1=self.dw1, dw2=self.dw2, db1=self.db1, db2=self.db2, dwg=self.dwg, dl=self.dl)

@@ -218,6 +218,94 @@ def test_other_activations(api, act):
     run_stagewise(api, cfg, inp, *W.placement_from_loads(W.prior_loads(cfg), cfg.V, 4))
 
 
+def run_full_backward(api, cfg, inp, rep_off, rep_ids, b1=None, b2=None):
+    """Gate path and bias gradients: each stage against the oracle fed with the GPU's own
+    upstream tensors, then every gradient of the layer against the staged oracle run on the
+    GPU's selection."""
+    binding, layer_mod = api
+    tol = TOL[cfg.dtype]
+    dev = upload(layer_mod, inp)
+    L = layer_mod.MoELayer.for_config(cfg)
+    L.forward(dev["x"], dev["wg"], dev["w1"], dev["w2"], rep_off, rep_ids, layer_mod.to_device(b1),
+              layer_mod.to_device(b2))
+    g = L.backward_full(dev["dy"], dev["wg"], dev["w1"], dev["w2"])
+    torch.cuda.synchronize()
+    k, E = cfg.k, cfg.E
+    xd, wgd, dyd = W.decode(inp.x), W.decode(inp.wg), W.decode(inp.dy)
+    b1d = None if b1 is None else W.decode(b1)
+    b2d = None if b2 is None else W.decode(b2)
+    idx_gpu, w_gpu = host(L.topk_idx), host(L.topk_w)
+    r = O.route(idx_gpu, E, rep_off, rep_ids)
+
+    # stage: dl from the GPU's yp and gate weights
+    dl_ref = O.topk_softmax_bwd(w_gpu, O.gate_value_grad(dyd, host(L.yp), r["dest"], k))
+    if k == 1:
+        assert not host(g["dl"]).any() and not host(g["dwg"]).any(), "a single kept logit carries no gradient"
+    else:
+        assert rel_err(host(g["dl"]), dl_ref) <= tol, "dl"
+    # stage: bias gradients from the GPU's dyp and hpre
+    db1_ref, db2_ref = O.expert_bias_grads(host(L.dyp), host(L.hpre), inp.w2, r["vexpert_off"], r["vexpert_owner"],
+                                           E, cfg.act)
+    assert rel_err(host(g["db1"]), db1_ref) <= tol, "db1"
+    assert rel_err(host(g["db2"]), db2_ref) <= tol, "db2"
+    # stage: dW_g from the GPU's dl
+    dwg_stage = np.zeros_like(wgd, dtype=np.float64)
+    dl_gpu = host(g["dl"]).astype(np.float64)
+    for j in range(k):
+        np.add.at(dwg_stage.T, idx_gpu[:, j], dl_gpu[:, j:j + 1] * xd)
+    if k > 1:
+        assert rel_err(host(g["dwg"]), dwg_stage) <= (tol if cfg.dtype == W.DT_F32 else 2.0 ** -8), "dwg stage"
+
+    # end to end on the GPU's selection with the exact gate weights
+    kept = np.take_along_axis(O.gate_logits(xd, wgd), idx_gpu.astype(np.int64), axis=1)
+    ex = np.exp(kept - kept.max(axis=1, keepdims=True))
+    w_sel = ex / ex.sum(axis=1, keepdims=True)
+    fwd = O.staged_forward(xd, wgd, inp.w1, b1d, inp.w2, b2d, k, cfg.act, rep_off, rep_ids, topk=(idx_gpu, w_sel))
+    ref = O.staged_backward(fwd, dyd, inp.w1, inp.w2, k, cfg.act, x=xd, wg=wgd)
+    assert rel_err(host(g["dx"]), ref["dx_total"]) <= tol, "dx (both paths)"
+    for name in ("dw1", "dw2", "db1", "db2"):
+        assert rel_err(host(g[name]), ref[name]) <= tol, name
+    if k > 1:
+        assert rel_err(host(g["dwg"]), ref["dwg"]) <= tol, "dwg"
+        assert np.abs(ref["dx_gate"]).max() > 1e-3 * np.abs(ref["dx"]).max(), "the case must exercise the gate path"
+    empty = np.nonzero(r["expert_count"] == 0)[0]
+    for e in empty:
+        assert not host(g["db1"][e]).any() and not host(g["db2"][e]).any() and not host(g["dwg"][:, e]).any()
+    return L, g
+
+
+def test_full_backward_fp32(api):
+    cfg = W.scaled(W.CONFIGS["tiny"], N=301, E=5, V=8, k=2, backward=True, max_rep=3)
+    inp = W.make_layer_inputs(cfg, seed=78)
+    rng = np.random.default_rng(0)
+    b1 = (rng.standard_normal((cfg.E, cfg.f)) * 0.05).astype(np.float32)
+    b2 = (rng.standard_normal((cfg.E, cfg.d)) * 0.05).astype(np.float32)
+    run_full_backward(api, cfg, inp, *W.placement_from_loads([5, 4, 3, 2, 1], cfg.V, 3, shuffle_seed=3), b1=b1, b2=b2)
+
+
+@pytest.mark.parametrize("name", ["gpt_small", "swin_small", "xl_small", "gpt_dma"])
+def test_full_backward_reduced_configs(api, name):
+    cfg = SMALL[name]
+    inp = W.make_layer_inputs(cfg)
+    rng = np.random.default_rng(2)
+    b1 = W.Bf16Tensor.from_f32((rng.standard_normal((cfg.E, cfg.f)) * 0.3).astype(np.float32))
+    b2 = W.Bf16Tensor.from_f32((rng.standard_normal((cfg.E, cfg.d)) * 0.3).astype(np.float32))
+    rep_off, rep_ids = W.placement_from_loads(W.prior_loads(cfg), cfg.V, cfg.max_rep, shuffle_seed=11)
+    run_full_backward(api, cfg, inp, rep_off, rep_ids, b1=b1, b2=b2)
+
+
+def test_full_backward_is_reproducible(api):
+    cfg = SMALL["gpt_small"]
+    inp = W.make_layer_inputs(cfg)
+    rep = W.placement_from_loads(W.prior_loads(cfg), cfg.V, cfg.max_rep, shuffle_seed=11)
+    runs = []
+    for _ in range(2):
+        _, g = run_full_backward(api, cfg, inp, *rep)
+        runs.append({n: host(t).copy() for n, t in g.items()})
+    for n in runs[0]:
+        assert np.array_equal(runs[0][n], runs[1][n]), n
+
+
 def _bf16_ulp(v):
     """Spacing of bf16 numbers at |v| (8 significand bits; subnormals below 2^-126)."""
     a = np.maximum(np.abs(np.asarray(v, dtype=np.float64)), 2.0 ** -126)
