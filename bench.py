@@ -177,12 +177,51 @@ def run_workload(name, steps, warmup, with_stages=True):
                 stages[st] = dict(ms=round(ms, 4), bound="hbm", achieved=round(ach, 1), unit="GB/s",
                                   frac=round(ach / HBM_PEAK_GBS, 4))
         out["stages"] = stages
+        if cfg.backward:
+            out["trainable_layer_extras"] = time_extras(r, steps)
         counts = r.L.expert_count.cpu().numpy()
         vc = r.L.vexpert_count.cpu().numpy()
         out["loads"] = dict(hottest_expert_share=round(float(counts.max()) / cfg.A, 4),
                             top10_share=round(float(sum(sorted(counts.tolist(), reverse=True)[:10])) / cfg.A, 4),
                             max_vexpert=int(vc.max()), mean_vexpert=round(float(vc.mean()), 1))
     return r, out
+
+
+def time_extras(r, steps):
+    """The gate-path backward and the bias gradients (what a trainable layer needs beyond the hot
+    path), timed on their own after a step has left its state in the layer's buffers; not part of
+    ms_per_step."""
+    import torch
+    from paper_2304_03946_amd import binding as B
+    L, cfg = r.L, r.cfg
+    s = 2 if cfg.dtype == r.W.DT_BF16 else 4
+    wg = r.wg_by_drift[0]
+    tdt = L.dx.dtype
+    db1 = torch.empty((cfg.E, cfg.f), dtype=tdt, device="cuda")
+    db2 = torch.empty((cfg.E, cfg.d), dtype=tdt, device="cuda")
+    dl = torch.empty((cfg.N, cfg.k), dtype=torch.float32, device="cuda")
+    dwg = torch.empty((cfg.d, cfg.E), dtype=tdt, device="cuda")
+    calls = {
+        "bias_grads": (lambda: B.flexmoe_expert_bias_grads(L.dyp, L.vexpert_off, L.vexpert_owner, cfg.f, cfg.E, db1,
+                                                           db2, L.ws),
+                       cfg.A * (cfg.f + cfg.d) * s),
+        "gate_bwd": (lambda: B.flexmoe_gate_bwd(wg, L.topk_idx, L.topk_w, r.dy, L.yp, L.xp, L.dest, L.src,
+                                                L.vexpert_off, L.vexpert_owner, dl, L.dx, dwg, L.ws),
+                     (3 * cfg.N + 2 * cfg.A) * cfg.d * s),
+    }
+    out = {}
+    for name, (fn, nbytes) in calls.items():
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        out[name] = dict(ms=round(ms, 4), bound="hbm", achieved=round(nbytes / (ms * 1e-3) / 1e9, 1), unit="GB/s",
+                         frac=round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
+    return out
 
 
 def cpu_baseline(name):
@@ -282,6 +321,8 @@ def main():
             r, o = run_workload(other, 20 if ob else 100, 3 if ob else 10)
             others[other] = dict(tokens_per_s=round(o["tokens_per_s"], 1), ms_per_step=round(o["ms_per_step"], 4),
                                  stages=o["stages"], loads=o["loads"])
+            if "trainable_layer_extras" in o:
+                others[other]["trainable_layer_extras"] = o["trainable_layer_extras"]
         line["all_workloads"] = others
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(name)

@@ -488,3 +488,19 @@ def expert_grad_columns(x, dy, idx, w, e: int, w1_e, w2_e, cols, act: int):
     do = w[tok, slot][:, None] * dy[tok]
     dh = (do @ W2r.T) * act_grad(h, act)
     return x[tok].T @ dh, act_fn(h, act).T @ do
+
+
+def expert_bias_grad_columns(x, dy, idx, w, e: int, w1_e, w2_e, cols, act: int):
+    """Entries `cols` of db1_e and the whole of db2_e from the definition (no biases in the
+    forward pass): db2_e is the gate-weighted sum of dY over the tokens that selected e, and
+    hidden unit j of db1_e needs only column j of W1_e and row j of W2_e (full-size samples)."""
+    x, dy = _f64(x), _f64(dy)
+    idx, w = np.asarray(idx), _f64(w)
+    cols = np.asarray(cols)
+    tok, slot = np.nonzero(idx == e)
+    if tok.size == 0:
+        return np.zeros(cols.size), np.zeros(x.shape[1])
+    h = x[tok] @ _f64(w1_e)[:, cols]
+    do = w[tok, slot][:, None] * dy[tok]
+    dh = (do @ _f64(w2_e)[cols, :].T) * act_grad(h, act)
+    return dh.sum(axis=0), do.sum(axis=0)

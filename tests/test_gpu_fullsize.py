@@ -119,3 +119,61 @@ def test_full_config_sampled(api, name):
         else:
             assert rel_err(g1, c1) <= tol, f"dw1 expert {e}"
             assert rel_err(g2, r2) <= tol, f"dw2 expert {e}"
+
+
+@pytest.mark.parametrize("name", ["gpt_m", "gpt_xl"])
+def test_full_config_gate_path_and_bias_gradients_sampled(api, name):
+    """flexmoe_gate_bwd and flexmoe_expert_bias_grads at the benchmark sizes: the logit gradients
+    and dX on sampled tokens, dW_g, db1 and db2 on sampled experts (db1 on sampled hidden units)."""
+    binding, layer_mod = api
+    cfg = W.CONFIGS[name]
+    tol = TOL[cfg.dtype]
+    k, E = cfg.k, cfg.E
+    print(f"[fullsize] {name}: generating inputs", flush=True)
+    inp = W.make_layer_inputs(cfg)
+    dev = upload(layer_mod, inp)
+    L = layer_mod.MoELayer.for_config(cfg)
+    L.gate(dev["x"], dev["wg"])
+    L.route(*W.config_placement(cfg))
+    torch.cuda.synchronize()
+    rep_off, rep_ids = W.placement_from_loads(host(L.expert_count), cfg.V, cfg.max_rep)
+    print(f"[fullsize] {name}: forward + full backward", flush=True)
+    L.forward(dev["x"], dev["wg"], dev["w1"], dev["w2"], rep_off, rep_ids)
+    g = L.backward_full(dev["dy"], dev["wg"], dev["w1"], dev["w2"])
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(cfg.cfg_id + 100)
+    idx_gpu, w_gpu = host(L.topk_idx), host(L.topk_w)
+    dest = host(L.dest)
+    xd, wgd, dyd = W.decode(inp.x), W.decode(inp.wg).astype(np.float64), W.decode(inp.dy)
+
+    print(f"[fullsize] {name}: logit gradients and dX on sampled tokens", flush=True)
+    st = np.unique(np.concatenate([[0, cfg.N - 1], rng.integers(0, cfg.N, size=384)]))
+    slots = (st[:, None] * k + np.arange(k)[None, :]).reshape(-1)
+    yp_rows = host(L.yp[torch.from_numpy(dest[slots]).cuda().long()]).astype(np.float64).reshape(len(st), k, cfg.d)
+    dg = np.einsum("td,tjd->tj", dyd[st].astype(np.float64), yp_rows)
+    dl_ref = O.topk_softmax_bwd(w_gpu[st], dg)
+    dl_gpu = host(g["dl"])
+    assert rel_err(dl_gpu[st], dl_ref) <= tol, "dl"
+    dx_exp, _, _ = O.moe_layer_backward(xd[st], None, inp.w1, None, inp.w2, k, cfg.act, dyd[st], topk=(idx_gpu[st], w_gpu[st]))
+    dx_gate = np.einsum("tj,tjd->td", dl_ref, wgd.T[idx_gpu[st]])
+    assert np.abs(dx_gate).max() > 1e-3 * np.abs(dx_exp).max()
+    assert rel_err(host(g["dx"][torch.from_numpy(st).cuda()]), dx_exp + dx_gate) <= tol, "dx (both paths)"
+
+    print(f"[fullsize] {name}: dW_g, db1, db2 on sampled experts", flush=True)
+    counts = host(L.expert_count)
+    order = np.argsort(-counts, kind="stable")
+    experts = sorted({int(order[0]), int(order[1]), int(order[E // 2]), int(order[-1])})
+    cols = np.sort(rng.choice(cfg.f, size=6, replace=False))
+    dwg_gpu, db1_gpu, db2_gpu = host(g["dwg"]), host(g["db1"]), host(g["db2"])
+    scale_wg = np.abs(dwg_gpu).max()
+    for e in experts:
+        tok, slot = np.nonzero(idx_gpu == e)
+        if tok.size == 0:
+            assert not dwg_gpu[:, e].any() and not db1_gpu[e].any() and not db2_gpu[e].any()
+            continue
+        # dW_g column from the GPU's own logit gradients (stage check), scale of the whole matrix
+        col_ref = (dl_gpu[tok, slot].astype(np.float64)[:, None] * xd[tok]).sum(axis=0)
+        assert np.abs(dwg_gpu[:, e] - col_ref).max() <= 2.0 ** -8 * scale_wg, f"dwg expert {e}"
+        c1, c2 = O.expert_bias_grad_columns(xd, dyd, idx_gpu, w_gpu, e, inp.w1[e], inp.w2[e], cols, cfg.act)
+        assert rel_err(db2_gpu[e], c2) <= tol, f"db2 expert {e}"
+        assert np.abs(db1_gpu[e][cols] - c1).max() <= tol * np.abs(db1_gpu[e]).max(), f"db1 expert {e}"

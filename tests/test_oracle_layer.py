@@ -312,3 +312,15 @@ def test_bias_gradients_are_bucket_column_sums_for_linear_experts():
         for j in range(2):
             want[fwd["topk_idx"][t, j]] += fwd["topk_w"][t, j] * dy[t]
     np.testing.assert_allclose(g["db2"], want, rtol=1e-12, atol=1e-14)
+
+
+def test_bias_gradient_columns_match_full_gradient():
+    x, wg, w1, b1, w2, b2 = _small_problem(91, N=33, E=4, k=2, bias=False)
+    dy = np.random.default_rng(9).standard_normal(x.shape)
+    _, g = _staged_full(x, wg, w1, None, w2, None, 2, O.ACT_GELU_ERF, dy)
+    idx, w, _ = O.gate_topk(x, wg, 2)
+    cols = np.array([1, 8, 17])
+    for e in range(4):
+        c1, c2 = O.expert_bias_grad_columns(x, dy, idx, w, e, w1[e], w2[e], cols, O.ACT_GELU_ERF)
+        np.testing.assert_allclose(c1, g["db1"][e][cols], rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(c2, g["db2"][e], rtol=1e-12, atol=1e-13)
