@@ -138,6 +138,21 @@ int flexmoe_combine(const void* yp, const int32_t* dest, const float* topk_w,
                     int N, int k, int d, int dtype, void* y, void* stream);
 
 /*
+ * flexmoe_permute followed by flexmoe_expert_ffn_fwd without materialising xp: bucket row p of the
+ * first product is read as row src[p] / k of x while the tile is loaded (Section 4's layout
+ * transformation folded into the expert computation).  Same results as the two calls, bit for bit.
+ *   x [N,d], src [A] (A = N*k) as written by flexmoe_route; everything else as in
+ *   flexmoe_expert_ffn_fwd.  For forward-only use: the backward pass reads xp.
+ * FLEXMOE_UNSUPPORTED unless dtype is bf16, d is a multiple of 128 and N*d < 2^32: callers then
+ * use the two separate calls.
+ */
+int flexmoe_expert_ffn_fwd_gather(const void* x, const int32_t* src, const int32_t* vexpert_off,
+                                  const int32_t* vexpert_owner, const void* w1, const void* b1,
+                                  const void* w2, const void* b2,
+                                  int N, int k, int d, int f, int E, int V, int act, int dtype,
+                                  void* hpre, void* yp, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Backward of the gate path (Eq. 3-4; the logits are x . W_g, the top-k kept, softmax over the
  * kept ones) for an upstream gradient dy of the layer output.  Completes a trainable layer
  * together with flexmoe_expert_ffn_bwd, which treats the gate values as constants.

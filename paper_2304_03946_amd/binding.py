@@ -22,7 +22,7 @@ OK, INVALID_ARG, BAD_PLACEMENT, WORKSPACE_TOO_SMALL, UNSUPPORTED, DEVICE_ERROR =
 
 EXPORTS = ["flexmoe_status_str", "flexmoe_workspace_bytes", "flexmoe_gate_topk", "flexmoe_route",
            "flexmoe_permute", "flexmoe_expert_ffn_fwd", "flexmoe_expert_ffn_bwd", "flexmoe_combine",
-           "flexmoe_gate_bwd", "flexmoe_expert_bias_grads"]
+           "flexmoe_gate_bwd", "flexmoe_expert_bias_grads", "flexmoe_expert_ffn_fwd_gather"]
 
 _lib = None
 
@@ -60,6 +60,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.flexmoe_expert_ffn_fwd.argtypes = [c_vp] * 7 + [c_int] * 7 + [c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.flexmoe_expert_ffn_bwd.restype = c_int
     lib.flexmoe_expert_ffn_bwd.argtypes = [c_vp] * 7 + [c_int] * 7 + [c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    lib.flexmoe_expert_ffn_fwd_gather.restype = c_int
+    lib.flexmoe_expert_ffn_fwd_gather.argtypes = [c_vp] * 8 + [c_int] * 8 + [c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.flexmoe_gate_bwd.restype = c_int
     lib.flexmoe_gate_bwd.argtypes = [c_vp] * 10 + [c_int] * 6 + [c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.flexmoe_expert_bias_grads.restype = c_int
@@ -182,3 +184,14 @@ def flexmoe_expert_bias_grads(dyp, vexpert_off, vexpert_owner, f, E, db1, db2, w
                                                   dtype_code(dyp), _ptr(db1), _ptr(db2), _ptr(ws),
                                                   ws.numel() * ws.element_size(), _stream())
     _check(st, "flexmoe_expert_bias_grads")
+
+
+def flexmoe_expert_ffn_fwd_gather(x, src, k, vexpert_off, vexpert_owner, w1, b1, w2, b2, act, hpre, yp, ws):
+    N, d = x.shape
+    E, _, f = w1.shape
+    V = vexpert_owner.shape[0]
+    st = load_library().flexmoe_expert_ffn_fwd_gather(_ptr(x), _ptr(src), _ptr(vexpert_off), _ptr(vexpert_owner),
+                                                      _ptr(w1), _ptr(b1), _ptr(w2), _ptr(b2), N, k, d, f, E, V, act,
+                                                      dtype_code(x), _ptr(hpre), _ptr(yp), _ptr(ws),
+                                                      ws.numel() * ws.element_size(), _stream())
+    _check(st, "flexmoe_expert_ffn_fwd_gather")

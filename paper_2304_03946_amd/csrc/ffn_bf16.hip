@@ -607,6 +607,19 @@ struct DmaSrc {
       off[q] = (uint32_t)(min(row, rows_valid - 1) * ld + c * 8);
     }
   }
+  // The same tile with its rows gathered: tile row r is row rows[r] / k of the matrix at b (the
+  // expert-wise layout transformation done on the fly: rows = the bucket's slice of `src`).
+  __device__ __forceinline__ void init_gather(const bf16_t* b, size_t ld, const int32_t* __restrict__ rows, int k,
+                                              int rows_valid) {
+    base = b;
+    const int w = threadIdx.x >> 6, i = threadIdx.x & 63;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int row = (w * 4 + q) * 16 + (i >> 2);
+      const int c = (i & 3) ^ ((row >> 2) & 3);
+      off[q] = (uint32_t)((size_t)(rows[min(row, rows_valid - 1)] / k) * ld + c * 8);
+    }
+  }
   // Fills the 16 KB LDS tile at `tile` with K columns k0..k0+31 of the operand's 256 rows.
   // The direct load is issued from inline assembly (M0 = LDS byte address of the wave's 1 KB
   // slice, lane i lands at M0 + 16*i): the compiler's wait-count insertion cannot tell which LDS
@@ -807,11 +820,13 @@ __device__ __forceinline__ void rows_dma_body(lds_byte_t* s0, lds_byte_t* s1, ld
                                               const RowTile& t, const bf16_t* __restrict__ in, const WSrc& w_src,
                                               const bf16_t* __restrict__ bias, int K, int NC,
                                               const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
-                                              bf16_t* __restrict__ out1, const lds_byte_t* lut) {
+                                              bf16_t* __restrict__ out1, const lds_byte_t* lut,
+                                              const int32_t* __restrict__ gsrc, int gk) {
   const int wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   DmaSrc a_src;
-  a_src.init(in + (size_t)t.row0 * K, K, t.rows_valid);
+  if (gsrc) a_src.init_gather(in, K, gsrc + t.row0, gk, t.rows_valid);
+  else a_src.init(in + (size_t)t.row0 * K, K, t.rows_valid);
   f32x16 acc[MB][NB];
   zero_acc(acc);
   RowsIssue<WSrc> issue{a_src, w_src, 0};
@@ -824,7 +839,8 @@ template <bool WT, int EPI, int ACT>
 __global__ __launch_bounds__(kGemmThreads) void rows_gemm_dma_bf16(
     const bf16_t* __restrict__ in, const bf16_t* __restrict__ w, const bf16_t* __restrict__ bias,
     const int32_t* __restrict__ voff, const int32_t* __restrict__ owner, int V, int K, int NC, int row_tiles_max,
-    int col_tiles, const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0, bf16_t* __restrict__ out1) {
+    int col_tiles, const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0, bf16_t* __restrict__ out1,
+    const int32_t* __restrict__ gsrc, int gk) {
   __shared__ __align__(1024) unsigned char stage0[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char stage1[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
@@ -857,11 +873,11 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_dma_bf16(
   if (WT) {
     DmaSrc w_src;
     w_src.init(w_e + (size_t)t.n0 * K, K, t.cols_valid);
-    rows_dma_body<true, DmaSrc, EPI, ACT>(s0, s1, s2, s3, t, in, w_src, bias, K, NC, hpre_in, out0, out1, lut);
+    rows_dma_body<true, DmaSrc, EPI, ACT>(s0, s1, s2, s3, t, in, w_src, bias, K, NC, hpre_in, out0, out1, lut, gsrc, gk);
   } else {
     DmaSrcT w_src;
     w_src.init(w_e + t.n0, NC, t.cols_valid);
-    rows_dma_body<false, DmaSrcT, EPI, ACT>(s0, s1, s2, s3, t, in, w_src, bias, K, NC, hpre_in, out0, out1, lut);
+    rows_dma_body<false, DmaSrcT, EPI, ACT>(s0, s1, s2, s3, t, in, w_src, bias, K, NC, hpre_in, out0, out1, lut, gsrc, gk);
   }
 }
 
@@ -1150,7 +1166,7 @@ static hipError_t ensure_act_lut(hipStream_t s) {
 
 template <bool WT, int EPI, int ACT>
 static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w, const void* bias, int K, int NC,
-                                const void* hpre_in, void* out0, void* out1, hipStream_t s) {
+                                const void* hpre_in, void* out0, void* out1, hipStream_t s, const int32_t* gsrc, int gk) {
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t err = allow_big_lds(rows_gemm_bf16<WT, EPI, ACT>);
@@ -1168,9 +1184,10 @@ static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w,
     }
     hipLaunchKernelGGL((rows_gemm_dma_bf16<WT, EPI, ACT>), dim3(grid), dim3(kGemmThreads), 0, s, (const bf16_t*)in,
                        (const bf16_t*)w, (const bf16_t*)bias, a.voff, a.owner, a.V, K, NC, row_tiles, col_tiles,
-                       (const bf16_t*)hpre_in, (bf16_t*)out0, (bf16_t*)out1);
+                       (const bf16_t*)hpre_in, (bf16_t*)out0, (bf16_t*)out1, gsrc, gk);
     return hipGetLastError();
   }
+  if (gsrc) return hipErrorInvalidValue;      // gathered rows only on the direct-to-LDS path (host check upstream)
   hipLaunchKernelGGL((rows_gemm_bf16<WT, EPI, ACT>), dim3(grid), dim3(kGemmThreads), kGemmLds, s, (const bf16_t*)in,
                      (const bf16_t*)w, (const bf16_t*)bias, a.voff, a.owner, a.V, K, NC, row_tiles, col_tiles,
                      (const bf16_t*)hpre_in, (bf16_t*)out0, (bf16_t*)out1);
@@ -1179,12 +1196,17 @@ static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w,
 
 template <bool WT, int EPI>
 static hipError_t launch_rows(const FfnArgs& a, const void* in, const void* w, const void* bias, int K, int NC,
-                              const void* hpre_in, void* out0, void* out1, hipStream_t s) {
-  if (EPI == EPI_PLAIN) return launch_rows_t<WT, EPI, FLEXMOE_RELU>(a, in, w, bias, K, NC, hpre_in, out0, out1, s);
+                              const void* hpre_in, void* out0, void* out1, hipStream_t s,
+                              const int32_t* gsrc = nullptr, int gk = 1) {
+  if (EPI == EPI_PLAIN)
+    return launch_rows_t<WT, EPI, FLEXMOE_RELU>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk);
   switch (a.act) {
-    case FLEXMOE_RELU: return launch_rows_t<WT, EPI, FLEXMOE_RELU>(a, in, w, bias, K, NC, hpre_in, out0, out1, s);
-    case FLEXMOE_GELU_ERF: return launch_rows_t<WT, EPI, FLEXMOE_GELU_ERF>(a, in, w, bias, K, NC, hpre_in, out0, out1, s);
-    default: return launch_rows_t<WT, EPI, FLEXMOE_GELU_TANH>(a, in, w, bias, K, NC, hpre_in, out0, out1, s);
+    case FLEXMOE_RELU:
+      return launch_rows_t<WT, EPI, FLEXMOE_RELU>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk);
+    case FLEXMOE_GELU_ERF:
+      return launch_rows_t<WT, EPI, FLEXMOE_GELU_ERF>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk);
+    default:
+      return launch_rows_t<WT, EPI, FLEXMOE_GELU_TANH>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk);
   }
 }
 
@@ -1213,6 +1235,18 @@ hipError_t launch_ffn_fwd_bf16(const FfnArgs& a, const void* xp, const void* w1,
   if (a.A == 0) return hipSuccess;
   void* h = ws;
   hipError_t err = launch_rows<false, EPI_FWD1>(a, xp, w1, b1, a.d, a.f, nullptr, hpre, h, s);
+  if (err != hipSuccess) return err;
+  return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, yp, nullptr, s);
+}
+
+// Forward with the expert-wise layout transformation folded into GEMM1's row loads: bucket row p
+// is row src[p] / k of x.  d must be a multiple of 128 (direct-to-LDS path).
+hipError_t launch_ffn_fwd_gather_bf16(const FfnArgs& a, const void* x, const int32_t* src, int k, const void* w1,
+                                      const void* b1, const void* w2, const void* b2, void* hpre, void* yp, void* ws,
+                                      hipStream_t s) {
+  if (a.A == 0) return hipSuccess;
+  void* h = ws;
+  hipError_t err = launch_rows<false, EPI_FWD1>(a, x, w1, b1, a.d, a.f, nullptr, hpre, h, s, src, k);
   if (err != hipSuccess) return err;
   return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, yp, nullptr, s);
 }

@@ -85,6 +85,19 @@ class MoELayer:
         B.flexmoe_combine(self.yp, self.dest, self.topk_w, self.k, self.y)
         return self.y
 
+    def gather_supported(self) -> bool:
+        return self.dtype_code == B.BF16 and self.d % 128 == 0 and self.N * self.d < 2 ** 32
+
+    def forward_fused(self, x, wg, w1, w2, rep_off, rep_ids, b1=None, b2=None):
+        """Forward-only variant: the permutation is folded into the first expert GEMM (xp is not
+        written, so `backward` cannot follow)."""
+        self.gate(x, wg)
+        self.route(rep_off, rep_ids)
+        B.flexmoe_expert_ffn_fwd_gather(x, self.src, self.k, self.vexpert_off, self.vexpert_owner, w1, b1, w2, b2,
+                                        self.act, self.hpre, self.yp, self.ws)
+        B.flexmoe_combine(self.yp, self.dest, self.topk_w, self.k, self.y)
+        return self.y
+
     def backward(self, dy, w1, w2):
         B.flexmoe_permute(dy, self.src, self.topk_w, self.k, self.dyp)
         B.flexmoe_expert_ffn_bwd(self.dyp, self.xp, self.hpre, w1, w2, self.vexpert_off, self.vexpert_owner,

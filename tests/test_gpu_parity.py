@@ -306,6 +306,45 @@ def test_full_backward_is_reproducible(api):
         assert np.array_equal(runs[0][n], runs[1][n]), n
 
 
+@pytest.mark.parametrize("name,bias", [("gpt_dma", False), ("gpt_dma", True)])
+def test_gathered_forward_equals_permute_then_ffn(api, name, bias):
+    """flexmoe_expert_ffn_fwd_gather must reproduce flexmoe_permute + flexmoe_expert_ffn_fwd bit for
+    bit (same tiles, same arithmetic, only the row addresses differ)."""
+    binding, layer_mod = api
+    cfg = SMALL[name]
+    inp = W.make_layer_inputs(cfg)
+    dev = upload(layer_mod, inp)
+    rng = np.random.default_rng(4)
+    b1 = layer_mod.to_device(W.Bf16Tensor.from_f32((rng.standard_normal((cfg.E, cfg.f)) * 0.3).astype(np.float32))) if bias else None
+    b2 = layer_mod.to_device(W.Bf16Tensor.from_f32((rng.standard_normal((cfg.E, cfg.d)) * 0.3).astype(np.float32))) if bias else None
+    rep = W.placement_from_loads(W.prior_loads(cfg), cfg.V, cfg.max_rep, shuffle_seed=11)
+    L = layer_mod.MoELayer.for_config(cfg)
+    assert L.gather_supported()
+    L.forward(dev["x"], dev["wg"], dev["w1"], dev["w2"], *rep, b1, b2)
+    torch.cuda.synchronize()
+    want = {n: host(getattr(L, n)).copy() for n in ("hpre", "yp", "y")}
+    for t in (L.hpre, L.yp, L.y, L.xp):
+        t.zero_()
+    L.forward_fused(dev["x"], dev["wg"], dev["w1"], dev["w2"], *rep, b1, b2)
+    torch.cuda.synchronize()
+    for n in want:
+        assert np.array_equal(host(getattr(L, n)), want[n]), n
+    assert not host(L.xp).any(), "the fused path must not touch xp"
+
+
+def test_gathered_forward_refuses_what_it_cannot_do(api):
+    binding, layer_mod = api
+    cfg = SMALL["bert_small"]                       # d = 328: not a multiple of 128
+    inp = W.make_layer_inputs(cfg)
+    dev = upload(layer_mod, inp)
+    L = layer_mod.MoELayer.for_config(cfg)
+    assert not L.gather_supported()
+    rep = W.placement_from_loads(W.prior_loads(cfg), cfg.V, cfg.max_rep)
+    with pytest.raises(binding.FlexMoEError) as ei:
+        L.forward_fused(dev["x"], dev["wg"], dev["w1"], dev["w2"], *rep)
+    assert ei.value.status == binding.UNSUPPORTED
+
+
 def _bf16_ulp(v):
     """Spacing of bf16 numbers at |v| (8 significand bits; subnormals below 2^-126)."""
     a = np.maximum(np.abs(np.asarray(v, dtype=np.float64)), 2.0 ** -126)
