@@ -160,13 +160,27 @@ __global__ __launch_bounds__(kBwdThreads) void bucket_colsum_partial_kernel(
 #pragma unroll
   for (int q = 0; q < VN; ++q) acc[q] = 0.f;
   if (col < C) {
-    for (int r = wave; r < rows; r += kBwdWaves) {
-      const int p = row0 + r;
-      float u[VN];
-      Vec16<T>::unpack(*(const uint4*)(in + (size_t)p * C + col), u);
-      const float wt = WEIGHTED ? row_w[src[p]] : 1.f;
+    // eight rows in flight per wave; the sum itself stays in ascending row order
+    constexpr int U = 8;
+    for (int r0 = wave; r0 < rows; r0 += kBwdWaves * U) {
+      uint4 raw[U];
+      float wt[U];
 #pragma unroll
-      for (int q = 0; q < VN; ++q) acc[q] = fmaf(wt, u[q], acc[q]);
+      for (int i = 0; i < U; ++i) {
+        const int r = r0 + i * kBwdWaves;
+        const int p = row0 + min(r, rows - 1);
+        raw[i] = *(const uint4*)(in + (size_t)p * C + col);
+        wt[i] = r < rows ? (WEIGHTED ? row_w[src[p]] : 1.f) : 0.f;
+      }
+#pragma unroll
+      for (int i = 0; i < U; ++i) {
+        if (r0 + i * kBwdWaves < rows) {
+          float u[VN];
+          Vec16<T>::unpack(raw[i], u);
+#pragma unroll
+          for (int q = 0; q < VN; ++q) acc[q] = fmaf(wt[i], u[q], acc[q]);
+        }
+      }
     }
   }
 #pragma unroll
@@ -182,23 +196,82 @@ __global__ __launch_bounds__(kBwdThreads) void bucket_colsum_partial_kernel(
   }
 }
 
-// Stage 2: out[e, c] = sum of the partials of e's chunks, buckets in ascending vExpert id and
-// chunks in ascending row order inside a bucket.  TRANSPOSED: out is [C, E] (the gate weights' layout).
+// Stage 2: out[e, c] = sum of the partials of e's chunks.  One workgroup per (expert, 64 columns):
+// the expert's chunks, numbered through its buckets in ascending vExpert id and ascending row
+// order, are dealt round-robin to the four waves; each wave adds its chunks in that order (four
+// loads in flight), then the waves' sums are added in wave order.  A fixed order: reproducible.
+// TRANSPOSED: out is [C, E] (the gate weights' layout).
 template <typename T, bool TRANSPOSED>
 __global__ __launch_bounds__(kBwdThreads) void bucket_colsum_final_kernel(
     const float* __restrict__ partial, const int32_t* __restrict__ voff, const int32_t* __restrict__ owner, int V,
     int E, int C, T* __restrict__ out) {
   __shared__ int chunk_start[FLEXMOE_MAX_VEXPERTS + 1];
+  __shared__ int list[FLEXMOE_MAX_VEXPERTS];          // the expert's buckets, ascending
+  __shared__ int nlist;
+  __shared__ float red[kBwdWaves][kWave];
   chunk_starts(voff, V, chunk_start);
   const int e = blockIdx.y;
-  const int c = blockIdx.x * kBwdThreads + threadIdx.x;
-  if (c >= C) return;
-  float s = 0.f;
-  for (int v = 0; v < V; ++v) {
-    if (owner[v] != e) continue;
-    for (int ch = chunk_start[v]; ch < chunk_start[v + 1]; ++ch) s += partial[(size_t)ch * C + c];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  {
+    // ascending list of the expert's buckets: ballot compaction, two buckets per thread
+    constexpr int kSeg = FLEXMOE_MAX_VEXPERTS / kWave;             // 64-bucket segments
+    __shared__ int seg_count[kSeg];
+    const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    bool mine[kSeg / kBwdWaves];
+    int pos[kSeg / kBwdWaves];
+#pragma unroll
+    for (int h = 0; h < kSeg / kBwdWaves; ++h) {
+      const int v = (h * kBwdWaves + wave) * kWave + lane;
+      mine[h] = v < V && owner[v] == e;
+      const unsigned long long m = __ballot(mine[h]);
+      pos[h] = __popcll(m & lt);
+      if (lane == 0) seg_count[h * kBwdWaves + wave] = __popcll(m);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < kSeg / kBwdWaves; ++h) {
+      const int seg = h * kBwdWaves + wave;
+      int base = 0;
+      for (int q = 0; q < seg; ++q) base += seg_count[q];
+      if (mine[h]) list[base + pos[h]] = seg * kWave + lane;
+    }
+    if (threadIdx.x == 0) {
+      int n = 0;
+      for (int q = 0; q < kSeg; ++q) n += seg_count[q];
+      nlist = n;
+    }
+    __syncthreads();
   }
-  Elem<T>::store(out + (TRANSPOSED ? (size_t)c * E + e : (size_t)e * C + c), s);
+  const int c = blockIdx.x * kWave + lane;
+  float s = 0.f;
+  if (c < C) {
+    int ord = 0;                                       // running number of the expert's chunks
+    for (int i = 0; i < nlist; ++i) {
+      const int v = list[i];
+      const int first = chunk_start[v], cnt = chunk_start[v + 1] - first;
+      // this wave's chunks of the bucket: ordinals congruent to `wave` modulo 4
+      int j = (wave - ord % kBwdWaves + kBwdWaves) % kBwdWaves;
+      for (; j + 3 * kBwdWaves < cnt; j += 4 * kBwdWaves) {
+        const float p0 = partial[(size_t)(first + j) * C + c];
+        const float p1 = partial[(size_t)(first + j + kBwdWaves) * C + c];
+        const float p2 = partial[(size_t)(first + j + 2 * kBwdWaves) * C + c];
+        const float p3 = partial[(size_t)(first + j + 3 * kBwdWaves) * C + c];
+        s += p0;
+        s += p1;
+        s += p2;
+        s += p3;
+      }
+      for (; j < cnt; j += kBwdWaves) s += partial[(size_t)(first + j) * C + c];
+      ord += cnt;
+    }
+  }
+  red[wave][lane] = s;
+  __syncthreads();
+  if (wave == 0 && c < C) {
+    float t = red[0][lane];
+    for (int ww = 1; ww < kBwdWaves; ++ww) t += red[ww][lane];
+    Elem<T>::store(out + (TRANSPOSED ? (size_t)c * E + e : (size_t)e * C + c), t);
+  }
 }
 
 static int max_chunks(int A, int V) { return A / kChunkRows + V; }
@@ -212,7 +285,7 @@ static hipError_t bucket_colsum(const void* in, const float* row_w, const int32_
   const dim3 grid1(max_chunks(A, V), (C + cols_per_block - 1) / cols_per_block);
   hipLaunchKernelGGL((bucket_colsum_partial_kernel<T, WEIGHTED>), grid1, dim3(kBwdThreads), 0, s, (const T*)in, row_w,
                      src, voff, V, C, partial);
-  const dim3 grid2((C + kBwdThreads - 1) / kBwdThreads, E);
+  const dim3 grid2((C + kWave - 1) / kWave, E);
   hipLaunchKernelGGL((bucket_colsum_final_kernel<T, TRANSPOSED>), grid2, dim3(kBwdThreads), 0, s, partial, voff, owner,
                      V, E, C, (T*)out);
   return hipGetLastError();
