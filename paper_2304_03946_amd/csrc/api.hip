@@ -41,7 +41,7 @@ size_t flexmoe_workspace_bytes(int N, int d, int f, int E, int k, int V, int dty
   const int A = N * k;
   size_t need = gate_ws_bytes(d, E, dtype);
   const size_t r = route_ws_bytes(A, E);
-  const size_t g = ffn_ws_bytes(A, f, dtype);
+  const size_t g = ffn_ws_bytes(A, d, f, E, V, dtype);
   const size_t gb = gate_bwd_ws_bytes(A, d, E, V, dtype);
   const size_t bg = bias_grads_ws_bytes(A, d, f, V, dtype);
   if (r > need) need = r;
@@ -119,7 +119,7 @@ static int ffn_common(int A, int d, int f, int E, int V, int act, int dtype, con
       V > FLEXMOE_MAX_VEXPERTS)
     return FLEXMOE_INVALID_ARG;
   if (!voff || !owner || !ws || !aligned16(ws)) return FLEXMOE_INVALID_ARG;
-  if (ws_bytes < ffn_ws_bytes(A, f, dtype)) return FLEXMOE_WORKSPACE_TOO_SMALL;
+  if (ws_bytes < ffn_ws_bytes(A, d, f, E, V, dtype)) return FLEXMOE_WORKSPACE_TOO_SMALL;
   return FLEXMOE_OK;
 }
 

@@ -153,7 +153,7 @@ struct FfnArgs {
   const int32_t* voff;
   const int32_t* owner;
 };
-size_t ffn_ws_bytes(int A, int f, int dtype);
+size_t ffn_ws_bytes(int A, int d, int f, int E, int V, int dtype);
 hipError_t launch_ffn_fwd_bf16(const FfnArgs& a, const void* xp, const void* w1, const void* b1,
                                const void* w2, const void* b2, void* hpre, void* yp, void* ws, hipStream_t s);
 hipError_t launch_ffn_fwd_gather_bf16(const FfnArgs& a, const void* x, const int32_t* src, int k, const void* w1,

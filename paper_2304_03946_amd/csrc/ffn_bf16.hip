@@ -19,7 +19,7 @@
 //    straight into one of four LDS stages (no register staging, no LDS store instructions); an
 //    operand whose contraction index is strided in memory is copied as stored and transposed on
 //    the way out of LDS by ds_read_tr16_b64.  The kernels are bound by L2 -> LDS bandwidth.
-//  * register-staged (rows_gemm_bf16, wgrad_gemm_bf16; any K that is a multiple of 8): 64-wide K
+//  * register-staged (rows_gemm_bf16; any K that is a multiple of 8): 64-wide K
 //    tiles through registers into two LDS stages, strided operands transposed 8x8 in registers.
 //
 // LDS tiles are XOR-swizzled at 16-byte chunk granularity so that fragment reads and tile
@@ -27,6 +27,7 @@
 // The MFMA is issued as (weights-fragment, activations-fragment) so that a lane ends up with 4
 // consecutive output columns of one output row; the epilogue passes the accumulators through a
 // wave-private LDS patch so that global stores fill whole 128-byte lines.
+#include <algorithm>
 #include <mutex>
 
 #include "common.h"
@@ -42,9 +43,6 @@ constexpr size_t kGemmLds = 2 * 2 * kTileElems * sizeof(bf16_t);   // 2 stages x
 enum { EPI_FWD1 = 0, EPI_PLAIN = 1, EPI_DH = 2 };
 #ifndef FLEXMOE_DMA_CPOL
 #define FLEXMOE_DMA_CPOL ""      // cache-policy modifiers of the direct-to-LDS loads
-#endif
-#ifndef FLEXMOE_WGRAD_DMA
-#define FLEXMOE_WGRAD_DMA 1
 #endif
 
 union Frag8 {
@@ -881,128 +879,126 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_dma_bf16(
   }
 }
 
-// Shared prologue of the weight-gradient kernels: per-expert loads from the bucket sizes, the
-// expert whose load has rank `want_rank` (descending load, ties by ascending id: hot experts'
-// tiles are issued first), and the list of its non-empty buckets in ascending vExpert id.
-__device__ __forceinline__ int wgrad_pick_expert(const int32_t* __restrict__ voff, const int32_t* __restrict__ owner,
-                                                 int E, int V, int want_rank, int* s_cnt, int* s_own, int* s_load,
-                                                 int* s_e_p, int* s_nb_p, int* s_bstart, int* s_brows) {
+// Work list of the weight-gradient kernels.  Experts are taken by descending load (ties by
+// ascending id: the long contractions start first).  An expert's contraction runs over its
+// non-empty buckets in ascending vExpert id, in K tiles of 32 tokens; with seg_tiles > 0 it is cut
+// into segments of seg_tiles K tiles that different workgroups contract (a hot expert would
+// otherwise be one long serial K loop): an expert with more than one segment leaves fp32 partial
+// tiles in the workspace, `slot` numbering them, which wgrad_reduce_kernel adds up in segment
+// order.  The whole list is a function of the bucket sizes only, so every workgroup re-derives it.
+struct WgradJob {
+  int e;        // expert, -1: no job
+  int seg;      // segment of the expert's contraction
+  int nseg;     // segments of this expert
+  int slot;     // index of the expert's first partial tile set (meaningful when nseg > 1)
+};
+struct WgradShared {
+  int cnt[FLEXMOE_MAX_VEXPERTS], own[FLEXMOE_MAX_VEXPERTS];
+  int load[FLEXMOE_MAX_EXPERTS], tiles[FLEXMOE_MAX_EXPERTS];
+  int rank_e[FLEXMOE_MAX_EXPERTS], rank_s[FLEXMOE_MAX_EXPERTS];
+  int job[4];
+  int nb;
+  int bstart[FLEXMOE_MAX_VEXPERTS], brows[FLEXMOE_MAX_VEXPERTS];
+};
+
+// `want` counts segments in work-list order (rank-major).  Also fills sh.bstart/brows/nb with the
+// expert's buckets.
+// `table` (optional, [E] entries of {expert, segments, first slot, 0} by load rank) is written by the
+// caller that passes it, for wgrad_reduce_kernel.
+__device__ __forceinline__ WgradJob wgrad_plan(const int32_t* __restrict__ voff, const int32_t* __restrict__ owner,
+                                               int E, int V, int seg_tiles, int want, WgradShared& sh,
+                                               int4* __restrict__ table) {
   for (int v = threadIdx.x; v < V; v += kGemmThreads) {
-    s_cnt[v] = voff[v + 1] - voff[v];
-    s_own[v] = owner[v];
+    sh.cnt[v] = voff[v + 1] - voff[v];
+    sh.own[v] = owner[v];
   }
-  for (int e = threadIdx.x; e < E; e += kGemmThreads) s_load[e] = 0;
-  __syncthreads();
-  for (int v = threadIdx.x; v < V; v += kGemmThreads) atomicAdd(&s_load[s_own[v]], s_cnt[v]);
-  __syncthreads();
-  // the expert whose load has rank `want_rank` (descending load, ties by ascending id)
   for (int e = threadIdx.x; e < E; e += kGemmThreads) {
-    const int l = s_load[e];
+    sh.load[e] = 0;
+    sh.tiles[e] = 0;
+  }
+  if (threadIdx.x == 0) sh.job[0] = -1;
+  __syncthreads();
+  for (int v = threadIdx.x; v < V; v += kGemmThreads) {
+    atomicAdd(&sh.load[sh.own[v]], sh.cnt[v]);
+    atomicAdd(&sh.tiles[sh.own[v]], (sh.cnt[v] + DK - 1) / DK);
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < E; e += kGemmThreads) {
+    const int l = sh.load[e];
     int rank = 0;
     for (int o = 0; o < E; ++o) {
-      const int lo = s_load[o];
+      const int lo = sh.load[o];
       rank += (lo > l || (lo == l && o < e)) ? 1 : 0;
     }
-    if (rank == want_rank) *s_e_p = e;
+    sh.rank_e[rank] = e;
+    sh.rank_s[rank] = seg_tiles > 0 ? max(1, (sh.tiles[e] + seg_tiles - 1) / seg_tiles) : 1;
   }
   __syncthreads();
-  const int e = *s_e_p;
-  if (threadIdx.x < kWave) {                   // its non-empty buckets, ascending vExpert id
+  if (threadIdx.x < kWave) {
+    // prefix over the ranks of the segment counts (and of the segment counts of split experts)
+    const int lane = threadIdx.x;
+    constexpr int kPer = FLEXMOE_MAX_EXPERTS / kWave;
+    int sum = 0, sum_split = 0;
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+      const int r = lane * kPer + q;
+      const int n = r < E ? sh.rank_s[r] : 0;
+      sum += n;
+      sum_split += n > 1 ? n : 0;
+    }
+    int incl = sum, incl_split = sum_split;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const int up = __shfl_up(incl, o), up2 = __shfl_up(incl_split, o);
+      if (lane >= o) {
+        incl += up;
+        incl_split += up2;
+      }
+    }
+    int start = incl - sum, slot = incl_split - sum_split;
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+      const int r = lane * kPer + q;
+      const int n = r < E ? sh.rank_s[r] : 0;
+      const bool hit = want >= start && want < start + n;
+      if (hit) {
+        sh.job[0] = sh.rank_e[r];
+        sh.job[1] = want - start;
+        sh.job[2] = n;
+        sh.job[3] = slot;
+      }
+      if (table && r < E) table[r] = make_int4(sh.rank_e[r], n, slot, 0);
+      start += n;
+      slot += n > 1 ? n : 0;
+    }
+  }
+  __syncthreads();
+  WgradJob job{sh.job[0], sh.job[1], sh.job[2], sh.job[3]};
+  if (job.e < 0) return job;                    // uniform
+  if (threadIdx.x < kWave) {                   // the expert's non-empty buckets, ascending vExpert id
     const int lane = threadIdx.x;
     const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
     int nbw = 0;
     for (int vb = 0; vb < V; vb += kWave) {
       const int v = vb + lane;
-      const bool hit = v < V && s_own[v] == e && s_cnt[v] > 0;
+      const bool hit = v < V && sh.own[v] == job.e && sh.cnt[v] > 0;
       const unsigned long long mask = __ballot(hit);
       if (hit) {
         const int pos = nbw + __popcll(mask & lt);
-        s_bstart[pos] = voff[v];
-        s_brows[pos] = s_cnt[v];
+        sh.bstart[pos] = voff[v];
+        sh.brows[pos] = sh.cnt[v];
       }
       nbw += __popcll(mask);
     }
-    if (lane == 0) *s_nb_p = nbw;
+    if (lane == 0) sh.nb = nbw;
   }
   __syncthreads();
-  return e;
+  return job;
 }
 
 // =============================================================================================
-// wgrad_gemm: dW_e[m, n] = sum_{v owned by e, ascending v} sum_{p in bucket v} L[p, m] * R[p, n]
-// =============================================================================================
-__global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_bf16(const bf16_t* __restrict__ L,
-                                                                const bf16_t* __restrict__ R,
-                                                                const int32_t* __restrict__ voff,
-                                                                const int32_t* __restrict__ owner, int E, int V, int M,
-                                                                int NC, int m_tiles, int n_tiles,
-                                                                bf16_t* __restrict__ dw) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16_t* smem = (bf16_t*)smem_raw;
-  __shared__ int s_cnt[FLEXMOE_MAX_VEXPERTS], s_own[FLEXMOE_MAX_VEXPERTS];
-  __shared__ int s_load[FLEXMOE_MAX_EXPERTS];
-  __shared__ int s_e;
-  __shared__ int s_nb;
-  __shared__ int s_bstart[FLEXMOE_MAX_VEXPERTS], s_brows[FLEXMOE_MAX_VEXPERTS];
-
-  // tile grid: rows = (expert by descending load, m tile), cols = n tile
-  int grow, nt;
-  if (!patched_tile(blockIdx.x, E * m_tiles, n_tiles, &grow, &nt)) return;
-  const int want_rank = grow / m_tiles, mt = grow % m_tiles;
-
-  const int e = wgrad_pick_expert(voff, owner, E, V, want_rank, s_cnt, s_own, s_load, &s_e, &s_nb, s_bstart, s_brows);
-  const int nb = s_nb;
-
-  const int m0 = mt * BM, n0 = nt * BN;
-  const int mvalid = min(BM, M - m0), nvalid = min(BN, NC - n0);
-  const int wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  f32x16 acc[MB][NB];
-  zero_acc(acc);
-
-  if (nb > 0) {
-    int T = 0;
-    for (int b = 0; b < nb; ++b) T += (s_brows[b] + BK - 1) / BK;
-    KStridedSrc l_src, r_src;
-    l_src.init(M, mvalid);
-    r_src.init(NC, nvalid);
-    // next K tile of each operand: 64 tokens of bucket bi starting at koff
-    struct Cursor {
-      int bi, koff;
-    } ca{0, 0}, cb{0, 0};
-    auto advance = [&](Cursor& c) {
-      c.koff += BK;
-      if (c.koff >= s_brows[c.bi]) {
-        c.koff = 0;
-        c.bi = min(c.bi + 1, nb - 1);
-      }
-    };
-    auto load_a = [&](uint4 (&ra)[8]) {
-      l_src.load(ra, L + ((size_t)s_bstart[ca.bi] + ca.koff) * M + m0, s_brows[ca.bi] - ca.koff);
-      advance(ca);
-    };
-    auto load_b = [&](uint4 (&rb)[8]) {
-      r_src.load(rb, R + ((size_t)s_bstart[cb.bi] + cb.koff) * NC + n0, s_brows[cb.bi] - cb.koff);
-      advance(cb);
-    };
-    run_pipeline<true>(smem, acc, T, KStridedSrc::store, KStridedSrc::store, load_a, load_b, wm, wn, MB * 2);
-  }
-
-  float* patch = (float*)smem + wave * (32 * 64);
-  bf16_t* out = dw + (size_t)e * M * NC;
-  const int col_base = n0 + wn * (NB * 32);
-  epilogue_rounds<false>(
-      patch, acc, [](int, int) { return make_uint2(0, 0); },
-      [](int, int, float4 c, uint2) { return EpiOut{pack4(c.x, c.y, c.z, c.w), make_uint2(0, 0)}; },
-      [&](int row_w, int col_w, const EpiOut& o) {
-        const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
-        const int col = col_base + col_w;
-        if (lrow < mvalid && col < NC) *(uint2*)(out + (size_t)(m0 + lrow) * NC + col) = o.a;
-      });
-}
-
-// =============================================================================================
-// wgrad_gemm_dma: the same weight-gradient product on the direct-to-LDS pipeline.  Both operands
+// wgrad_gemm_dma: dW_e[m, n] = sum_{v owned by e, ascending v} sum_{p in bucket v} L[p, m] * R[p, n]
+// on the direct-to-LDS pipeline.  Both operands
 // are token-major ([tokens, M] and [tokens, NC]), i.e. contraction-strided: their 32-token K tiles
 // are copied to LDS as stored and transposed by the LDS reads.  Tokens past the end of a bucket
 // (the ragged last K tile of each vExpert, and the padding that rounds the tile count up to the
@@ -1076,23 +1072,23 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_dma_bf16(const bf16_t
                                                                     const int32_t* __restrict__ voff,
                                                                     const int32_t* __restrict__ owner, int E, int V,
                                                                     int M, int NC, int m_tiles, int n_tiles,
+                                                                    int seg_tiles, int seg_rows_max,
+                                                                    float* __restrict__ partial,
+                                                                    int4* __restrict__ table,
                                                                     bf16_t* __restrict__ dw) {
   __shared__ __align__(1024) unsigned char stage0[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char stage1[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char stage3[kDmaStageBytes];
-  __shared__ int s_cnt[FLEXMOE_MAX_VEXPERTS];
-  __shared__ int s_own[FLEXMOE_MAX_VEXPERTS];
-  __shared__ int s_load[FLEXMOE_MAX_EXPERTS];
-  __shared__ int s_e, s_nb;
-  __shared__ int s_bstart[FLEXMOE_MAX_VEXPERTS], s_brows[FLEXMOE_MAX_VEXPERTS];
+  __shared__ WgradShared sh;
 
-  // tile grid: rows = (expert by descending load, m tile), cols = n tile
+  // tile grid: rows = (work-list segment, m tile), cols = n tile
   int grow, nt;
-  if (!patched_tile(blockIdx.x, E * m_tiles, n_tiles, &grow, &nt)) return;
-  const int want_rank = grow / m_tiles, mt = grow % m_tiles;
-  const int e = wgrad_pick_expert(voff, owner, E, V, want_rank, s_cnt, s_own, s_load, &s_e, &s_nb, s_bstart, s_brows);
-  const int nb = s_nb;
+  if (!patched_tile(blockIdx.x, seg_rows_max * m_tiles, n_tiles, &grow, &nt)) return;
+  const int mt = grow % m_tiles;
+  const WgradJob job = wgrad_plan(voff, owner, E, V, seg_tiles, grow / m_tiles, sh, blockIdx.x == 0 ? table : nullptr);
+  if (job.e < 0) return;
+  const int nb = sh.nb;
 
   const int m0 = mt * BM, n0 = nt * BN;
   const int mvalid = min(BM, M - m0), nvalid = min(BN, NC - n0);
@@ -1103,35 +1099,104 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_dma_bf16(const bf16_t
   lds_byte_t* s0 = (lds_byte_t*)stage0;
 
   if (nb > 0) {
-    int T = 0;
-    for (int b = 0; b < nb; ++b) T += (s_brows[b] + DK - 1) / DK;
+    int Te = 0;
+    for (int b = 0; b < nb; ++b) Te += (sh.brows[b] + DK - 1) / DK;
+    // this job's K tiles [lo, hi) of the expert's sequence, and the bucket / offset where they start
+    const int lo = job.nseg > 1 ? job.seg * seg_tiles : 0;
+    const int hi = job.nseg > 1 ? min(Te, lo + seg_tiles) : Te;
+    int bi = 0, skip = lo;
+    while (bi < nb - 1 && skip >= (sh.brows[bi] + DK - 1) / DK) {
+      skip -= (sh.brows[bi] + DK - 1) / DK;
+      ++bi;
+    }
+    const int T = hi - lo;
     const int KT = (T + 3) & ~3;                 // padded with all-zero tiles
     DmaSrcTok l_src, r_src;
     l_src.init(M, mvalid);
     r_src.init(NC, nvalid);
-    WgradIssue issue{l_src, r_src, L, R, s_bstart, s_brows, M, NC, m0, n0, nb, T, 0, 0, 0, nullptr, nullptr, 0};
+    WgradIssue issue{l_src, r_src, L, R, sh.bstart, sh.brows, M, NC, m0, n0, nb, T, bi, skip * DK, 0, nullptr, nullptr, 0};
     dma_pipeline<true, true>(s0, (lds_byte_t*)stage1, (lds_byte_t*)stage2, (lds_byte_t*)stage3, acc, issue, KT, wm, wn);
   }
 
   float* patch = (float*)stage0 + wave * (32 * 64);
-  bf16_t* out = dw + (size_t)e * M * NC;
   const int col_base = n0 + wn * (NB * 32);
-  epilogue_rounds<false>(
-      patch, acc, [](int, int) { return make_uint2(0, 0); },
-      [](int, int, float4 c, uint2) { return EpiOut{pack4(c.x, c.y, c.z, c.w), make_uint2(0, 0)}; },
-      [&](int row_w, int col_w, const EpiOut& o) {
-        const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
-        const int col = col_base + col_w;
-        if (lrow < mvalid && col < NC) *(uint2*)(out + (size_t)(m0 + lrow) * NC + col) = o.a;
-      });
+  auto tile_row = [&](int row_w) { return (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31); };
+  if (job.nseg == 1) {
+    bf16_t* out = dw + (size_t)job.e * M * NC;
+    epilogue_rounds<false>(
+        patch, acc, [](int, int) { return make_uint2(0, 0); },
+        [](int, int, float4 c, uint2) { return EpiOut{pack4(c.x, c.y, c.z, c.w), make_uint2(0, 0)}; },
+        [&](int row_w, int col_w, const EpiOut& o) {
+          const int lrow = tile_row(row_w);
+          const int col = col_base + col_w;
+          if (lrow < mvalid && col < NC) *(uint2*)(out + (size_t)(m0 + lrow) * NC + col) = o.a;
+        });
+  } else {
+    // one of several segments: the fp32 tile goes to the workspace for wgrad_reduce_kernel
+    float* out = partial + (size_t)(job.slot + job.seg) * M * NC;
+    epilogue_rounds<false>(
+        patch, acc, [](int, int) { return make_uint2(0, 0); },
+        [](int, int, float4 c, uint2) {
+          return EpiOut{make_uint2(__float_as_uint(c.x), __float_as_uint(c.y)),
+                        make_uint2(__float_as_uint(c.z), __float_as_uint(c.w))};
+        },
+        [&](int row_w, int col_w, const EpiOut& o) {
+          const int lrow = tile_row(row_w);
+          const int col = col_base + col_w;
+          if (lrow < mvalid && col < NC)
+            *(uint4*)(out + (size_t)(m0 + lrow) * NC + col) = make_uint4(o.a.x, o.a.y, o.b.x, o.b.y);
+        });
+  }
+}
+
+// dW_e = sum of the expert's partial tiles in segment order, for the experts that were split.
+// Grid: (element blocks of the [M, NC] matrix, load rank); `table` as left by the GEMM kernel.
+__global__ __launch_bounds__(kGemmThreads) void wgrad_reduce_kernel(const int4* __restrict__ table, int M, int NC,
+                                                                    const float* __restrict__ partial,
+                                                                    bf16_t* __restrict__ dw) {
+  const int4 t = table[blockIdx.y];             // {expert, segments, first slot}
+  if (t.y <= 1) return;
+  const size_t n4 = (size_t)M * NC / 4;
+  const float4* p = (const float4*)(partial + (size_t)t.z * M * NC);
+  uint2* out = (uint2*)(dw + (size_t)t.x * M * NC);
+  for (size_t i = (size_t)blockIdx.x * kGemmThreads + threadIdx.x; i < n4; i += (size_t)gridDim.x * kGemmThreads) {
+    float4 s4 = p[i];
+    for (int sgm = 1; sgm < t.y; ++sgm) {
+      const float4 v = p[(size_t)sgm * n4 + i];
+      s4.x += v.x; s4.y += v.y; s4.z += v.z; s4.w += v.w;
+    }
+    out[i] = pack4(s4.x, s4.y, s4.z, s4.w);
+  }
 }
 
 // =============================================================================================
 // host side
 // =============================================================================================
-size_t ffn_ws_bytes(int A, int f, int dtype) {
+// Weight gradient: how many 32-token K tiles one workgroup contracts before the expert's sum is
+// cut into a further segment: a compute unit's even share of all (output tile, K tile) pairs
+// (shorter segments measured slower: more fp32 partial tiles), so that the hottest expert's contraction is no longer one serial K loop.  0 = no cutting:
+// when a segment would hold more than a quarter of all tokens (many output tiles per expert: the
+// grid is busy anyway, and the fp32 partial tiles would be large).
+constexpr int kComputeUnits = 256;
+static int wgrad_seg_tiles(int A, int d, int f) {
+  const long long out_tiles = (long long)((d + BM - 1) / BM) * ((f + BN - 1) / BN);
+  const long long k_tiles = A / DK;
+  long long seg = k_tiles * out_tiles / kComputeUnits;
+  if (seg < 32) seg = 32;
+  return 4 * seg <= k_tiles ? (int)seg : 0;
+}
+// Upper bounds over all load distributions: extra segments (beyond one per expert), and partial
+// tile sets (segments of experts that have more than one).
+static int wgrad_extra_segments(int A, int V, int seg_tiles) { return seg_tiles ? (A / DK + V) / seg_tiles : 0; }
+static int wgrad_partial_slots(int A, int V, int seg_tiles) { return seg_tiles ? 2 * ((A / DK + V) / seg_tiles) + 1 : 0; }
+static size_t wgrad_table_bytes() { return FLEXMOE_MAX_EXPERTS * sizeof(int4); }
+
+size_t ffn_ws_bytes(int A, int d, int f, int E, int V, int dtype) {
   const size_t s = dtype == FLEXMOE_BF16 ? 2 : 4;
-  return align_up((size_t)A * f * s, 256) * 2;      // dHpre (or H in forward) + H
+  size_t need = align_up((size_t)A * f * s, 256) * 2;      // dHpre (or H in forward) + H
+  if (dtype == FLEXMOE_BF16 && wgrad_seg_tiles(A, d, f))
+    need += wgrad_table_bytes() + (size_t)wgrad_partial_slots(A, V, wgrad_seg_tiles(A, d, f)) * d * f * sizeof(float);
+  return need;
 }
 
 template <typename Kern> static hipError_t allow_big_lds(Kern kern) {
@@ -1210,23 +1275,21 @@ static hipError_t launch_rows(const FfnArgs& a, const void* in, const void* w, c
   }
 }
 
-static hipError_t launch_wgrad(const FfnArgs& a, const void* L, const void* R, int M, int NC, void* dw, hipStream_t s) {
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t err = allow_big_lds(wgrad_gemm_bf16);
-    if (err != hipSuccess) return err;
-    attr_done = true;
-  }
+static hipError_t launch_wgrad(const FfnArgs& a, const void* L, const void* R, int M, int NC, void* dw, void* ws_tail,
+                               hipStream_t s) {
   const int m_tiles = (M + BM - 1) / BM, n_tiles = (NC + BN - 1) / BN;
-  if (FLEXMOE_WGRAD_DMA) {
-    hipLaunchKernelGGL(wgrad_gemm_dma_bf16, dim3(patched_grid(a.E * m_tiles, n_tiles)), dim3(kGemmThreads), 0, s,
-                       (const bf16_t*)L, (const bf16_t*)R, a.voff, a.owner, a.E, a.V, M, NC, m_tiles, n_tiles,
-                       (bf16_t*)dw);
-    return hipGetLastError();
+  const int seg_tiles = wgrad_seg_tiles(a.A, a.d, a.f);
+  int4* table = seg_tiles ? (int4*)ws_tail : nullptr;
+  float* partial = seg_tiles ? (float*)((char*)ws_tail + wgrad_table_bytes()) : nullptr;
+  const int seg_rows_max = a.E + wgrad_extra_segments(a.A, a.V, seg_tiles);
+  hipLaunchKernelGGL(wgrad_gemm_dma_bf16, dim3(patched_grid(seg_rows_max * m_tiles, n_tiles)), dim3(kGemmThreads), 0,
+                     s, (const bf16_t*)L, (const bf16_t*)R, a.voff, a.owner, a.E, a.V, M, NC, m_tiles, n_tiles,
+                     seg_tiles, seg_rows_max, partial, table, (bf16_t*)dw);
+  if (seg_tiles) {
+    const int blocks = (int)std::min<size_t>(((size_t)M * NC / 4 + kGemmThreads - 1) / kGemmThreads, 2048);
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(blocks, a.E), dim3(kGemmThreads), 0, s, (const int4*)table, M, NC,
+                       (const float*)partial, (bf16_t*)dw);
   }
-  hipLaunchKernelGGL(wgrad_gemm_bf16, dim3(patched_grid(a.E * m_tiles, n_tiles)), dim3(kGemmThreads), kGemmLds, s,
-                     (const bf16_t*)L, (const bf16_t*)R, a.voff, a.owner, a.E, a.V, M, NC, m_tiles, n_tiles,
-                     (bf16_t*)dw);
   return hipGetLastError();
 }
 
@@ -1264,9 +1327,10 @@ hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp
     err = launch_rows<true, EPI_PLAIN>(a, dhpre, w1, nullptr, a.f, a.d, nullptr, dxp, nullptr, s);
     if (err != hipSuccess) return err;
   }
-  err = launch_wgrad(a, h, dyp, a.f, a.d, dw2, s);
+  void* ws_tail = (char*)ws + 2 * align_up((size_t)a.A * a.f * sizeof(bf16_t), 256);
+  err = launch_wgrad(a, h, dyp, a.f, a.d, dw2, ws_tail, s);
   if (err != hipSuccess) return err;
-  return launch_wgrad(a, xp, dhpre, a.d, a.f, dw1, s);
+  return launch_wgrad(a, xp, dhpre, a.d, a.f, dw1, ws_tail, s);
 }
 
 }  // namespace flexmoe
