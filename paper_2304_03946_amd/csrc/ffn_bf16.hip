@@ -252,13 +252,16 @@ __device__ __forceinline__ uint32_t lut_offset(uint32_t zu) {
   const uint32_t m = (zu >> 16) & 0x7fffu;
   return (min(max(m, (uint32_t)kLutLo), (uint32_t)kLutHi) - kLutLo) << 3;
 }
+// max(z, 0) on the bit pattern: as a signed integer every negative float (and -0) is below zero
+// and every positive float keeps its order, so one integer max does it (no NaN canonicalisation).
+__device__ __forceinline__ float relu_bits(uint32_t zu) { return __int_as_float(max((int32_t)zu, 0)); }
 __device__ __forceinline__ float lut_act(const lds_byte_t* lut, uint32_t zu) {
   const float r = *(const __attribute__((address_space(3))) float*)(lut + lut_offset(zu));
-  return fmaxf(__uint_as_float(zu), 0.f) + r;
+  return relu_bits(zu) + r;
 }
 __device__ __forceinline__ void lut_act_both(const lds_byte_t* lut, uint32_t zu, float* a, float* da) {
   const f32x2_t rq = *(const __attribute__((address_space(3))) f32x2_t*)(lut + lut_offset(zu));
-  *a = fmaxf(__uint_as_float(zu), 0.f) + rq[0];
+  *a = relu_bits(zu) + rq[0];
   *da = (int32_t)zu < 0 ? -rq[1] : 1.f + rq[1];
 }
 template <int EPI, int ACT> constexpr bool epilogue_uses_lut() { return EPI != EPI_PLAIN && ACT != FLEXMOE_RELU; }
@@ -266,7 +269,7 @@ template <int EPI, int ACT> constexpr bool epilogue_uses_lut() { return EPI != E
 // ---- epilogue ---------------------------------------------------------------------------------
 // A lane's accumulators hold 4-column pieces of 32 different rows, which would make every global
 // store touch 32 cache lines.  Instead the wave's 128x128 fp32 block goes out in eight rounds of
-// 32 rows x 64 columns: accumulator registers -> wave-private 8 KB LDS patch (16-byte chunks,
+// 32 rows x 64 columns: accumulator registers -> one of two wave-private 8 KB LDS patches (16-byte chunks,
 // chunk index XORed with row & 15: conflict free both ways) -> read back so that 16 lanes cover
 // 64 consecutive columns of one row -> per-element epilogue in fp32 -> bf16 -> 8-byte stores that
 // fill whole 128-byte lines.  The K loop ends with a barrier, so the LDS tiles are free.
@@ -281,43 +284,56 @@ struct EpiOut {
   uint2 a, b;
 };
 template <bool FETCH, typename Fetch, typename Compute, typename Store>
-__device__ __forceinline__ void epilogue_rounds(float* patch, const f32x16 (&acc)[MB][NB], Fetch fetch, Compute compute,
-                                                Store store) {
+__device__ __forceinline__ void epilogue_rounds(float* patch0, float* patch1, const f32x16 (&acc)[MB][NB], Fetch fetch,
+                                                Compute compute, Store store) {
   const int lane = threadIdx.x & 63;
   const int r = lane & 31, h = lane >> 5;
   const int rsub = lane >> 4, c = lane & 15;
+  constexpr int kRounds = MB * (NB / 2);
   uint2 side[2][8];
   if (FETCH) {
 #pragma unroll
     for (int it = 0; it < 8; ++it) side[0][it] = fetch(it * 4 + rsub, c * 4);
   }
+  // Two patches per wave: round n+1's accumulators are written while round n is processed.  A
+  // wave's LDS instructions execute in issue order, so the reads that follow the writes need no
+  // wait, only a compiler barrier (the dependence runs across lanes, which the compiler cannot see).
+  auto write_round = [&](int i, int jh, float* patch) {
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int cc = jj * 8 + 2 * g + h;
+        const f32x16& a = acc[i][jh * 2 + jj];
+        *(float4*)(patch + r * 64 + ((cc ^ (r & 15)) << 2)) = make_float4(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]);
+      }
+  };
+  write_round(0, 0, patch0);
 #pragma unroll
   for (int i = 0; i < MB; ++i) {
 #pragma unroll
     for (int jh = 0; jh < NB / 2; ++jh) {
       const int round = i * (NB / 2) + jh;
-      if (FETCH && round + 1 < MB * (NB / 2)) {
+      float* patch = (round & 1) ? patch1 : patch0;
+      if (FETCH && round + 1 < kRounds) {
         const int ni = (round + 1) / (NB / 2), njh = (round + 1) % (NB / 2);
 #pragma unroll
         for (int it = 0; it < 8; ++it) side[(round + 1) & 1][it] = fetch(ni * 32 + it * 4 + rsub, njh * 64 + c * 4);
       }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-#pragma unroll
-      for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int cc = jj * 8 + 2 * g + h;
-          const f32x16& a = acc[i][jh * 2 + jj];
-          *(float4*)(patch + r * 64 + ((cc ^ (r & 15)) << 2)) = make_float4(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]);
-        }
-      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront", "local");
-      EpiOut o[8];
+      asm volatile("" ::: "memory");
+      float4 v[8];
 #pragma unroll
       for (int it = 0; it < 8; ++it) {
         const int row = it * 4 + rsub;
-        const float4 v = *(const float4*)(patch + row * 64 + ((c ^ (row & 15)) << 2));
-        o[it] = compute(i * 32 + row, jh * 64 + c * 4, v, FETCH ? side[round & 1][it] : make_uint2(0, 0));
+        v[it] = *(const float4*)(patch + row * 64 + ((c ^ (row & 15)) << 2));
       }
+      asm volatile("" ::: "memory");
+      if (round + 1 < kRounds) write_round((round + 1) / (NB / 2), (round + 1) % (NB / 2), (round & 1) ? patch0 : patch1);
+      asm volatile("" ::: "memory");
+      EpiOut o[8];
+#pragma unroll
+      for (int it = 0; it < 8; ++it)
+        o[it] = compute(i * 32 + it * 4 + rsub, jh * 64 + c * 4, v[it], FETCH ? side[round & 1][it] : make_uint2(0, 0));
 #pragma unroll
       for (int it = 0; it < 8; ++it) store(i * 32 + it * 4 + rsub, jh * 64 + c * 4, o[it]);
     }
@@ -413,13 +429,14 @@ __device__ __forceinline__ void rows_mainloop(bf16_t* smem, f32x16 (&acc)[MB][NB
 // LUT: the activation comes from the LDS copy `lut` of the activation table ({r, q} pairs, see
 // above); otherwise it is evaluated arithmetically.
 template <int EPI, int ACT, bool LUT, bool BIAS>
-__device__ __forceinline__ void rows_epilogue_t(float* lds, const f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ bias,
+__device__ __forceinline__ void rows_epilogue_t(float* lds, float* lds_alt, const f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ bias,
                                                 int NC, int row0, int rows_valid, int e, int n0,
                                                 const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
                                                 bf16_t* __restrict__ out1, const lds_byte_t* lut) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   float* patch = lds + wave * (32 * 64);
+  float* patch_alt = lds_alt + wave * (32 * 64);
   const int col_base = n0 + wn * (NB * 32);
   // tile-relative 32-bit offsets on top of uniform per-tile base pointers (scalar base + vector
   // offset addressing instead of 64-bit vector address arithmetic per store)
@@ -474,16 +491,16 @@ __device__ __forceinline__ void rows_epilogue_t(float* lds, const f32x16 (&acc)[
       if (EPI != EPI_PLAIN) *(uint2*)(out1_t + off) = o.b;
     }
   };
-  epilogue_rounds<EPI == EPI_DH>(patch, acc, fetch, compute, store);
+  epilogue_rounds<EPI == EPI_DH>(patch, patch_alt, acc, fetch, compute, store);
 }
 
 template <int EPI, int ACT, bool LUT = false>
-__device__ __forceinline__ void rows_epilogue(float* lds, const f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ bias,
+__device__ __forceinline__ void rows_epilogue(float* lds, float* lds_alt, const f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ bias,
                                               int NC, int row0, int rows_valid, int e, int n0,
                                               const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
                                               bf16_t* __restrict__ out1, const lds_byte_t* lut = nullptr) {
-  if (bias) rows_epilogue_t<EPI, ACT, LUT, true>(lds, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1, lut);
-  else rows_epilogue_t<EPI, ACT, LUT, false>(lds, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1, lut);
+  if (bias) rows_epilogue_t<EPI, ACT, LUT, true>(lds, lds_alt, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1, lut);
+  else rows_epilogue_t<EPI, ACT, LUT, false>(lds, lds_alt, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1, lut);
 }
 
 // One output tile of rows_gemm: main loop and epilogue.  FULL = all eight 32-row blocks hold rows.
@@ -503,7 +520,7 @@ __device__ __forceinline__ void rows_tile(bf16_t* smem, const bf16_t* __restrict
   zero_acc(acc);
   rows_mainloop<WT, FULL>(smem, acc, a_base, w_e, K, NC, n0, rows_valid, cols_valid, wm, wn, nblk_rows);
 
-  rows_epilogue<EPI, ACT>((float*)smem, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1);
+  rows_epilogue<EPI, ACT>((float*)smem, (float*)smem + kGemmThreads / kWave * (32 * 64), acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1);
 }
 
 // flat row-tile index -> (vExpert, tile inside it): one wave scans the buckets' tile counts.
@@ -829,7 +846,7 @@ __device__ __forceinline__ void rows_dma_body(lds_byte_t* s0, lds_byte_t* s1, ld
   zero_acc(acc);
   RowsIssue<WSrc> issue{a_src, w_src, 0};
   dma_pipeline<false, !WT>(s0, s1, s2, s3, acc, issue, K / DK, wm, wn);   // K % 128 == 0 (host check)
-  rows_epilogue<EPI, ACT, epilogue_uses_lut<EPI, ACT>()>((float*)s0, acc, bias, NC, t.row0, t.rows_valid, t.e, t.n0, hpre_in, out0,
+  rows_epilogue<EPI, ACT, epilogue_uses_lut<EPI, ACT>()>((float*)s0, (float*)s1, acc, bias, NC, t.row0, t.rows_valid, t.e, t.n0, hpre_in, out0,
                                                           out1, lut);
 }
 
@@ -1119,12 +1136,13 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_dma_bf16(const bf16_t
   }
 
   float* patch = (float*)stage0 + wave * (32 * 64);
+  float* patch_alt = (float*)stage1 + wave * (32 * 64);
   const int col_base = n0 + wn * (NB * 32);
   auto tile_row = [&](int row_w) { return (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31); };
   if (job.nseg == 1) {
     bf16_t* out = dw + (size_t)job.e * M * NC;
     epilogue_rounds<false>(
-        patch, acc, [](int, int) { return make_uint2(0, 0); },
+        patch, patch_alt, acc, [](int, int) { return make_uint2(0, 0); },
         [](int, int, float4 c, uint2) { return EpiOut{pack4(c.x, c.y, c.z, c.w), make_uint2(0, 0)}; },
         [&](int row_w, int col_w, const EpiOut& o) {
           const int lrow = tile_row(row_w);
@@ -1135,7 +1153,7 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_dma_bf16(const bf16_t
     // one of several segments: the fp32 tile goes to the workspace for wgrad_reduce_kernel
     float* out = partial + (size_t)(job.slot + job.seg) * M * NC;
     epilogue_rounds<false>(
-        patch, acc, [](int, int) { return make_uint2(0, 0); },
+        patch, patch_alt, acc, [](int, int) { return make_uint2(0, 0); },
         [](int, int, float4 c, uint2) {
           return EpiOut{make_uint2(__float_as_uint(c.x), __float_as_uint(c.y)),
                         make_uint2(__float_as_uint(c.z), __float_as_uint(c.w))};
