@@ -535,13 +535,19 @@ __device__ __forceinline__ bool lookup_row_tile(const int32_t* __restrict__ voff
     const int lane = threadIdx.x;
     if (lane == 0) s_tile[0] = -1;
     const int per = (V + kWave - 1) / kWave;     // <= 8 buckets per lane
-    int cnt[FLEXMOE_MAX_VEXPERTS / kWave];
+    int cnt[FLEXMOE_MAX_VEXPERTS / kWave], lo[FLEXMOE_MAX_VEXPERTS / kWave], hi[FLEXMOE_MAX_VEXPERTS / kWave];
+    int own[FLEXMOE_MAX_VEXPERTS / kWave];
     int sum = 0;
 #pragma unroll
     for (int q = 0; q < FLEXMOE_MAX_VEXPERTS / kWave; ++q) {
       const int v = lane * per + q;
-      cnt[q] = 0;
-      if (q < per && v < V) cnt[q] = (voff[v + 1] - voff[v] + BM - 1) / BM;
+      cnt[q] = lo[q] = hi[q] = own[q] = 0;
+      if (q < per && v < V) {
+        lo[q] = voff[v];
+        hi[q] = voff[v + 1];
+        own[q] = owner[v];                         // fetched now: no second round trip once the bucket is known
+        cnt[q] = (hi[q] - lo[q] + BM - 1) / BM;
+      }
       sum += cnt[q];
     }
     int incl = sum;
@@ -556,22 +562,22 @@ __device__ __forceinline__ bool lookup_row_tile(const int32_t* __restrict__ voff
 #pragma unroll
     for (int q = 0; q < FLEXMOE_MAX_VEXPERTS / kWave; ++q) {
       if (rt >= start && rt < start + cnt[q]) {
-        s_tile[0] = lane * per + q;
-        s_tile[1] = rt - start;
-        s_tile[2] = ct;
+        const int row0 = lo[q] + (rt - start) * BM;
+        s_tile[0] = row0;
+        s_tile[1] = min(BM, hi[q] - row0);
+        s_tile[2] = own[q];
+        s_tile[3] = ct;
       }
       start += cnt[q];
     }
   }
   __syncthreads();
-  const int v = s_tile[0];
-  if (v < 0) return false;                            // beyond the last tile (uniform)
+  if (s_tile[0] < 0) return false;                    // beyond the last tile (uniform)
   // workgroup-uniform values: keep them in scalar registers (scalar base addresses, scalar compares)
-  const int row0 = __builtin_amdgcn_readfirstlane(voff[v] + s_tile[1] * BM);
-  out->row0 = row0;
-  out->rows_valid = __builtin_amdgcn_readfirstlane(min(BM, voff[v + 1] - row0));
-  out->e = __builtin_amdgcn_readfirstlane(owner[v]);
-  out->n0 = __builtin_amdgcn_readfirstlane(s_tile[2] * BN);
+  out->row0 = __builtin_amdgcn_readfirstlane(s_tile[0]);
+  out->rows_valid = __builtin_amdgcn_readfirstlane(s_tile[1]);
+  out->e = __builtin_amdgcn_readfirstlane(s_tile[2]);
+  out->n0 = __builtin_amdgcn_readfirstlane(s_tile[3] * BN);
   out->cols_valid = min(BN, NC - out->n0);
   return true;
 }
@@ -583,7 +589,7 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_bf16(
     int col_tiles, const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0, bf16_t* __restrict__ out1) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t* smem = (bf16_t*)smem_raw;
-  __shared__ int s_tile[3];
+  __shared__ int s_tile[4];
   RowTile t;
   if (!lookup_row_tile(voff, owner, V, NC, row_tiles_max, col_tiles, s_tile, &t)) return;
   // Ragged tiles run the full-tile code (rows past the bucket are clamped on load and dropped
@@ -862,7 +868,7 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_dma_bf16(
   __shared__ __align__(1024) unsigned char stage3[kDmaStageBytes];
   constexpr bool kLut = epilogue_uses_lut<EPI, ACT>();
   __shared__ __align__(1024) unsigned char lut_lds[kLut ? kLutBytes : 16];
-  __shared__ int s_tile[3];
+  __shared__ int s_tile[4];
   RowTile t;
   if (!lookup_row_tile(voff, owner, V, NC, row_tiles_max, col_tiles, s_tile, &t)) return;
   const lds_byte_t* lut = nullptr;
