@@ -387,6 +387,24 @@ def test_activation_on_every_bf16_value(api, act):
         assert (err <= 0.5 * _bf16_ulp(ref) + 2.0 ** -24).mean() > 0.999        # correctly rounded almost everywhere
 
 
+@pytest.mark.parametrize("N,d,E,k", [(333, 136, 5, 1), (333, 136, 33, 2), (1000, 72, 64, 8), (97, 520, 100, 3),
+                                     (515, 264, 256, 8), (40000, 64, 16, 2), (33000, 136, 64, 2), (70001, 72, 48, 1)])
+def test_gate_alone_shapes(api, N, d, E, k):
+    """The gate on its own over expert counts on both sides of the 64-expert kernel switch, ragged
+    token tiles, K tails that are not a multiple of the 64-wide tile, and every launch shape."""
+    binding, layer_mod = api
+    rng = np.random.default_rng(N + d + E)
+    x = W.Bf16Tensor.from_f32(rng.standard_normal((N, d)).astype(np.float32))
+    wg = W.Bf16Tensor.from_f32((rng.standard_normal((d, E)) / np.sqrt(d) * 3.0).astype(np.float32))
+    xd, wgd = layer_mod.to_device(x), layer_mod.to_device(wg)
+    idx = torch.full((N, k), -1, dtype=torch.int32, device="cuda")
+    w = torch.zeros((N, k), dtype=torch.float32, device="cuda")
+    ws = torch.empty(binding.flexmoe_workspace_bytes(N, d, 64, E, k, E, W.DT_BF16), dtype=torch.uint8, device="cuda")
+    binding.flexmoe_gate_topk(xd, wgd, k, idx, w, ws)
+    torch.cuda.synchronize()
+    check_gate(host(idx), host(w), x, wg, k, W.DT_BF16)
+
+
 def test_exact_ties_pick_lower_expert(api):
     """Small-integer inputs make every fp32 sum exact, so ties are real ties on both sides."""
     binding, layer_mod = api
