@@ -1055,7 +1055,9 @@ struct DmaSrcTok {
 };
 
 // Tile sequence of the weight-gradient kernel: 32-token K tiles of the expert's buckets in
-// ascending vExpert id, then all-zero tiles up to the padded count.
+// ascending vExpert id, then all-zero tiles up to the padded count.  The position (row pointers of
+// both operands, rows left in the bucket) lives in workgroup-uniform values and advances by
+// pointer increments; the bucket list in LDS is read only when a bucket is exhausted.
 struct WgradIssue {
   const DmaSrcTok& l_src;
   const DmaSrcTok& r_src;
@@ -1064,29 +1066,31 @@ struct WgradIssue {
   const int* bstart;
   const int* brows;
   int M, NC, m0, n0, nb, T;
-  int bi, koff, issued;             // next K tile: 32 tokens of bucket bi from koff
-  const bf16_t* lp;
+  int bi, issued;
+  const bf16_t* lp;                 // token row 0 of the next K tile, first column of the tile
   const bf16_t* rp;
-  int kv;
-  __device__ __forceinline__ void begin() {
-    const size_t p0 = (size_t)bstart[bi] + koff;
-    kv = issued < T ? brows[bi] - koff : 0;
-    lp = L + p0 * M + m0;
-    rp = R + p0 * NC + n0;
+  int rows_left;                    // rows of bucket bi from that row on
+  __device__ __forceinline__ void seek(int bucket, int koff) {
+    bi = bucket;
+    const int start = __builtin_amdgcn_readfirstlane(bstart[bi]);
+    rows_left = __builtin_amdgcn_readfirstlane(brows[bi]) - koff;
+    lp = L + ((size_t)start + koff) * M + m0;
+    rp = R + ((size_t)start + koff) * NC + n0;
   }
+  __device__ __forceinline__ void begin() {}
   __device__ __forceinline__ void part(lds_byte_t* stage, int q) const {
+    const int kv = issued < T ? rows_left : 0;
     if (q < 4) l_src.part(stage, lp, kv, q);
     else r_src.part(stage + kDmaTileBytes, rp, kv, q - 4);
   }
   __device__ __forceinline__ void end() {
-    if (issued < T) {
-      koff += DK;
-      if (koff >= brows[bi]) {
-        koff = 0;
-        bi = min(bi + 1, nb - 1);
-      }
-    }
     ++issued;
+    if (issued < T) {
+      rows_left -= DK;
+      lp += (size_t)DK * M;
+      rp += (size_t)DK * NC;
+      if (rows_left <= 0) seek(min(bi + 1, nb - 1), 0);
+    }
   }
 };
 
@@ -1137,7 +1141,8 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_dma_bf16(const bf16_t
     DmaSrcTok l_src, r_src;
     l_src.init(M, mvalid);
     r_src.init(NC, nvalid);
-    WgradIssue issue{l_src, r_src, L, R, sh.bstart, sh.brows, M, NC, m0, n0, nb, T, bi, skip * DK, 0, nullptr, nullptr, 0};
+    WgradIssue issue{l_src, r_src, L, R, sh.bstart, sh.brows, M, NC, m0, n0, nb, T, 0, 0, nullptr, nullptr, 0};
+    issue.seek(bi, skip * DK);
     dma_pipeline<true, true>(s0, (lds_byte_t*)stage1, (lds_byte_t*)stage2, (lds_byte_t*)stage3, acc, issue, KT, wm, wn);
   }
 
