@@ -59,7 +59,7 @@ def stage_work(cfg):
 
 
 class Runner:
-    def __init__(self, name, seed=None, fused=True):
+    def __init__(self, name, seed=None, fused=False):
         import torch
         from paper_2304_03946_amd import binding, layer, workloads as W
         self.torch, self.W, self.layer_mod = torch, W, layer
@@ -149,7 +149,7 @@ class StageTimers:
         return out
 
 
-def run_workload(name, steps, warmup, with_stages=True, fused=True):
+def run_workload(name, steps, warmup, with_stages=True, fused=False):
     import torch
     r = Runner(name, fused=fused)
     cfg = r.cfg
@@ -164,6 +164,21 @@ def run_workload(name, steps, warmup, with_stages=True, fused=True):
     dt = time.perf_counter() - t0
     ms_per_step = dt / steps * 1e3
     out = dict(tokens_per_s=cfg.N / (dt / steps), ms_per_step=ms_per_step, fused=r.fused)
+    if not r.fused and not cfg.backward and r.L.gather_supported():
+        # the same forward pass with the permutation folded into the first expert GEMM (no Xp written):
+        # reported beside the step, which keeps every stage as a call of its own
+        r.fused = True
+        for _ in range(warmup):
+            r.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            r.step()
+        torch.cuda.synchronize()
+        dtf = time.perf_counter() - t0
+        out["fused_permute"] = dict(ms_per_step=round(dtf / steps * 1e3, 4), tokens_per_s=round(cfg.N / (dtf / steps), 1),
+                                    call="flexmoe_expert_ffn_fwd_gather replaces flexmoe_permute + flexmoe_expert_ffn_fwd")
+        r.fused = False
     if with_stages:
         timers = StageTimers(torch)
         for _ in range(steps):
@@ -285,8 +300,9 @@ def main():
     ap.add_argument("--workload", default="bert", choices=list(WORKLOAD_TEXT))
     ap.add_argument("--all-workloads", action="store_true", help="also time the other configurations (extra JSON field)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--unfused", action="store_true",
-                    help="forward-only workloads: separate flexmoe_permute + flexmoe_expert_ffn_fwd calls")
+    ap.add_argument("--fused", action="store_true",
+                    help="forward-only workloads: time the step with flexmoe_expert_ffn_fwd_gather instead of "
+                         "flexmoe_permute + flexmoe_expert_ffn_fwd")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device copy (calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -309,7 +325,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    r, res = run_workload(name, steps, warmup, fused=not args.unfused)
+    r, res = run_workload(name, steps, warmup, fused=args.fused)
     cfg = r.cfg
     ffn = res["stages"]["ffn_fwd"]
     dom_ms = ffn["ms"]
@@ -330,7 +346,7 @@ def main():
                    "tokens": cfg.N, "d_model": cfg.d, "d_ff": cfg.f, "experts": cfg.E, "top_k": cfg.k,
                    "vexperts": cfg.V, "loads": res["loads"],
                    "permute": "folded into the first expert GEMM (flexmoe_expert_ffn_fwd_gather)" if res["fused"]
-                              else "flexmoe_permute"},
+                              else "flexmoe_permute", **({"fused_permute": res["fused_permute"]} if "fused_permute" in res else {})},
         "roofline": {"kernel": ("flexmoe_expert_ffn_fwd_gather" if res["fused"] else "flexmoe_expert_ffn_fwd") +
                                " (two grouped-GEMM launches: rows_gemm_dma_bf16 x2)",
                      "bound": ffn["bound"], "achieved": ffn["achieved"],
@@ -348,7 +364,7 @@ def main():
             del r
             torch.cuda.empty_cache()
             ob = other == "gpt_xl"
-            r, o = run_workload(other, 20 if ob else 100, 3 if ob else 10, fused=not args.unfused)
+            r, o = run_workload(other, 20 if ob else 100, 3 if ob else 10, fused=args.fused)
             others[other] = dict(tokens_per_s=round(o["tokens_per_s"], 1), ms_per_step=round(o["ms_per_step"], 4),
                                  stages=o["stages"], loads=o["loads"])
             if "trainable_layer_extras" in o:
