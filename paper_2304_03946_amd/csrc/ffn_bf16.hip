@@ -11,14 +11,19 @@
 //  * weight-gradient GEMMs: dW_e = sum over the vExperts v of e of L_v^T . R_v -- the contraction
 //    runs over the tokens of every bucket of e in ascending vExpert id inside one accumulator,
 //    which is the single-GPU image of the paper's replica gradient synchronisation.  Output tiles
-//    are issued hottest expert first so the long contractions start early.
+//    are issued hottest expert first so the long contractions start early; when one expert's
+//    contraction is much longer than the chip-wide average per compute unit it is cut into
+//    segments that accumulate into fp32 partial tiles, summed in a fixed order by a second kernel
+//    (the result does not depend on scheduling).
 //
 // Two operand pipelines:
 //  * direct-to-LDS (rows_gemm_dma_bf16, wgrad_gemm_dma_bf16; used whenever K is a multiple of
 //    128, i.e. for every benchmark shape): global_load_lds_dwordx4 copies 32-wide K tiles
 //    straight into one of four LDS stages (no register staging, no LDS store instructions); an
 //    operand whose contraction index is strided in memory is copied as stored and transposed on
-//    the way out of LDS by ds_read_tr16_b64.  The kernels are bound by L2 -> LDS bandwidth.
+//    the way out of LDS by ds_read_tr16_b64.  The loads of the tile three steps ahead are
+//    spread between the MFMAs of the current one, and one LDS-only barrier per K tile orders
+//    stage reuse.  The kernels are bound by L2 -> LDS bandwidth.
 //  * register-staged (rows_gemm_bf16; any K that is a multiple of 8): 64-wide K
 //    tiles through registers into two LDS stages, strided operands transposed 8x8 in registers.
 //
@@ -27,6 +32,9 @@
 // The MFMA is issued as (weights-fragment, activations-fragment) so that a lane ends up with 4
 // consecutive output columns of one output row; the epilogue passes the accumulators through a
 // wave-private LDS patch so that global stores fill whole 128-byte lines.
+// GELU and its derivative act on bf16-rounded arguments, so both are read from a table indexed
+// by the argument's bits (filled once per device from the fp64 formulas; outside the table's
+// range GELU equals ReLU to below bf16 resolution).
 #include <algorithm>
 #include <mutex>
 
