@@ -22,7 +22,10 @@ OK, INVALID_ARG, BAD_PLACEMENT, WORKSPACE_TOO_SMALL, UNSUPPORTED, DEVICE_ERROR =
 
 EXPORTS = ["flexmoe_status_str", "flexmoe_workspace_bytes", "flexmoe_gate_topk", "flexmoe_route",
            "flexmoe_permute", "flexmoe_expert_ffn_fwd", "flexmoe_expert_ffn_bwd", "flexmoe_combine",
-           "flexmoe_gate_bwd", "flexmoe_expert_bias_grads", "flexmoe_expert_ffn_fwd_gather"]
+           "flexmoe_gate_bwd", "flexmoe_expert_bias_grads", "flexmoe_expert_ffn_fwd_gather",
+           # host-side scheduler (include/flexmoe_scheduler.h; Python face in scheduler.py)
+           "flexmoe_balance_ratio", "flexmoe_step_cost", "flexmoe_make_scheduling_plan", "flexmoe_schedule",
+           "flexmoe_placement_table"]
 
 _lib = None
 
@@ -66,6 +69,18 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.flexmoe_gate_bwd.argtypes = [c_vp] * 10 + [c_int] * 6 + [c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.flexmoe_expert_bias_grads.restype = c_int
     lib.flexmoe_expert_bias_grads.argtypes = [c_vp] * 3 + [c_int] * 6 + [c_vp, c_vp, c_vp, c_sz, c_vp]
+    c_i64, c_dbl = ctypes.c_int64, ctypes.c_double
+    lib.flexmoe_balance_ratio.restype = c_int
+    lib.flexmoe_balance_ratio.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_vp, c_vp]
+    lib.flexmoe_step_cost.restype = c_int
+    lib.flexmoe_step_cost.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_i64, c_vp, c_vp]
+    lib.flexmoe_make_scheduling_plan.restype = c_int
+    lib.flexmoe_make_scheduling_plan.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_i64, c_vp, c_vp, c_vp, c_vp]
+    lib.flexmoe_schedule.restype = c_int
+    lib.flexmoe_schedule.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_i64, c_vp, c_dbl, c_int, c_vp, c_vp, c_vp,
+                                     c_vp]
+    lib.flexmoe_placement_table.restype = c_int
+    lib.flexmoe_placement_table.argtypes = [c_vp, c_int, c_int, c_vp, c_vp, c_vp]
     if path == LIB_PATH:
         _lib = lib
     return lib

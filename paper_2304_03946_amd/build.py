@@ -10,7 +10,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libflexmoe.so")
-SOURCES = ["api.hip", "gate.hip", "route.hip", "permute_combine.hip", "ffn_f32.hip", "ffn_bf16.hip", "gate_bwd.hip"]
+SOURCES = ["api.hip", "gate.hip", "route.hip", "permute_combine.hip", "ffn_f32.hip", "ffn_bf16.hip", "gate_bwd.hip",
+           "scheduler.cpp"]     # .cpp = host-only code
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
@@ -19,7 +20,7 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
 
 
 def _compile(src: str) -> str:
-    obj = os.path.join(CSRC, src.replace(".hip", ".o"))
+    obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
     cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)

@@ -76,6 +76,19 @@ class MoELayer:
         B.flexmoe_route(self.topk_idx, self.E, rep_off, rep_ids, self.expert_count, self.vexpert_count,
                         self.vexpert_off, self.vexpert_owner, self.dest, self.src, self.ws)
 
+    def post_loads(self):
+        """Start copying this step's expert loads I_e (expert_count, as the router wrote it) into
+        pinned host memory on the current stream.  Returns (host int32 tensor, event): the host-side
+        scheduler reads the tensor once the event has completed -- normally while later steps run --
+        so the stream never waits for the host (Section 3.3: the Scheduler monitors the workloads
+        next to the training loop)."""
+        if not hasattr(self, "_loads_host"):
+            self._loads_host = torch.empty(self.E, dtype=torch.int32, pin_memory=True)
+        self._loads_host.copy_(self.expert_count, non_blocking=True)
+        ev = torch.cuda.Event()
+        ev.record()
+        return self._loads_host, ev
+
     def forward(self, x, wg, w1, w2, rep_off, rep_ids, b1=None, b2=None):
         self.gate(x, wg)
         self.route(rep_off, rep_ids)

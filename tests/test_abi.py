@@ -8,9 +8,13 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "flexmoe.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(flexmoe_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for fn in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(flexmoe_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def _lib():
@@ -24,7 +28,8 @@ def _lib():
 def test_header_declares_the_entry_points():
     assert set(_declared()) >= {"flexmoe_gate_topk", "flexmoe_route", "flexmoe_permute", "flexmoe_expert_ffn_fwd",
                                 "flexmoe_expert_ffn_bwd", "flexmoe_combine", "flexmoe_workspace_bytes",
-                                "flexmoe_status_str"}
+                                "flexmoe_status_str", "flexmoe_balance_ratio", "flexmoe_make_scheduling_plan",
+                                "flexmoe_schedule", "flexmoe_placement_table"}
 
 
 def test_library_exports_every_declared_symbol():

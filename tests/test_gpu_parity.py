@@ -516,3 +516,42 @@ def test_two_runs_are_bit_identical(api):
     for a, b in zip(*outs):
         assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a,
                            b.view(torch.int16) if b.dtype == torch.bfloat16 else b)
+
+
+def test_scheduler_in_the_loop_keeps_the_layer_output(api):
+    """Alg. 1 next to the training loop: the router's expert counts reach the host without a stream
+    wait, one scheduler pass turns them into a new placement, and the router takes the new table on
+    the next step.  Replicating experts and re-partitioning their tokens leaves the model untouched
+    (Section 3), so the layer output must not change by a single bit, while the balance ratio of
+    the emulated cluster (4 GPUs x 4 vExpert slots, computed here on the one GPU) drops."""
+    from oracle import scheduler_oracle as SO
+    from paper_2304_03946_amd import scheduler as sch
+    binding, layer_mod = api
+    G, S = 4, 4
+    cfg = W.scaled(W.CONFIGS["gpt_m"], N=1900, d=384, f=640, E=8, V=G * S, max_rep=8)
+    inp = W.make_layer_inputs(cfg)
+    dev = upload(layer_mod, inp)
+    L = layer_mod.MoELayer.for_config(cfg)
+    owner = np.repeat(np.arange(cfg.E), 2).astype(np.int32)       # GPU g hosts experts 2g and 2g+1, two slots each
+    rep = sch.flexmoe_placement_table(owner, cfg.E)
+    L.forward(dev["x"], dev["wg"], dev["w1"], dev["w2"], *rep)
+    loads, ev = L.post_loads()
+    y_before = L.y.clone()
+    ev.synchronize()
+    I = loads.numpy().astype(np.int64)
+    assert np.array_equal(I, np.bincount(host(L.topk_idx).ravel(), minlength=cfg.E))
+
+    ops, new_owner, before, after = sch.flexmoe_schedule(I, owner, G, 1, 1.0, 32)
+    r_ops, r_owner, r_before, r_after = SO.schedule(I.tolist(), owner.tolist(), G, 1, 1.0, 32)
+    assert [tuple(o) for o in ops.tolist()] == r_ops and new_owner.tolist() == r_owner
+    assert (before, after) == (r_before, r_after)
+    assert len(ops) > 0 and after < before
+
+    rep2 = sch.flexmoe_placement_table(new_owner, cfg.E)
+    L.forward(dev["x"], dev["wg"], dev["w1"], dev["w2"], *rep2)
+    torch.cuda.synchronize()
+    assert torch.equal(L.y.view(torch.int16), y_before.view(torch.int16))
+    # the shares the router handed out are the ones the scheduler planned with
+    assert host(L.vexpert_count).tolist() == SO.vexpert_shares(I.tolist(), r_owner)
+    ratio, gpu_load = sch.flexmoe_balance_ratio(I, new_owner, G)
+    assert host(L.vexpert_count).reshape(G, S).sum(1).tolist() == gpu_load.tolist() and ratio == after
