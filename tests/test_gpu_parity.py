@@ -186,6 +186,9 @@ SMALL = {
     "xl_small": W.scaled(W.CONFIGS["gpt_xl"], N=2600, d=192, f=384, E=64, V=96, max_rep=8),
     # d and f multiples of 128 with ragged column tiles: the backward GEMMs take the direct-to-LDS path
     "gpt_dma": W.scaled(W.CONFIGS["gpt_m"], N=1900, d=384, f=640, E=8, V=13, max_rep=4),
+    # the same with enough tokens (A/32 >= 128 K tiles) that the hot experts' weight-gradient contraction is
+    # cut into segments (fp32 partial tiles + reduce kernel) inside the shared dXp/dW2/dW1 launch
+    "gpt_dma_seg": W.scaled(W.CONFIGS["gpt_m"], N=2300, d=384, f=640, E=8, V=13, max_rep=4),
 }
 
 
@@ -283,7 +286,7 @@ def test_full_backward_fp32(api):
     run_full_backward(api, cfg, inp, *W.placement_from_loads([5, 4, 3, 2, 1], cfg.V, 3, shuffle_seed=3), b1=b1, b2=b2)
 
 
-@pytest.mark.parametrize("name", ["gpt_small", "swin_small", "xl_small", "gpt_dma"])
+@pytest.mark.parametrize("name", ["gpt_small", "swin_small", "xl_small", "gpt_dma", "gpt_dma_seg"])
 def test_full_backward_reduced_configs(api, name):
     cfg = SMALL[name]
     inp = W.make_layer_inputs(cfg)
