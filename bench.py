@@ -75,6 +75,7 @@ class Runner:
         self.drifting = name == "gpt_xl"
         # without a backward pass nothing reads Xp again: fold the permutation into the expert GEMM
         self.fused = fused and not cfg.backward and self.L.gather_supported()
+        self.keep_hpre = True
         # placement: the benchmark's table for the BERT-like layer; otherwise the greedy
         # capacity rule on the loads observed on a first (untimed) pass
         self.rep = W.config_placement(cfg)
@@ -115,7 +116,8 @@ class Runner:
         if self.fused:
             # forward-only layer: the layout transformation rides on GEMM1's row loads (no Xp)
             B.flexmoe_expert_ffn_fwd_gather(self.x, L.src, cfg.k, L.vexpert_off, L.vexpert_owner, self.w1, None,
-                                            self.w2, None, cfg.act, L.hpre, L.yp, L.ws); rec("ffn_fwd")
+                                            self.w2, None, cfg.act, L.hpre if self.keep_hpre else None, L.yp,
+                                            L.ws); rec("ffn_fwd")
         else:
             B.flexmoe_permute(self.x, L.src, None, cfg.k, L.xp); rec("permute")
             B.flexmoe_expert_ffn_fwd(L.xp, L.vexpert_off, L.vexpert_owner, self.w1, None, self.w2, None, cfg.act,
@@ -185,6 +187,19 @@ def run_workload(name, steps, warmup, with_stages=True, fused=False):
         dtf = time.perf_counter() - t0
         out["fused_permute"] = dict(ms_per_step=round(dtf / steps * 1e3, 4), tokens_per_s=round(cfg.N / (dtf / steps), 1),
                                     call="flexmoe_expert_ffn_fwd_gather replaces flexmoe_permute + flexmoe_expert_ffn_fwd")
+        # and the inference form of that call: hpre = NULL, the pre-activations (kept for a backward pass) are not stored
+        r.keep_hpre = False
+        for _ in range(warmup):
+            r.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            r.step()
+        torch.cuda.synchronize()
+        dti = time.perf_counter() - t0
+        out["fused_permute"]["without_stored_preactivations"] = dict(ms_per_step=round(dti / steps * 1e3, 4),
+                                                                     tokens_per_s=round(cfg.N / (dti / steps), 1))
+        r.keep_hpre = True
         r.fused = False
     if with_stages:
         timers = StageTimers(torch)

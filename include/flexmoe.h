@@ -104,6 +104,8 @@ int flexmoe_permute(const void* x, const int32_t* src, const float* row_scale,
  *   xp [A,d], w1 [E,d,f], b1 [E,f] or NULL, w2 [E,f,d], b2 [E,d] or NULL, all dtype;
  *   vexpert_off [V+1], vexpert_owner [V] as written by flexmoe_route.
  *   -> hpre [A,f] dtype (pre-activation, kept for the backward pass), yp [A,d] dtype.
+ *   hpre may be NULL when no backward pass follows (inference): the pre-activations are then not
+ *   stored, which halves what the first product writes; yp is the same, bit for bit.
  * The activation is applied to hpre as stored (i.e. after rounding to dtype).
  * The first bf16 GELU call on a device (forward or backward) fills that device's activation
  * tables and waits once for `stream`; under stream capture the fill is recorded instead.
@@ -142,7 +144,7 @@ int flexmoe_combine(const void* yp, const int32_t* dest, const float* topk_w,
  * first product is read as row src[p] / k of x while the tile is loaded (Section 4's layout
  * transformation folded into the expert computation).  Same results as the two calls, bit for bit.
  *   x [N,d], src [A] (A = N*k) as written by flexmoe_route; everything else as in
- *   flexmoe_expert_ffn_fwd.  For forward-only use: the backward pass reads xp.
+ *   flexmoe_expert_ffn_fwd (hpre may be NULL as well).  For forward-only use: the backward pass reads xp.
  * FLEXMOE_UNSUPPORTED unless dtype is bf16, d is a multiple of 128 and N*d < 2^32: callers then
  * use the two separate calls.
  */

@@ -129,7 +129,7 @@ int flexmoe_expert_ffn_fwd(const void* xp, const int32_t* vexpert_off, const int
   const int st = ffn_common(A, d, f, E, V, act, dtype, vexpert_off, vexpert_owner, ws, ws_bytes);
   if (st != FLEXMOE_OK) return st;
   if (!w1 || !w2 || !aligned16(w1) || !aligned16(w2) || !aligned16(b1) || !aligned16(b2)) return FLEXMOE_INVALID_ARG;
-  if (A > 0 && (!xp || !hpre || !yp || !aligned16(xp) || !aligned16(hpre) || !aligned16(yp)))
+  if (A > 0 && (!xp || !yp || !aligned16(xp) || !aligned16(hpre) || !aligned16(yp)))      // hpre may be NULL
     return FLEXMOE_INVALID_ARG;
   const FfnArgs a{A, d, f, E, V, act, vexpert_off, vexpert_owner};
   const hipStream_t s = (hipStream_t)stream;
@@ -148,7 +148,7 @@ int flexmoe_expert_ffn_fwd_gather(const void* x, const int32_t* src, const int32
   // gathered row loads exist on the bf16 direct-to-LDS path only; row offsets are 32-bit
   if (dtype != FLEXMOE_BF16 || (d % 128) || (long long)N * d >= (1ll << 32)) return FLEXMOE_UNSUPPORTED;
   if (!w1 || !w2 || !aligned16(w1) || !aligned16(w2) || !aligned16(b1) || !aligned16(b2)) return FLEXMOE_INVALID_ARG;
-  if (A > 0 && (!x || !src || !hpre || !yp || !aligned16(x) || !aligned16(hpre) || !aligned16(yp)))
+  if (A > 0 && (!x || !src || !yp || !aligned16(x) || !aligned16(hpre) || !aligned16(yp)))    // hpre may be NULL
     return FLEXMOE_INVALID_ARG;
   const FfnArgs a{A, d, f, E, V, act, vexpert_off, vexpert_owner};
   return dev_status(launch_ffn_fwd_gather_bf16(a, x, src, k, w1, b1, w2, b2, hpre, yp, ws, (hipStream_t)stream));

@@ -495,7 +495,7 @@ __device__ __forceinline__ void rows_epilogue_t(float* lds, float* lds_alt, cons
     const int lrow = tile_row(row_w);
     if (lrow < rows_valid && col_w < cols_left) {
       const uint32_t off = (uint32_t)(lrow * NC + col_w);
-      *(uint2*)(out0_t + off) = o.a;
+      if (EPI != EPI_FWD1 || out0) *(uint2*)(out0_t + off) = o.a;     // forward: the pre-activations are optional
       if (EPI != EPI_PLAIN) *(uint2*)(out1_t + off) = o.b;
     }
   };

@@ -39,7 +39,7 @@ __global__ __launch_bounds__(kF32Threads) void rows_gemm_f32(const float* __rest
   for (int kk = 0; kk < K; ++kk) acc = fmaf(row[kk], WT ? we[(size_t)n * K + kk] : we[(size_t)kk * NC + n], acc);
   if (bias) acc += bias[(size_t)e * NC + n];
   if (EPI == EPI_FWD1) {          // out0 = pre-activation (kept), out1 = activation
-    out0[o] = acc;
+    if (out0) out0[o] = acc;
     out1[o] = act_apply(acc, act);
   } else if (EPI == EPI_PLAIN) {
     out0[o] = acc;

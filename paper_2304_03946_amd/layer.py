@@ -89,25 +89,26 @@ class MoELayer:
         ev.record()
         return self._loads_host, ev
 
-    def forward(self, x, wg, w1, w2, rep_off, rep_ids, b1=None, b2=None):
+    def forward(self, x, wg, w1, w2, rep_off, rep_ids, b1=None, b2=None, keep_hpre=True):
+        """keep_hpre=False (inference): the pre-activations are not stored; `backward` cannot follow."""
         self.gate(x, wg)
         self.route(rep_off, rep_ids)
         B.flexmoe_permute(x, self.src, None, self.k, self.xp)
         B.flexmoe_expert_ffn_fwd(self.xp, self.vexpert_off, self.vexpert_owner, w1, b1, w2, b2, self.act,
-                                 self.hpre, self.yp, self.ws)
+                                 self.hpre if keep_hpre else None, self.yp, self.ws)
         B.flexmoe_combine(self.yp, self.dest, self.topk_w, self.k, self.y)
         return self.y
 
     def gather_supported(self) -> bool:
         return self.dtype_code == B.BF16 and self.d % 128 == 0 and self.N * self.d < 2 ** 32
 
-    def forward_fused(self, x, wg, w1, w2, rep_off, rep_ids, b1=None, b2=None):
+    def forward_fused(self, x, wg, w1, w2, rep_off, rep_ids, b1=None, b2=None, keep_hpre=True):
         """Forward-only variant: the permutation is folded into the first expert GEMM (xp is not
-        written, so `backward` cannot follow)."""
+        written, so `backward` cannot follow); keep_hpre=False also drops the pre-activations."""
         self.gate(x, wg)
         self.route(rep_off, rep_ids)
         B.flexmoe_expert_ffn_fwd_gather(x, self.src, self.k, self.vexpert_off, self.vexpert_owner, w1, b1, w2, b2,
-                                        self.act, self.hpre, self.yp, self.ws)
+                                        self.act, self.hpre if keep_hpre else None, self.yp, self.ws)
         B.flexmoe_combine(self.yp, self.dest, self.topk_w, self.k, self.y)
         return self.y
 

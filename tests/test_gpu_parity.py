@@ -335,6 +335,31 @@ def test_gathered_forward_equals_permute_then_ffn(api, name, bias):
     assert not host(L.xp).any(), "the fused path must not touch xp"
 
 
+@pytest.mark.parametrize("name", ["tiny_f32", "bert_small", "gpt_dma"])
+def test_forward_without_stored_preactivations(api, name):
+    """hpre = NULL (inference): yp and y are the same bits, the hpre buffer is not touched.
+    Covers the fp32 kernels, the register-staged bf16 kernels and the direct-to-LDS ones (both entry points)."""
+    binding, layer_mod = api
+    cfg = W.CONFIGS["tiny"] if name == "tiny_f32" else SMALL[name]
+    inp = W.make_layer_inputs(cfg)
+    dev = upload(layer_mod, inp)
+    rep = W.config_placement(cfg) if name == "tiny_f32" else W.placement_from_loads(W.prior_loads(cfg), cfg.V, cfg.max_rep)
+    L = layer_mod.MoELayer.for_config(cfg)
+    L.forward(dev["x"], dev["wg"], dev["w1"], dev["w2"], *rep)
+    torch.cuda.synchronize()
+    want = {n: host(getattr(L, n)).copy() for n in ("yp", "y")}
+    variants = [L.forward] + ([L.forward_fused] if L.gather_supported() else [])
+    for fwd in variants:
+        for t in (L.yp, L.y):
+            t.zero_()
+        L.hpre.fill_(7.0)
+        fwd(dev["x"], dev["wg"], dev["w1"], dev["w2"], *rep, keep_hpre=False)
+        torch.cuda.synchronize()
+        for n in want:
+            assert np.array_equal(host(getattr(L, n)), want[n]), n
+        assert bool((L.hpre == 7.0).all()), "hpre must stay untouched"
+
+
 def test_gathered_forward_refuses_what_it_cannot_do(api):
     binding, layer_mod = api
     cfg = SMALL["bert_small"]                       # d = 328: not a multiple of 128
