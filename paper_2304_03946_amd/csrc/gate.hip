@@ -5,7 +5,8 @@
 // row operand (32 experts per tile) and 32 tokens as the column operand, hence after the
 // K loop every lane holds half of one token's logits and its partner lane (lane ^ 32) the
 // other half -- the top-k selection is a register scan plus one cross-lane exchange per pick.
-// W_g is first transposed to [E_pad, d_pad] in the workspace (tiny, stays in L2).
+// W_g is first transposed to [E_pad, d_pad] in the workspace (tiny, stays in L2), except in the
+// small-batch kernel with up to 64 experts, which gathers its fragments from W_g as stored.
 // Large batches with up to 64 experts (gate_dma_kernel): every wave owns 32 tokens and the whole contraction; x and
 // W_g^T travel global -> LDS with direct loads that fetch whole 128-byte lines of a row (eight
 // rows per instruction), several 64-wide K tiles in flight per workgroup, and the MFMA fragments
@@ -45,6 +46,7 @@ __global__ void gate_transpose_wg_kernel(const bf16_t* __restrict__ wg, int d, i
 union Frag {
   uint4 u;
   bf16x8 v;
+  bf16_t h[8];
 };
 
 // Top-k selection and softmax for one tile of 32 tokens whose logits sit in MFMA layout:
@@ -114,7 +116,11 @@ __device__ __forceinline__ void gate_select_store(f32x16 (&acc)[NT], int t, int 
 // the 64-wide K chunks w, w+4, ...), so even a small batch puts four waves on every compute
 // unit and each wave keeps two chunks of loads in flight; the partial logits are then added in
 // a fixed order (3, 2, 1, 0) through LDS, so results do not depend on timing, and wave 0 selects.
-template <int NT, int CT>   // NT tiles of 32 experts, CT tiles of 32 tokens
+// DIRECT: `wgt` is W_g itself, [d, E]: a lane gathers the eight values of a fragment with 2-byte
+// loads (stride E) instead of reading a transposed copy -- 32 NT small loads per chunk from a
+// matrix that sits in L2, which saves the launch that writes the copy.  Lanes of experts >= E
+// re-read expert E-1 (their logits are discarded) and rows past d re-read row d-1 (x is zero there).
+template <int NT, int CT, bool DIRECT>   // NT tiles of 32 experts, CT tiles of 32 tokens
 __global__ __launch_bounds__(kGateThreads) void gate_bf16_kernel(const bf16_t* __restrict__ x,
                                                                  const bf16_t* __restrict__ wgt, int N, int d,
                                                                  int E, int k, int32_t* __restrict__ topk_idx,
@@ -137,6 +143,19 @@ __global__ __launch_bounds__(kGateThreads) void gate_bf16_kernel(const bf16_t* _
   for (int ct = 0; ct < CT; ++ct) xrow[ct] = x + (size_t)min(t0 + ct * 32 + j, N - 1) * d + 32 * h;   // clamp the ragged last tile
   const bf16_t* wrow = wgt + (size_t)j * d + 32 * h;
   const int nchunks = (d + 63) / 64;
+  // DIRECT: column of W_g for the lane's expert in tile r, at row 32 h
+  const bf16_t* wcol[NT];
+#pragma unroll
+  for (int r = 0; r < NT; ++r) wcol[r] = wgt + (size_t)(32 * h) * E + min(r * 32 + j, E - 1);
+  auto gather_w = [&](int r, int k0, bool full) -> uint4 {        // W_g[k0 + 32 h + 0..7, expert]
+    Frag f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int kk = full ? k0 + i : min(k0 + i, d - 1 - 32 * h);
+      f.h[i] = wcol[r][(size_t)kk * E];
+    }
+    return f.u;
+  };
 
   // lane reads k = 64c + 32h + 8s .. +8 of its row for s = 0..3 (64 contiguous bytes); pieces past d are zero
   auto load_chunk = [&](int c, Frag (&xb)[CT][4], Frag (&wa)[NT][4]) {
@@ -148,7 +167,8 @@ __global__ __launch_bounds__(kGateThreads) void gate_bf16_kernel(const bf16_t* _
 #pragma unroll
       for (int r = 0; r < NT; ++r)
 #pragma unroll
-        for (int s = 0; s < 4; ++s) wa[r][s].u = *(const uint4*)(wrow + (size_t)r * 32 * d + c * 64 + s * 8);
+        for (int s = 0; s < 4; ++s)
+          wa[r][s].u = DIRECT ? gather_w(r, c * 64 + s * 8, true) : *(const uint4*)(wrow + (size_t)r * 32 * d + c * 64 + s * 8);
     } else {
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
@@ -156,7 +176,10 @@ __global__ __launch_bounds__(kGateThreads) void gate_bf16_kernel(const bf16_t* _
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) xb[ct][s].u = ok ? *(const uint4*)(xrow[ct] + c * 64 + s * 8) : make_uint4(0, 0, 0, 0);
 #pragma unroll
-        for (int r = 0; r < NT; ++r) wa[r][s].u = ok ? *(const uint4*)(wrow + (size_t)r * 32 * d + c * 64 + s * 8) : make_uint4(0, 0, 0, 0);
+        for (int r = 0; r < NT; ++r) {
+          if (DIRECT) wa[r][s].u = gather_w(r, c * 64 + s * 8, false);
+          else wa[r][s].u = ok ? *(const uint4*)(wrow + (size_t)r * 32 * d + c * 64 + s * 8) : make_uint4(0, 0, 0, 0);
+        }
       }
     }
   };
@@ -436,16 +459,19 @@ hipError_t launch_gate(const void* x, const void* wg, int N, int d, int E, int k
     return hipGetLastError();
   }
   // small batches (a few waves per compute unit at most) and more than 64 experts: split-K kernel
-  hipLaunchKernelGGL(gate_transpose_wg_kernel, dim3((d + 255) / 256, epad), dim3(256), 0, s, (const bf16_t*)wg, d, E,
-                     epad, d, wgt);
   const dim3 block(kGateThreads);
   const dim3 grid((N + 31) / 32);
-  switch (nt) {
-    case 1: hipLaunchKernelGGL((gate_bf16_kernel<1, 1>), grid, block, 0, s, xb, wgt, N, d, E, k, idx, w); break;
-    case 2: hipLaunchKernelGGL((gate_bf16_kernel<2, 1>), grid, block, 0, s, xb, wgt, N, d, E, k, idx, w); break;
-    case 4: hipLaunchKernelGGL((gate_bf16_kernel<4, 1>), grid, block, 0, s, xb, wgt, N, d, E, k, idx, w); break;
-    default: hipLaunchKernelGGL((gate_bf16_kernel<8, 1>), grid, block, 0, s, xb, wgt, N, d, E, k, idx, w); break;
+  if (nt <= 2) {
+    // up to 64 experts: the fragments of W_g are gathered from the matrix as stored (one launch)
+    const bf16_t* wgb = (const bf16_t*)wg;
+    if (nt == 1) hipLaunchKernelGGL((gate_bf16_kernel<1, 1, true>), grid, block, 0, s, xb, wgb, N, d, E, k, idx, w);
+    else hipLaunchKernelGGL((gate_bf16_kernel<2, 1, true>), grid, block, 0, s, xb, wgb, N, d, E, k, idx, w);
+    return hipGetLastError();
   }
+  hipLaunchKernelGGL(gate_transpose_wg_kernel, dim3((d + 255) / 256, epad), dim3(256), 0, s, (const bf16_t*)wg, d, E,
+                     epad, d, wgt);
+  if (nt == 4) hipLaunchKernelGGL((gate_bf16_kernel<4, 1, false>), grid, block, 0, s, xb, wgt, N, d, E, k, idx, w);
+  else hipLaunchKernelGGL((gate_bf16_kernel<8, 1, false>), grid, block, 0, s, xb, wgt, N, d, E, k, idx, w);
   return hipGetLastError();
 }
 
