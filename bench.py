@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per call of flexmoe_expert_ffn_fwd from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the
 # same counters' reading of a plain 1 GiB copy (summary and commands: profiles/*_hbm_traffic.txt).
-MEASURED_FFN_FWD_TRAFFIC_BYTES = {"bert": 657.4e6}
+MEASURED_FFN_FWD_TRAFFIC_BYTES = {"bert": 657.8e6}
 
 WORKLOAD_TEXT = {
     "tiny": "configs[0] tiny fp32 MoE layer, forward",
@@ -158,7 +158,7 @@ class StageTimers:
         return out
 
 
-def run_workload(name, steps, warmup, with_stages=True, fused=False):
+def run_workload(name, steps, warmup, with_stages=True, fused=False, variants=True):
     import torch
     r = Runner(name, fused=fused)
     cfg = r.cfg
@@ -173,7 +173,7 @@ def run_workload(name, steps, warmup, with_stages=True, fused=False):
     dt = time.perf_counter() - t0
     ms_per_step = dt / steps * 1e3
     out = dict(tokens_per_s=cfg.N / (dt / steps), ms_per_step=ms_per_step, fused=r.fused)
-    if not r.fused and not cfg.backward and r.L.gather_supported():
+    if variants and not r.fused and not cfg.backward and r.L.gather_supported():
         # the same forward pass with the permutation folded into the first expert GEMM (no Xp written):
         # reported beside the step, which keeps every stage as a call of its own
         r.fused = True
@@ -347,6 +347,9 @@ def main():
     ap.add_argument("--fused", action="store_true",
                     help="forward-only workloads: time the step with flexmoe_expert_ffn_fwd_gather instead of "
                          "flexmoe_permute + flexmoe_expert_ffn_fwd")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="do not also time the forward variants reported beside the step (fused permutation, no stored "
+                         "pre-activations): profiles then hold the step's own launches only")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device copy (calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -369,7 +372,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    r, res = run_workload(name, steps, warmup, fused=args.fused)
+    r, res = run_workload(name, steps, warmup, fused=args.fused, variants=not args.no_variants)
     cfg = r.cfg
     ffn = res["stages"]["ffn_fwd"]
     dom_ms = ffn["ms"]
