@@ -193,16 +193,21 @@ __global__ __launch_bounds__(kGateThreads) void gate_bf16_kernel(const bf16_t* _
           acc[ct][r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[r][s].v, xb[ct][s].v, acc[ct][r], 0, 0, 0);
   };
 
-  Frag xb0[CT][4], wa0[NT][4], xb1[CT][4], wa1[NT][4];
+  // kSets chunks of loads in flight per wave (register sets used in rotation): the kernel is bound by
+  // the latency of these round trips, so with few experts (small fragments) a third set pays
+  constexpr int kSets = NT <= 2 ? 3 : (NT == 8 ? 1 : 2);     // 256 experts: one set, or the fragments spill
+  Frag xb[kSets][CT][4], wa[kSets][NT][4];
   int c = wave;
-  if (c < nchunks) load_chunk(c, xb0, wa0);
-  for (; c < nchunks; c += 8) {              // two chunks per trip: the register sets alternate
-    if (c + 4 < nchunks) load_chunk(c + 4, xb1, wa1);
-    mma_chunk(xb0, wa0);
-    if (c + 4 < nchunks) {
-      if (c + 8 < nchunks) load_chunk(c + 8, xb0, wa0);
-      mma_chunk(xb1, wa1);
-    }
+#pragma unroll
+  for (int q = 0; q < kSets; ++q)
+    if (c + 4 * q < nchunks) load_chunk(c + 4 * q, xb[q], wa[q]);
+  for (; c < nchunks; c += 4 * kSets) {
+#pragma unroll
+    for (int q = 0; q < kSets; ++q)
+      if (c + 4 * q < nchunks) {
+        mma_chunk(xb[q], wa[q]);
+        if (c + 4 * (q + kSets) < nchunks) load_chunk(c + 4 * (q + kSets), xb[q], wa[q]);
+      }
   }
 
   // fixed-order sum of the four partial results: wave 3 writes, waves 2 and 1 add, wave 0 finishes
