@@ -535,10 +535,29 @@ __device__ __forceinline__ void rows_tile(bf16_t* smem, const bf16_t* __restrict
 // Returns false (for the whole workgroup) when the workgroup has no tile.
 struct RowTile {
   int row0, rows_valid, e, n0, cols_valid;
+  int seg, nseg, slot;        // K segment of a split tile (nseg > 1) and its partial-tile slot
 };
+// Splitting the last, partly filled round of workgroups along K (plain-epilogue products with a long
+// contraction).  With T valid tiles on 256 compute units, the tiles of the row tiles from
+// r_split = floor(floor(T / 256) * 256 / col_tiles) on are the ones left for that last round; when
+// they fill at most a quarter of the chip, each is contracted by S = 4 workgroups (K segments of equal
+// length, a whole number of pipeline rounds each): segment 0 by the tile's own workgroup, segments
+// 1..S-1 by extra workgroups appended to the grid (block >= normal_grid).  Every segment leaves an
+// fp32 partial tile; rows_split_reduce_kernel adds them in segment order (fixed order: results do
+// not depend on scheduling).  The plan is a function of the bucket sizes: every workgroup derives
+// the same one.
+constexpr int kSplitMax = 4;
+constexpr int kSplitUnits = 256;                      // compute units a round of workgroups fills
+constexpr int kSplitMaxSlots = kSplitUnits;           // tail tiles x S <= 256
+struct SplitArg {
+  unsigned normal_grid;      // blocks of the unsplit grid; 0 = no splitting
+  int k_tiles;               // K / 32
+  int tail_tile;             // >= 0: look up this tail tile (reduce kernel) instead of `block`
+};
+template <bool SPLIT = false>
 __device__ __forceinline__ bool lookup_row_tile(const int32_t* __restrict__ voff, const int32_t* __restrict__ owner,
                                                 int V, int NC, int row_tiles_max, int col_tiles, unsigned block,
-                                                int* s_tile, RowTile* out) {
+                                                int* s_tile, RowTile* out, SplitArg sp = SplitArg{0, 0, -1}) {
   if (threadIdx.x < kWave) {
     const int lane = threadIdx.x;
     if (lane == 0) s_tile[0] = -1;
@@ -565,7 +584,36 @@ __device__ __forceinline__ bool lookup_row_tile(const int32_t* __restrict__ voff
       if (lane >= o) incl += up;
     }
     int rt = -1, ct = 0;
-    if (!patched_tile(block, row_tiles_max, col_tiles, &rt, &ct)) rt = -1;
+    int seg = 0, nseg = 1, slot = 0;
+    if (SPLIT && sp.normal_grid) {
+      const int rows_act = __shfl(incl, kWave - 1);
+      const int full = rows_act * col_tiles / kSplitUnits;
+      const int r_split = full * kSplitUnits / col_tiles;
+      const int tail_tiles = (rows_act - r_split) * col_tiles;
+      // four segments or none: cutting in two (tails of 65 to 128 tiles) measured no faster than not
+      // cutting, the fp32 round trip of the partial tiles eats what the shorter last round gains
+      const int S = (full >= 1 && tail_tiles > 0 && kSplitMax * tail_tiles <= kSplitUnits &&
+                     sp.k_tiles % (4 * kSplitMax) == 0) ? kSplitMax : 1;
+      if (sp.tail_tile < 0 && block < sp.normal_grid) {
+        if (!patched_tile(block, row_tiles_max, col_tiles, &rt, &ct)) rt = -1;
+        if (S > 1 && rt >= r_split && rt < rows_act) {
+          nseg = S;
+          slot = ((rt - r_split) * col_tiles + ct) * S;
+        }
+      } else if (S > 1) {
+        const int x = sp.tail_tile >= 0 ? sp.tail_tile * (S - 1) : (int)(block - sp.normal_grid);
+        const int tt = x / (S - 1);
+        if (tt < tail_tiles) {
+          rt = r_split + tt / col_tiles;
+          ct = tt % col_tiles;
+          nseg = S;
+          seg = 1 + x % (S - 1);
+          slot = tt * S + seg;
+        }
+      }
+    } else {
+      if (!patched_tile(block, row_tiles_max, col_tiles, &rt, &ct)) rt = -1;
+    }
     int start = incl - sum;
 #pragma unroll
     for (int q = 0; q < FLEXMOE_MAX_VEXPERTS / kWave; ++q) {
@@ -575,6 +623,11 @@ __device__ __forceinline__ bool lookup_row_tile(const int32_t* __restrict__ voff
         s_tile[1] = min(BM, hi[q] - row0);
         s_tile[2] = own[q];
         s_tile[3] = ct;
+        if (SPLIT) {
+          s_tile[4] = seg;
+          s_tile[5] = nseg;
+          s_tile[6] = slot;
+        }
       }
       start += cnt[q];
     }
@@ -587,6 +640,9 @@ __device__ __forceinline__ bool lookup_row_tile(const int32_t* __restrict__ voff
   out->e = __builtin_amdgcn_readfirstlane(s_tile[2]);
   out->n0 = __builtin_amdgcn_readfirstlane(s_tile[3] * BN);
   out->cols_valid = min(BN, NC - out->n0);
+  out->seg = SPLIT ? __builtin_amdgcn_readfirstlane(s_tile[4]) : 0;
+  out->nseg = SPLIT ? __builtin_amdgcn_readfirstlane(s_tile[5]) : 1;
+  out->slot = SPLIT ? __builtin_amdgcn_readfirstlane(s_tile[6]) : 0;
   return true;
 }
 
@@ -850,7 +906,8 @@ __device__ __forceinline__ void rows_dma_body(lds_byte_t* s0, lds_byte_t* s1, ld
                                               const bf16_t* __restrict__ bias, int K, int NC,
                                               const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
                                               bf16_t* __restrict__ out1, const lds_byte_t* lut,
-                                              const int32_t* __restrict__ gsrc, int gk) {
+                                              const int32_t* __restrict__ gsrc, int gk,
+                                              float* __restrict__ split_partial = nullptr) {
   const int wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   DmaSrc a_src;
@@ -858,6 +915,26 @@ __device__ __forceinline__ void rows_dma_body(lds_byte_t* s0, lds_byte_t* s1, ld
   else a_src.init(in + (size_t)t.row0 * K, K, t.rows_valid);
   f32x16 acc[MB][NB];
   zero_acc(acc);
+  if (EPI == EPI_PLAIN && t.nseg > 1) {
+    // one K segment of a split tile: fp32 partial tile (all 256 x 256 entries) for the reduce kernel
+    const int kt = K / DK / t.nseg;
+    RowsIssue<WSrc> issue{a_src, w_src, t.seg * kt * DK};
+    dma_pipeline<false, !WT>(s0, s1, s2, s3, acc, issue, kt, wm, wn);
+    float* out = split_partial + (size_t)t.slot * (BM * BN);
+    float* patch = (float*)s0 + wave * (32 * 64);
+    float* patch_alt = (float*)s1 + wave * (32 * 64);
+    epilogue_rounds<false>(
+        patch, patch_alt, acc, [](int, int) { return make_uint2(0, 0); },
+        [](int, int, float4 c, uint2) {
+          return EpiOut{make_uint2(__float_as_uint(c.x), __float_as_uint(c.y)),
+                        make_uint2(__float_as_uint(c.z), __float_as_uint(c.w))};
+        },
+        [&](int row_w, int col_w, const EpiOut& o) {
+          const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
+          *(uint4*)(out + lrow * BN + wn * (NB * 32) + col_w) = make_uint4(o.a.x, o.a.y, o.b.x, o.b.y);
+        });
+    return;
+  }
   RowsIssue<WSrc> issue{a_src, w_src, 0};
   dma_pipeline<false, !WT>(s0, s1, s2, s3, acc, issue, K / DK, wm, wn);   // K % 128 == 0 (host check)
   rows_epilogue<EPI, ACT, epilogue_uses_lut<EPI, ACT>()>((float*)s0, (float*)s1, acc, bias, NC, t.row0, t.rows_valid, t.e, t.n0, hpre_in, out0,
@@ -877,6 +954,8 @@ struct RowsDmaArgs {
   bf16_t* out1;
   const int32_t* gsrc;
   int gk;
+  float* split_partial;      // fp32 partial tiles of split tail tiles, or null: no splitting
+  unsigned normal_grid;      // blocks before the extra segment workgroups (meaningful with split_partial)
 };
 
 // One workgroup's tile of a rows GEMM; `block` is its index in that GEMM's (patched) grid.
@@ -885,7 +964,12 @@ __device__ __forceinline__ void rows_dma_block(const RowsDmaArgs& p, unsigned bl
                                                lds_byte_t* s2, lds_byte_t* s3, unsigned char* lut_lds, int* s_tile) {
   constexpr bool kLut = epilogue_uses_lut<EPI, ACT>();
   RowTile t;
-  if (!lookup_row_tile(p.voff, p.owner, p.V, p.NC, p.row_tiles_max, p.col_tiles, block, s_tile, &t)) return;
+  if (EPI == EPI_PLAIN) {
+    const SplitArg sp{p.split_partial ? p.normal_grid : 0u, p.K / DK, -1};
+    if (!lookup_row_tile<true>(p.voff, p.owner, p.V, p.NC, p.row_tiles_max, p.col_tiles, block, s_tile, &t, sp)) return;
+  } else {
+    if (!lookup_row_tile(p.voff, p.owner, p.V, p.NC, p.row_tiles_max, p.col_tiles, block, s_tile, &t)) return;
+  }
   const lds_byte_t* lut = nullptr;
   if (kLut) {
     // the table rides in front of the operand tiles: its direct loads are the oldest in every
@@ -906,12 +990,12 @@ __device__ __forceinline__ void rows_dma_block(const RowsDmaArgs& p, unsigned bl
     DmaSrc w_src;
     w_src.init(w_e + (size_t)t.n0 * p.K, p.K, t.cols_valid);
     rows_dma_body<true, DmaSrc, EPI, ACT>(s0, s1, s2, s3, t, p.in, w_src, p.bias, p.K, p.NC, p.hpre_in, p.out0, p.out1,
-                                          lut, p.gsrc, p.gk);
+                                          lut, p.gsrc, p.gk, p.split_partial);
   } else {
     DmaSrcT w_src;
     w_src.init(w_e + t.n0, p.NC, t.cols_valid);
     rows_dma_body<false, DmaSrcT, EPI, ACT>(s0, s1, s2, s3, t, p.in, w_src, p.bias, p.K, p.NC, p.hpre_in, p.out0,
-                                            p.out1, lut, p.gsrc, p.gk);
+                                            p.out1, lut, p.gsrc, p.gk, p.split_partial);
   }
 }
 
@@ -922,9 +1006,52 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_dma_bf16(const RowsDma
   __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char stage3[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char lut_lds[epilogue_uses_lut<EPI, ACT>() ? kLutBytes : 16];
-  __shared__ int s_tile[4];
+  __shared__ int s_tile[8];
   rows_dma_block<WT, EPI, ACT>(p, blockIdx.x, (lds_byte_t*)stage0, (lds_byte_t*)stage1, (lds_byte_t*)stage2,
                                (lds_byte_t*)stage3, lut_lds, s_tile);
+}
+
+// Sum of the K segments of the split tail tiles (see lookup_row_tile): out = bf16(sum over
+// segments in order + bias).  Grid: (kSplitSlices row slices of a tile, kSplitUnits / kSplitMax tail tiles).
+constexpr int kSplitSlices = 16;
+__global__ __launch_bounds__(kGemmThreads) void rows_split_reduce_kernel(const RowsDmaArgs p) {
+  __shared__ int s_tile[8];
+  RowTile t;
+  const SplitArg sp{p.normal_grid, p.K / DK, (int)blockIdx.y};
+  if (!lookup_row_tile<true>(p.voff, p.owner, p.V, p.NC, p.row_tiles_max, p.col_tiles, 0u, s_tile, &t, sp)) return;
+  const float* part = p.split_partial + (size_t)(t.slot - t.seg) * (BM * BN);     // slot of segment 0
+  constexpr int kRows = BM / kSplitSlices;                                        // rows per block
+  constexpr int kIters = kRows * (BN / 4) / kGemmThreads;
+  const int r0 = blockIdx.x * kRows;
+  if (r0 >= t.rows_valid) return;
+  float4 v[kIters][kSplitMax];
+#pragma unroll
+  for (int it = 0; it < kIters; ++it) {
+    const int i4 = it * kGemmThreads + threadIdx.x;
+    const int off = (r0 + i4 / (BN / 4)) * BN + (i4 % (BN / 4)) * 4;
+#pragma unroll
+    for (int sg = 0; sg < kSplitMax; ++sg)
+      if (sg < t.nseg) v[it][sg] = *(const float4*)(part + (size_t)sg * (BM * BN) + off);
+  }
+#pragma unroll
+  for (int it = 0; it < kIters; ++it) {
+    const int i4 = it * kGemmThreads + threadIdx.x;
+    const int row = r0 + i4 / (BN / 4), col = (i4 % (BN / 4)) * 4;
+    float4 acc = v[it][0];
+#pragma unroll
+    for (int sg = 1; sg < kSplitMax; ++sg)
+      if (sg < t.nseg) {
+        acc.x += v[it][sg].x; acc.y += v[it][sg].y; acc.z += v[it][sg].z; acc.w += v[it][sg].w;
+      }
+    if (row < t.rows_valid && col < t.cols_valid) {
+      if (p.bias) {
+        float b[4];
+        unpack4(*(const uint2*)(p.bias + (size_t)t.e * p.NC + t.n0 + col), b);
+        acc.x += b[0]; acc.y += b[1]; acc.z += b[2]; acc.w += b[3];
+      }
+      *(uint2*)(p.out0 + (size_t)(t.row0 + row) * p.NC + t.n0 + col) = pack4(acc.x, acc.y, acc.z, acc.w);
+    }
+  }
 }
 
 // Work list of the weight-gradient kernels.  Experts are taken by descending load (ties by
@@ -1232,7 +1359,7 @@ __global__ __launch_bounds__(kGemmThreads) void bwd_tail_dma_bf16(const RowsDmaA
   __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char stage3[kDmaStageBytes];
   __shared__ WgradShared sh;
-  __shared__ int s_tile[4];
+  __shared__ int s_tile[8];
   const unsigned b = blockIdx.x;
   if (b < n_dx)
     rows_dma_block<true, EPI_PLAIN, FLEXMOE_RELU>(dx, b, (lds_byte_t*)stage0, (lds_byte_t*)stage1, (lds_byte_t*)stage2,
@@ -1284,6 +1411,18 @@ static int wgrad_extra_segments(int A, int V, int seg_tiles) { return seg_tiles 
 static int wgrad_partial_slots(int A, int V, int seg_tiles) { return seg_tiles ? 2 * ((A / DK + V) / seg_tiles) + 1 : 0; }
 static size_t wgrad_table_bytes() { return FLEXMOE_MAX_EXPERTS * sizeof(int4); }
 
+static int max_row_tiles(int A, int V) { return A / BM + V; }
+
+// Partial tiles of the split last round (see lookup_row_tile): none for grids that can never fill a
+// round of workgroups or whose contraction is short (the fp32 round trip would cost more than the idle
+// compute units).
+constexpr int kSplitMinK = 1024;
+static size_t rows_split_bytes(int A, int V, int K, int NC) {
+  if (K % 128 || K < kSplitMinK) return 0;
+  if ((long long)max_row_tiles(A, V) * ((NC + BN - 1) / BN) <= kSplitUnits) return 0;
+  return (size_t)kSplitMaxSlots * BM * BN * sizeof(float);
+}
+
 // Job table + fp32 partial tiles of one segmented weight-gradient product (0 when not segmented).
 static size_t wgrad_tail_bytes(int A, int d, int f, int V) {
   const int seg_tiles = wgrad_seg_tiles(A, d, f);
@@ -1294,15 +1433,20 @@ static size_t wgrad_tail_bytes(int A, int d, int f, int V) {
 size_t ffn_ws_bytes(int A, int d, int f, int E, int V, int dtype) {
   const size_t s = dtype == FLEXMOE_BF16 ? 2 : 4;
   size_t need = align_up((size_t)A * f * s, 256) * 2;      // dHpre (or H in forward) + H
-  if (dtype == FLEXMOE_BF16) need += 2 * wgrad_tail_bytes(A, d, f, V);      // one region per weight gradient
+  if (dtype == FLEXMOE_BF16) {
+    need += 2 * wgrad_tail_bytes(A, d, f, V);      // one region per weight gradient
+    need += rows_split_bytes(A, V, f, d);          // GEMM2 / dXp: partial tiles of the split last round
+  }
   return need;
+}
+static void* rows_split_ws(const FfnArgs& a, void* ws) {
+  return (char*)ws + 2 * align_up((size_t)a.A * a.f * sizeof(bf16_t), 256) + 2 * wgrad_tail_bytes(a.A, a.d, a.f, a.V);
 }
 
 template <typename Kern> static hipError_t allow_big_lds(Kern kern) {
   return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLds);
 }
 
-static int max_row_tiles(int A, int V) { return A / BM + V; }
 
 // Fills the activation tables of the current device the first time a kernel that reads them is
 // launched there.  The fill runs on the caller's stream and is waited for before the device is
@@ -1332,12 +1476,13 @@ static RowsDmaArgs rows_dma_args(const FfnArgs& a, const void* in, const void* w
                                  const void* hpre_in, void* out0, void* out1, const int32_t* gsrc, int gk) {
   return RowsDmaArgs{(const bf16_t*)in, (const bf16_t*)w, (const bf16_t*)bias, a.voff, a.owner, a.V, K, NC,
                      max_row_tiles(a.A, a.V), (NC + BN - 1) / BN, (const bf16_t*)hpre_in, (bf16_t*)out0,
-                     (bf16_t*)out1, gsrc, gk};
+                     (bf16_t*)out1, gsrc, gk, nullptr, 0u};
 }
 
 template <bool WT, int EPI, int ACT>
 static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w, const void* bias, int K, int NC,
-                                const void* hpre_in, void* out0, void* out1, hipStream_t s, const int32_t* gsrc, int gk) {
+                                const void* hpre_in, void* out0, void* out1, hipStream_t s, const int32_t* gsrc, int gk,
+                                void* split_ws) {
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t err = allow_big_lds(rows_gemm_bf16<WT, EPI, ACT>);
@@ -1353,7 +1498,16 @@ static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w,
       hipError_t err = ensure_act_lut(s);
       if (err != hipSuccess) return err;
     }
-    const RowsDmaArgs p = rows_dma_args(a, in, w, bias, K, NC, hpre_in, out0, out1, gsrc, gk);
+    RowsDmaArgs p = rows_dma_args(a, in, w, bias, K, NC, hpre_in, out0, out1, gsrc, gk);
+    if (EPI == EPI_PLAIN && split_ws && rows_split_bytes(a.A, a.V, K, NC)) {
+      // the last, partly filled round of workgroups is cut along K: extra workgroups for the further
+      // segments behind the normal grid, then the sum of the partial tiles
+      p.split_partial = (float*)split_ws;
+      p.normal_grid = grid;
+      hipLaunchKernelGGL((rows_gemm_dma_bf16<WT, EPI, ACT>), dim3(grid + kSplitUnits), dim3(kGemmThreads), 0, s, p);
+      hipLaunchKernelGGL(rows_split_reduce_kernel, dim3(kSplitSlices, kSplitUnits / kSplitMax), dim3(kGemmThreads), 0, s, p);
+      return hipGetLastError();
+    }
     hipLaunchKernelGGL((rows_gemm_dma_bf16<WT, EPI, ACT>), dim3(grid), dim3(kGemmThreads), 0, s, p);
     return hipGetLastError();
   }
@@ -1367,16 +1521,16 @@ static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w,
 template <bool WT, int EPI>
 static hipError_t launch_rows(const FfnArgs& a, const void* in, const void* w, const void* bias, int K, int NC,
                               const void* hpre_in, void* out0, void* out1, hipStream_t s,
-                              const int32_t* gsrc = nullptr, int gk = 1) {
+                              const int32_t* gsrc = nullptr, int gk = 1, void* split_ws = nullptr) {
   if (EPI == EPI_PLAIN)
-    return launch_rows_t<WT, EPI, FLEXMOE_RELU>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk);
+    return launch_rows_t<WT, EPI, FLEXMOE_RELU>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, split_ws);
   switch (a.act) {
     case FLEXMOE_RELU:
-      return launch_rows_t<WT, EPI, FLEXMOE_RELU>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk);
+      return launch_rows_t<WT, EPI, FLEXMOE_RELU>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, nullptr);
     case FLEXMOE_GELU_ERF:
-      return launch_rows_t<WT, EPI, FLEXMOE_GELU_ERF>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk);
+      return launch_rows_t<WT, EPI, FLEXMOE_GELU_ERF>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, nullptr);
     default:
-      return launch_rows_t<WT, EPI, FLEXMOE_GELU_TANH>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk);
+      return launch_rows_t<WT, EPI, FLEXMOE_GELU_TANH>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, nullptr);
   }
 }
 
@@ -1416,7 +1570,7 @@ hipError_t launch_ffn_fwd_bf16(const FfnArgs& a, const void* xp, const void* w1,
   void* h = ws;
   hipError_t err = launch_rows<false, EPI_FWD1>(a, xp, w1, b1, a.d, a.f, nullptr, hpre, h, s);
   if (err != hipSuccess) return err;
-  return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, yp, nullptr, s);
+  return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, yp, nullptr, s, nullptr, 1, rows_split_ws(a, ws));
 }
 
 // Forward with the expert-wise layout transformation folded into GEMM1's row loads: bucket row p
@@ -1428,7 +1582,7 @@ hipError_t launch_ffn_fwd_gather_bf16(const FfnArgs& a, const void* x, const int
   void* h = ws;
   hipError_t err = launch_rows<false, EPI_FWD1>(a, x, w1, b1, a.d, a.f, nullptr, hpre, h, s, src, k);
   if (err != hipSuccess) return err;
-  return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, yp, nullptr, s);
+  return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, yp, nullptr, s, nullptr, 1, rows_split_ws(a, ws));
 }
 
 hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp, const void* hpre, const void* w1,
@@ -1463,7 +1617,8 @@ hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp
   }
   if (a.A > 0) {
     // dXp = dHpre . W1^T; W1_e is [d, f], contraction index f contiguous
-    err = launch_rows<true, EPI_PLAIN>(a, dhpre, w1, nullptr, a.f, a.d, nullptr, dxp, nullptr, s);
+    err = launch_rows<true, EPI_PLAIN>(a, dhpre, w1, nullptr, a.f, a.d, nullptr, dxp, nullptr, s, nullptr, 1,
+                                       rows_split_ws(a, ws));
     if (err != hipSuccess) return err;
   }
   err = launch_wgrad(a, h, dyp, a.f, a.d, dw2, ws_tail2, s);

@@ -189,6 +189,10 @@ SMALL = {
     # the same with enough tokens (A/32 >= 128 K tiles) that the hot experts' weight-gradient contraction is
     # cut into segments (fp32 partial tiles + reduce kernel) inside the shared dXp/dW2/dW1 launch
     "gpt_dma_seg": W.scaled(W.CONFIGS["gpt_m"], N=2300, d=384, f=640, E=8, V=13, max_rep=4),
+    # more than one round of workgroups in the second forward product (66000 rows, one column tile -> about 265
+    # tiles for 256 compute units) and a long contraction: the tiles left for the last round are cut along K
+    # into four segments (fp32 partial tiles + reduce kernel)
+    "split_tail": W.scaled(W.CONFIGS["swin"], N=66000, d=128, f=1024, E=8, V=12, max_rep=4, backward=False),
 }
 
 
