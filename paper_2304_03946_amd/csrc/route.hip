@@ -135,6 +135,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_assign_kernel(
         int c = hist[(size_t)u * E + e];
         tot += c;
         if (u < u0) pre += c;
+        else if (u < u0 + kRouteWaves) wbase[u - u0][e] = c;     // this block's own units: kept for the wave bases
       }
     part_tot[tid] = tot;
     part_pre[tid] = pre;
@@ -149,8 +150,9 @@ __global__ __launch_bounds__(kRouteThreads) void route_assign_kernel(
     }
     int run = pre;
     for (int ww = 0; ww < kRouteWaves; ++ww) {
+      const int own = (u0 + ww < units) ? wbase[ww][e] : 0;       // histogram of unit u0 + ww, left there above
       wbase[ww][e] = run;
-      if (u0 + ww < units) run += hist[(size_t)(u0 + ww) * E + e];
+      run += own;
     }
     split_expert(e, tot, roff, rids, eq, em, vcount, vstart, vexpert_owner, blockIdx.x == 0);
     if (blockIdx.x == 0) expert_count[e] = tot;
@@ -161,18 +163,23 @@ __global__ __launch_bounds__(kRouteThreads) void route_assign_kernel(
   {
     const int a0 = (2 * tid < V) ? vcount[2 * tid] : 0;
     const int a1 = (2 * tid + 1 < V) ? vcount[2 * tid + 1] : 0;
-    scan[tid] = a0 + a1;
-    __syncthreads();
-    for (int s = 1; s < kRouteThreads; s <<= 1) {
-      int add = (tid >= s) ? scan[tid - s] : 0;
-      __syncthreads();
-      scan[tid] += add;
-      __syncthreads();
+    // inclusive scan inside each wave by shuffles, then the waves' totals through LDS
+    int incl = a0 + a1;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const int up = __shfl_up(incl, o);
+      if (lane >= o) incl += up;
     }
-    const int excl = scan[tid] - (a0 + a1);
+    if (lane == kWave - 1) scan[w] = incl;
+    __syncthreads();
+    int before = 0;
+#pragma unroll
+    for (int ww = 0; ww < kRouteWaves; ++ww)
+      if (ww < w) before += scan[ww];
+    const int excl = before + incl - (a0 + a1);
     if (2 * tid < V) voff[2 * tid] = excl;
     if (2 * tid + 1 < V) voff[2 * tid + 1] = excl + a0;
-    if (tid == kRouteThreads - 1) voff[V] = scan[tid];   // == A for valid input
+    if (tid == kRouteThreads - 1) voff[V] = before + incl;   // == A for valid input
   }
   __syncthreads();
   if (blockIdx.x == 0) {
