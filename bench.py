@@ -248,6 +248,33 @@ def copy_ceiling_gbs(nbytes=1 << 28, reps=20):
     return round(2 * nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
 
 
+def dense_gemm_ceiling_tflops(name, reps=10):
+    """What the vendor library reaches on this machine for the layer's two forward products taken as
+    plain dense GEMMs (all A rows against one expert's weights, no buckets, no fused epilogue):
+    torch.matmul in bf16.  A practical ceiling beside the 2.5 PFLOP/s peak, not part of the path."""
+    import torch
+    from paper_2304_03946_amd import workloads as W
+    cfg = W.CONFIGS[name]
+    if cfg.dtype != W.DT_BF16:
+        return None
+    out = {}
+    for tag, (m, k, n) in {"gemm1": (cfg.A, cfg.d, cfg.f), "gemm2": (cfg.A, cfg.f, cfg.d)}.items():
+        a = torch.randn((m, k), device="cuda", dtype=torch.float32).mul_(0.5).to(torch.bfloat16)
+        b = torch.randn((k, n), device="cuda", dtype=torch.float32).mul_(0.02).to(torch.bfloat16)
+        c = torch.empty((m, n), device="cuda", dtype=torch.bfloat16)
+        for _ in range(3):
+            torch.matmul(a, b, out=c)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            torch.matmul(a, b, out=c)
+        e1.record()
+        torch.cuda.synchronize()
+        out[tag] = round(2.0 * m * k * n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+        del a, b, c
+    return out
+
+
 def time_extras(r, steps):
     """The gate-path backward and the bias gradients (what a trainable layer needs beyond the hot
     path), timed on their own after a step has left its state in the layer's buffers; not part of
@@ -404,6 +431,8 @@ def main():
     }
     if args.all_workloads:
         line["copy_ceiling_GBs"] = {"256MiB": copy_ceiling_gbs(1 << 28), "32MiB": copy_ceiling_gbs(1 << 25, 100)}
+        torch.cuda.empty_cache()
+        line["dense_gemm_ceiling_TFLOPs"] = {w: dense_gemm_ceiling_tflops(w) for w in ("bert", "gpt_m", "swin", "gpt_xl")}
         others = {}
         for other in ("gpt_m", "swin", "gpt_xl", "bert", "tiny"):
             if other == name:
