@@ -309,6 +309,30 @@ def time_extras(r, steps):
         ms = e0.elapsed_time(e1) / steps
         out[name] = dict(ms=round(ms, 4), bound="hbm", achieved=round(nbytes / (ms * 1e-3) / 1e9, 1), unit="GB/s",
                          frac=round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
+    if L.top1_supported():
+        # top-1 layer, forward only: the staged expert path (permute, FFN, combine) against the one call that
+        # gathers on load and scatters on store (flexmoe_expert_ffn_fwd_top1); gate and route are the same
+        def staged():
+            B.flexmoe_permute(r.x, L.src, None, cfg.k, L.xp)
+            B.flexmoe_expert_ffn_fwd(L.xp, L.vexpert_off, L.vexpert_owner, r.w1, None, r.w2, None, cfg.act, L.hpre,
+                                     L.yp, L.ws)
+            B.flexmoe_combine(L.yp, L.dest, L.topk_w, cfg.k, L.y)
+
+        def fused():
+            B.flexmoe_expert_ffn_fwd_top1(r.x, L.src, L.vexpert_off, L.vexpert_owner, r.w1, None, r.w2, None, cfg.act,
+                                          L.hpre, L.y, L.ws)
+        for name, fn in (("forward_expert_path_staged", staged), ("forward_expert_path_top1_call", fused)):
+            fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / steps
+            flops = 4.0 * cfg.A * cfg.d * cfg.f
+            out[name] = dict(ms=round(ms, 4), bound="mfma", achieved=round(flops / (ms * 1e-3) / 1e12, 1), unit="TFLOP/s",
+                             frac=round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4))
     return out
 
 
@@ -429,6 +453,8 @@ def main():
                      "launch_ms": dom_ms, "algorithmic_flops": 4 * cfg.A * cfg.d * cfg.f,
                      "stages": res["stages"]},
     }
+    if "trainable_layer_extras" in res:
+        line["trainable_layer_extras"] = res["trainable_layer_extras"]
     if args.all_workloads:
         line["copy_ceiling_GBs"] = {"256MiB": copy_ceiling_gbs(1 << 28), "32MiB": copy_ceiling_gbs(1 << 25, 100)}
         torch.cuda.empty_cache()

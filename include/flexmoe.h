@@ -155,6 +155,22 @@ int flexmoe_expert_ffn_fwd_gather(const void* x, const int32_t* src, const int32
                                   void* hpre, void* yp, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The expert path of a top-1 layer (k = 1) in one call, without xp and yp: bucket row p is read as row
+ * src[p] of x while the first product's tiles are loaded, and the second product's rows are stored
+ * straight to y[src[p], :] (Section 4's layout transformation and the reverse routing of Eq. 4 folded
+ * into the expert computation; with one expert per token the gate value is exactly 1).  Same y as
+ * flexmoe_permute + flexmoe_expert_ffn_fwd + flexmoe_combine, bit for bit.
+ *   x [N,d], src [N] as written by flexmoe_route with k = 1 -> hpre [N,f] (may be NULL), y [N,d].
+ * For forward-only use.  FLEXMOE_UNSUPPORTED unless dtype is bf16, d and f are multiples of 128 and
+ * N*d < 2^32.
+ */
+int flexmoe_expert_ffn_fwd_top1(const void* x, const int32_t* src, const int32_t* vexpert_off,
+                                const int32_t* vexpert_owner, const void* w1, const void* b1,
+                                const void* w2, const void* b2,
+                                int N, int d, int f, int E, int V, int act, int dtype,
+                                void* hpre, void* y, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Backward of the gate path (Eq. 3-4; the logits are x . W_g, the top-k kept, softmax over the
  * kept ones) for an upstream gradient dy of the layer output.  Completes a trainable layer
  * together with flexmoe_expert_ffn_bwd, which treats the gate values as constants.

@@ -154,6 +154,22 @@ int flexmoe_expert_ffn_fwd_gather(const void* x, const int32_t* src, const int32
   return dev_status(launch_ffn_fwd_gather_bf16(a, x, src, k, w1, b1, w2, b2, hpre, yp, ws, (hipStream_t)stream));
 }
 
+int flexmoe_expert_ffn_fwd_top1(const void* x, const int32_t* src, const int32_t* vexpert_off,
+                                const int32_t* vexpert_owner, const void* w1, const void* b1, const void* w2,
+                                const void* b2, int N, int d, int f, int E, int V, int act, int dtype,
+                                void* hpre, void* y, void* ws, size_t ws_bytes, void* stream) {
+  if (N < 0 || N >= (1 << 30)) return FLEXMOE_INVALID_ARG;
+  const int st = ffn_common(N, d, f, E, V, act, dtype, vexpert_off, vexpert_owner, ws, ws_bytes);
+  if (st != FLEXMOE_OK) return st;
+  // gathered loads and scattered stores exist on the bf16 direct-to-LDS path only; row offsets are 32-bit
+  if (dtype != FLEXMOE_BF16 || (d % 128) || (f % 128) || (long long)N * d >= (1ll << 32)) return FLEXMOE_UNSUPPORTED;
+  if (!w1 || !w2 || !aligned16(w1) || !aligned16(w2) || !aligned16(b1) || !aligned16(b2)) return FLEXMOE_INVALID_ARG;
+  if (N > 0 && (!x || !src || !y || !aligned16(x) || !aligned16(hpre) || !aligned16(y)))    // hpre may be NULL
+    return FLEXMOE_INVALID_ARG;
+  const FfnArgs a{N, d, f, E, V, act, vexpert_off, vexpert_owner};
+  return dev_status(launch_ffn_fwd_top1_bf16(a, x, src, w1, b1, w2, b2, hpre, y, ws, (hipStream_t)stream));
+}
+
 int flexmoe_expert_ffn_bwd(const void* dyp, const void* xp, const void* hpre, const void* w1, const void* w2,
                            const int32_t* vexpert_off, const int32_t* vexpert_owner, int A, int d, int f, int E, int V,
                            int act, int dtype, void* dxp, void* dw1, void* dw2, void* ws, size_t ws_bytes,

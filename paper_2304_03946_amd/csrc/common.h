@@ -159,6 +159,8 @@ hipError_t launch_ffn_fwd_bf16(const FfnArgs& a, const void* xp, const void* w1,
 hipError_t launch_ffn_fwd_gather_bf16(const FfnArgs& a, const void* x, const int32_t* src, int k, const void* w1,
                                       const void* b1, const void* w2, const void* b2, void* hpre, void* yp, void* ws,
                                       hipStream_t s);
+hipError_t launch_ffn_fwd_top1_bf16(const FfnArgs& a, const void* x, const int32_t* src, const void* w1, const void* b1,
+                                    const void* w2, const void* b2, void* hpre, void* y, void* ws, hipStream_t s);
 hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp, const void* hpre,
                                const void* w1, const void* w2, void* dxp, void* dw1, void* dw2,
                                void* ws, hipStream_t s);

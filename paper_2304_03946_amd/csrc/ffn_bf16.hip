@@ -256,6 +256,7 @@ __global__ void act_lut_init_kernel() {
 
 // Table entry for the bf16 value whose fp32 bit pattern is zu (LDS copy of one table).
 typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+typedef __attribute__((address_space(3))) int lds_int_t;
 __device__ __forceinline__ uint32_t lut_offset(uint32_t zu) {
   const uint32_t m = (zu >> 16) & 0x7fffu;
   return (min(max(m, (uint32_t)kLutLo), (uint32_t)kLutHi) - kLutLo) << 3;
@@ -440,7 +441,8 @@ template <int EPI, int ACT, bool LUT, bool BIAS>
 __device__ __forceinline__ void rows_epilogue_t(float* lds, float* lds_alt, const f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ bias,
                                                 int NC, int row0, int rows_valid, int e, int n0,
                                                 const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
-                                                bf16_t* __restrict__ out1, const lds_byte_t* lut) {
+                                                bf16_t* __restrict__ out1, const lds_byte_t* lut,
+                                                const lds_int_t* smap) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   float* patch = lds + wave * (32 * 64);
@@ -495,7 +497,10 @@ __device__ __forceinline__ void rows_epilogue_t(float* lds, float* lds_alt, cons
     const int lrow = tile_row(row_w);
     if (lrow < rows_valid && col_w < cols_left) {
       const uint32_t off = (uint32_t)(lrow * NC + col_w);
-      if (EPI != EPI_FWD1 || out0) *(uint2*)(out0_t + off) = o.a;     // forward: the pre-activations are optional
+      if (EPI == EPI_PLAIN && smap) {
+        // scattered store: tile row lrow is row smap[lrow] of the output (reverse routing of a top-1 layer)
+        *(uint2*)(out0 + (size_t)smap[lrow] * NC + col_base + col_w) = o.a;
+      } else if (EPI != EPI_FWD1 || out0) *(uint2*)(out0_t + off) = o.a;     // forward: the pre-activations are optional
       if (EPI != EPI_PLAIN) *(uint2*)(out1_t + off) = o.b;
     }
   };
@@ -506,9 +511,10 @@ template <int EPI, int ACT, bool LUT = false>
 __device__ __forceinline__ void rows_epilogue(float* lds, float* lds_alt, const f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ bias,
                                               int NC, int row0, int rows_valid, int e, int n0,
                                               const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
-                                              bf16_t* __restrict__ out1, const lds_byte_t* lut = nullptr) {
-  if (bias) rows_epilogue_t<EPI, ACT, LUT, true>(lds, lds_alt, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1, lut);
-  else rows_epilogue_t<EPI, ACT, LUT, false>(lds, lds_alt, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1, lut);
+                                              bf16_t* __restrict__ out1, const lds_byte_t* lut = nullptr,
+                                              const lds_int_t* smap = nullptr) {
+  if (bias) rows_epilogue_t<EPI, ACT, LUT, true>(lds, lds_alt, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1, lut, smap);
+  else rows_epilogue_t<EPI, ACT, LUT, false>(lds, lds_alt, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1, lut, smap);
 }
 
 // One output tile of rows_gemm: main loop and epilogue.  FULL = all eight 32-row blocks hold rows.
@@ -907,7 +913,8 @@ __device__ __forceinline__ void rows_dma_body(lds_byte_t* s0, lds_byte_t* s1, ld
                                               const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
                                               bf16_t* __restrict__ out1, const lds_byte_t* lut,
                                               const int32_t* __restrict__ gsrc, int gk,
-                                              float* __restrict__ split_partial = nullptr) {
+                                              float* __restrict__ split_partial = nullptr,
+                                              const int32_t* __restrict__ scatter_rows = nullptr) {
   const int wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   DmaSrc a_src;
@@ -937,8 +944,16 @@ __device__ __forceinline__ void rows_dma_body(lds_byte_t* s0, lds_byte_t* s1, ld
   }
   RowsIssue<WSrc> issue{a_src, w_src, 0};
   dma_pipeline<false, !WT>(s0, s1, s2, s3, acc, issue, K / DK, wm, wn);   // K % 128 == 0 (host check)
+  const lds_int_t* smap = nullptr;
+  if (EPI == EPI_PLAIN && scatter_rows) {
+    // output rows of this tile (the epilogue's patches live in stages 0 and 1; stage 2 is free)
+    lds_int_t* m = (lds_int_t*)s2;
+    m[threadIdx.x] = scatter_rows[t.row0 + min((int)threadIdx.x, t.rows_valid - 1)];
+    __syncthreads();
+    smap = m;
+  }
   rows_epilogue<EPI, ACT, epilogue_uses_lut<EPI, ACT>()>((float*)s0, (float*)s1, acc, bias, NC, t.row0, t.rows_valid, t.e, t.n0, hpre_in, out0,
-                                                          out1, lut);
+                                                          out1, lut, smap);
 }
 
 // Arguments of one rows GEMM (device pointers; see rows_gemm_dma_bf16).
@@ -956,6 +971,7 @@ struct RowsDmaArgs {
   int gk;
   float* split_partial;      // fp32 partial tiles of split tail tiles, or null: no splitting
   unsigned normal_grid;      // blocks before the extra segment workgroups (meaningful with split_partial)
+  const int32_t* scatter_rows;   // plain epilogue only: bucket row p is stored as output row scatter_rows[p]; or null
 };
 
 // One workgroup's tile of a rows GEMM; `block` is its index in that GEMM's (patched) grid.
@@ -990,12 +1006,12 @@ __device__ __forceinline__ void rows_dma_block(const RowsDmaArgs& p, unsigned bl
     DmaSrc w_src;
     w_src.init(w_e + (size_t)t.n0 * p.K, p.K, t.cols_valid);
     rows_dma_body<true, DmaSrc, EPI, ACT>(s0, s1, s2, s3, t, p.in, w_src, p.bias, p.K, p.NC, p.hpre_in, p.out0, p.out1,
-                                          lut, p.gsrc, p.gk, p.split_partial);
+                                          lut, p.gsrc, p.gk, p.split_partial, p.scatter_rows);
   } else {
     DmaSrcT w_src;
     w_src.init(w_e + t.n0, p.NC, t.cols_valid);
     rows_dma_body<false, DmaSrcT, EPI, ACT>(s0, s1, s2, s3, t, p.in, w_src, p.bias, p.K, p.NC, p.hpre_in, p.out0,
-                                            p.out1, lut, p.gsrc, p.gk, p.split_partial);
+                                            p.out1, lut, p.gsrc, p.gk, p.split_partial, p.scatter_rows);
   }
 }
 
@@ -1049,7 +1065,8 @@ __global__ __launch_bounds__(kGemmThreads) void rows_split_reduce_kernel(const R
         unpack4(*(const uint2*)(p.bias + (size_t)t.e * p.NC + t.n0 + col), b);
         acc.x += b[0]; acc.y += b[1]; acc.z += b[2]; acc.w += b[3];
       }
-      *(uint2*)(p.out0 + (size_t)(t.row0 + row) * p.NC + t.n0 + col) = pack4(acc.x, acc.y, acc.z, acc.w);
+      const size_t orow = p.scatter_rows ? (size_t)p.scatter_rows[t.row0 + row] : (size_t)(t.row0 + row);
+      *(uint2*)(p.out0 + orow * p.NC + t.n0 + col) = pack4(acc.x, acc.y, acc.z, acc.w);
     }
   }
 }
@@ -1476,13 +1493,13 @@ static RowsDmaArgs rows_dma_args(const FfnArgs& a, const void* in, const void* w
                                  const void* hpre_in, void* out0, void* out1, const int32_t* gsrc, int gk) {
   return RowsDmaArgs{(const bf16_t*)in, (const bf16_t*)w, (const bf16_t*)bias, a.voff, a.owner, a.V, K, NC,
                      max_row_tiles(a.A, a.V), (NC + BN - 1) / BN, (const bf16_t*)hpre_in, (bf16_t*)out0,
-                     (bf16_t*)out1, gsrc, gk, nullptr, 0u};
+                     (bf16_t*)out1, gsrc, gk, nullptr, 0u, nullptr};
 }
 
 template <bool WT, int EPI, int ACT>
 static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w, const void* bias, int K, int NC,
                                 const void* hpre_in, void* out0, void* out1, hipStream_t s, const int32_t* gsrc, int gk,
-                                void* split_ws) {
+                                void* split_ws, const int32_t* scatter_rows) {
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t err = allow_big_lds(rows_gemm_bf16<WT, EPI, ACT>);
@@ -1499,6 +1516,7 @@ static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w,
       if (err != hipSuccess) return err;
     }
     RowsDmaArgs p = rows_dma_args(a, in, w, bias, K, NC, hpre_in, out0, out1, gsrc, gk);
+    p.scatter_rows = scatter_rows;
     if (EPI == EPI_PLAIN && split_ws && rows_split_bytes(a.A, a.V, K, NC)) {
       // the last, partly filled round of workgroups is cut along K: extra workgroups for the further
       // segments behind the normal grid, then the sum of the partial tiles
@@ -1511,7 +1529,7 @@ static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w,
     hipLaunchKernelGGL((rows_gemm_dma_bf16<WT, EPI, ACT>), dim3(grid), dim3(kGemmThreads), 0, s, p);
     return hipGetLastError();
   }
-  if (gsrc) return hipErrorInvalidValue;      // gathered rows only on the direct-to-LDS path (host check upstream)
+  if (gsrc || scatter_rows) return hipErrorInvalidValue;   // gathered / scattered rows only on the direct-to-LDS path (host check upstream)
   hipLaunchKernelGGL((rows_gemm_bf16<WT, EPI, ACT>), dim3(grid), dim3(kGemmThreads), kGemmLds, s, (const bf16_t*)in,
                      (const bf16_t*)w, (const bf16_t*)bias, a.voff, a.owner, a.V, K, NC, row_tiles, col_tiles,
                      (const bf16_t*)hpre_in, (bf16_t*)out0, (bf16_t*)out1);
@@ -1521,16 +1539,18 @@ static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w,
 template <bool WT, int EPI>
 static hipError_t launch_rows(const FfnArgs& a, const void* in, const void* w, const void* bias, int K, int NC,
                               const void* hpre_in, void* out0, void* out1, hipStream_t s,
-                              const int32_t* gsrc = nullptr, int gk = 1, void* split_ws = nullptr) {
+                              const int32_t* gsrc = nullptr, int gk = 1, void* split_ws = nullptr,
+                              const int32_t* scatter_rows = nullptr) {
   if (EPI == EPI_PLAIN)
-    return launch_rows_t<WT, EPI, FLEXMOE_RELU>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, split_ws);
+    return launch_rows_t<WT, EPI, FLEXMOE_RELU>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, split_ws,
+                                                scatter_rows);
   switch (a.act) {
     case FLEXMOE_RELU:
-      return launch_rows_t<WT, EPI, FLEXMOE_RELU>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, nullptr);
+      return launch_rows_t<WT, EPI, FLEXMOE_RELU>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, nullptr, nullptr);
     case FLEXMOE_GELU_ERF:
-      return launch_rows_t<WT, EPI, FLEXMOE_GELU_ERF>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, nullptr);
+      return launch_rows_t<WT, EPI, FLEXMOE_GELU_ERF>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, nullptr, nullptr);
     default:
-      return launch_rows_t<WT, EPI, FLEXMOE_GELU_TANH>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, nullptr);
+      return launch_rows_t<WT, EPI, FLEXMOE_GELU_TANH>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, nullptr, nullptr);
   }
 }
 
@@ -1583,6 +1603,18 @@ hipError_t launch_ffn_fwd_gather_bf16(const FfnArgs& a, const void* x, const int
   hipError_t err = launch_rows<false, EPI_FWD1>(a, x, w1, b1, a.d, a.f, nullptr, hpre, h, s, src, k);
   if (err != hipSuccess) return err;
   return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, yp, nullptr, s, nullptr, 1, rows_split_ws(a, ws));
+}
+
+// The expert path of a top-1 layer without Xp and Yp: rows gathered through src on load (as above)
+// and the second product's rows stored straight to y[src[p], :] -- with one expert per token the gate
+// weight is exactly 1, so this is flexmoe_combine folded into the epilogue.  d and f multiples of 128.
+hipError_t launch_ffn_fwd_top1_bf16(const FfnArgs& a, const void* x, const int32_t* src, const void* w1, const void* b1,
+                                    const void* w2, const void* b2, void* hpre, void* y, void* ws, hipStream_t s) {
+  if (a.A == 0) return hipSuccess;
+  void* h = ws;
+  hipError_t err = launch_rows<false, EPI_FWD1>(a, x, w1, b1, a.d, a.f, nullptr, hpre, h, s, src, 1);
+  if (err != hipSuccess) return err;
+  return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, y, nullptr, s, nullptr, 1, rows_split_ws(a, ws), src);
 }
 
 hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp, const void* hpre, const void* w1,

@@ -112,6 +112,18 @@ class MoELayer:
         B.flexmoe_combine(self.yp, self.dest, self.topk_w, self.k, self.y)
         return self.y
 
+    def top1_supported(self) -> bool:
+        return self.k == 1 and self.gather_supported() and self.f % 128 == 0
+
+    def forward_top1(self, x, wg, w1, w2, rep_off, rep_ids, b1=None, b2=None, keep_hpre=True):
+        """Forward-only top-1 layer: gate, route and one expert call that reads x through src and
+        stores y through src (neither xp nor yp is written)."""
+        self.gate(x, wg)
+        self.route(rep_off, rep_ids)
+        B.flexmoe_expert_ffn_fwd_top1(x, self.src, self.vexpert_off, self.vexpert_owner, w1, b1, w2, b2, self.act,
+                                      self.hpre if keep_hpre else None, self.y, self.ws)
+        return self.y
+
     def backward(self, dy, w1, w2):
         B.flexmoe_permute(dy, self.src, self.topk_w, self.k, self.dyp)
         B.flexmoe_expert_ffn_bwd(self.dyp, self.xp, self.hpre, w1, w2, self.vexpert_off, self.vexpert_owner,

@@ -86,6 +86,18 @@ def test_full_config_sampled(api, name):
     y_ref = O.moe_layer_forward(xd[st], None, inp.w1, None, inp.w2, None, k, cfg.act, topk=(idx_gpu[st], w_gpu[st]))
     assert rel_err(host(L.y[torch.from_numpy(st).cuda()]), y_ref) <= tol, "layer output"
 
+    if L.top1_supported():
+        # top-1 layer: the one-call expert path (gather on load, scatter on store) gives the same y and hpre
+        print(f"[fullsize] {name}: top-1 fused expert path", flush=True)
+        want = {n: getattr(L, n).clone() for n in ("hpre", "y")}
+        for n in want:
+            getattr(L, n).zero_()
+        binding.flexmoe_expert_ffn_fwd_top1(dev["x"], L.src, L.vexpert_off, L.vexpert_owner, dev["w1"], None, dev["w2"],
+                                            None, cfg.act, L.hpre, L.y, L.ws)
+        torch.cuda.synchronize()
+        for n in want:
+            assert torch.equal(getattr(L, n), want[n]), f"top-1 fused forward: {n}"
+
     if not cfg.backward:
         # bench.py runs forward-only layers with the permutation folded into the first GEMM:
         # that call must reproduce the separate calls bit for bit

@@ -364,6 +364,38 @@ def test_forward_without_stored_preactivations(api, name):
         assert bool((L.hpre == 7.0).all()), "hpre must stay untouched"
 
 
+@pytest.mark.parametrize("bias", [False, True])
+def test_top1_forward_equals_the_staged_forward(api, bias):
+    """flexmoe_expert_ffn_fwd_top1 (rows gathered on load, results scattered on store) must give the y
+    of permute + FFN + combine bit for bit, and must not touch xp or yp."""
+    binding, layer_mod = api
+    cfg = SMALL["swin_small"]                       # k = 1, d = 256, f = 512
+    inp = W.make_layer_inputs(cfg)
+    dev = upload(layer_mod, inp)
+    rng = np.random.default_rng(5)
+    b1 = layer_mod.to_device(W.Bf16Tensor.from_f32((rng.standard_normal((cfg.E, cfg.f)) * 0.3).astype(np.float32))) if bias else None
+    b2 = layer_mod.to_device(W.Bf16Tensor.from_f32((rng.standard_normal((cfg.E, cfg.d)) * 0.3).astype(np.float32))) if bias else None
+    rep = W.placement_from_loads(W.prior_loads(cfg), cfg.V, cfg.max_rep, shuffle_seed=7)
+    L = layer_mod.MoELayer.for_config(cfg)
+    assert L.top1_supported()
+    L.forward(dev["x"], dev["wg"], dev["w1"], dev["w2"], *rep, b1, b2)
+    torch.cuda.synchronize()
+    want = {n: host(getattr(L, n)).copy() for n in ("hpre", "y")}
+    for t in (L.hpre, L.y, L.xp, L.yp):
+        t.zero_()
+    L.forward_top1(dev["x"], dev["wg"], dev["w1"], dev["w2"], *rep, b1, b2)
+    torch.cuda.synchronize()
+    for n in want:
+        assert np.array_equal(host(getattr(L, n)), want[n]), n
+    assert not host(L.xp).any() and not host(L.yp).any(), "the fused path must not touch xp or yp"
+    # inference form: no pre-activations either
+    L.y.zero_()
+    L.hpre.fill_(3.0)
+    L.forward_top1(dev["x"], dev["wg"], dev["w1"], dev["w2"], *rep, b1, b2, keep_hpre=False)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(L.y), want["y"]) and bool((L.hpre == 3.0).all())
+
+
 def test_gathered_forward_refuses_what_it_cannot_do(api):
     binding, layer_mod = api
     cfg = SMALL["bert_small"]                       # d = 328: not a multiple of 128
