@@ -1,0 +1,409 @@
+// Direct-to-LDS pipeline (global_load_lds) and the rows kernels built on it, incl. the split last round.
+// Part of the bf16 expert-FFN kernels; included by ffn_bf16.hip only (one translation unit).
+#pragma once
+#include "common.h"
+#include "ffn_bf16_tile.h"
+namespace flexmoe {
+// =============================================================================================
+// rows_gemm_dma: the same product for operands that are both contraction-contiguous
+// (In [rows, K], W_e [NC, K]) and K a multiple of 128, with global -> LDS direct loads
+// (global_load_lds, 16 bytes per lane, no register staging, no LDS store instructions).
+// Four LDS stages of a 32-wide K tile (2 x 16 KB each): while tile t is multiplied, tiles
+// t+1..t+3 are landed or in flight and tile t+4 is issued half-way through the step.  A direct load writes lane i's 16 bytes at
+// the wave's LDS base + 16*i, so one instruction fills 16 rows x 64 bytes; the bank swizzle
+// (16-byte chunk index XOR (row>>2)&3) is applied by choosing which global chunk a lane fetches.
+// =============================================================================================
+constexpr int DK = 32;
+constexpr int kDmaStages = 4;
+constexpr int kDmaTileBytes = 256 * DK * 2;            // one operand tile: 16 KB
+constexpr int kDmaStageBytes = 2 * kDmaTileBytes;      // A + B
+
+__device__ __forceinline__ int dma_off(int row, int c) { return row * (DK * 2) + ((c ^ ((row >> 2) & 3)) << 4); }
+
+struct DmaSrc {
+  const bf16_t* base;
+  uint32_t off[4];
+  __device__ __forceinline__ void init(const bf16_t* b, size_t ld, int rows_valid) {
+    base = b;
+    const int w = threadIdx.x >> 6, i = threadIdx.x & 63;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int row = (w * 4 + q) * 16 + (i >> 2);
+      const int c = (i & 3) ^ ((row >> 2) & 3);
+      off[q] = (uint32_t)(min(row, rows_valid - 1) * ld + c * 8);
+    }
+  }
+  // The same tile with its rows gathered: tile row r is row rows[r] / k of the matrix at b (the
+  // expert-wise layout transformation done on the fly: rows = the bucket's slice of `src`).
+  __device__ __forceinline__ void init_gather(const bf16_t* b, size_t ld, const int32_t* __restrict__ rows, int k,
+                                              int rows_valid) {
+    base = b;
+    const int w = threadIdx.x >> 6, i = threadIdx.x & 63;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int row = (w * 4 + q) * 16 + (i >> 2);
+      const int c = (i & 3) ^ ((row >> 2) & 3);
+      off[q] = (uint32_t)((size_t)(rows[min(row, rows_valid - 1)] / k) * ld + c * 8);
+    }
+  }
+  // Fills the 16 KB LDS tile at `tile` with K columns k0..k0+31 of the operand's 256 rows.
+  // The direct load is issued from inline assembly (M0 = LDS byte address of the wave's 1 KB
+  // slice, lane i lands at M0 + 16*i): the compiler's wait-count insertion cannot tell which LDS
+  // stage a direct load writes and would wait for every outstanding load before any LDS read;
+  // here the waits are placed by hand (wait_vmcnt_le) before the barrier that publishes a stage.
+  // q-th of the wave's four direct loads of one tile
+  __device__ __forceinline__ void part(lds_byte_t* tile, int k0, int q) const {
+    const unsigned w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)tile) + w * 4096;
+    const bf16_t* g = base + k0 + off[q];
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" FLEXMOE_DMA_CPOL ::"v"(g), "s"(lds0 + q * 1024) : "memory");
+  }
+};
+
+// Operand stored [K, ld] with the output index contiguous (the forward weights W_e [K, NC]): the
+// 32 x 256 tile is copied to LDS as it lies in memory, one k-row = 512 bytes = 32 chunks, two
+// k-rows per direct-load instruction, and transposed on the way out of LDS by ds_read_tr16_b64.
+// Chunk index XOR (k & 3) << 2 keeps those transposing reads free of bank conflicts.  Columns
+// past cols_valid are clamped to the last valid 8-column chunk.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ int dmat_chunk(int krow, int c) { return c ^ ((krow & 3) << 2); }
+
+struct DmaSrcT {
+  const bf16_t* base;     // first contraction row, first column of the tile
+  uint32_t off[4];
+  size_t ld;
+  __device__ __forceinline__ void init(const bf16_t* b, size_t ld_, int cols_valid) {
+    base = b;
+    ld = ld_;
+    const int w = threadIdx.x >> 6, i = threadIdx.x & 63;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int krow = (w * 4 + q) * 2 + (i >> 5);
+      const int c = min(dmat_chunk(krow, i & 31), cols_valid / 8 - 1);
+      off[q] = (uint32_t)(krow * ld + c * 8);
+    }
+  }
+  __device__ __forceinline__ void part(lds_byte_t* tile, int k0, int q) const {
+    const unsigned w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)tile) + w * 4096;
+    const bf16_t* g = base + (size_t)k0 * ld + off[q];
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" FLEXMOE_DMA_CPOL ::"v"(g), "s"(lds0 + q * 1024) : "memory");
+  }
+};
+
+// MFMA fragment (8 consecutive k of output column nb0 + lane%32, k = 16*ks + 8*(lane/32) ..) from
+// a [32 k][256 n] tile.  ds_read_tr16_b64 works on groups of 16 lanes: lanes 4m..4m+3 of a group
+// address 16 consecutive elements of row m (4 each) and lane i of the group receives column i of
+// those four rows.  So lane L (group g = L/16, i = L%16) points at row k' + i/4, columns
+// nb0 + 16*(g%2) + 4*(i%4), with k' = 16*ks + 8*(g/2) (+4 for the second read).
+__device__ __forceinline__ bf16x8 dmat_read_frag(const lds_byte_t* tile, int nb0, int ks) {
+  const int L = threadIdx.x & 63;
+  const int g = L >> 4, i = L & 15;
+  const int col = nb0 + 16 * (g & 1) + 4 * (i & 3);
+  const int k_lo = 16 * ks + 8 * (g >> 1) + (i >> 2);
+  const int k_hi = k_lo + 4;
+  const int a_lo = k_lo * 512 + (dmat_chunk(k_lo, col >> 3) << 4) + ((col & 7) << 1);
+  const int a_hi = k_hi * 512 + (dmat_chunk(k_hi, col >> 3) << 4) + ((col & 7) << 1);
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(tile + a_lo));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(tile + a_hi));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// s_waitcnt vmcnt(8 * tiles) only (expcnt / lgkmcnt fields left at "no wait"): returns once at
+// most `tiles` of the most recently issued K tiles (8 direct loads per wave each) are in flight.
+__device__ __forceinline__ void wait_tiles_in_flight(int tiles) {
+  if (tiles >= 3) __builtin_amdgcn_s_waitcnt(0x4F78);        // vmcnt(24)
+  else if (tiles == 2) __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16)
+  else if (tiles == 1) __builtin_amdgcn_s_waitcnt(0x0F78);   // vmcnt(8)
+  else __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0)
+}
+
+struct DmaFrags {
+  Frag8 a[MB], b[NB];
+};
+// TRA / TRB: the operand's LDS tile is [k][256] (transposing reads) instead of [256][k].
+template <bool TRA, bool TRB>
+__device__ __forceinline__ void dma_read_frags(DmaFrags& f, const lds_byte_t* stage, int ks, int wm, int wn) {
+  const int lane = threadIdx.x & 63;
+  const int r = lane & 31, h = lane >> 5;
+  const lds_byte_t* As = stage;
+  const lds_byte_t* Bs = stage + kDmaTileBytes;
+#pragma unroll
+  for (int i = 0; i < MB; ++i) {
+    if (TRA) f.a[i].v = dmat_read_frag(As, (wm + 2 * i) * 32, ks);
+    else f.a[i].v = *(const __attribute__((address_space(3))) bf16x8*)(As + dma_off((wm + 2 * i) * 32 + r, 2 * ks + h));
+  }
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    if (TRB) f.b[j].v = dmat_read_frag(Bs, (wn * NB + j) * 32, ks);
+    else f.b[j].v = *(const __attribute__((address_space(3))) bf16x8*)(Bs + dma_off((wn * NB + j) * 32 + r, 2 * ks + h));
+  }
+}
+__device__ __forceinline__ void dma_mma(f32x16 (&acc)[MB][NB], const DmaFrags& f) {
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j].v, f.a[i].v, acc[i][j], 0, 0, 0);
+}
+
+// One K tile (two 16-wide k steps).  On entry f0 holds the fragments of (tile kt, k step 0).
+// The barrier sits between the two k steps: before it the wave has fetched everything it needs
+// from `cur`, so after it `cur` is free for tile kt+4; and tile kt+1 is published, so its first
+// fragments can be fetched while the second k step's MFMAs run -- no LDS latency after the barrier.
+// The direct loads are spread evenly between the MFMAs, one after every four (128 cycles of
+// matrix-pipe work): the four waves share one address path, and a wave that issues its loads back
+// to back leaves its matrix pipe idle while it queues there.  So a tile's eight loads per wave go
+// out in two halves: loads 0..3 of tile kt+4 after the barrier of step kt (into `cur`, just
+// freed), loads 4..7 before the barrier of step kt+1 (into that step's `prev`).
+// Issue: begin() prepares the next tile in sequence, part(stage, q) starts its q-th direct load
+// (q = 0..7) into `stage`, end() moves on to the tile after it.
+// PRE: tile kt+3 exists (its second half is issued here).  POST: tile kt+4 exists.
+// NEXT: tile kt+1 exists; WAIT = how many younger tiles may still be in flight once this wave's
+// part of tile kt+1 has landed.
+template <bool TRA, bool TRB, bool PRE, bool POST, int WAIT, bool NEXT, typename Issue>
+__device__ __forceinline__ void dma_step(lds_byte_t* prev, lds_byte_t* cur, const lds_byte_t* nxt,
+                                         f32x16 (&acc)[MB][NB], DmaFrags& f0, DmaFrags& f1, Issue& issue, int wm,
+                                         int wn) {
+  dma_read_frags<TRA, TRB>(f1, cur, 1, wm, wn);
+#pragma unroll
+  for (int i = 0; i < MB; ++i) {
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.b[j].v, f0.a[i].v, acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (PRE) issue.part(prev, 4 + i);
+  }
+  if (PRE) issue.end();
+  __builtin_amdgcn_sched_barrier(0);     // everything above is queued before the wave goes to wait
+  if (NEXT) wait_tiles_in_flight(WAIT);
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  if (NEXT) dma_read_frags<TRA, TRB>(f0, nxt, 0, wm, wn);
+  if (POST) issue.begin();
+#pragma unroll
+  for (int i = 0; i < MB; ++i) {
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.b[j].v, f1.a[i].v, acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (POST) issue.part(cur, i);
+  }
+}
+
+// The whole K loop: KT tiles (a multiple of 4) through the four stages; the last four tiles,
+// which have nothing left to prefetch, run as a peeled tail so that the steady-state loop body is
+// branch-free.
+template <bool TRA, bool TRB, typename Issue>
+__device__ __forceinline__ void dma_pipeline(lds_byte_t* s0, lds_byte_t* s1, lds_byte_t* s2, lds_byte_t* s3,
+                                             f32x16 (&acc)[MB][NB], Issue& issue, int KT, int wm, int wn) {
+  lds_byte_t* const stages[4] = {s0, s1, s2, s3};
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    issue.begin();
+#pragma unroll
+    for (int q = 0; q < (t < 3 ? 8 : 4); ++q) issue.part(stages[t], q);   // tile 3: first half only
+    if (t < 3) issue.end();
+  }
+  __builtin_amdgcn_s_waitcnt(0x4F74);                  // vmcnt(20): tile 0 has landed
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  DmaFrags f0, f1;
+  dma_read_frags<TRA, TRB>(f0, s0, 0, wm, wn);
+  for (int kt = 0; kt < KT - 4; kt += 4) {
+    dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f0, f1, issue, wm, wn);
+    dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f0, f1, issue, wm, wn);
+    dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f0, f1, issue, wm, wn);
+    dma_step<TRA, TRB, true, true, 2, true>(s2, s3, s0, acc, f0, f1, issue, wm, wn);
+  }
+  dma_step<TRA, TRB, true, false, 2, true>(s3, s0, s1, acc, f0, f1, issue, wm, wn);
+  dma_step<TRA, TRB, false, false, 1, true>(s0, s1, s2, acc, f0, f1, issue, wm, wn);
+  dma_step<TRA, TRB, false, false, 0, true>(s1, s2, s3, acc, f0, f1, issue, wm, wn);
+  dma_step<TRA, TRB, false, false, 0, false>(s2, s3, s0, acc, f0, f1, issue, wm, wn);
+  __syncthreads();                                     // all waves done with the last tile: LDS is free
+}
+
+// Tile sequence of the rows kernels: K tile t of both operands starts at contraction index 32 t.
+template <typename WSrc> struct RowsIssue {
+  const DmaSrc& a_src;
+  const WSrc& w_src;
+  int k_next;
+  __device__ __forceinline__ void begin() {}
+  __device__ __forceinline__ void part(lds_byte_t* stage, int q) const {
+    if (q < 4) a_src.part(stage, k_next, q);
+    else w_src.part(stage + kDmaTileBytes, k_next, q - 4);
+  }
+  __device__ __forceinline__ void end() { k_next += DK; }
+};
+
+template <bool WT, typename WSrc, int EPI, int ACT>
+__device__ __forceinline__ void rows_dma_body(lds_byte_t* s0, lds_byte_t* s1, lds_byte_t* s2, lds_byte_t* s3,
+                                              const RowTile& t, const bf16_t* __restrict__ in, const WSrc& w_src,
+                                              const bf16_t* __restrict__ bias, int K, int NC,
+                                              const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
+                                              bf16_t* __restrict__ out1, const lds_byte_t* lut,
+                                              const int32_t* __restrict__ gsrc, int gk,
+                                              float* __restrict__ split_partial = nullptr,
+                                              const int32_t* __restrict__ scatter_rows = nullptr) {
+  const int wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  DmaSrc a_src;
+  if (gsrc) a_src.init_gather(in, K, gsrc + t.row0, gk, t.rows_valid);
+  else a_src.init(in + (size_t)t.row0 * K, K, t.rows_valid);
+  f32x16 acc[MB][NB];
+  zero_acc(acc);
+  if (EPI == EPI_PLAIN && t.nseg > 1) {
+    // one K segment of a split tile: fp32 partial tile (all 256 x 256 entries) for the reduce kernel
+    const int kt = K / DK / t.nseg;
+    RowsIssue<WSrc> issue{a_src, w_src, t.seg * kt * DK};
+    dma_pipeline<false, !WT>(s0, s1, s2, s3, acc, issue, kt, wm, wn);
+    float* out = split_partial + (size_t)t.slot * (BM * BN);
+    float* patch = (float*)s0 + wave * (32 * 64);
+    float* patch_alt = (float*)s1 + wave * (32 * 64);
+    epilogue_rounds<false>(
+        patch, patch_alt, acc, [](int, int) { return make_uint2(0, 0); },
+        [](int, int, float4 c, uint2) {
+          return EpiOut{make_uint2(__float_as_uint(c.x), __float_as_uint(c.y)),
+                        make_uint2(__float_as_uint(c.z), __float_as_uint(c.w))};
+        },
+        [&](int row_w, int col_w, const EpiOut& o) {
+          const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
+          *(uint4*)(out + lrow * BN + wn * (NB * 32) + col_w) = make_uint4(o.a.x, o.a.y, o.b.x, o.b.y);
+        });
+    return;
+  }
+  RowsIssue<WSrc> issue{a_src, w_src, 0};
+  dma_pipeline<false, !WT>(s0, s1, s2, s3, acc, issue, K / DK, wm, wn);   // K % 128 == 0 (host check)
+  const lds_int_t* smap = nullptr;
+  if (EPI == EPI_PLAIN && scatter_rows) {
+    // output rows of this tile (the epilogue's patches live in stages 0 and 1; stage 2 is free)
+    lds_int_t* m = (lds_int_t*)s2;
+    m[threadIdx.x] = scatter_rows[t.row0 + min((int)threadIdx.x, t.rows_valid - 1)];
+    __syncthreads();
+    smap = m;
+  }
+  rows_epilogue<EPI, ACT, epilogue_uses_lut<EPI, ACT>()>((float*)s0, (float*)s1, acc, bias, NC, t.row0, t.rows_valid, t.e, t.n0, hpre_in, out0,
+                                                          out1, lut, smap);
+}
+
+// Arguments of one rows GEMM (device pointers; see rows_gemm_dma_bf16).
+struct RowsDmaArgs {
+  const bf16_t* in;
+  const bf16_t* w;
+  const bf16_t* bias;
+  const int32_t* voff;
+  const int32_t* owner;
+  int V, K, NC, row_tiles_max, col_tiles;
+  const bf16_t* hpre_in;
+  bf16_t* out0;
+  bf16_t* out1;
+  const int32_t* gsrc;
+  int gk;
+  float* split_partial;      // fp32 partial tiles of split tail tiles, or null: no splitting
+  unsigned normal_grid;      // blocks before the extra segment workgroups (meaningful with split_partial)
+  const int32_t* scatter_rows;   // plain epilogue only: bucket row p is stored as output row scatter_rows[p]; or null
+};
+
+// One workgroup's tile of a rows GEMM; `block` is its index in that GEMM's (patched) grid.
+template <bool WT, int EPI, int ACT>
+__device__ __forceinline__ void rows_dma_block(const RowsDmaArgs& p, unsigned block, lds_byte_t* s0, lds_byte_t* s1,
+                                               lds_byte_t* s2, lds_byte_t* s3, unsigned char* lut_lds, int* s_tile) {
+  constexpr bool kLut = epilogue_uses_lut<EPI, ACT>();
+  RowTile t;
+  if (EPI == EPI_PLAIN) {
+    const SplitArg sp{p.split_partial ? p.normal_grid : 0u, p.K / DK, -1};
+    if (!lookup_row_tile<true>(p.voff, p.owner, p.V, p.NC, p.row_tiles_max, p.col_tiles, block, s_tile, &t, sp)) return;
+  } else {
+    if (!lookup_row_tile(p.voff, p.owner, p.V, p.NC, p.row_tiles_max, p.col_tiles, block, s_tile, &t)) return;
+  }
+  const lds_byte_t* lut = nullptr;
+  if (kLut) {
+    // the table rides in front of the operand tiles: its direct loads are the oldest in every
+    // wave's queue, so the first wait of the K loop covers them and its barrier publishes them
+    lut = (const lds_byte_t*)lut_lds;
+    const unsigned w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)lut) + w * (kLutBytes / 4);
+    const unsigned char* g = (const unsigned char*)g_act_lut[ACT == FLEXMOE_GELU_ERF ? 0 : 1] + w * (kLutBytes / 4) +
+                             (threadIdx.x & 63) * 16;
+#pragma unroll
+    for (int q = 0; q < kLutBytes / 4 / 1024; ++q) {
+      const unsigned char* gq = g + q * 1024;
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" FLEXMOE_DMA_CPOL ::"v"(gq), "s"(lds0 + q * 1024) : "memory");
+    }
+  }
+  const bf16_t* w_e = p.w + (size_t)t.e * p.K * p.NC;
+  if (WT) {
+    DmaSrc w_src;
+    w_src.init(w_e + (size_t)t.n0 * p.K, p.K, t.cols_valid);
+    rows_dma_body<true, DmaSrc, EPI, ACT>(s0, s1, s2, s3, t, p.in, w_src, p.bias, p.K, p.NC, p.hpre_in, p.out0, p.out1,
+                                          lut, p.gsrc, p.gk, p.split_partial, p.scatter_rows);
+  } else {
+    DmaSrcT w_src;
+    w_src.init(w_e + t.n0, p.NC, t.cols_valid);
+    rows_dma_body<false, DmaSrcT, EPI, ACT>(s0, s1, s2, s3, t, p.in, w_src, p.bias, p.K, p.NC, p.hpre_in, p.out0,
+                                            p.out1, lut, p.gsrc, p.gk, p.split_partial, p.scatter_rows);
+  }
+}
+
+template <bool WT, int EPI, int ACT>
+__global__ __launch_bounds__(kGemmThreads) void rows_gemm_dma_bf16(const RowsDmaArgs p) {
+  __shared__ __align__(1024) unsigned char stage0[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage1[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage3[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char lut_lds[epilogue_uses_lut<EPI, ACT>() ? kLutBytes : 16];
+  __shared__ int s_tile[8];
+  rows_dma_block<WT, EPI, ACT>(p, blockIdx.x, (lds_byte_t*)stage0, (lds_byte_t*)stage1, (lds_byte_t*)stage2,
+                               (lds_byte_t*)stage3, lut_lds, s_tile);
+}
+
+// Sum of the K segments of the split tail tiles (see lookup_row_tile): out = bf16(sum over
+// segments in order + bias).  Grid: (kSplitSlices row slices of a tile, kSplitUnits / kSplitMax tail tiles).
+constexpr int kSplitSlices = 16;
+__global__ __launch_bounds__(kGemmThreads) void rows_split_reduce_kernel(const RowsDmaArgs p) {
+  __shared__ int s_tile[8];
+  RowTile t;
+  const SplitArg sp{p.normal_grid, p.K / DK, (int)blockIdx.y};
+  if (!lookup_row_tile<true>(p.voff, p.owner, p.V, p.NC, p.row_tiles_max, p.col_tiles, 0u, s_tile, &t, sp)) return;
+  const float* part = p.split_partial + (size_t)(t.slot - t.seg) * (BM * BN);     // slot of segment 0
+  constexpr int kRows = BM / kSplitSlices;                                        // rows per block
+  constexpr int kIters = kRows * (BN / 4) / kGemmThreads;
+  const int r0 = blockIdx.x * kRows;
+  if (r0 >= t.rows_valid) return;
+  float4 v[kIters][kSplitMax];
+#pragma unroll
+  for (int it = 0; it < kIters; ++it) {
+    const int i4 = it * kGemmThreads + threadIdx.x;
+    const int off = (r0 + i4 / (BN / 4)) * BN + (i4 % (BN / 4)) * 4;
+#pragma unroll
+    for (int sg = 0; sg < kSplitMax; ++sg)
+      if (sg < t.nseg) v[it][sg] = *(const float4*)(part + (size_t)sg * (BM * BN) + off);
+  }
+#pragma unroll
+  for (int it = 0; it < kIters; ++it) {
+    const int i4 = it * kGemmThreads + threadIdx.x;
+    const int row = r0 + i4 / (BN / 4), col = (i4 % (BN / 4)) * 4;
+    float4 acc = v[it][0];
+#pragma unroll
+    for (int sg = 1; sg < kSplitMax; ++sg)
+      if (sg < t.nseg) {
+        acc.x += v[it][sg].x; acc.y += v[it][sg].y; acc.z += v[it][sg].z; acc.w += v[it][sg].w;
+      }
+    if (row < t.rows_valid && col < t.cols_valid) {
+      if (p.bias) {
+        float b[4];
+        unpack4(*(const uint2*)(p.bias + (size_t)t.e * p.NC + t.n0 + col), b);
+        acc.x += b[0]; acc.y += b[1]; acc.z += b[2]; acc.w += b[3];
+      }
+      const size_t orow = p.scatter_rows ? (size_t)p.scatter_rows[t.row0 + row] : (size_t)(t.row0 + row);
+      *(uint2*)(p.out0 + orow * p.NC + t.n0 + col) = pack4(acc.x, acc.y, acc.z, acc.w);
+    }
+  }
+}
+
+}  // namespace flexmoe

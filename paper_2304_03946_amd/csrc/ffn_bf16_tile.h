@@ -1,0 +1,635 @@
+// Tile mapping, register-staged operand loads, LDS -> MFMA fragments, activation tables, epilogues and the register-staged rows kernel.
+// Part of the bf16 expert-FFN kernels; included by ffn_bf16.hip only (one translation unit).
+#pragma once
+#include "common.h"
+
+namespace flexmoe {
+
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int kGemmThreads = 256;
+constexpr int MB = 4, NB = 4;                       // 32x32 MFMA tiles per wave: 4 x 4
+constexpr int kTileElems = BM * BK;                 // one operand tile in LDS (elements)
+constexpr size_t kGemmLds = 2 * 2 * kTileElems * sizeof(bf16_t);   // 2 stages x (A + B) = 128 KB
+
+enum { EPI_FWD1 = 0, EPI_PLAIN = 1, EPI_DH = 2 };
+#ifndef FLEXMOE_DMA_CPOL
+#define FLEXMOE_DMA_CPOL ""      // cache-policy modifiers of the direct-to-LDS loads
+#endif
+
+union Frag8 {
+  uint4 u;
+  bf16x8 v;
+};
+
+__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
+__device__ __forceinline__ int lds_off(int row, int chunk) { return row * BK + ((chunk ^ swz(row)) << 3); }
+
+// ---- workgroup id -> tile, XCD aware ---------------------------------------------------------
+// Workgroups are dealt round-robin to the 8 XCDs (id % 8), each with its own L2, and an XCD runs
+// its workgroups in ascending id.  The rows x cols tile grid is cut into patches of ph x pw tiles
+// (about 32 = one per CU of an XCD; pw divides cols whenever a divisor in 5..8 exists, so patches
+// are full and every XCD gets the same work); the j-th workgroup of XCD x gets tile j % (ph*pw) of
+// patch (j / (ph*pw)) * 8 + x.  The workgroups that run together on one XCD then share ph row
+// operands and pw column operands in its L2, and the 8 patches in flight on the 8 XCDs are
+// neighbours in the grid, so what they share is fetched from HBM once.
+constexpr int kXcds = 8, kPatch = 32;
+__host__ __device__ inline int patch_width(int cols) {
+  if (cols <= 8) return cols;
+  for (int pw = 8; pw >= 5; --pw)
+    if (cols % pw == 0) return pw;
+  return 8;
+}
+__host__ __device__ inline unsigned patched_grid(int rows, int cols) {
+  const int pw = patch_width(cols), ph = kPatch / pw;
+  const int np = ((rows + ph - 1) / ph) * ((cols + pw - 1) / pw);
+  return (unsigned)((np + kXcds - 1) / kXcds * kXcds) * (ph * pw);
+}
+// returns false when the workgroup falls into the padding of the patch grid
+__device__ __forceinline__ bool patched_tile(unsigned b, int rows, int cols, int* r, int* c) {
+  const int pw = patch_width(cols), ph = kPatch / pw, psize = ph * pw;
+  const int npc = (cols + pw - 1) / pw;
+  const unsigned x = b % kXcds, j = b / kXcds;
+  const unsigned P = (j / psize) * kXcds + x, q = j % psize;
+  *r = (int)(P / npc) * ph + (int)(q / pw);
+  *c = (int)(P % npc) * pw + (int)(q % pw);
+  return *r < rows && *c < cols;
+}
+
+// ---- global -> registers -> LDS -------------------------------------------------------------
+// Workgroup barrier that orders LDS traffic only: global loads issued for a later tile stay in
+// flight across it (a full __syncthreads would wait for them).
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Operand stored [rows, ld] with the contraction index contiguous.  Thread t owns 16-byte chunk
+// t&7 of rows (t>>3) + 32*i.  Rows past rows_valid are clamped to the last valid row (their
+// products are never stored), so full-K tiles load without predication; a ragged last K tile
+// reads chunks past K as zero.
+struct KContigSrc {
+  const bf16_t* base;
+  uint32_t off[8];
+  int K;
+  __device__ __forceinline__ void init(const bf16_t* b, size_t ld, int rows_valid, int K_) {
+    base = b;
+    K = K_;
+    const int c = threadIdx.x & 7, rr = threadIdx.x >> 3;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) off[i] = (uint32_t)(min(rr + 32 * i, rows_valid - 1) * ld + c * 8);
+  }
+  __device__ __forceinline__ void load(uint4 (&r)[8], int k0) const {
+    if (k0 + BK <= K) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) r[i] = *(const uint4*)(base + k0 + off[i]);
+    } else {
+      const bool kok = k0 + (int)(threadIdx.x & 7) * 8 < K;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        r[i] = make_uint4(0, 0, 0, 0);
+        if (kok) r[i] = *(const uint4*)(base + k0 + off[i]);
+      }
+    }
+  }
+  static __device__ __forceinline__ void store(bf16_t* tile, const uint4 (&r)[8]) {
+    const int c = threadIdx.x & 7, rr = threadIdx.x >> 3;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) *(uint4*)(tile + lds_off(rr + 32 * i, c)) = r[i];
+  }
+};
+
+// Operand stored [K, ld] with the output index contiguous.  Thread t owns the 8x8 block at
+// k = 8*(t>>5).., column 8*(t&31)..; columns past cols_valid are clamped to the last valid
+// 8-column group; contraction rows >= k_valid read as zero (they would add to the sums).
+struct KStridedSrc {
+  uint32_t off[8];
+  __device__ __forceinline__ void init(size_t ld, int cols_valid) {
+    const int nc = min((int)(threadIdx.x & 31), cols_valid / 8 - 1), kc = threadIdx.x >> 5;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) off[j] = (uint32_t)((kc * 8 + j) * ld + nc * 8);
+  }
+  // `p` points at contraction row 0 of this tile, first column of the tile
+  __device__ __forceinline__ void load(uint4 (&r)[8], const bf16_t* __restrict__ p, int k_valid) const {
+    if (k_valid >= BK) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) r[j] = *(const uint4*)(p + off[j]);
+    } else {
+      const int kc = threadIdx.x >> 5;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        r[j] = make_uint4(0, 0, 0, 0);
+        if (kc * 8 + j < k_valid) r[j] = *(const uint4*)(p + off[j]);
+      }
+    }
+  }
+  static __device__ __forceinline__ uint32_t lo16(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
+  static __device__ __forceinline__ uint32_t hi16(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
+  // r[j] holds columns 0..7 of k-row j; emit, per column n, its 8 k-values as one 16-byte chunk
+  static __device__ __forceinline__ void store(bf16_t* tile, const uint4 (&r)[8]) {
+    const int nc = threadIdx.x & 31, kc = threadIdx.x >> 5;
+    uint4 o;
+#define FLEXMOE_TR(n, comp, pick)                                                                    \
+  o = make_uint4(pick(r[0].comp, r[1].comp), pick(r[2].comp, r[3].comp), pick(r[4].comp, r[5].comp), \
+                 pick(r[6].comp, r[7].comp));                                                        \
+  *(uint4*)(tile + lds_off(nc * 8 + n, kc)) = o;
+    FLEXMOE_TR(0, x, lo16) FLEXMOE_TR(1, x, hi16) FLEXMOE_TR(2, y, lo16) FLEXMOE_TR(3, y, hi16)
+    FLEXMOE_TR(4, z, lo16) FLEXMOE_TR(5, z, hi16) FLEXMOE_TR(6, w, lo16) FLEXMOE_TR(7, w, hi16)
+#undef FLEXMOE_TR
+  }
+};
+
+// ---- LDS -> MFMA ---------------------------------------------------------------------------
+// One 16-wide k step of the wave's 128x128 block.
+// acc[i][j]: output rows (wm + 2*i)*32 + lane%32, columns (wn*NB + j)*32 + 8*(q/4) + 4*(lane/32) + q%4.
+template <bool FULL>
+__device__ __forceinline__ void mma_kstep(const bf16_t* __restrict__ As, const bf16_t* __restrict__ Bs, int s,
+                                          f32x16 (&acc)[MB][NB], int wm, int wn, int nblk_rows) {
+  const int lane = threadIdx.x & 63;
+  const int r = lane & 31, h = lane >> 5;
+  Frag8 af[MB], bfr[NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+    if (FULL || wm + 2 * i < nblk_rows) af[i].u = *(const uint4*)(As + lds_off((wm + 2 * i) * 32 + r, 2 * s + h));
+#pragma unroll
+  for (int j = 0; j < NB; ++j) bfr[j].u = *(const uint4*)(Bs + lds_off((wn * NB + j) * 32 + r, 2 * s + h));
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+    if (FULL || wm + 2 * i < nblk_rows) {
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j].v, af[i].v, acc[i][j], 0, 0, 0);
+    }
+}
+
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[MB][NB]) {
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+}
+
+__device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
+  return make_uint2(pack_bf16x2(a, b), pack_bf16x2(c, d));
+}
+__device__ __forceinline__ void unpack4(uint2 u, float* v) {
+  v[0] = __uint_as_float(u.x << 16);
+  v[1] = __uint_as_float(u.x & 0xffff0000u);
+  v[2] = __uint_as_float(u.y << 16);
+  v[3] = __uint_as_float(u.y & 0xffff0000u);
+}
+
+// ---- activation tables -------------------------------------------------------------------------
+// The GELU epilogues act on pre-activations already rounded to bf16, so the activation has only
+// 2^16 possible arguments.  Both GELU forms are z*F(z) with F(z) + F(-z) = 1, which makes
+//   GELU(z)  = max(z, 0) + r(|z|),          r(a) = GELU(a) - a   (= GELU(-a), even in z)
+//   GELU'(z) = [z >= 0] + sign(z) * q(|z|),  q(a) = GELU'(a) - 1
+// so one table over the bf16 magnitudes serves both signs.  r and q vanish (below 1e-13) from
+// |z| = 8 on and r(a) -> -a/2, q -> -1/2 as a -> 0: magnitudes are clamped to [2^-24, 8], which
+// costs an absolute error below 2^-25.  Entries are computed in double precision on the device,
+// once per device, and held as {r, q} fp32 pairs: 3457 entries, padded to 28 KB so that the GEMM
+// kernels can pull the table into LDS with whole 1 KB direct loads.
+constexpr int kLutLo = 103 << 7;                    // bf16 bits of 2^-24
+constexpr int kLutHi = 130 << 7;                    // bf16 bits of 8.0
+constexpr int kLutBytes = 28 * 1024;
+constexpr int kLutEntries = kLutBytes / 8;
+static_assert(kLutHi - kLutLo + 1 <= kLutEntries, "table does not fit its padding");
+__device__ __align__(1024) float2 g_act_lut[2][kLutEntries];    // [0] erf form, [1] tanh form
+
+__global__ void act_lut_init_kernel() {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= kLutEntries) return;
+  const int m = min(kLutLo + i, kLutHi);
+  const double a = (double)__uint_as_float((uint32_t)m << 16);
+  double Fneg, dF;                                   // F(-a) and F'(a)
+  if (blockIdx.y == 0) {
+    Fneg = 0.5 * erfc(a * 0.70710678118654752440);
+    dF = 0.39894228040143267794 * exp(-0.5 * a * a);
+  } else {
+    const double c = 0.79788456080286535588, u = c * (a + 0.044715 * a * a * a);
+    const double th = tanh(u);
+    Fneg = 0.5 * (1.0 - th);
+    dF = 0.5 * (1.0 - th * th) * c * (1.0 + 3.0 * 0.044715 * a * a);
+  }
+  // r = -a F(-a);  GELU'(a) = F(a) + a F'(a) = 1 - F(-a) + a F'(a)
+  g_act_lut[blockIdx.y][i] = make_float2((float)(-a * Fneg), (float)(a * dF - Fneg));
+}
+
+// Table entry for the bf16 value whose fp32 bit pattern is zu (LDS copy of one table).
+typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+typedef __attribute__((address_space(3))) int lds_int_t;
+__device__ __forceinline__ uint32_t lut_offset(uint32_t zu) {
+  const uint32_t m = (zu >> 16) & 0x7fffu;
+  return (min(max(m, (uint32_t)kLutLo), (uint32_t)kLutHi) - kLutLo) << 3;
+}
+// max(z, 0) on the bit pattern: as a signed integer every negative float (and -0) is below zero
+// and every positive float keeps its order, so one integer max does it (no NaN canonicalisation).
+__device__ __forceinline__ float relu_bits(uint32_t zu) { return __int_as_float(max((int32_t)zu, 0)); }
+__device__ __forceinline__ float lut_act(const lds_byte_t* lut, uint32_t zu) {
+  const float r = *(const __attribute__((address_space(3))) float*)(lut + lut_offset(zu));
+  return relu_bits(zu) + r;
+}
+__device__ __forceinline__ void lut_act_both(const lds_byte_t* lut, uint32_t zu, float* a, float* da) {
+  const f32x2_t rq = *(const __attribute__((address_space(3))) f32x2_t*)(lut + lut_offset(zu));
+  *a = relu_bits(zu) + rq[0];
+  *da = (int32_t)zu < 0 ? -rq[1] : 1.f + rq[1];
+}
+template <int EPI, int ACT> constexpr bool epilogue_uses_lut() { return EPI != EPI_PLAIN && ACT != FLEXMOE_RELU; }
+
+// ---- epilogue ---------------------------------------------------------------------------------
+// A lane's accumulators hold 4-column pieces of 32 different rows, which would make every global
+// store touch 32 cache lines.  Instead the wave's 128x128 fp32 block goes out in eight rounds of
+// 32 rows x 64 columns: accumulator registers -> one of two wave-private 8 KB LDS patches (16-byte chunks,
+// chunk index XORed with row & 15: conflict free both ways) -> read back so that 16 lanes cover
+// 64 consecutive columns of one row -> per-element epilogue in fp32 -> bf16 -> 8-byte stores that
+// fill whole 128-byte lines.  The K loop ends with a barrier, so the LDS tiles are free.
+// Per round, all eight 4-element pieces are first computed (compute(row in the wave's block
+// (0..127), column in the wave's block (multiple of 4), float4 accumulators, uint2 side input)
+// -> EpiOut, unconditional: straight-line code the scheduler can interleave) and then stored
+// (store(row, col, EpiOut), where the ragged-edge predicates live).
+// fetch(row, col) -> uint2: an optional per-element side input (the saved pre-activations of the
+// backward epilogue); the fetches of round n+1 are issued before round n is processed so that
+// their latency hides behind it.
+struct EpiOut {
+  uint2 a, b;
+};
+template <bool FETCH, typename Fetch, typename Compute, typename Store>
+__device__ __forceinline__ void epilogue_rounds(float* patch0, float* patch1, const f32x16 (&acc)[MB][NB], Fetch fetch,
+                                                Compute compute, Store store) {
+  const int lane = threadIdx.x & 63;
+  const int r = lane & 31, h = lane >> 5;
+  const int rsub = lane >> 4, c = lane & 15;
+  constexpr int kRounds = MB * (NB / 2);
+  uint2 side[2][8];
+  if (FETCH) {
+#pragma unroll
+    for (int it = 0; it < 8; ++it) side[0][it] = fetch(it * 4 + rsub, c * 4);
+  }
+  // Two patches per wave: round n+1's accumulators are written while round n is processed.  A
+  // wave's LDS instructions execute in issue order, so the reads that follow the writes need no
+  // wait, only a compiler barrier (the dependence runs across lanes, which the compiler cannot see).
+  auto write_round = [&](int i, int jh, float* patch) {
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int cc = jj * 8 + 2 * g + h;
+        const f32x16& a = acc[i][jh * 2 + jj];
+        *(float4*)(patch + r * 64 + ((cc ^ (r & 15)) << 2)) = make_float4(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]);
+      }
+  };
+  write_round(0, 0, patch0);
+#pragma unroll
+  for (int i = 0; i < MB; ++i) {
+#pragma unroll
+    for (int jh = 0; jh < NB / 2; ++jh) {
+      const int round = i * (NB / 2) + jh;
+      float* patch = (round & 1) ? patch1 : patch0;
+      if (FETCH && round + 1 < kRounds) {
+        const int ni = (round + 1) / (NB / 2), njh = (round + 1) % (NB / 2);
+#pragma unroll
+        for (int it = 0; it < 8; ++it) side[(round + 1) & 1][it] = fetch(ni * 32 + it * 4 + rsub, njh * 64 + c * 4);
+      }
+      asm volatile("" ::: "memory");
+      float4 v[8];
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int row = it * 4 + rsub;
+        v[it] = *(const float4*)(patch + row * 64 + ((c ^ (row & 15)) << 2));
+      }
+      asm volatile("" ::: "memory");
+      if (round + 1 < kRounds) write_round((round + 1) / (NB / 2), (round + 1) % (NB / 2), (round & 1) ? patch0 : patch1);
+      asm volatile("" ::: "memory");
+      EpiOut o[8];
+#pragma unroll
+      for (int it = 0; it < 8; ++it)
+        o[it] = compute(i * 32 + it * 4 + rsub, jh * 64 + c * 4, v[it], FETCH ? side[round & 1][it] : make_uint2(0, 0));
+#pragma unroll
+      for (int it = 0; it < 8; ++it) store(i * 32 + it * 4 + rsub, jh * 64 + c * 4, o[it]);
+    }
+  }
+}
+
+// One K tile of the software pipeline.  On entry LDS stage `cur` holds tile t and the registers
+// ra/rb hold tile t+1 (loaded during the previous step).  The tile is multiplied in four k
+// steps; early in the step each register set is written to stage `nxt` and immediately reused
+// for the loads of tile t+2, which then have most of a step of MFMA work to land.
+template <bool FULL, bool STORE, bool LOAD, typename StoreA, typename StoreB, typename LoadA, typename LoadB>
+__device__ __forceinline__ void pipe_step(bf16_t* cur, bf16_t* nxt, f32x16 (&acc)[MB][NB], uint4 (&ra)[8],
+                                          uint4 (&rb)[8], StoreA store_a, StoreB store_b, LoadA& load_a, LoadB& load_b,
+                                          int wm, int wn, int nblk_rows) {
+  mma_kstep<FULL>(cur, cur + kTileElems, 0, acc, wm, wn, nblk_rows);
+  if (STORE) store_a(nxt, ra);
+  if (LOAD) load_a(ra);
+  mma_kstep<FULL>(cur, cur + kTileElems, 1, acc, wm, wn, nblk_rows);
+  if (STORE) store_b(nxt + kTileElems, rb);
+  if (LOAD) load_b(rb);
+  mma_kstep<FULL>(cur, cur + kTileElems, 2, acc, wm, wn, nblk_rows);
+  mma_kstep<FULL>(cur, cur + kTileElems, 3, acc, wm, wn, nblk_rows);
+  lds_barrier();
+}
+
+// Drives T tiles through the pipeline.  load_a(ra) / load_b(rb) fetch the next tile in sequence.
+template <bool FULL, typename StoreA, typename StoreB, typename LoadA, typename LoadB>
+__device__ __forceinline__ void run_pipeline(bf16_t* smem, f32x16 (&acc)[MB][NB], int T, StoreA store_a,
+                                             StoreB store_b, LoadA& load_a, LoadB& load_b, int wm, int wn,
+                                             int nblk_rows) {
+  uint4 ra[8], rb[8];
+  load_a(ra);
+  load_b(rb);
+  store_a(smem, ra);
+  store_b(smem + kTileElems, rb);
+  if (T > 1) {
+    load_a(ra);
+    load_b(rb);
+  }
+  lds_barrier();
+  int t = 0;
+  for (; t + 2 < T; ++t) {
+    bf16_t* cur = smem + (t & 1) * 2 * kTileElems;
+    bf16_t* nxt = smem + ((t & 1) ^ 1) * 2 * kTileElems;
+    pipe_step<FULL, true, true>(cur, nxt, acc, ra, rb, store_a, store_b, load_a, load_b, wm, wn, nblk_rows);
+  }
+  if (t + 1 < T) {
+    bf16_t* cur = smem + (t & 1) * 2 * kTileElems;
+    bf16_t* nxt = smem + ((t & 1) ^ 1) * 2 * kTileElems;
+    pipe_step<FULL, true, false>(cur, nxt, acc, ra, rb, store_a, store_b, load_a, load_b, wm, wn, nblk_rows);
+    ++t;
+  }
+  {
+    bf16_t* cur = smem + (t & 1) * 2 * kTileElems;
+    pipe_step<FULL, false, false>(cur, cur, acc, ra, rb, store_a, store_b, load_a, load_b, wm, wn, nblk_rows);
+  }
+}
+
+// K loop of rows_gemm.
+template <bool WT, bool FULL>
+__device__ __forceinline__ void rows_mainloop(bf16_t* smem, f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ a_base,
+                                              const bf16_t* __restrict__ w_e, int K, int NC, int n0, int rows_valid,
+                                              int cols_valid, int wm, int wn, int nblk_rows) {
+  const int KT = (K + BK - 1) / BK;
+  KContigSrc a_src;
+  a_src.init(a_base, K, rows_valid, K);
+  int ka = 0, kb = 0;
+  auto load_a = [&](uint4 (&ra)[8]) {
+    a_src.load(ra, ka);
+    ka += BK;
+  };
+  if (WT) {
+    KContigSrc w_src;
+    w_src.init(w_e + (size_t)n0 * K, K, cols_valid, K);
+    auto load_b = [&](uint4 (&rb)[8]) {
+      w_src.load(rb, kb);
+      kb += BK;
+    };
+    run_pipeline<FULL>(smem, acc, KT, KContigSrc::store, KContigSrc::store, load_a, load_b, wm, wn, nblk_rows);
+  } else {
+    KStridedSrc w_src;
+    w_src.init(NC, cols_valid);
+    const bf16_t* wp = w_e + n0;
+    auto load_b = [&](uint4 (&rb)[8]) {
+      w_src.load(rb, wp + (size_t)kb * NC, K - kb);
+      kb += BK;
+    };
+    run_pipeline<FULL>(smem, acc, KT, KContigSrc::store, KStridedSrc::store, load_a, load_b, wm, wn, nblk_rows);
+  }
+}
+
+// Epilogue of the rows kernels: bias, then plain store / pre-activation + activation / dH*act' + H.
+// LUT: the activation comes from the LDS copy `lut` of the activation table ({r, q} pairs, see
+// above); otherwise it is evaluated arithmetically.
+template <int EPI, int ACT, bool LUT, bool BIAS>
+__device__ __forceinline__ void rows_epilogue_t(float* lds, float* lds_alt, const f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ bias,
+                                                int NC, int row0, int rows_valid, int e, int n0,
+                                                const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
+                                                bf16_t* __restrict__ out1, const lds_byte_t* lut,
+                                                const lds_int_t* smap) {
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  float* patch = lds + wave * (32 * 64);
+  float* patch_alt = lds_alt + wave * (32 * 64);
+  const int col_base = n0 + wn * (NB * 32);
+  // tile-relative 32-bit offsets on top of uniform per-tile base pointers (scalar base + vector
+  // offset addressing instead of 64-bit vector address arithmetic per store)
+  const size_t tile_base = (size_t)row0 * NC + col_base;
+  const bf16_t* hpre_t = hpre_in + tile_base;
+  bf16_t* out0_t = out0 + tile_base;
+  bf16_t* out1_t = out1 + tile_base;
+  const bf16_t* bias_t = bias + (size_t)e * NC + col_base;
+  const int cols_left = NC - col_base;
+  auto tile_row = [&](int row_w) { return (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31); };
+  auto fetch = [&](int row_w, int col_w) -> uint2 {
+    const int lrow = tile_row(row_w);
+    if (lrow < rows_valid && col_w < cols_left) return *(const uint2*)(hpre_t + (uint32_t)(lrow * NC + col_w));
+    return make_uint2(0, 0);
+  };
+  auto compute = [&](int row_w, int col_w, float4 c, uint2 pre_in) -> EpiOut {
+    EpiOut o;
+    if (BIAS) {
+      float b[4];
+      unpack4(*(const uint2*)(bias_t + min(col_w, cols_left - 4)), b);
+      c.x += b[0]; c.y += b[1]; c.z += b[2]; c.w += b[3];
+    }
+    if (EPI == EPI_PLAIN) {
+      o.a = pack4(c.x, c.y, c.z, c.w);
+      o.b = make_uint2(0, 0);
+    } else if (EPI == EPI_FWD1) {
+      // keep the pre-activation; the activation is taken of the value as stored
+      o.a = pack4(c.x, c.y, c.z, c.w);
+      float z[4], a[4];
+      unpack4(o.a, z);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) a[q] = LUT ? lut_act(lut, __float_as_uint(z[q])) : act_fast<ACT>(z[q]);
+      o.b = pack4(a[0], a[1], a[2], a[3]);
+    } else {
+      float z[4], a[4], d[4];
+      unpack4(pre_in, z);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (LUT) lut_act_both(lut, __float_as_uint(z[q]), &a[q], &d[q]);
+        else act_both<ACT>(z[q], &a[q], &d[q]);
+      }
+      o.a = pack4(c.x * d[0], c.y * d[1], c.z * d[2], c.w * d[3]);
+      o.b = pack4(a[0], a[1], a[2], a[3]);
+    }
+    return o;
+  };
+  auto store = [&](int row_w, int col_w, const EpiOut& o) {
+    const int lrow = tile_row(row_w);
+    if (lrow < rows_valid && col_w < cols_left) {
+      const uint32_t off = (uint32_t)(lrow * NC + col_w);
+      if (EPI == EPI_PLAIN && smap) {
+        // scattered store: tile row lrow is row smap[lrow] of the output (reverse routing of a top-1 layer)
+        *(uint2*)(out0 + (size_t)smap[lrow] * NC + col_base + col_w) = o.a;
+      } else if (EPI != EPI_FWD1 || out0) *(uint2*)(out0_t + off) = o.a;     // forward: the pre-activations are optional
+      if (EPI != EPI_PLAIN) *(uint2*)(out1_t + off) = o.b;
+    }
+  };
+  epilogue_rounds<EPI == EPI_DH>(patch, patch_alt, acc, fetch, compute, store);
+}
+
+template <int EPI, int ACT, bool LUT = false>
+__device__ __forceinline__ void rows_epilogue(float* lds, float* lds_alt, const f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ bias,
+                                              int NC, int row0, int rows_valid, int e, int n0,
+                                              const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
+                                              bf16_t* __restrict__ out1, const lds_byte_t* lut = nullptr,
+                                              const lds_int_t* smap = nullptr) {
+  if (bias) rows_epilogue_t<EPI, ACT, LUT, true>(lds, lds_alt, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1, lut, smap);
+  else rows_epilogue_t<EPI, ACT, LUT, false>(lds, lds_alt, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1, lut, smap);
+}
+
+// One output tile of rows_gemm: main loop and epilogue.  FULL = all eight 32-row blocks hold rows.
+// (Kept as two separate instantiations with their own accumulators: merging the accumulators of
+// a full-tile and a ragged-tile path costs hundreds of register copies.)
+template <bool WT, int EPI, int ACT, bool FULL>
+__device__ __forceinline__ void rows_tile(bf16_t* smem, const bf16_t* __restrict__ in, const bf16_t* __restrict__ w,
+                                          const bf16_t* __restrict__ bias, int K, int NC, int row0, int rows_valid,
+                                          int e, int n0, int cols_valid, const bf16_t* __restrict__ hpre_in,
+                                          bf16_t* __restrict__ out0, bf16_t* __restrict__ out1) {
+  const int nblk_rows = (rows_valid + 31) >> 5;
+  const bf16_t* a_base = in + (size_t)row0 * K;
+  const bf16_t* w_e = w + (size_t)e * K * NC;
+  const int wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  f32x16 acc[MB][NB];
+  zero_acc(acc);
+  rows_mainloop<WT, FULL>(smem, acc, a_base, w_e, K, NC, n0, rows_valid, cols_valid, wm, wn, nblk_rows);
+
+  rows_epilogue<EPI, ACT>((float*)smem, (float*)smem + kGemmThreads / kWave * (32 * 64), acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1);
+}
+
+// flat row-tile index -> (vExpert, tile inside it): one wave scans the buckets' tile counts.
+// Returns false (for the whole workgroup) when the workgroup has no tile.
+struct RowTile {
+  int row0, rows_valid, e, n0, cols_valid;
+  int seg, nseg, slot;        // K segment of a split tile (nseg > 1) and its partial-tile slot
+};
+// Splitting the last, partly filled round of workgroups along K (plain-epilogue products with a long
+// contraction).  With T valid tiles on 256 compute units, the tiles of the row tiles from
+// r_split = floor(floor(T / 256) * 256 / col_tiles) on are the ones left for that last round; when
+// they fill at most a quarter of the chip, each is contracted by S = 4 workgroups (K segments of equal
+// length, a whole number of pipeline rounds each): segment 0 by the tile's own workgroup, segments
+// 1..S-1 by extra workgroups appended to the grid (block >= normal_grid).  Every segment leaves an
+// fp32 partial tile; rows_split_reduce_kernel adds them in segment order (fixed order: results do
+// not depend on scheduling).  The plan is a function of the bucket sizes: every workgroup derives
+// the same one.
+constexpr int kSplitMax = 4;
+constexpr int kSplitUnits = 256;                      // compute units a round of workgroups fills
+constexpr int kSplitMaxSlots = kSplitUnits;           // tail tiles x S <= 256
+struct SplitArg {
+  unsigned normal_grid;      // blocks of the unsplit grid; 0 = no splitting
+  int k_tiles;               // K / 32
+  int tail_tile;             // >= 0: look up this tail tile (reduce kernel) instead of `block`
+};
+template <bool SPLIT = false>
+__device__ __forceinline__ bool lookup_row_tile(const int32_t* __restrict__ voff, const int32_t* __restrict__ owner,
+                                                int V, int NC, int row_tiles_max, int col_tiles, unsigned block,
+                                                int* s_tile, RowTile* out, SplitArg sp = SplitArg{0, 0, -1}) {
+  if (threadIdx.x < kWave) {
+    const int lane = threadIdx.x;
+    if (lane == 0) s_tile[0] = -1;
+    const int per = (V + kWave - 1) / kWave;     // <= 8 buckets per lane
+    int cnt[FLEXMOE_MAX_VEXPERTS / kWave], lo[FLEXMOE_MAX_VEXPERTS / kWave], hi[FLEXMOE_MAX_VEXPERTS / kWave];
+    int own[FLEXMOE_MAX_VEXPERTS / kWave];
+    int sum = 0;
+#pragma unroll
+    for (int q = 0; q < FLEXMOE_MAX_VEXPERTS / kWave; ++q) {
+      const int v = lane * per + q;
+      cnt[q] = lo[q] = hi[q] = own[q] = 0;
+      if (q < per && v < V) {
+        lo[q] = voff[v];
+        hi[q] = voff[v + 1];
+        own[q] = owner[v];                         // fetched now: no second round trip once the bucket is known
+        cnt[q] = (hi[q] - lo[q] + BM - 1) / BM;
+      }
+      sum += cnt[q];
+    }
+    int incl = sum;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const int up = __shfl_up(incl, o);
+      if (lane >= o) incl += up;
+    }
+    int rt = -1, ct = 0;
+    int seg = 0, nseg = 1, slot = 0;
+    if (SPLIT && sp.normal_grid) {
+      const int rows_act = __shfl(incl, kWave - 1);
+      const int full = rows_act * col_tiles / kSplitUnits;
+      const int r_split = full * kSplitUnits / col_tiles;
+      const int tail_tiles = (rows_act - r_split) * col_tiles;
+      // four segments or none: cutting in two (tails of 65 to 128 tiles) measured no faster than not
+      // cutting, the fp32 round trip of the partial tiles eats what the shorter last round gains
+      const int S = (full >= 1 && tail_tiles > 0 && kSplitMax * tail_tiles <= kSplitUnits &&
+                     sp.k_tiles % (4 * kSplitMax) == 0) ? kSplitMax : 1;
+      if (sp.tail_tile < 0 && block < sp.normal_grid) {
+        if (!patched_tile(block, row_tiles_max, col_tiles, &rt, &ct)) rt = -1;
+        if (S > 1 && rt >= r_split && rt < rows_act) {
+          nseg = S;
+          slot = ((rt - r_split) * col_tiles + ct) * S;
+        }
+      } else if (S > 1) {
+        const int x = sp.tail_tile >= 0 ? sp.tail_tile * (S - 1) : (int)(block - sp.normal_grid);
+        const int tt = x / (S - 1);
+        if (tt < tail_tiles) {
+          rt = r_split + tt / col_tiles;
+          ct = tt % col_tiles;
+          nseg = S;
+          seg = 1 + x % (S - 1);
+          slot = tt * S + seg;
+        }
+      }
+    } else {
+      if (!patched_tile(block, row_tiles_max, col_tiles, &rt, &ct)) rt = -1;
+    }
+    int start = incl - sum;
+#pragma unroll
+    for (int q = 0; q < FLEXMOE_MAX_VEXPERTS / kWave; ++q) {
+      if (rt >= start && rt < start + cnt[q]) {
+        const int row0 = lo[q] + (rt - start) * BM;
+        s_tile[0] = row0;
+        s_tile[1] = min(BM, hi[q] - row0);
+        s_tile[2] = own[q];
+        s_tile[3] = ct;
+        if (SPLIT) {
+          s_tile[4] = seg;
+          s_tile[5] = nseg;
+          s_tile[6] = slot;
+        }
+      }
+      start += cnt[q];
+    }
+  }
+  __syncthreads();
+  if (s_tile[0] < 0) return false;                    // beyond the last tile (uniform)
+  // workgroup-uniform values: keep them in scalar registers (scalar base addresses, scalar compares)
+  out->row0 = __builtin_amdgcn_readfirstlane(s_tile[0]);
+  out->rows_valid = __builtin_amdgcn_readfirstlane(s_tile[1]);
+  out->e = __builtin_amdgcn_readfirstlane(s_tile[2]);
+  out->n0 = __builtin_amdgcn_readfirstlane(s_tile[3] * BN);
+  out->cols_valid = min(BN, NC - out->n0);
+  out->seg = SPLIT ? __builtin_amdgcn_readfirstlane(s_tile[4]) : 0;
+  out->nseg = SPLIT ? __builtin_amdgcn_readfirstlane(s_tile[5]) : 1;
+  out->slot = SPLIT ? __builtin_amdgcn_readfirstlane(s_tile[6]) : 0;
+  return true;
+}
+
+template <bool WT, int EPI, int ACT>
+__global__ __launch_bounds__(kGemmThreads) void rows_gemm_bf16(
+    const bf16_t* __restrict__ in, const bf16_t* __restrict__ w, const bf16_t* __restrict__ bias,
+    const int32_t* __restrict__ voff, const int32_t* __restrict__ owner, int V, int K, int NC, int row_tiles_max,
+    int col_tiles, const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0, bf16_t* __restrict__ out1) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t* smem = (bf16_t*)smem_raw;
+  __shared__ int s_tile[4];
+  RowTile t;
+  if (!lookup_row_tile(voff, owner, V, NC, row_tiles_max, col_tiles, blockIdx.x, s_tile, &t)) return;
+  // Ragged tiles run the full-tile code (rows past the bucket are clamped on load and dropped
+  // on store): skipping their empty 32-row MFMA blocks needs conditional MFMA groups, which the
+  // register allocator only handles by spilling the accumulators.
+  rows_tile<WT, EPI, ACT, true>(smem, in, w, bias, K, NC, t.row0, t.rows_valid, t.e, t.n0, t.cols_valid, hpre_in,
+                                out0, out1);
+}
+
+}  // namespace flexmoe

@@ -1,0 +1,342 @@
+// Weight-gradient kernels on the direct-to-LDS pipeline, the shared backward launch and the segment reduce.
+// Part of the bf16 expert-FFN kernels; included by ffn_bf16.hip only (one translation unit).
+#pragma once
+#include "common.h"
+#include "ffn_bf16_dma.h"
+namespace flexmoe {
+// Work list of the weight-gradient kernels.  Experts are taken by descending load (ties by
+// ascending id: the long contractions start first).  An expert's contraction runs over its
+// non-empty buckets in ascending vExpert id, in K tiles of 32 tokens; with seg_tiles > 0 it is cut
+// into segments of seg_tiles K tiles that different workgroups contract (a hot expert would
+// otherwise be one long serial K loop): an expert with more than one segment leaves fp32 partial
+// tiles in the workspace, `slot` numbering them, which wgrad_reduce_kernel adds up in segment
+// order.  The whole list is a function of the bucket sizes only, so every workgroup re-derives it.
+struct WgradJob {
+  int e;        // expert, -1: no job
+  int seg;      // segment of the expert's contraction
+  int nseg;     // segments of this expert
+  int slot;     // index of the expert's first partial tile set (meaningful when nseg > 1)
+};
+struct WgradShared {
+  int cnt[FLEXMOE_MAX_VEXPERTS], own[FLEXMOE_MAX_VEXPERTS];
+  int load[FLEXMOE_MAX_EXPERTS], tiles[FLEXMOE_MAX_EXPERTS];
+  int rank_e[FLEXMOE_MAX_EXPERTS], rank_s[FLEXMOE_MAX_EXPERTS];
+  int job[4];
+  int nb;
+  int bstart[FLEXMOE_MAX_VEXPERTS], brows[FLEXMOE_MAX_VEXPERTS];
+};
+
+// `want` counts segments in work-list order (rank-major).  Also fills sh.bstart/brows/nb with the
+// expert's buckets.
+// `table` (optional, [E] entries of {expert, segments, first slot, 0} by load rank) is written by the
+// caller that passes it, for wgrad_reduce_kernel.
+__device__ __forceinline__ WgradJob wgrad_plan(const int32_t* __restrict__ voff, const int32_t* __restrict__ owner,
+                                               int E, int V, int seg_tiles, int want, WgradShared& sh,
+                                               int4* __restrict__ table) {
+  for (int v = threadIdx.x; v < V; v += kGemmThreads) {
+    sh.cnt[v] = voff[v + 1] - voff[v];
+    sh.own[v] = owner[v];
+  }
+  for (int e = threadIdx.x; e < E; e += kGemmThreads) {
+    sh.load[e] = 0;
+    sh.tiles[e] = 0;
+  }
+  if (threadIdx.x == 0) sh.job[0] = -1;
+  __syncthreads();
+  for (int v = threadIdx.x; v < V; v += kGemmThreads) {
+    atomicAdd(&sh.load[sh.own[v]], sh.cnt[v]);
+    atomicAdd(&sh.tiles[sh.own[v]], (sh.cnt[v] + DK - 1) / DK);
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < E; e += kGemmThreads) {
+    const int l = sh.load[e];
+    int rank = 0;
+    for (int o = 0; o < E; ++o) {
+      const int lo = sh.load[o];
+      rank += (lo > l || (lo == l && o < e)) ? 1 : 0;
+    }
+    sh.rank_e[rank] = e;
+    sh.rank_s[rank] = seg_tiles > 0 ? max(1, (sh.tiles[e] + seg_tiles - 1) / seg_tiles) : 1;
+  }
+  __syncthreads();
+  if (threadIdx.x < kWave) {
+    // prefix over the ranks of the segment counts (and of the segment counts of split experts)
+    const int lane = threadIdx.x;
+    constexpr int kPer = FLEXMOE_MAX_EXPERTS / kWave;
+    int sum = 0, sum_split = 0;
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+      const int r = lane * kPer + q;
+      const int n = r < E ? sh.rank_s[r] : 0;
+      sum += n;
+      sum_split += n > 1 ? n : 0;
+    }
+    int incl = sum, incl_split = sum_split;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const int up = __shfl_up(incl, o), up2 = __shfl_up(incl_split, o);
+      if (lane >= o) {
+        incl += up;
+        incl_split += up2;
+      }
+    }
+    int start = incl - sum, slot = incl_split - sum_split;
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+      const int r = lane * kPer + q;
+      const int n = r < E ? sh.rank_s[r] : 0;
+      const bool hit = want >= start && want < start + n;
+      if (hit) {
+        sh.job[0] = sh.rank_e[r];
+        sh.job[1] = want - start;
+        sh.job[2] = n;
+        sh.job[3] = slot;
+      }
+      if (table && r < E) table[r] = make_int4(sh.rank_e[r], n, slot, 0);
+      start += n;
+      slot += n > 1 ? n : 0;
+    }
+  }
+  __syncthreads();
+  WgradJob job{sh.job[0], sh.job[1], sh.job[2], sh.job[3]};
+  if (job.e < 0) return job;                    // uniform
+  if (threadIdx.x < kWave) {                   // the expert's non-empty buckets, ascending vExpert id
+    const int lane = threadIdx.x;
+    const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    int nbw = 0;
+    for (int vb = 0; vb < V; vb += kWave) {
+      const int v = vb + lane;
+      const bool hit = v < V && sh.own[v] == job.e && sh.cnt[v] > 0;
+      const unsigned long long mask = __ballot(hit);
+      if (hit) {
+        const int pos = nbw + __popcll(mask & lt);
+        sh.bstart[pos] = voff[v];
+        sh.brows[pos] = sh.cnt[v];
+      }
+      nbw += __popcll(mask);
+    }
+    if (lane == 0) sh.nb = nbw;
+  }
+  __syncthreads();
+  return job;
+}
+
+// =============================================================================================
+// wgrad_gemm_dma: dW_e[m, n] = sum_{v owned by e, ascending v} sum_{p in bucket v} L[p, m] * R[p, n]
+// on the direct-to-LDS pipeline.  Both operands
+// are token-major ([tokens, M] and [tokens, NC]), i.e. contraction-strided: their 32-token K tiles
+// are copied to LDS as stored and transposed by the LDS reads.  Tokens past the end of a bucket
+// (the ragged last K tile of each vExpert, and the padding that rounds the tile count up to the
+// pipeline's multiple of 4) are fetched from a row of zeros instead, since direct loads cannot
+// be predicated to zero.
+// =============================================================================================
+__device__ const uint4 kZeroRow[32] = {};
+
+struct DmaSrcTok {
+  uint32_t off[4];
+  int krow[4];
+  size_t ld;
+  __device__ __forceinline__ void init(size_t ld_, int cols_valid) {
+    ld = ld_;
+    const int w = threadIdx.x >> 6, i = threadIdx.x & 63;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      krow[q] = (w * 4 + q) * 2 + (i >> 5);
+      const int c = min(dmat_chunk(krow[q], i & 31), cols_valid / 8 - 1);
+      off[q] = (uint32_t)(krow[q] * ld + c * 8);
+    }
+  }
+  // `p`: token row 0 of this K tile, first column of the tile; rows >= k_valid come from kZeroRow
+  __device__ __forceinline__ void part(lds_byte_t* tile, const bf16_t* __restrict__ p, int k_valid, int q) const {
+    const unsigned w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)tile) + w * 4096;
+    const bf16_t* z = (const bf16_t*)kZeroRow + (threadIdx.x & 31) * 8;
+    const bf16_t* g = (k_valid >= DK || krow[q] < k_valid) ? p + off[q] : z;
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" FLEXMOE_DMA_CPOL ::"v"(g), "s"(lds0 + q * 1024) : "memory");
+  }
+};
+
+// Tile sequence of the weight-gradient kernel: 32-token K tiles of the expert's buckets in
+// ascending vExpert id, then all-zero tiles up to the padded count.  The position (row pointers of
+// both operands, rows left in the bucket) lives in workgroup-uniform values and advances by
+// pointer increments; the bucket list in LDS is read only when a bucket is exhausted.
+struct WgradIssue {
+  const DmaSrcTok& l_src;
+  const DmaSrcTok& r_src;
+  const bf16_t* L;
+  const bf16_t* R;
+  const int* bstart;
+  const int* brows;
+  int M, NC, m0, n0, nb, T;
+  int bi, issued;
+  const bf16_t* lp;                 // token row 0 of the next K tile, first column of the tile
+  const bf16_t* rp;
+  int rows_left;                    // rows of bucket bi from that row on
+  __device__ __forceinline__ void seek(int bucket, int koff) {
+    bi = bucket;
+    const int start = __builtin_amdgcn_readfirstlane(bstart[bi]);
+    rows_left = __builtin_amdgcn_readfirstlane(brows[bi]) - koff;
+    lp = L + ((size_t)start + koff) * M + m0;
+    rp = R + ((size_t)start + koff) * NC + n0;
+  }
+  __device__ __forceinline__ void begin() {}
+  __device__ __forceinline__ void part(lds_byte_t* stage, int q) const {
+    const int kv = issued < T ? rows_left : 0;
+    if (q < 4) l_src.part(stage, lp, kv, q);
+    else r_src.part(stage + kDmaTileBytes, rp, kv, q - 4);
+  }
+  __device__ __forceinline__ void end() {
+    ++issued;
+    if (issued < T) {
+      rows_left -= DK;
+      lp += (size_t)DK * M;
+      rp += (size_t)DK * NC;
+      if (rows_left <= 0) seek(min(bi + 1, nb - 1), 0);
+    }
+  }
+};
+
+// Arguments of one weight-gradient GEMM (device pointers; see wgrad_gemm_dma_bf16).
+struct WgradDmaArgs {
+  const bf16_t* L;
+  const bf16_t* R;
+  const int32_t* voff;
+  const int32_t* owner;
+  int E, V, M, NC, m_tiles, n_tiles, seg_tiles, seg_rows_max;
+  float* partial;
+  int4* table;
+  bf16_t* dw;
+};
+
+// One workgroup's tile of a weight-gradient GEMM; `block` is its index in that GEMM's (patched) grid.
+__device__ __forceinline__ void wgrad_dma_block(const WgradDmaArgs& p, unsigned block, unsigned char* stage0,
+                                                unsigned char* stage1, unsigned char* stage2, unsigned char* stage3,
+                                                WgradShared& sh) {
+  const bf16_t* __restrict__ L = p.L;
+  const bf16_t* __restrict__ R = p.R;
+  const int M = p.M, NC = p.NC, m_tiles = p.m_tiles, seg_tiles = p.seg_tiles;
+  float* __restrict__ partial = p.partial;
+  bf16_t* __restrict__ dw = p.dw;
+  // tile grid: rows = (work-list segment, m tile), cols = n tile
+  int grow, nt;
+  if (!patched_tile(block, p.seg_rows_max * p.m_tiles, p.n_tiles, &grow, &nt)) return;
+  const int mt = grow % m_tiles;
+  const WgradJob job = wgrad_plan(p.voff, p.owner, p.E, p.V, seg_tiles, grow / m_tiles, sh, block == 0 ? p.table : nullptr);
+  if (job.e < 0) return;
+  const int nb = sh.nb;
+
+  const int m0 = mt * BM, n0 = nt * BN;
+  const int mvalid = min(BM, M - m0), nvalid = min(BN, NC - n0);
+  const int wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  f32x16 acc[MB][NB];
+  zero_acc(acc);
+  lds_byte_t* s0 = (lds_byte_t*)stage0;
+
+  if (nb > 0) {
+    int Te = 0;
+    for (int b = 0; b < nb; ++b) Te += (sh.brows[b] + DK - 1) / DK;
+    // this job's K tiles [lo, hi) of the expert's sequence, and the bucket / offset where they start
+    const int lo = job.nseg > 1 ? job.seg * seg_tiles : 0;
+    const int hi = job.nseg > 1 ? min(Te, lo + seg_tiles) : Te;
+    int bi = 0, skip = lo;
+    while (bi < nb - 1 && skip >= (sh.brows[bi] + DK - 1) / DK) {
+      skip -= (sh.brows[bi] + DK - 1) / DK;
+      ++bi;
+    }
+    const int T = hi - lo;
+    const int KT = (T + 3) & ~3;                 // padded with all-zero tiles
+    DmaSrcTok l_src, r_src;
+    l_src.init(M, mvalid);
+    r_src.init(NC, nvalid);
+    WgradIssue issue{l_src, r_src, L, R, sh.bstart, sh.brows, M, NC, m0, n0, nb, T, 0, 0, nullptr, nullptr, 0};
+    issue.seek(bi, skip * DK);
+    dma_pipeline<true, true>(s0, (lds_byte_t*)stage1, (lds_byte_t*)stage2, (lds_byte_t*)stage3, acc, issue, KT, wm, wn);
+  }
+
+  float* patch = (float*)stage0 + wave * (32 * 64);
+  float* patch_alt = (float*)stage1 + wave * (32 * 64);
+  const int col_base = n0 + wn * (NB * 32);
+  auto tile_row = [&](int row_w) { return (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31); };
+  if (job.nseg == 1) {
+    bf16_t* out = dw + (size_t)job.e * M * NC;
+    epilogue_rounds<false>(
+        patch, patch_alt, acc, [](int, int) { return make_uint2(0, 0); },
+        [](int, int, float4 c, uint2) { return EpiOut{pack4(c.x, c.y, c.z, c.w), make_uint2(0, 0)}; },
+        [&](int row_w, int col_w, const EpiOut& o) {
+          const int lrow = tile_row(row_w);
+          const int col = col_base + col_w;
+          if (lrow < mvalid && col < NC) *(uint2*)(out + (size_t)(m0 + lrow) * NC + col) = o.a;
+        });
+  } else {
+    // one of several segments: the fp32 tile goes to the workspace for wgrad_reduce_kernel
+    float* out = partial + (size_t)(job.slot + job.seg) * M * NC;
+    epilogue_rounds<false>(
+        patch, patch_alt, acc, [](int, int) { return make_uint2(0, 0); },
+        [](int, int, float4 c, uint2) {
+          return EpiOut{make_uint2(__float_as_uint(c.x), __float_as_uint(c.y)),
+                        make_uint2(__float_as_uint(c.z), __float_as_uint(c.w))};
+        },
+        [&](int row_w, int col_w, const EpiOut& o) {
+          const int lrow = tile_row(row_w);
+          const int col = col_base + col_w;
+          if (lrow < mvalid && col < NC)
+            *(uint4*)(out + (size_t)(m0 + lrow) * NC + col) = make_uint4(o.a.x, o.a.y, o.b.x, o.b.y);
+        });
+  }
+}
+
+
+__global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_dma_bf16(const WgradDmaArgs p) {
+  __shared__ __align__(1024) unsigned char stage0[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage1[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage3[kDmaStageBytes];
+  __shared__ WgradShared sh;
+  wgrad_dma_block(p, blockIdx.x, stage0, stage1, stage2, stage3, sh);
+}
+
+// The three GEMMs of the backward pass that only depend on the dH kernel -- dXp = dHpre . W1^T,
+// dW2 and dW1 -- as one launch: workgroups [0, n_dx) take dXp's tiles, the next n_w2 dW2's, the rest
+// dW1's.  Each product alone ends in a partly filled last round of workgroups; in one grid the
+// next product's tiles fill those compute units.  n_dx and n_w2 are multiples of 8, so every
+// product keeps its workgroup -> XCD mapping.
+__global__ __launch_bounds__(kGemmThreads) void bwd_tail_dma_bf16(const RowsDmaArgs dx, unsigned n_dx,
+                                                                  const WgradDmaArgs g2, unsigned n_w2,
+                                                                  const WgradDmaArgs g1) {
+  __shared__ __align__(1024) unsigned char stage0[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage1[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage3[kDmaStageBytes];
+  __shared__ WgradShared sh;
+  __shared__ int s_tile[8];
+  const unsigned b = blockIdx.x;
+  if (b < n_dx)
+    rows_dma_block<true, EPI_PLAIN, FLEXMOE_RELU>(dx, b, (lds_byte_t*)stage0, (lds_byte_t*)stage1, (lds_byte_t*)stage2,
+                                                   (lds_byte_t*)stage3, nullptr, s_tile);
+  else
+    wgrad_dma_block(b < n_dx + n_w2 ? g2 : g1, b < n_dx + n_w2 ? b - n_dx : b - n_dx - n_w2, stage0, stage1, stage2,
+                    stage3, sh);
+}
+
+// dW_e = sum of the expert's partial tiles in segment order, for the experts that were split.
+// Grid: (element blocks of the [M, NC] matrix, load rank); `table` as left by the GEMM kernel.
+__global__ __launch_bounds__(kGemmThreads) void wgrad_reduce_kernel(const int4* __restrict__ table, int M, int NC,
+                                                                    const float* __restrict__ partial,
+                                                                    bf16_t* __restrict__ dw) {
+  const int4 t = table[blockIdx.y];             // {expert, segments, first slot}
+  if (t.y <= 1) return;
+  const size_t n4 = (size_t)M * NC / 4;
+  const float4* p = (const float4*)(partial + (size_t)t.z * M * NC);
+  uint2* out = (uint2*)(dw + (size_t)t.x * M * NC);
+  for (size_t i = (size_t)blockIdx.x * kGemmThreads + threadIdx.x; i < n4; i += (size_t)gridDim.x * kGemmThreads) {
+    float4 s4 = p[i];
+    for (int sgm = 1; sgm < t.y; ++sgm) {
+      const float4 v = p[(size_t)sgm * n4 + i];
+      s4.x += v.x; s4.y += v.y; s4.z += v.z; s4.w += v.w;
+    }
+    out[i] = pack4(s4.x, s4.y, s4.z, s4.w);
+  }
+}
+
+}  // namespace flexmoe
