@@ -396,6 +396,38 @@ def test_top1_forward_equals_the_staged_forward(api, bias):
     assert np.array_equal(host(L.y), want["y"]) and bool((L.hpre == 3.0).all())
 
 
+@pytest.mark.parametrize("N,d,f,E,V,k,bias", [(70000, 128, 1024, 4, 7, 1, False), (40000, 256, 1024, 6, 9, 1, True),
+                                               (36000, 384, 1024, 5, 9, 2, False), (33000, 256, 2048, 8, 16, 2, True),
+                                               (66100, 128, 1152, 3, 5, 1, True)])
+def test_forward_variants_agree_bit_for_bit(api, N, d, f, E, V, k, bias):
+    """The staged forward, the gathered forward, the top-1 call and their hpre = NULL forms run the same
+    tiles with the same arithmetic: identical bits on shapes that reach one or several rounds of workgroups,
+    with and without a split last round (no oracle needed: the staged forward is checked against it elsewhere)."""
+    binding, layer_mod = api
+    cfg = W.scaled(W.CONFIGS["gpt_m"], N=N, d=d, f=f, E=E, V=V, k=k, max_rep=4, backward=False)
+    inp = W.make_layer_inputs(cfg)
+    dev = upload(layer_mod, inp)
+    rng = np.random.default_rng(N)
+    b1 = layer_mod.to_device(W.Bf16Tensor.from_f32((rng.standard_normal((E, f)) * 0.3).astype(np.float32))) if bias else None
+    b2 = layer_mod.to_device(W.Bf16Tensor.from_f32((rng.standard_normal((E, d)) * 0.3).astype(np.float32))) if bias else None
+    rep = W.placement_from_loads(W.prior_loads(cfg), V, cfg.max_rep, shuffle_seed=N)
+    L = layer_mod.MoELayer.for_config(cfg)
+    L.forward(dev["x"], dev["wg"], dev["w1"], dev["w2"], *rep, b1, b2)
+    torch.cuda.synchronize()
+    want = {n: getattr(L, n).clone() for n in ("hpre", "yp", "y")}
+    variants = [("gathered", L.forward_fused, True, ("hpre", "yp", "y")), ("gathered, no hpre", L.forward_fused, False, ("yp", "y")),
+                ("staged, no hpre", L.forward, False, ("yp", "y"))]
+    if L.top1_supported():
+        variants += [("top-1", L.forward_top1, True, ("hpre", "y")), ("top-1, no hpre", L.forward_top1, False, ("y",))]
+    for tag, fn, keep, outs in variants:
+        for n in ("hpre", "yp", "y"):
+            getattr(L, n).zero_()
+        fn(dev["x"], dev["wg"], dev["w1"], dev["w2"], *rep, b1, b2, keep_hpre=keep)
+        torch.cuda.synchronize()
+        for n in outs:
+            assert torch.equal(getattr(L, n), want[n]), f"{tag}: {n}"
+
+
 def test_gathered_forward_refuses_what_it_cannot_do(api):
     binding, layer_mod = api
     cfg = SMALL["bert_small"]                       # d = 328: not a multiple of 128
