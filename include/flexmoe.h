@@ -131,6 +131,20 @@ int flexmoe_expert_ffn_bwd(const void* dyp, const void* xp, const void* hpre,
                            void* dxp, void* dw1, void* dw2, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * flexmoe_expert_ffn_bwd for a top-1 layer (k = 1) with the backward reverse routing folded in: bucket
+ * row p of dXp is stored as row src[p] of dx, i.e. dx [N,d] is the expert-path gradient of the layer
+ * input and flexmoe_combine(dxp, dest, NULL) is not needed (same bits).  dw1, dw2 as in
+ * flexmoe_expert_ffn_bwd; the workspace afterwards serves flexmoe_expert_bias_grads in the same way.
+ *   src [N] as written by flexmoe_route with k = 1.
+ * FLEXMOE_UNSUPPORTED unless dtype is bf16 and f is a multiple of 128.
+ */
+int flexmoe_expert_ffn_bwd_top1(const void* dyp, const void* xp, const void* hpre,
+                                const void* w1, const void* w2,
+                                const int32_t* vexpert_off, const int32_t* vexpert_owner, const int32_t* src,
+                                int N, int d, int f, int E, int V, int act, int dtype,
+                                void* dx, void* dw1, void* dw2, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Reverse routing and gate-weighted sum, Eq. 4:
  *   y[t,:] = sum_j (topk_w ? topk_w[t*k+j] : 1) * yp[dest[t*k+j], :]
  *   yp [A,d] dtype, dest [A], topk_w [N,k] float or NULL -> y [N,d] dtype (fp32 accumulation).

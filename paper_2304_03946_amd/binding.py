@@ -23,7 +23,7 @@ OK, INVALID_ARG, BAD_PLACEMENT, WORKSPACE_TOO_SMALL, UNSUPPORTED, DEVICE_ERROR =
 EXPORTS = ["flexmoe_status_str", "flexmoe_workspace_bytes", "flexmoe_gate_topk", "flexmoe_route",
            "flexmoe_permute", "flexmoe_expert_ffn_fwd", "flexmoe_expert_ffn_bwd", "flexmoe_combine",
            "flexmoe_gate_bwd", "flexmoe_expert_bias_grads", "flexmoe_expert_ffn_fwd_gather",
-           "flexmoe_expert_ffn_fwd_top1",
+           "flexmoe_expert_ffn_fwd_top1", "flexmoe_expert_ffn_bwd_top1",
            # host-side scheduler (include/flexmoe_scheduler.h; Python face in scheduler.py)
            "flexmoe_balance_ratio", "flexmoe_step_cost", "flexmoe_make_scheduling_plan", "flexmoe_schedule",
            "flexmoe_placement_table"]
@@ -68,6 +68,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.flexmoe_expert_ffn_fwd_gather.argtypes = [c_vp] * 8 + [c_int] * 8 + [c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.flexmoe_expert_ffn_fwd_top1.restype = c_int
     lib.flexmoe_expert_ffn_fwd_top1.argtypes = [c_vp] * 8 + [c_int] * 7 + [c_vp, c_vp, c_vp, c_sz, c_vp]
+    lib.flexmoe_expert_ffn_bwd_top1.restype = c_int
+    lib.flexmoe_expert_ffn_bwd_top1.argtypes = [c_vp] * 8 + [c_int] * 7 + [c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.flexmoe_gate_bwd.restype = c_int
     lib.flexmoe_gate_bwd.argtypes = [c_vp] * 10 + [c_int] * 6 + [c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.flexmoe_expert_bias_grads.restype = c_int
@@ -155,6 +157,17 @@ def flexmoe_permute(x, src, row_scale, k, xp):
     N, d = x.shape
     st = load_library().flexmoe_permute(_ptr(x), _ptr(src), _ptr(row_scale), N, k, d, dtype_code(x), _ptr(xp), _stream())
     _check(st, "flexmoe_permute")
+
+
+def flexmoe_expert_ffn_bwd_top1(dyp, xp, hpre, w1, w2, vexpert_off, vexpert_owner, src, act, dx, dw1, dw2, ws):
+    N, d = xp.shape
+    E, _, f = w1.shape
+    V = vexpert_owner.shape[0]
+    st = load_library().flexmoe_expert_ffn_bwd_top1(_ptr(dyp), _ptr(xp), _ptr(hpre), _ptr(w1), _ptr(w2),
+                                                    _ptr(vexpert_off), _ptr(vexpert_owner), _ptr(src), N, d, f, E, V,
+                                                    act, dtype_code(xp), _ptr(dx), _ptr(dw1), _ptr(dw2), _ptr(ws),
+                                                    ws.numel() * ws.element_size(), _stream())
+    _check(st, "flexmoe_expert_ffn_bwd_top1")
 
 
 def flexmoe_combine(yp, dest, topk_w, k, y):

@@ -187,6 +187,24 @@ int flexmoe_expert_ffn_bwd(const void* dyp, const void* xp, const void* hpre, co
                                           : launch_ffn_bwd_f32(a, dyp, xp, hpre, w1, w2, dxp, dw1, dw2, ws, s));
 }
 
+int flexmoe_expert_ffn_bwd_top1(const void* dyp, const void* xp, const void* hpre, const void* w1, const void* w2,
+                                const int32_t* vexpert_off, const int32_t* vexpert_owner, const int32_t* src,
+                                int N, int d, int f, int E, int V, int act, int dtype,
+                                void* dx, void* dw1, void* dw2, void* ws, size_t ws_bytes, void* stream) {
+  if (N < 0 || N >= (1 << 30)) return FLEXMOE_INVALID_ARG;
+  const int st = ffn_common(N, d, f, E, V, act, dtype, vexpert_off, vexpert_owner, ws, ws_bytes);
+  if (st != FLEXMOE_OK) return st;
+  // scattered stores exist on the bf16 direct-to-LDS path only (dXp contracts over f)
+  if (dtype != FLEXMOE_BF16 || (f % 128)) return FLEXMOE_UNSUPPORTED;
+  if (!w1 || !w2 || !dw1 || !dw2 || !aligned16(w1) || !aligned16(w2) || !aligned16(dw1) || !aligned16(dw2))
+    return FLEXMOE_INVALID_ARG;
+  if (N > 0 && (!dyp || !xp || !hpre || !dx || !src || !aligned16(dyp) || !aligned16(xp) || !aligned16(hpre) ||
+                !aligned16(dx)))
+    return FLEXMOE_INVALID_ARG;
+  const FfnArgs a{N, d, f, E, V, act, vexpert_off, vexpert_owner};
+  return dev_status(launch_ffn_bwd_bf16(a, dyp, xp, hpre, w1, w2, dx, dw1, dw2, ws, (hipStream_t)stream, src));
+}
+
 int flexmoe_gate_bwd(const void* wg, const int32_t* topk_idx, const float* topk_w, const void* dy, const void* yp,
                      const void* xp, const int32_t* dest, const int32_t* src, const int32_t* vexpert_off,
                      const int32_t* vexpert_owner, int N, int d, int E, int k, int V, int dtype, float* dl, void* dx,

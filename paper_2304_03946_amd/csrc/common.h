@@ -163,7 +163,8 @@ hipError_t launch_ffn_fwd_top1_bf16(const FfnArgs& a, const void* x, const int32
                                     const void* w2, const void* b2, void* hpre, void* y, void* ws, hipStream_t s);
 hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp, const void* hpre,
                                const void* w1, const void* w2, void* dxp, void* dw1, void* dw2,
-                               void* ws, hipStream_t s);
+                               void* ws, hipStream_t s,
+                               const int32_t* scatter_src = nullptr);
 // gate-path backward and bias gradients (gate_bwd.hip)
 size_t gate_bwd_ws_bytes(int A, int d, int E, int V, int dtype);
 hipError_t launch_gate_bwd(const void* wg, const int32_t* idx, const float* w, const void* dy,

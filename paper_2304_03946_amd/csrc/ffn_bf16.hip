@@ -260,8 +260,11 @@ hipError_t launch_ffn_fwd_top1_bf16(const FfnArgs& a, const void* x, const int32
   return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, y, nullptr, s, nullptr, 1, rows_split_ws(a, ws), src);
 }
 
+// scatter_src (top-1 layers, needs f % 128 == 0): bucket row p of dXp is stored as row scatter_src[p] of
+// `dxp`, which is then dX [N, d] itself -- the backward reverse routing folded into the epilogue.
 hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp, const void* hpre, const void* w1,
-                               const void* w2, void* dxp, void* dw1, void* dw2, void* ws, hipStream_t s) {
+                               const void* w2, void* dxp, void* dw1, void* dw2, void* ws, hipStream_t s,
+                               const int32_t* scatter_src) {
   bf16_t* dhpre = (bf16_t*)ws;
   bf16_t* h = (bf16_t*)((char*)ws + align_up((size_t)a.A * a.f * sizeof(bf16_t), 256));
   hipError_t err;
@@ -281,7 +284,8 @@ hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp
   if (a.A > 0 && a.f % 128 == 0 && dx_tiles <= 8 * 256) {
     auto round8 = [](unsigned n) { return (n + 7u) & ~7u; };
     unsigned grid2, grid1;
-    const RowsDmaArgs dx = rows_dma_args(a, dhpre, w1, nullptr, a.f, a.d, nullptr, dxp, nullptr, nullptr, 1);
+    RowsDmaArgs dx = rows_dma_args(a, dhpre, w1, nullptr, a.f, a.d, nullptr, dxp, nullptr, nullptr, 1);
+    dx.scatter_rows = scatter_src;
     const WgradDmaArgs g2 = wgrad_dma_args(a, h, dyp, a.f, a.d, dw2, ws_tail2, &grid2);
     const WgradDmaArgs g1 = wgrad_dma_args(a, xp, dhpre, a.d, a.f, dw1, ws_tail1, &grid1);
     const unsigned n_dx = round8(patched_grid(dx.row_tiles_max, dx.col_tiles)), n_w2 = round8(grid2);
@@ -293,7 +297,7 @@ hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp
   if (a.A > 0) {
     // dXp = dHpre . W1^T; W1_e is [d, f], contraction index f contiguous
     err = launch_rows<true, EPI_PLAIN>(a, dhpre, w1, nullptr, a.f, a.d, nullptr, dxp, nullptr, s, nullptr, 1,
-                                       rows_split_ws(a, ws));
+                                       rows_split_ws(a, ws), scatter_src);
     if (err != hipSuccess) return err;
   }
   err = launch_wgrad(a, h, dyp, a.f, a.d, dw2, ws_tail2, s);

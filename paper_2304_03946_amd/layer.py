@@ -131,6 +131,13 @@ class MoELayer:
         B.flexmoe_combine(self.dxp, self.dest, None, self.k, self.dx)
         return self.dx, self.dw1, self.dw2
 
+    def backward_top1(self, dy, w1, w2):
+        """`backward` for a top-1 layer: dX comes straight out of the expert backward (no dXp, no combine)."""
+        B.flexmoe_permute(dy, self.src, self.topk_w, self.k, self.dyp)
+        B.flexmoe_expert_ffn_bwd_top1(self.dyp, self.xp, self.hpre, w1, w2, self.vexpert_off, self.vexpert_owner,
+                                      self.src, self.act, self.dx, self.dw1, self.dw2, self.ws)
+        return self.dx, self.dw1, self.dw2
+
     def backward_full(self, dy, wg, w1, w2):
         """Backward of everything trainable: the expert path as in `backward`, plus the bias
         gradients and the gate path (dW_g, and the gate's share of dX added to self.dx)."""

@@ -98,6 +98,8 @@ def test_argument_validation_needs_no_device():
                                            one, one, 1 << 20, null) == binding.UNSUPPORTED
     assert lib.flexmoe_expert_ffn_fwd_top1(one, one, one, one, one, null, one, null, 64, 128, 128, 4, 4, relu, bf16, one,
                                            null, one, 1 << 20, null) == binding.INVALID_ARG
+    assert lib.flexmoe_expert_ffn_bwd_top1(one, one, one, one, one, one, one, one, 64, 128, 64, 4, 4, relu, bf16, one,
+                                           one, one, one, 1 << 20, null) == binding.UNSUPPORTED
     # a placement table that leaves an expert without a vExpert (host arrays: these are read)
     off = (ctypes.c_int32 * 3)(0, 2, 2)
     ids = (ctypes.c_int32 * 2)(0, 1)

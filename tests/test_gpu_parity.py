@@ -428,6 +428,33 @@ def test_forward_variants_agree_bit_for_bit(api, N, d, f, E, V, k, bias):
             assert torch.equal(getattr(L, n), want[n]), f"{tag}: {n}"
 
 
+@pytest.mark.parametrize("name", ["swin_small", "many_rounds"])
+def test_top1_backward_equals_the_staged_backward(api, name):
+    """flexmoe_expert_ffn_bwd_top1 stores dXp's rows through src: the same dX as the staged backward's
+    combine, and the same weight gradients, bit for bit (shared launch and, at the larger size, the
+    separate dXp launch)."""
+    binding, layer_mod = api
+    if name == "swin_small":
+        cfg = SMALL[name]
+    else:   # dXp alone: more than eight rounds of workgroups are needed for the separate launch
+        cfg = W.scaled(W.CONFIGS["swin"], N=70000, d=2048, f=128, E=4, V=6, max_rep=2)
+    inp = W.make_layer_inputs(cfg)
+    dev = upload(layer_mod, inp)
+    rep = W.placement_from_loads(W.prior_loads(cfg), cfg.V, cfg.max_rep, shuffle_seed=9)
+    L = layer_mod.MoELayer.for_config(cfg)
+    L.forward(dev["x"], dev["wg"], dev["w1"], dev["w2"], *rep)
+    L.backward(dev["dy"], dev["w1"], dev["w2"])
+    torch.cuda.synchronize()
+    want = {n: getattr(L, n).clone() for n in ("dx", "dw1", "dw2")}
+    for n in ("dx", "dw1", "dw2", "dxp"):
+        getattr(L, n).zero_()
+    L.backward_top1(dev["dy"], dev["w1"], dev["w2"])
+    torch.cuda.synchronize()
+    for n in want:
+        assert torch.equal(getattr(L, n), want[n]), n
+    assert not bool(L.dxp.any()), "the fused backward must not touch dxp"
+
+
 def test_gathered_forward_refuses_what_it_cannot_do(api):
     binding, layer_mod = api
     cfg = SMALL["bert_small"]                       # d = 328: not a multiple of 128
