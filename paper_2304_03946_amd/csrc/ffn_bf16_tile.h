@@ -255,6 +255,19 @@ template <int EPI, int ACT> constexpr bool epilogue_uses_lut() { return EPI != E
 struct EpiOut {
   uint2 a, b;
 };
+// 8-byte store with the non-temporal hint.  Used for the large outputs of the epilogues that carry an
+// activation (Hpre and H of the forward, dHpre and H of the backward) and for the weight gradients:
+// streamed out, they do not displace the operands the running product keeps re-reading in L2 and the
+// Infinity Cache (measured: -4.5 % on the BERT-like layer's step, -2.4 % on the GPT-medium-like one,
+// -1 % on the GPT-XL-like one).  The plain epilogue's output (Yp, dXp) keeps the default policy: the
+// combine kernel reads it straight away, and streaming it out costs there what it gains here.
+__device__ __forceinline__ void store_nt8(bf16_t* p, uint2 v) {
+  typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+  u32x2_t v2;
+  v2[0] = v.x;
+  v2[1] = v.y;
+  __builtin_nontemporal_store(v2, (u32x2_t*)p);
+}
 template <bool FETCH, typename Fetch, typename Compute, typename Store>
 __device__ __forceinline__ void epilogue_rounds(float* patch0, float* patch1, const f32x16 (&acc)[MB][NB], Fetch fetch,
                                                 Compute compute, Store store) {
@@ -463,8 +476,11 @@ __device__ __forceinline__ void rows_epilogue_t(float* lds, float* lds_alt, cons
       if (EPI == EPI_PLAIN && smap) {
         // scattered store: tile row lrow is row smap[lrow] of the output (reverse routing of a top-1 layer)
         *(uint2*)(out0 + (size_t)smap[lrow] * NC + col_base + col_w) = o.a;
-      } else if (EPI != EPI_FWD1 || out0) *(uint2*)(out0_t + off) = o.a;     // forward: the pre-activations are optional
-      if (EPI != EPI_PLAIN) *(uint2*)(out1_t + off) = o.b;
+      } else if (EPI != EPI_FWD1 || out0) {     // forward: the pre-activations are optional
+        if (EPI == EPI_PLAIN) *(uint2*)(out0_t + off) = o.a;
+        else store_nt8(out0_t + off, o.a);
+      }
+      if (EPI != EPI_PLAIN) store_nt8(out1_t + off, o.b);
     }
   };
   epilogue_rounds<EPI == EPI_DH>(patch, patch_alt, acc, fetch, compute, store);

@@ -266,7 +266,7 @@ __device__ __forceinline__ void wgrad_dma_block(const WgradDmaArgs& p, unsigned 
         [&](int row_w, int col_w, const EpiOut& o) {
           const int lrow = tile_row(row_w);
           const int col = col_base + col_w;
-          if (lrow < mvalid && col < NC) *(uint2*)(out + (size_t)(m0 + lrow) * NC + col) = o.a;
+          if (lrow < mvalid && col < NC) store_nt8(out + (size_t)(m0 + lrow) * NC + col, o.a);   // written once
         });
   } else {
     // one of several segments: the fp32 tile goes to the workspace for wgrad_reduce_kernel
@@ -335,7 +335,7 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_reduce_kernel(const int4* 
       const float4 v = p[(size_t)sgm * n4 + i];
       s4.x += v.x; s4.y += v.y; s4.z += v.z; s4.w += v.w;
     }
-    out[i] = pack4(s4.x, s4.y, s4.z, s4.w);
+    store_nt8((bf16_t*)(out + i), pack4(s4.x, s4.y, s4.z, s4.w));   // written once, like the unsplit experts' tiles
   }
 }
 
