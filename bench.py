@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per call of flexmoe_expert_ffn_fwd from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the
 # same counters' reading of a plain 1 GiB copy (summary and commands: profiles/*_hbm_traffic.txt).
-MEASURED_FFN_FWD_TRAFFIC_BYTES = {"bert": 657.8e6}
+MEASURED_FFN_FWD_TRAFFIC_BYTES = {"bert": 654.0e6}
 
 WORKLOAD_TEXT = {
     "tiny": "configs[0] tiny fp32 MoE layer, forward",
