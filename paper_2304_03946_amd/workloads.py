@@ -155,21 +155,109 @@ def _expert_weights(seed: int, base_stream: int, E: int, rows: int, cols: int, d
     return Bf16Tensor(out) if dtype == DT_BF16 else out
 
 
-def expert_bias(cfg: LayerConfig, seed: int, drift: int = 0) -> np.ndarray:
-    """Per-expert additive logit bias b_e that produces the configured load skew."""
+def target_shares(cfg: LayerConfig, seed: int, drift: int = 0):
+    """Share of the N*k assignments that each expert should receive under the configured routing
+    law (sums to 1), or None when the configuration states the logit bias itself ("log") or has no
+    skew.  "zipf": share proportional to rank^-s, ranks dealt by a seeded permutation that rotates by
+    four places per drift (the hot set moves smoothly); "dirichlet": one seeded draw of
+    Dirichlet(alpha).  No expert can take more than 1/k of the assignments (k distinct experts per
+    token): shares above that are cut to 1/k and the rest rescaled."""
+    E, k = cfg.E, cfg.k
+    if cfg.skew == "zipf":
+        pi0 = _rng(seed, 7).permutation(E)
+        rank = (pi0 + 4 * drift) % E
+        p = (rank + 1.0) ** (-cfg.skew_s)
+    elif cfg.skew == "dirichlet":
+        p = np.maximum(_rng(seed, 7).dirichlet(np.full(E, cfg.skew_s)), 1e-7)
+    else:
+        return None
+    p = p / p.sum()
+    cap = 0.98 / k if k > 1 else 1.0
+    for _ in range(E):
+        over = p > cap
+        if not over.any():
+            break
+        rest = 1.0 - cap * over.sum()
+        p = np.where(over, cap, p * rest / p[~over].sum())
+    return p
+
+
+def _norm_cdf(z):
+    from math import sqrt
+    try:
+        from scipy.special import ndtr
+        return ndtr(z)
+    except ImportError:            # pragma: no cover
+        from math import erf
+        return 0.5 * (1.0 + np.vectorize(erf)(z / sqrt(2.0)))
+
+
+def inclusion_probabilities(b: np.ndarray, sigma: np.ndarray, k: int, grid: int = 481) -> np.ndarray:
+    """P(expert e is among the k largest of l_j = b_j + sigma_j z_j, z iid N(0,1)), for every e.
+
+    This is the statistics of the synthetic gate INPUTS, not the gate: with x ~ N(0, I) the
+    logit noise of expert j is exactly N(0, |W_g[:, j]|^2), independent over tokens.  Quadrature
+    over z_e; the number of rivals above l_e is Poisson-binomial, summed by a k-state recursion."""
+    b = np.asarray(b, dtype=np.float64)
+    sigma = np.asarray(sigma, dtype=np.float64)
+    E = b.shape[0]
+    u = np.linspace(-8.0, 8.0, grid)
+    wq = np.exp(-0.5 * u * u)
+    wq /= wq.sum()
+    le = b[:, None] + sigma[:, None] * u[None, :]                    # [E, G]  value of l_e
+    q = 1.0 - _norm_cdf((le[:, :, None] - b[None, None, :]) / sigma[None, None, :])   # [E, G, E]  P(l_j > l_e)
+    idx = np.arange(E)
+    q[idx, :, idx] = 0.0
+    state = np.zeros((k, E, grid))                                    # state[c] = P(c rivals above so far)
+    state[0] = 1.0
+    for j in range(E):
+        qj = q[:, :, j]
+        for c in range(k - 1, 0, -1):
+            state[c] = state[c] * (1.0 - qj) + state[c - 1] * qj
+        state[0] = state[0] * (1.0 - qj)
+    return (state.sum(axis=0) * wq[None, :]).sum(axis=1)
+
+
+def solve_bias(p: np.ndarray, sigma: np.ndarray, k: int, tol: float = 2e-3, iters: int = 60) -> np.ndarray:
+    """Logit biases b (max b = 0) under which `inclusion_probabilities` equals k*p: the expected
+    share of assignments per expert is then p.  Secant iteration per coordinate."""
+    p = np.asarray(p, dtype=np.float64)
+    want = np.log(np.minimum(k * p, 1.0 - 1e-9))
+    b = np.log(p / p.max()) * np.mean(sigma)
+    got = np.log(np.maximum(inclusion_probabilities(b, sigma, k), 1e-300))
+    slope = np.ones_like(b)
+    for _ in range(iters):
+        err = want - got
+        if np.max(np.abs(err)) < tol:
+            break
+        step = np.clip(err / slope, -1.0, 1.0)
+        b_new = b + step
+        b_new -= b_new.max()
+        got_new = np.log(np.maximum(inclusion_probabilities(b_new, sigma, k), 1e-300))
+        db = b_new - b
+        ok = np.abs(db) > 1e-9
+        est = np.where(ok, (got_new - got) / np.where(ok, db, 1.0), slope)
+        slope = np.clip(np.where(np.isfinite(est) & (est > 0), est, slope), 0.2, 20.0)
+        b, got = b_new, got_new
+    return b
+
+
+def expert_bias(cfg: LayerConfig, seed: int, drift: int = 0, sigma: np.ndarray | None = None) -> np.ndarray:
+    """Per-expert additive logit bias b_e that produces the configured load skew.
+
+    "log": the bias is stated outright, b_e = s * ln(1/(e+1)).  "zipf" / "dirichlet": the
+    configuration states the routing law, so b is solved such that the expected share of
+    assignments per expert equals `target_shares` given the logit noise the inputs carry
+    (`sigma[e]` = standard deviation of expert e's logit noise; 1 when not given)."""
     E = cfg.E
     if cfg.skew == "none":
         return np.zeros(E, dtype=np.float64)
     if cfg.skew == "log":            # b_e = s * ln(1/(e+1)), hottest expert is e = 0
         return cfg.skew_s * np.log(1.0 / (np.arange(E) + 1.0))
-    if cfg.skew == "zipf":           # Zipf ranks through a seeded permutation, rotated by drift
-        pi0 = _rng(seed, 7).permutation(E)
-        rank = (pi0 + 4 * drift) % E
-        return cfg.skew_s * np.log(1.0 / (rank + 1.0))
-    if cfg.skew == "dirichlet":
-        p = _rng(seed, 7).dirichlet(np.full(E, cfg.skew_s))
-        return np.maximum(np.log(np.maximum(p, 1e-300)), -20.0)
-    raise ValueError(cfg.skew)
+    p = target_shares(cfg, seed, drift)
+    if sigma is None:
+        sigma = np.ones(E)
+    return solve_bias(p, np.asarray(sigma, dtype=np.float64), cfg.k)
 
 
 @dataclasses.dataclass
@@ -185,11 +273,18 @@ class LayerInputs:
 
 
 def make_gate_weights(cfg: LayerConfig, seed: int, drift: int = 0):
-    """W_g [d,E] ~ N(0,1)/sqrt(d); for skewed configs the last row holds b_e."""
+    """W_g [d,E] ~ N(0,1)/sqrt(d); for skewed configs the last row holds b_e.
+
+    The bias is solved against the noise these very weights give the logits: features 0..d-2 of x
+    are N(0,1), so expert e's logit noise has standard deviation |W_g[0:d-1, e]| (of the values as
+    stored, i.e. after rounding to the config dtype)."""
     wg = _normal_f32(seed, 2, (cfg.d, cfg.E), 1.0 / math.sqrt(cfg.d))
-    b = expert_bias(cfg, seed, drift)
-    if cfg.skew != "none":
-        wg[cfg.d - 1, :] = b.astype(np.float32)
+    if cfg.skew == "none":
+        return _store(wg, cfg.dtype), np.zeros(cfg.E)
+    stored = decode(_store(wg[:cfg.d - 1], cfg.dtype)).astype(np.float64)
+    sigma = np.sqrt((stored * stored).sum(axis=0))
+    b = expert_bias(cfg, seed, drift, sigma)
+    wg[cfg.d - 1, :] = b.astype(np.float32)
     return _store(wg, cfg.dtype), b
 
 
@@ -223,7 +318,8 @@ def sample_topk_idx(cfg: LayerConfig, seed: int, log_p: np.ndarray | None = None
     Returns int32 [N, k] with k distinct experts per token.
     """
     if log_p is None:
-        log_p = expert_bias(cfg, seed)
+        p = target_shares(cfg, seed)
+        log_p = np.log(p) if p is not None else expert_bias(cfg, seed)
     g = _rng(seed, 11).gumbel(size=(cfg.N, cfg.E))
     s = g + np.asarray(log_p, dtype=np.float64)[None, :]
     return np.argsort(-s, axis=1, kind="stable")[:, :cfg.k].astype(np.int32)
@@ -271,12 +367,15 @@ def placement_from_loads(loads, V: int, max_rep: int, shuffle_seed: int | None =
 
 
 def prior_loads(cfg: LayerConfig, seed: int | None = None, drift: int = 0) -> np.ndarray:
-    """Loads implied by the skew bias alone: N*k*softmax(b), capped at N per expert."""
+    """Expected loads before any step has been observed: N*k*target share; where the configuration
+    states the bias instead of the law, N*k*softmax(b) capped at N per expert."""
     if seed is None:
         seed = BASE_SEED + cfg.cfg_id
-    b = expert_bias(cfg, seed, drift)
-    p = np.exp(b - b.max())
-    p /= p.sum()
+    p = target_shares(cfg, seed, drift)
+    if p is None:
+        b = expert_bias(cfg, seed, drift)
+        p = np.exp(b - b.max())
+        p /= p.sum()
     return np.minimum(cfg.A * p, cfg.N)
 
 

@@ -10,9 +10,3 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
-
-
-def pytest_collection_modifyitems(config, items):
-    # GPU tests are skipped, not failed, when no device is visible and they were
-    # not asked for explicitly with -m gpu.
-    pass

@@ -38,6 +38,33 @@ def rel_err(gpu, ref):
     return float(np.abs(gpu - ref).max() / scale)
 
 
+def group_err(gpu, ref, groups):
+    """Worst max|gpu - ref| / max|ref| over `groups`, each an index (slice, array or tuple) into both
+    arrays, normalised by the GROUP's own largest reference value: an expert's slice of a weight
+    gradient, a vExpert's bucket of rows, a column of dW_g.  A tensor-wide norm would let the hottest
+    expert's scale hide an error in a cold expert's few-token contraction."""
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    worst = 0.0
+    for g in groups:
+        a, b = gpu[g], ref[g]
+        if b.size == 0:
+            continue
+        scale = np.abs(b).max()
+        err = np.abs(a - b).max()
+        worst = max(worst, float(err if scale == 0 else err / scale))
+    return worst
+
+
+def bucket_groups(r):
+    off = r["vexpert_off"]
+    return [slice(int(off[v]), int(off[v + 1])) for v in range(len(off) - 1) if off[v + 1] > off[v]]
+
+
+def expert_groups(r):
+    return [int(e) for e in np.nonzero(r["expert_count"] > 0)[0]]
+
+
 def host(t):
     return t.detach().float().cpu().numpy() if t.dtype != torch.int32 else t.cpu().numpy()
 
@@ -59,7 +86,7 @@ def check_gate(idx_gpu, w_gpu, x, wg, k, dtype, tokens=None):
     idx_ref, w_ref, logits = O.gate_topk(xs, wgd, k)
     bound = gate_error_bound(xs, wgd, dtype)
     pinned = O.topk_margin(logits, k) > 2.0 * bound
-    assert pinned.mean() > 0.9, f"too many near-tie tokens: {1 - pinned.mean():.4f}"
+    assert pinned.mean() >= 0.99, f"too many near-tie tokens: {1 - pinned.mean():.4f}"
     assert np.array_equal(idx_gpu[pinned], idx_ref[pinned]), "top-k indices differ on pinned tokens"
     # near-tie tokens: the selection must be a set of distinct experts whose exact logits are
     # within the error bound of the exact top-k values, slot by slot
@@ -115,6 +142,9 @@ def run_stagewise(api, cfg, inp, rep_off, rep_ids, b1=None, b2=None):
     hpre_ref, yp_ref = O.expert_ffn_fwd(xp_ref, r["vexpert_off"], r["vexpert_owner"], w1, b1d, w2, b2d, cfg.act)
     assert rel_err(host(L.hpre), hpre_ref) <= tol, "hpre"
     assert rel_err(host(L.yp), yp_ref) <= tol, "yp"
+    buckets, live = bucket_groups(r), expert_groups(r)
+    assert group_err(host(L.hpre), hpre_ref, buckets) <= tol, "hpre, bucket by bucket"
+    assert group_err(host(L.yp), yp_ref, buckets) <= tol, "yp, bucket by bucket"
 
     # a6 combine, fed with the GPU's yp and gate weights
     y_stage = O.combine(host(L.yp), r["dest"], w_gpu, k)
@@ -140,6 +170,11 @@ def run_stagewise(api, cfg, inp, rep_off, rep_ids, b1=None, b2=None):
     assert rel_err(host(L.dxp), dxp_ref) <= tol, "dxp"
     assert rel_err(host(L.dw1), dw1_ref) <= tol, "dw1"
     assert rel_err(host(L.dw2), dw2_ref) <= tol, "dw2"
+    # the same on every group's own scale: each vExpert's rows, each expert's weight gradient
+    assert group_err(host(L.dyp), dyp_ref, buckets) <= (tol if cfg.dtype == W.DT_F32 else 2.0 ** -8), "dyp, bucket by bucket"
+    assert group_err(host(L.dxp), dxp_ref, buckets) <= tol, "dxp, bucket by bucket"
+    assert group_err(host(L.dw1), dw1_ref, live) <= tol, "dw1, expert by expert"
+    assert group_err(host(L.dw2), dw2_ref, live) <= tol, "dw2, expert by expert"
     dx_stage = O.combine(host(L.dxp), r["dest"], None, k)
     assert rel_err(host(L.dx), dx_stage) <= (tol if cfg.dtype == W.DT_F32 else 2.0 ** -8), "dx combine"
     # end to end gradients against the definition with the GPU's selection and the exact gate weights
@@ -152,6 +187,8 @@ def run_stagewise(api, cfg, inp, rep_off, rep_ids, b1=None, b2=None):
     assert rel_err(host(L.dx), dx_def) <= tol, "dx"
     assert rel_err(host(L.dw1), dw1_def) <= tol, "dw1 end to end"
     assert rel_err(host(L.dw2), dw2_def) <= tol, "dw2 end to end"
+    assert group_err(host(L.dw1), dw1_def, live) <= tol, "dw1 end to end, expert by expert"
+    assert group_err(host(L.dw2), dw2_def, live) <= tol, "dw2 end to end, expert by expert"
     empty = np.nonzero(r["expert_count"] == 0)[0]
     for e in empty:
         assert not host(L.dw1[e]).any() and not host(L.dw2[e]).any(), "empty expert must get zero gradient"
@@ -255,6 +292,9 @@ def run_full_backward(api, cfg, inp, rep_off, rep_ids, b1=None, b2=None):
                                            E, cfg.act)
     assert rel_err(host(g["db1"]), db1_ref) <= tol, "db1"
     assert rel_err(host(g["db2"]), db2_ref) <= tol, "db2"
+    live = expert_groups(r)
+    assert group_err(host(g["db1"]), db1_ref, live) <= tol, "db1, expert by expert"
+    assert group_err(host(g["db2"]), db2_ref, live) <= tol, "db2, expert by expert"
     # stage: dW_g from the GPU's dl
     dwg_stage = np.zeros_like(wgd, dtype=np.float64)
     dl_gpu = host(g["dl"]).astype(np.float64)
@@ -262,6 +302,8 @@ def run_full_backward(api, cfg, inp, rep_off, rep_ids, b1=None, b2=None):
         np.add.at(dwg_stage.T, idx_gpu[:, j], dl_gpu[:, j:j + 1] * xd)
     if k > 1:
         assert rel_err(host(g["dwg"]), dwg_stage) <= (tol if cfg.dtype == W.DT_F32 else 2.0 ** -8), "dwg stage"
+        cols = [(slice(None), e) for e in live]
+        assert group_err(host(g["dwg"]), dwg_stage, cols) <= (tol if cfg.dtype == W.DT_F32 else 2.0 ** -8), "dwg stage, column by column"
 
     # end to end on the GPU's selection with the exact gate weights
     kept = np.take_along_axis(O.gate_logits(xd, wgd), idx_gpu.astype(np.int64), axis=1)
@@ -272,8 +314,13 @@ def run_full_backward(api, cfg, inp, rep_off, rep_ids, b1=None, b2=None):
     assert rel_err(host(g["dx"]), ref["dx_total"]) <= tol, "dx (both paths)"
     for name in ("dw1", "dw2", "db1", "db2"):
         assert rel_err(host(g[name]), ref[name]) <= tol, name
+        assert group_err(host(g[name]), ref[name], live) <= tol, name + ", expert by expert"
     if k > 1:
         assert rel_err(host(g["dwg"]), ref["dwg"]) <= tol, "dwg"
+        # column by column for the experts with enough tokens that the logit gradients' own rounding
+        # noise (dl is a difference of dot products over bf16 rows) averages out
+        busy = [(slice(None), e) for e in live if r["expert_count"][e] >= 64]
+        assert group_err(host(g["dwg"]), ref["dwg"], busy) <= tol, "dwg, column by column"
         assert np.abs(ref["dx_gate"]).max() > 1e-3 * np.abs(ref["dx"]).max(), "the case must exercise the gate path"
     empty = np.nonzero(r["expert_count"] == 0)[0]
     for e in empty:
@@ -639,6 +686,46 @@ def test_two_runs_are_bit_identical(api):
     for a, b in zip(*outs):
         assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a,
                            b.view(torch.int16) if b.dtype == torch.bfloat16 else b)
+
+
+def test_hot_set_drift_with_a_new_table_each_time(api):
+    """Routing fluctuation (Observation 2): three drifts of the hot set, each with a new bias row in
+    W_g and a new placement table built from the loads of the step before, on one set of layer
+    buffers.  After every drift routing is bit-exact and every float output within tolerance, group
+    by group."""
+    binding, layer_mod = api
+    cfg = W.scaled(W.CONFIGS["gpt_xl"], N=2400, d=256, f=512, E=16, V=24, max_rep=4)
+    inp = W.make_layer_inputs(cfg)
+    tol = TOL[cfg.dtype]
+    dev = upload(layer_mod, inp)
+    L = layer_mod.MoELayer.for_config(cfg)
+    xd, dyd = W.decode(inp.x), W.decode(inp.dy)
+    loads = W.prior_loads(cfg)
+    hottest = []
+    for drift in range(4):
+        wg, _ = W.make_gate_weights(cfg, inp.seed, drift=drift)
+        wg_dev = layer_mod.to_device(wg)
+        rep_off, rep_ids = W.placement_from_loads(loads, cfg.V, cfg.max_rep, shuffle_seed=drift)
+        L.forward(dev["x"], wg_dev, dev["w1"], dev["w2"], rep_off, rep_ids)
+        L.backward(dev["dy"], dev["w1"], dev["w2"])
+        torch.cuda.synchronize()
+        idx_gpu, w_gpu = host(L.topk_idx), host(L.topk_w)
+        check_gate(idx_gpu, w_gpu, inp.x, wg, cfg.k, cfg.dtype)
+        r = O.route(idx_gpu, cfg.E, rep_off, rep_ids)
+        for name in ("expert_count", "vexpert_count", "vexpert_off", "vexpert_owner", "dest", "src"):
+            assert np.array_equal(host(getattr(L, name)), r[name]), (drift, name)
+        fwd = O.staged_forward(xd, W.decode(wg), inp.w1, None, inp.w2, None, cfg.k, cfg.act, rep_off, rep_ids,
+                               topk=(idx_gpu, w_gpu))
+        ref = O.staged_backward(fwd, dyd, inp.w1, inp.w2, cfg.k, cfg.act)
+        live, buckets = expert_groups(r), bucket_groups(r)
+        assert rel_err(host(L.y), fwd["y"]) <= tol and rel_err(host(L.dx), ref["dx"]) <= tol, drift
+        assert group_err(host(L.yp), fwd["yp"], buckets) <= tol, drift
+        assert group_err(host(L.dw1), ref["dw1"], live) <= tol and group_err(host(L.dw2), ref["dw2"], live) <= tol, drift
+        for e in np.nonzero(r["expert_count"] == 0)[0]:
+            assert not host(L.dw1[e]).any() and not host(L.dw2[e]).any()
+        loads = r["expert_count"]
+        hottest.append(int(np.argmax(loads)))
+    assert len(set(hottest)) > 1, "the hot set must have moved"
 
 
 def test_scheduler_in_the_loop_keeps_the_layer_output(api):
