@@ -13,9 +13,12 @@
  *     16-byte aligned.  The only HOST pointers are the placement table arguments of
  *     flexmoe_route (rep_off_host, rep_ids_host).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
- *     enqueue work; they never allocate, free or synchronise.  Scratch memory comes from the
- *     caller: `ws` with at least flexmoe_workspace_bytes(...) bytes, 256-byte aligned.  The
- *     workspace carries nothing between calls.
+ *     enqueue work; they never allocate, free or synchronise, and the library keeps no state
+ *     between calls (tables it needs are constant data of the code object).  Scratch memory comes
+ *     from the caller: `ws` with at least flexmoe_workspace_bytes(...) bytes, 256-byte aligned.
+ *     An entry point may overwrite all of `ws`; its contents mean nothing to the next call, with one
+ *     stated exception: flexmoe_expert_ffn_bwd (and _bwd_top1) leaves dHpre at the start of `ws`,
+ *     where flexmoe_expert_bias_grads reads it when called next with the same `ws`.
  *   - Arguments are validated on the host before anything is launched; on an error nothing
  *     is written.  Return value: a flexmoe_status code.
  *   - Notation: N tokens, d = d_model, f = d_ff, E experts, k experts per token, V vExperts,
@@ -107,8 +110,6 @@ int flexmoe_permute(const void* x, const int32_t* src, const float* row_scale,
  *   hpre may be NULL when no backward pass follows (inference): the pre-activations are then not
  *   stored, which halves what the first product writes; yp is the same, bit for bit.
  * The activation is applied to hpre as stored (i.e. after rounding to dtype).
- * The first bf16 GELU call on a device (forward or backward) fills that device's activation
- * tables and waits once for `stream`; under stream capture the fill is recorded instead.
  */
 int flexmoe_expert_ffn_fwd(const void* xp, const int32_t* vexpert_off, const int32_t* vexpert_owner,
                            const void* w1, const void* b1, const void* w2, const void* b2,
@@ -209,7 +210,8 @@ int flexmoe_gate_bwd(const void* wg, const int32_t* topk_idx, const float* topk_
  * dyp (the gate-scaled, permuted upstream gradient that flexmoe_expert_ffn_bwd consumed).
  *   db1 [E,f], db2 [E,d] dtype, overwritten (zeros for experts without tokens); either may be NULL.
  * `ws` must be the workspace of the preceding flexmoe_expert_ffn_bwd call of the same sizes,
- * untouched since: dHpre is read from it, and the part behind dHpre is overwritten.
+ * untouched since (the one place where a workspace carries data from call to call, see the
+ * conventions above): dHpre [A,f] is read from its start, and the part behind dHpre is overwritten.
  * Fixed summation order: reproducible bit for bit.
  */
 int flexmoe_expert_bias_grads(const void* dyp, const int32_t* vexpert_off, const int32_t* vexpert_owner,

@@ -31,8 +31,18 @@ def _compile(src: str) -> str:
     return obj
 
 
+def generate_tables() -> str:
+    """Constant data compiled into the library: the GELU residual tables (csrc/gen_act_lut.py)."""
+    out = os.path.join(CSRC, "act_lut_data.inc")
+    r = subprocess.run([sys.executable, os.path.join(CSRC, "gen_act_lut.py"), out], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("gen_act_lut.py failed:\n" + r.stderr)
+    return out
+
+
 def build_library(verbose: bool = True) -> str:
     """Compile every source and link the shared library; always rebuilds."""
+    generate_tables()
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs],

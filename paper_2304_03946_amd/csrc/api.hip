@@ -64,31 +64,47 @@ int flexmoe_gate_topk(const void* x, const void* wg, int N, int d, int E, int k,
   return dev_status(launch_gate(x, wg, N, d, E, k, dtype, topk_idx, topk_w, ws, (hipStream_t)stream));
 }
 
-int flexmoe_route(const int32_t* topk_idx, int N, int k, int E, int V, const int32_t* rep_off_host,
-                  const int32_t* rep_ids_host, int32_t* expert_count, int32_t* vexpert_count, int32_t* vexpert_off,
-                  int32_t* vexpert_owner, int32_t* dest, int32_t* src, void* ws, size_t ws_bytes, void* stream) {
+}  // extern "C"
+
+// Argument check of the router and conversion of the host table; shared by both router entry points.
+int flexmoe::route_check(const int32_t* topk_idx, int N, int k, int E, int V, const int32_t* rep_off_host,
+                       const int32_t* rep_ids_host, const int32_t* expert_count, const int32_t* vexpert_count,
+                       const int32_t* vexpert_off, const int32_t* vexpert_owner, const int32_t* dest,
+                       const int32_t* src, PlacementArg* tab) {
   if (N < 0 || E < 1 || E > FLEXMOE_MAX_EXPERTS || k < 1 || k > E || k > FLEXMOE_MAX_TOPK || V < E ||
       V > FLEXMOE_MAX_VEXPERTS || (long long)N * k >= (1ll << 30))
     return FLEXMOE_INVALID_ARG;
-  if (!rep_off_host || !rep_ids_host || !expert_count || !vexpert_count || !vexpert_off || !vexpert_owner || !ws)
+  if (!rep_off_host || !rep_ids_host || !expert_count || !vexpert_count || !vexpert_off || !vexpert_owner)
     return FLEXMOE_INVALID_ARG;
-  const int A = N * k;
-  if (A > 0 && (!topk_idx || !dest || !src)) return FLEXMOE_INVALID_ARG;
+  if (N * k > 0 && (!topk_idx || !dest || !src)) return FLEXMOE_INVALID_ARG;
   // the table must partition the vExpert ids 0..V-1 into non-empty per-expert lists
   if (rep_off_host[0] != 0 || rep_off_host[E] != V) return FLEXMOE_BAD_PLACEMENT;
-  PlacementArg tab;
   for (int e = 0; e < E; ++e) {
     if (rep_off_host[e + 1] <= rep_off_host[e] || rep_off_host[e + 1] > V) return FLEXMOE_BAD_PLACEMENT;
-    tab.rep_off[e] = (uint16_t)rep_off_host[e];
+    tab->rep_off[e] = (uint16_t)rep_off_host[e];
   }
-  tab.rep_off[E] = (uint16_t)V;
+  tab->rep_off[E] = (uint16_t)V;
   bool seen[FLEXMOE_MAX_VEXPERTS] = {false};
   for (int i = 0; i < V; ++i) {
     const int v = rep_ids_host[i];
     if (v < 0 || v >= V || seen[v]) return FLEXMOE_BAD_PLACEMENT;
     seen[v] = true;
-    tab.rep_ids[i] = (uint16_t)v;
+    tab->rep_ids[i] = (uint16_t)v;
   }
+  return FLEXMOE_OK;
+}
+
+extern "C" {
+
+int flexmoe_route(const int32_t* topk_idx, int N, int k, int E, int V, const int32_t* rep_off_host,
+                  const int32_t* rep_ids_host, int32_t* expert_count, int32_t* vexpert_count, int32_t* vexpert_off,
+                  int32_t* vexpert_owner, int32_t* dest, int32_t* src, void* ws, size_t ws_bytes, void* stream) {
+  PlacementArg tab = {};
+  const int st = route_check(topk_idx, N, k, E, V, rep_off_host, rep_ids_host, expert_count, vexpert_count, vexpert_off,
+                             vexpert_owner, dest, src, &tab);
+  if (st != FLEXMOE_OK) return st;
+  if (!ws) return FLEXMOE_INVALID_ARG;
+  const int A = N * k;
   if (ws_bytes < route_ws_bytes(A, E)) return FLEXMOE_WORKSPACE_TOO_SMALL;
   return dev_status(launch_route(topk_idx, A, E, V, tab, expert_count, vexpert_count, vexpert_off, vexpert_owner,
                                  dest, src, ws, (hipStream_t)stream));

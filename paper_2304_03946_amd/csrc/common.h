@@ -124,11 +124,16 @@ template <int ACT> __device__ __forceinline__ float act_fast(float z) {
   return a;
 }
 
-// Expert->vExpert table handed to the route kernels by value (it is a host-side input).
-struct PlacementArg {
-  uint16_t rep_off[FLEXMOE_MAX_EXPERTS + 1];
-  uint16_t rep_ids[FLEXMOE_MAX_VEXPERTS];
+// Expert->vExpert table handed to the route kernels by value (it is a host-side input): CSR in
+// uint16.  Two sizes, so that the usual layer (up to 64 experts, 128 vExperts) carries 386 bytes of
+// kernel arguments instead of 1538.
+template <int EMAX, int VMAX> struct PlacementArgT {
+  static constexpr int kMaxExperts = EMAX, kMaxVexperts = VMAX;
+  uint16_t rep_off[EMAX + 1];
+  uint16_t rep_ids[VMAX];
 };
+typedef PlacementArgT<FLEXMOE_MAX_EXPERTS, FLEXMOE_MAX_VEXPERTS> PlacementArg;
+typedef PlacementArgT<64, 128> PlacementArgSmall;
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -137,6 +142,11 @@ size_t gate_ws_bytes(int d, int E, int dtype);
 hipError_t launch_gate(const void* x, const void* wg, int N, int d, int E, int k, int dtype,
                        int32_t* idx, float* w, void* ws, hipStream_t s);
 
+// host-side argument check of the router entry points; fills the by-value table (api.hip)
+int route_check(const int32_t* topk_idx, int N, int k, int E, int V, const int32_t* rep_off_host,
+                const int32_t* rep_ids_host, const int32_t* expert_count, const int32_t* vexpert_count,
+                const int32_t* vexpert_off, const int32_t* vexpert_owner, const int32_t* dest, const int32_t* src,
+                PlacementArg* tab);
 int route_units(int A, int* unit_len);
 size_t route_ws_bytes(int A, int E);
 hipError_t launch_route(const int32_t* idx, int A, int E, int V, const PlacementArg& tab,

@@ -33,14 +33,13 @@
 // consecutive output columns of one output row; the epilogue passes the accumulators through a
 // wave-private LDS patch so that global stores fill whole 128-byte lines.
 // GELU and its derivative act on bf16-rounded arguments, so both are read from a table indexed
-// by the argument's bits (filled once per device from the fp64 formulas; outside the table's
-// range GELU equals ReLU to below bf16 resolution).
+// by the argument's bits (constant data in the code object, computed from the fp64 formulas when the
+// library is built; outside the table's range GELU equals ReLU to below bf16 resolution).
 //
 // Layout of the sources: ffn_bf16_tile.h (tile mapping, fragments, activation tables, epilogues, the
 // register-staged kernel), ffn_bf16_dma.h (direct-to-LDS pipeline and its rows kernels),
 // ffn_bf16_wgrad.h (weight-gradient kernels, the shared backward launch); this file holds the host side.
 #include <algorithm>
-#include <mutex>
 
 #include "common.h"
 #include "ffn_bf16_tile.h"
@@ -103,35 +102,6 @@ static void* rows_split_ws(const FfnArgs& a, void* ws) {
   return (char*)ws + 2 * align_up((size_t)a.A * a.f * sizeof(bf16_t), 256) + 2 * wgrad_tail_bytes(a.A, a.d, a.f, a.V);
 }
 
-template <typename Kern> static hipError_t allow_big_lds(Kern kern) {
-  return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLds);
-}
-
-
-// Fills the activation tables of the current device the first time a kernel that reads them is
-// launched there.  The fill runs on the caller's stream and is waited for before the device is
-// marked ready (other streams may launch next); under stream capture nothing can be waited for,
-// so the fill is recorded into the capture and the device stays unmarked.
-static hipError_t ensure_act_lut(hipStream_t s) {
-  static std::mutex mu;
-  static bool ready[64] = {};
-  int dev = 0;
-  hipError_t err = hipGetDevice(&dev);
-  if (err != hipSuccess) return err;
-  std::lock_guard<std::mutex> lock(mu);
-  if (dev < 64 && ready[dev]) return hipSuccess;
-  hipLaunchKernelGGL(act_lut_init_kernel, dim3((kLutEntries + 255) / 256, 2), dim3(256), 0, s);
-  err = hipGetLastError();
-  if (err != hipSuccess) return err;
-  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-  err = hipStreamIsCapturing(s, &cap);
-  if (err != hipSuccess) return err;
-  if (cap != hipStreamCaptureStatusNone) return hipSuccess;
-  err = hipStreamSynchronize(s);
-  if (err == hipSuccess && dev < 64) ready[dev] = true;
-  return err;
-}
-
 static RowsDmaArgs rows_dma_args(const FfnArgs& a, const void* in, const void* w, const void* bias, int K, int NC,
                                  const void* hpre_in, void* out0, void* out1, const int32_t* gsrc, int gk) {
   return RowsDmaArgs{(const bf16_t*)in, (const bf16_t*)w, (const bf16_t*)bias, a.voff, a.owner, a.V, K, NC,
@@ -143,21 +113,11 @@ template <bool WT, int EPI, int ACT>
 static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w, const void* bias, int K, int NC,
                                 const void* hpre_in, void* out0, void* out1, hipStream_t s, const int32_t* gsrc, int gk,
                                 void* split_ws, const int32_t* scatter_rows) {
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t err = allow_big_lds(rows_gemm_bf16<WT, EPI, ACT>);
-    if (err != hipSuccess) return err;
-    attr_done = true;
-  }
   const int col_tiles = (NC + BN - 1) / BN;
   const int row_tiles = max_row_tiles(a.A, a.V);
   const unsigned grid = patched_grid(row_tiles, col_tiles);
   if (K % 128 == 0) {
     // K is a whole number of pipeline rounds: direct-to-LDS path
-    if (epilogue_uses_lut<EPI, ACT>()) {
-      hipError_t err = ensure_act_lut(s);
-      if (err != hipSuccess) return err;
-    }
     RowsDmaArgs p = rows_dma_args(a, in, w, bias, K, NC, hpre_in, out0, out1, gsrc, gk);
     p.scatter_rows = scatter_rows;
     if (EPI == EPI_PLAIN && split_ws && rows_split_bytes(a.A, a.V, K, NC)) {
@@ -173,7 +133,7 @@ static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w,
     return hipGetLastError();
   }
   if (gsrc || scatter_rows) return hipErrorInvalidValue;   // gathered / scattered rows only on the direct-to-LDS path (host check upstream)
-  hipLaunchKernelGGL((rows_gemm_bf16<WT, EPI, ACT>), dim3(grid), dim3(kGemmThreads), kGemmLds, s, (const bf16_t*)in,
+  hipLaunchKernelGGL((rows_gemm_bf16<WT, EPI, ACT>), dim3(grid), dim3(kGemmThreads), 0, s, (const bf16_t*)in,
                      (const bf16_t*)w, (const bf16_t*)bias, a.voff, a.owner, a.V, K, NC, row_tiles, col_tiles,
                      (const bf16_t*)hpre_in, (bf16_t*)out0, (bf16_t*)out1);
   return hipGetLastError();

@@ -188,34 +188,22 @@ __device__ __forceinline__ void unpack4(uint2 u, float* v) {
 //   GELU'(z) = [z >= 0] + sign(z) * q(|z|),  q(a) = GELU'(a) - 1
 // so one table over the bf16 magnitudes serves both signs.  r and q vanish (below 1e-13) from
 // |z| = 8 on and r(a) -> -a/2, q -> -1/2 as a -> 0: magnitudes are clamped to [2^-24, 8], which
-// costs an absolute error below 2^-25.  Entries are computed in double precision on the device,
-// once per device, and held as {r, q} fp32 pairs: 3457 entries, padded to 28 KB so that the GEMM
-// kernels can pull the table into LDS with whole 1 KB direct loads.
+// costs an absolute error below 2^-25.  Entries are computed in double precision when the library is
+// built (gen_act_lut.py writes act_lut_data.inc) and live in the code object as constant {r, q} fp32
+// pairs: 3457 entries, padded to 28 KB so that the GEMM kernels can pull the table into LDS with
+// whole 1 KB direct loads.  Nothing is filled in at run time: no first-call set-up, no host-side state.
 constexpr int kLutLo = 103 << 7;                    // bf16 bits of 2^-24
 constexpr int kLutHi = 130 << 7;                    // bf16 bits of 8.0
 constexpr int kLutBytes = 28 * 1024;
 constexpr int kLutEntries = kLutBytes / 8;
 static_assert(kLutHi - kLutLo + 1 <= kLutEntries, "table does not fit its padding");
-__device__ __align__(1024) float2 g_act_lut[2][kLutEntries];    // [0] erf form, [1] tanh form
-
-__global__ void act_lut_init_kernel() {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= kLutEntries) return;
-  const int m = min(kLutLo + i, kLutHi);
-  const double a = (double)__uint_as_float((uint32_t)m << 16);
-  double Fneg, dF;                                   // F(-a) and F'(a)
-  if (blockIdx.y == 0) {
-    Fneg = 0.5 * erfc(a * 0.70710678118654752440);
-    dF = 0.39894228040143267794 * exp(-0.5 * a * a);
-  } else {
-    const double c = 0.79788456080286535588, u = c * (a + 0.044715 * a * a * a);
-    const double th = tanh(u);
-    Fneg = 0.5 * (1.0 - th);
-    dF = 0.5 * (1.0 - th * th) * c * (1.0 + 3.0 * 0.044715 * a * a);
-  }
-  // r = -a F(-a);  GELU'(a) = F(a) + a F'(a) = 1 - F(-a) + a F'(a)
-  g_act_lut[blockIdx.y][i] = make_float2((float)(-a * Fneg), (float)(a * dF - Fneg));
-}
+struct ActLutEntry {
+  float r, q;
+};
+__device__ __align__(1024) const ActLutEntry g_act_lut[2][kLutEntries] = {      // [0] erf form, [1] tanh form
+#include "act_lut_data.inc"
+};
+static_assert(sizeof(g_act_lut) == 2 * kLutBytes, "generated table and layout constants disagree");
 
 // Table entry for the bf16 value whose fp32 bit pattern is zu (LDS copy of one table).
 typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
@@ -636,7 +624,7 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_bf16(
     const bf16_t* __restrict__ in, const bf16_t* __restrict__ w, const bf16_t* __restrict__ bias,
     const int32_t* __restrict__ voff, const int32_t* __restrict__ owner, int V, int K, int NC, int row_tiles_max,
     int col_tiles, const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0, bf16_t* __restrict__ out1) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
+  __shared__ __align__(16) unsigned char smem_raw[kGemmLds];     // 128 KB of the 160 KB a compute unit has
   bf16_t* smem = (bf16_t*)smem_raw;
   __shared__ int s_tile[4];
   RowTile t;

@@ -104,8 +104,9 @@ __global__ __launch_bounds__(kRouteThreads) void route_hist_kernel(const int32_t
     for (int e = lane; e < E; e += kWave) hist[(size_t)u * E + e] = h[w][e];
 }
 
+template <typename Tab>
 __global__ __launch_bounds__(kRouteThreads) void route_assign_kernel(
-    const int32_t* __restrict__ idx, int A, int E, int V, int units, int unit_len, PlacementArg tab,
+    const int32_t* __restrict__ idx, int A, int E, int V, int units, int unit_len, Tab tab,
     const int32_t* __restrict__ hist, int32_t* __restrict__ expert_count, int32_t* __restrict__ vexpert_count,
     int32_t* __restrict__ vexpert_off, int32_t* __restrict__ vexpert_owner, int32_t* __restrict__ dest,
     int32_t* __restrict__ src) {
@@ -222,8 +223,9 @@ constexpr int kFusedWaves = kFusedThreads / kWave;
 constexpr int kFusedRounds = 4;
 constexpr int kFusedMaxA = kFusedWaves * kWave * kFusedRounds;
 
+template <typename Tab>
 __global__ __launch_bounds__(kFusedThreads) void route_fused_kernel(
-    const int32_t* __restrict__ idx, int A, int E, int V, PlacementArg tab, int32_t* __restrict__ expert_count,
+    const int32_t* __restrict__ idx, int A, int E, int V, Tab tab, int32_t* __restrict__ expert_count,
     int32_t* __restrict__ vexpert_count, int32_t* __restrict__ vexpert_off, int32_t* __restrict__ vexpert_owner,
     int32_t* __restrict__ dest, int32_t* __restrict__ src) {
   __shared__ int32_t wbase[kFusedWaves][FLEXMOE_MAX_EXPERTS];       // histograms, then prefixes over waves
@@ -299,11 +301,12 @@ __global__ __launch_bounds__(kFusedThreads) void route_fused_kernel(
       place_round(lo + r * kWave + lane, ev[r], lane, wbase[w], eq, em, roff, rids, voff, vstart, dest, src);
 }
 
-hipError_t launch_route(const int32_t* idx, int A, int E, int V, const PlacementArg& tab, int32_t* expert_count,
-                        int32_t* vexpert_count, int32_t* vexpert_off, int32_t* vexpert_owner, int32_t* dest,
-                        int32_t* src, void* ws, hipStream_t s) {
+template <typename Tab>
+static hipError_t launch_route_t(const int32_t* idx, int A, int E, int V, const Tab& tab, int32_t* expert_count,
+                                 int32_t* vexpert_count, int32_t* vexpert_off, int32_t* vexpert_owner, int32_t* dest,
+                                 int32_t* src, void* ws, hipStream_t s) {
   if (A <= kFusedMaxA) {
-    hipLaunchKernelGGL(route_fused_kernel, dim3(1), dim3(kFusedThreads), 0, s, idx, A, E, V, tab, expert_count,
+    hipLaunchKernelGGL(route_fused_kernel<Tab>, dim3(1), dim3(kFusedThreads), 0, s, idx, A, E, V, tab, expert_count,
                        vexpert_count, vexpert_off, vexpert_owner, dest, src);
     return hipGetLastError();
   }
@@ -312,9 +315,22 @@ hipError_t launch_route(const int32_t* idx, int A, int E, int V, const Placement
   const int blocks = (units + kRouteWaves - 1) / kRouteWaves;
   int32_t* hist = (int32_t*)ws;
   hipLaunchKernelGGL(route_hist_kernel, dim3(blocks), dim3(kRouteThreads), 0, s, idx, A, E, units, unit_len, hist);
-  hipLaunchKernelGGL(route_assign_kernel, dim3(blocks), dim3(kRouteThreads), 0, s, idx, A, E, V, units, unit_len,
+  hipLaunchKernelGGL(route_assign_kernel<Tab>, dim3(blocks), dim3(kRouteThreads), 0, s, idx, A, E, V, units, unit_len,
                      tab, hist, expert_count, vexpert_count, vexpert_off, vexpert_owner, dest, src);
   return hipGetLastError();
+}
+
+hipError_t launch_route(const int32_t* idx, int A, int E, int V, const PlacementArg& tab, int32_t* expert_count,
+                        int32_t* vexpert_count, int32_t* vexpert_off, int32_t* vexpert_owner, int32_t* dest,
+                        int32_t* src, void* ws, hipStream_t s) {
+  if (E <= PlacementArgSmall::kMaxExperts && V <= PlacementArgSmall::kMaxVexperts) {
+    PlacementArgSmall small;
+    for (int e = 0; e <= E; ++e) small.rep_off[e] = tab.rep_off[e];
+    for (int e = E + 1; e <= PlacementArgSmall::kMaxExperts; ++e) small.rep_off[e] = 0;
+    for (int v = 0; v < PlacementArgSmall::kMaxVexperts; ++v) small.rep_ids[v] = v < V ? tab.rep_ids[v] : 0;
+    return launch_route_t(idx, A, E, V, small, expert_count, vexpert_count, vexpert_off, vexpert_owner, dest, src, ws, s);
+  }
+  return launch_route_t(idx, A, E, V, tab, expert_count, vexpert_count, vexpert_off, vexpert_owner, dest, src, ws, s);
 }
 
 }  // namespace flexmoe
