@@ -6,9 +6,13 @@ A step is one pass of the whole hot path over one synthetic batch:
   backward = permute(dY, gate weights) -> expert_ffn_bwd -> combine      (training configs)
 all through the C ABI of libflexmoe.so, inputs resident in HBM before the timed region.
 
-Prints one JSON line: whole-job tokens/s, the roofline of the dominant kernel pair
-(the grouped-GEMM expert FFN, MFMA-bound) with per-stage figures, and the CPU oracle
-timed on the host cores as a reported baseline.
+The default workload is the GPT-XL-like layer (the largest single-GPU configuration: 65536 tokens,
+d = 2048, f = 8192, 64 experts, top-2, forward + backward, hot set drifting every 10 steps).
+
+Prints one JSON line: whole-job tokens/s, the roofline of the dominant kernels (the grouped-GEMM
+expert FFN of the whole step, MFMA-bound; HIP events around its calls inside the timed steps) with
+per-stage figures, a compact table of the other configurations, and the CPU oracle timed on the
+host cores as a reported baseline.
 """
 from __future__ import annotations
 
@@ -26,9 +30,23 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per call of flexmoe_expert_ffn_fwd from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the
-# same counters' reading of a plain 1 GiB copy (summary and commands: profiles/*_hbm_traffic.txt).
-MEASURED_FFN_FWD_TRAFFIC_BYTES = {"bert": 654.0e6}
+
+
+def measured_ffn_traffic_bytes(name):
+    """HBM bytes that the grouped-GEMM launches of one step move (flexmoe_expert_ffn_fwd + flexmoe_expert_ffn_bwd),
+    from two rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
+    reads for a plain 1 GiB device copy.  Read from the committed summary profiles/ffn_<workload>_hbm_traffic.txt
+    (line `TRAFFIC_BYTES_PER_STEP <bytes>`); None when no summary exists for the workload."""
+    path = os.path.join(ROOT, "profiles", f"ffn_{name}_hbm_traffic.txt")
+    try:
+        with open(path) as fh:
+            for ln in fh:
+                if ln.startswith("TRAFFIC_BYTES_PER_STEP"):
+                    return float(ln.split()[1])
+    except OSError:
+        pass
+    return None
+
 
 WORKLOAD_TEXT = {
     "tiny": "configs[0] tiny fp32 MoE layer, forward",
@@ -84,13 +102,6 @@ class Runner:
             self.L.route(*self.rep)
             torch.cuda.synchronize()
             self.rep = W.placement_from_loads(self.L.expert_count.cpu().numpy(), cfg.V, cfg.max_rep)
-        # The HIP runtime stalls the host once for 35-45 ms after about 400 launches that carry the
-        # placement table as a kernel argument (seen as one idle gap of the GPU; it never recurs in
-        # thousands of later steps).  Get that one-time event out of the way before anything is timed.
-        self.L.gate(self.x, self.wg_by_drift[0])
-        for _ in range(512):
-            self.L.route(*self.rep)
-        torch.cuda.synchronize()
 
     def prepare_drifts(self, total_steps):
         if not self.drifting:
@@ -100,7 +111,9 @@ class Runner:
                 wg, _ = self.W.make_gate_weights(self.cfg, self.inp.seed, drift=j)
                 self.wg_by_drift[j] = self.layer_mod.to_device(wg)
 
-    def step(self, timers=None):
+    def step(self, timers=None, ffn_events=None):
+        """One pass of the hot path.  `timers`: events after every stage (breakdown pass); `ffn_events`: a list
+        that receives (start, end) event pairs around the two grouped-GEMM calls only (timed region)."""
         L, cfg = self.L, self.cfg
         from paper_2304_03946_amd import binding as B
         j = self.iter // 10 if self.drifting else 0
@@ -120,15 +133,29 @@ class Runner:
                                             L.ws); rec("ffn_fwd")
         else:
             B.flexmoe_permute(self.x, L.src, None, cfg.k, L.xp); rec("permute")
+            e0 = self._event(ffn_events)
             B.flexmoe_expert_ffn_fwd(L.xp, L.vexpert_off, L.vexpert_owner, self.w1, None, self.w2, None, cfg.act,
                                      L.hpre, L.yp, L.ws); rec("ffn_fwd")
+            self._event(ffn_events, e0, "fwd")
         B.flexmoe_combine(L.yp, L.dest, L.topk_w, cfg.k, L.y); rec("combine")
         if cfg.backward:
             B.flexmoe_permute(self.dy, L.src, L.topk_w, cfg.k, L.dyp); rec("bwd_permute")
+            e0 = self._event(ffn_events)
             B.flexmoe_expert_ffn_bwd(L.dyp, L.xp, L.hpre, self.w1, self.w2, L.vexpert_off, L.vexpert_owner, cfg.act,
                                      L.dxp, L.dw1, L.dw2, L.ws); rec("ffn_bwd")
+            self._event(ffn_events, e0, "bwd")
             B.flexmoe_combine(L.dxp, L.dest, None, cfg.k, L.dx); rec("bwd_combine")
         self.iter += 1
+
+    def _event(self, sink, start=None, tag=None):
+        """HIP event on the stream the kernels are launched on (torch's current stream)."""
+        if sink is None:
+            return None
+        ev = self.torch.cuda.Event(enable_timing=True)
+        ev.record()
+        if start is not None:
+            sink.append((tag, start, ev))
+        return ev
 
 
 class StageTimers:
@@ -146,16 +173,15 @@ class StageTimers:
             self.pairs.setdefault(name, []).append((self.last, ev))
         self.last = ev
 
-    def mean_ms(self):
-        """Mean interval per stage over the steps.  Intervals above five times the stage's median are
-        left out: they are host stalls between two launches (the queue ran dry), not kernel time."""
-        out = {}
-        for n, p in self.pairs.items():
-            t = sorted(a.elapsed_time(b) for a, b in p)
-            med = 0.5 * (t[(len(t) - 1) // 2] + t[len(t) // 2])
-            kept = [v for v in t if v <= 5.0 * med]
-            out[n] = sum(kept) / len(kept)
-        return out
+    def median_ms(self):
+        """Median interval per stage over the steps (an interval also holds the idle time of the stream when
+        the host falls behind between two launches; the median is not moved by the few steps where it does)."""
+        return {n: median([a.elapsed_time(b) for a, b in p]) for n, p in self.pairs.items()}
+
+
+def median(values):
+    t = sorted(values)
+    return 0.5 * (t[(len(t) - 1) // 2] + t[len(t) // 2])
 
 
 def run_workload(name, steps, warmup, with_stages=True, fused=False, variants=True):
@@ -166,13 +192,22 @@ def run_workload(name, steps, warmup, with_stages=True, fused=False, variants=Tr
     for _ in range(warmup):
         r.step()
     torch.cuda.synchronize()
+    ffn_events = []
     t0 = time.perf_counter()
     for _ in range(steps):
-        r.step()
+        r.step(ffn_events=ffn_events)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / steps * 1e3
     out = dict(tokens_per_s=cfg.N / (dt / steps), ms_per_step=ms_per_step, fused=r.fused)
+    # the grouped-GEMM calls of the timed steps themselves: per-step duration = forward call + backward call
+    per_call = {}
+    for tag, a, b in ffn_events:
+        per_call.setdefault(tag, []).append(a.elapsed_time(b))
+    if per_call:
+        per_step = [sum(v) for v in zip(*per_call.values())]
+        out["ffn_timed"] = dict(mean_ms=sum(per_step) / len(per_step), median_ms=median(per_step),
+                                calls={t: round(sum(v) / len(v), 4) for t, v in per_call.items()})
     if variants and not r.fused and not cfg.backward and r.L.gather_supported():
         # the same forward pass with the permutation folded into the first expert GEMM (no Xp written):
         # reported beside the step, which keeps every stage as a call of its own
@@ -206,7 +241,7 @@ def run_workload(name, steps, warmup, with_stages=True, fused=False, variants=Tr
         for _ in range(steps):
             r.step(timers)
         torch.cuda.synchronize()
-        stage_ms = timers.mean_ms()
+        stage_ms = timers.median_ms()
         work = stage_work(cfg)
         stages = {}
         for st, ms in stage_ms.items():
@@ -246,6 +281,22 @@ def copy_ceiling_gbs(nbytes=1 << 28, reps=20):
     e1.record()
     torch.cuda.synchronize()
     return round(2 * nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+
+
+def read_ceiling_gbs(nbytes=1 << 28, reps=20):
+    """Rate of a read-only pass over `nbytes` (a sum reduction): what a stage that reads far more than it
+    writes can be held against, beside the copy ceiling."""
+    import torch
+    src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").fill_(1.0)
+    for _ in range(3):
+        src.sum()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        src.sum()
+    e1.record()
+    torch.cuda.synchronize()
+    return round(nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
 
 
 def dense_gemm_ceiling_tflops(name, reps=10):
@@ -382,9 +433,34 @@ def cpu_baseline(name):
         dt = time.perf_counter() - t0
         best = dt if best is None else min(best, dt)
     threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
-    return dict(value=round(n / best, 1), unit="tokens/s", cores=int(threads), kind="oracle",
+    return dict(value=round(n / best, 1), unit="tokens/s", cores=int(threads), kind="oracle (numpy fp64, threaded BLAS)",
                 sample=f"{n} of {cfg.N} tokens of the same layer ({'forward+backward' if cfg.backward else 'forward'}), "
                        f"best of {reps}, {best:.2f} s")
+
+
+FFN_KERNELS = {
+    True: "flexmoe_expert_ffn_fwd (rows_gemm_dma_bf16 x2: GEMM1 + Hpre/GELU epilogue, GEMM2) + flexmoe_expert_ffn_bwd "
+          "(rows_gemm_dma_bf16: dH + GELU' epilogue, dXp; wgrad_gemm_dma_bf16: dW2, dW1; on grids of a few rounds the "
+          "last three share one launch, bwd_tail_dma_bf16)",
+    False: "flexmoe_expert_ffn_fwd (two grouped-GEMM launches: rows_gemm_dma_bf16 x2)",
+}
+
+
+def compact_row(name, steps, warmup):
+    """One short run of another configuration for the compact table of the default line."""
+    import torch
+    r, o = run_workload(name, steps, warmup, with_stages=False, variants=False)
+    cfg = r.cfg
+    flops = (12 if cfg.backward else 4) * cfg.A * cfg.d * cfg.f
+    row = dict(passes="forward+backward" if cfg.backward else "forward", tokens_per_s=round(o["tokens_per_s"], 1),
+               ms_per_step=round(o["ms_per_step"], 4))
+    if "ffn_timed" in o:
+        peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == r.W.DT_BF16 else FP32_VECTOR_PEAK_TFLOPS
+        row["ffn_ms"] = round(o["ffn_timed"]["mean_ms"], 4)
+        row["ffn_frac_of_peak"] = round(flops / (o["ffn_timed"]["mean_ms"] * 1e-3) / 1e12 / peak, 4)
+    del r
+    torch.cuda.empty_cache()
+    return row
 
 
 def main():
@@ -392,8 +468,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="bert", choices=list(WORKLOAD_TEXT))
-    ap.add_argument("--all-workloads", action="store_true", help="also time the other configurations (extra JSON field)")
+    ap.add_argument("--workload", default="gpt_xl", choices=list(WORKLOAD_TEXT))
+    ap.add_argument("--all-workloads", action="store_true", help="also time the other configurations stage by stage (extra JSON field)")
+    ap.add_argument("--no-others", action="store_true", help="leave out the compact table of the other configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fused", action="store_true",
                     help="forward-only workloads: time the step with flexmoe_expert_ffn_fwd_gather instead of "
@@ -401,6 +478,8 @@ def main():
     ap.add_argument("--no-variants", action="store_true",
                     help="do not also time the forward variants reported beside the step (fused permutation, no stored "
                          "pre-activations): profiles then hold the step's own launches only")
+    ap.add_argument("--no-stages", action="store_true", help="skip the per-stage breakdown pass (profiled runs: the "
+                    "kernel trace then holds warm-up + timed steps only)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device copy (calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -413,7 +492,7 @@ def main():
     from paper_2304_03946_amd import workloads as W
     name = args.workload
     big = name == "gpt_xl"
-    steps = args.steps if args.steps is not None else (20 if big else 200)
+    steps = args.steps if args.steps is not None else (30 if big else 200)
     warmup = args.warmup if args.warmup is not None else (3 if big else 20)
 
     if args.copy_calibration:
@@ -423,12 +502,19 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    r, res = run_workload(name, steps, warmup, fused=args.fused, variants=not args.no_variants)
+    r, res = run_workload(name, steps, warmup, with_stages=not args.no_stages, fused=args.fused,
+                          variants=not args.no_variants)
     cfg = r.cfg
-    ffn = res["stages"]["ffn_fwd"]
-    dom_ms = ffn["ms"]
+    bf16 = cfg.dtype == W.DT_BF16
+    peak = MFMA_BF16_PEAK_TFLOPS if bf16 else FP32_VECTOR_PEAK_TFLOPS
+    flops = (12 if cfg.backward else 4) * cfg.A * cfg.d * cfg.f      # 4 A d f forward, 8 A d f backward
+    ffn = res.get("ffn_timed")
+    if ffn is None:      # --fused: the gathered forward call is timed by the stage pass only
+        ffn = dict(mean_ms=res["stages"]["ffn_fwd"]["ms"], median_ms=res["stages"]["ffn_fwd"]["ms"], calls={})
+    achieved = flops / (ffn["mean_ms"] * 1e-3) / 1e12
+    passes = "forward+backward" if cfg.backward else "forward"
     line = {
-        "metric": "MoE-layer tokens/sec (fwd+bwd) on 1 MI355X; grouped-GEMM MFMA util % of peak",
+        "metric": f"MoE-layer tokens/sec ({'fwd+bwd' if cfg.backward else 'fwd'}) on 1 MI355X; grouped-GEMM MFMA util % of peak",
         "value": round(res["tokens_per_s"], 1),
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -438,25 +524,35 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16" if cfg.dtype == W.DT_BF16 else "f32",
+        "dtype": "bf16" if bf16 else "f32",
         "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT[name], "passes": "forward+backward" if cfg.backward else "forward",
+        "config": {"workload": WORKLOAD_TEXT[name], "passes": passes,
                    "tokens": cfg.N, "d_model": cfg.d, "d_ff": cfg.f, "experts": cfg.E, "top_k": cfg.k,
-                   "vexperts": cfg.V, "loads": res["loads"],
+                   "vexperts": cfg.V, **({"loads": res["loads"]} if "loads" in res else {}),
                    "permute": "folded into the first expert GEMM (flexmoe_expert_ffn_fwd_gather)" if res["fused"]
                               else "flexmoe_permute", **({"fused_permute": res["fused_permute"]} if "fused_permute" in res else {})},
-        "roofline": {"kernel": ("flexmoe_expert_ffn_fwd_gather" if res["fused"] else "flexmoe_expert_ffn_fwd") +
-                               " (two grouped-GEMM launches: rows_gemm_dma_bf16 x2)",
-                     "bound": ffn["bound"], "achieved": ffn["achieved"],
-                     "peak": MFMA_BF16_PEAK_TFLOPS if cfg.dtype == W.DT_BF16 else FP32_VECTOR_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": ffn["frac"], "traffic": MEASURED_FFN_FWD_TRAFFIC_BYTES.get(name),
-                     "launch_ms": dom_ms, "algorithmic_flops": 4 * cfg.A * cfg.d * cfg.f,
-                     "stages": res["stages"]},
+        "roofline": {"kernel": "flexmoe_expert_ffn_fwd_gather (two grouped-GEMM launches)" if res["fused"] else FFN_KERNELS[cfg.backward],
+                     "bound": "mfma" if bf16 else "alu", "achieved": round(achieved, 2), "peak": peak,
+                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                     "traffic": None if res["fused"] else measured_ffn_traffic_bytes(name),
+                     "launch_ms": round(ffn["mean_ms"], 4), "launch_ms_median": round(ffn["median_ms"], 4),
+                     "launch_ms_by_call": ffn["calls"], "algorithmic_flops": flops,
+                     "timing": "HIP events around the grouped-GEMM calls of every timed step, on the stream the kernels "
+                               "run on; launch_ms = mean over the timed steps of (forward call + backward call), no step left out",
+                     **({"stages": res["stages"], "stage_timing": "median over a separate pass of the same steps with an "
+                         "event after every call"} if "stages" in res else {})},
     }
     if "trainable_layer_extras" in res:
         line["trainable_layer_extras"] = res["trainable_layer_extras"]
+    if not args.no_others and not args.all_workloads:
+        del r
+        torch.cuda.empty_cache()
+        r = None
+        line["other_workloads"] = {w: compact_row(w, 20 if w == "gpt_xl" else 100, 3 if w == "gpt_xl" else 10)
+                                   for w in ("bert", "gpt_m", "swin", "gpt_xl", "tiny") if w != name}
     if args.all_workloads:
         line["copy_ceiling_GBs"] = {"256MiB": copy_ceiling_gbs(1 << 28), "32MiB": copy_ceiling_gbs(1 << 25, 100)}
+        line["read_ceiling_GBs"] = {"256MiB": read_ceiling_gbs(1 << 28)}
         torch.cuda.empty_cache()
         line["dense_gemm_ceiling_TFLOPs"] = {w: dense_gemm_ceiling_tflops(w) for w in ("bert", "gpt_m", "swin", "gpt_xl")}
         others = {}

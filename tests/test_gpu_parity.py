@@ -86,7 +86,10 @@ def check_gate(idx_gpu, w_gpu, x, wg, k, dtype, tokens=None):
     idx_ref, w_ref, logits = O.gate_topk(xs, wgd, k)
     bound = gate_error_bound(xs, wgd, dtype)
     pinned = O.topk_margin(logits, k) > 2.0 * bound
-    assert pinned.mean() >= 0.99, f"too many near-tie tokens: {1 - pinned.mean():.4f}"
+    # The bound is the worst case over all rounding patterns (linear in d), so at d = 1024..2048 a few
+    # per cent of the tokens fall under it although their fp32 logits order as the exact ones do; the
+    # selection must still be the oracle's on at least 99.5 % of ALL tokens (checked below).
+    assert pinned.mean() >= 0.95, f"too many near-tie tokens: {1 - pinned.mean():.4f}"
     assert np.array_equal(idx_gpu[pinned], idx_ref[pinned]), "top-k indices differ on pinned tokens"
     # near-tie tokens: the selection must be a set of distinct experts whose exact logits are
     # within the error bound of the exact top-k values, slot by slot
@@ -97,6 +100,7 @@ def check_gate(idx_gpu, w_gpu, x, wg, k, dtype, tokens=None):
         assert np.all(np.abs(logits[t, sel] - ref_sorted) <= 2.0 * bound[t] + 1e-30)
     # gate weights: softmax of the kept logits; an error e in each logit moves a weight by < 2e
     same = np.all(idx_gpu == idx_ref, axis=1)
+    assert same.mean() >= 0.995, f"selection differs from the oracle's on {1 - same.mean():.4f} of the tokens"
     assert np.all(np.abs(w_gpu[same] - w_ref[same]) <= 4.0 * bound[same, None] + 2e-6)
     np.testing.assert_allclose(w_gpu.sum(axis=1), 1.0, atol=1e-5)
     return same
@@ -742,7 +746,10 @@ def test_scheduler_in_the_loop_keeps_the_layer_output(api):
     inp = W.make_layer_inputs(cfg)
     dev = upload(layer_mod, inp)
     L = layer_mod.MoELayer.for_config(cfg)
-    owner = np.repeat(np.arange(cfg.E), 2).astype(np.int32)       # GPU g hosts experts 2g and 2g+1, two slots each
+    # GPU g hosts experts g and g + 4, two slots each (the hottest and the coldest expert of this
+    # workload do not share a GPU: Alg. 2 as printed finds no plan when the slot the coldest expert
+    # releases sits on the very GPU it is meant to relieve)
+    owner = np.array([e for g in range(G) for e in (g, g, g + 4, g + 4)], dtype=np.int32)
     rep = sch.flexmoe_placement_table(owner, cfg.E)
     L.forward(dev["x"], dev["wg"], dev["w1"], dev["w2"], *rep)
     loads, ev = L.post_loads()
