@@ -48,7 +48,8 @@ enum flexmoe_status {
   FLEXMOE_BAD_PLACEMENT = 2,       /* table is not a partition of 0..V-1 with >=1 vExpert per expert */
   FLEXMOE_WORKSPACE_TOO_SMALL = 3,
   FLEXMOE_UNSUPPORTED = 4,         /* unknown dtype or activation */
-  FLEXMOE_DEVICE_ERROR = 5         /* a kernel launch failed */
+  FLEXMOE_DEVICE_ERROR = 5,        /* a kernel launch failed */
+  FLEXMOE_SCRATCH_LIMIT = 6        /* flexmoe_route_static: the problem needs more than its fixed scratch */
 };
 
 enum flexmoe_dtype { FLEXMOE_F32 = 0, FLEXMOE_BF16 = 1 };
@@ -217,6 +218,26 @@ int flexmoe_gate_bwd(const void* wg, const int32_t* topk_idx, const float* topk_
 int flexmoe_expert_bias_grads(const void* dyp, const int32_t* vexpert_off, const int32_t* vexpert_owner,
                               int A, int d, int f, int E, int V, int dtype,
                               void* db1, void* db2, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * flexmoe_route for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus
+ * ws / ws_bytes), same kernels, same results bit for bit.  The scratch (per-unit expert histograms)
+ * is a fixed array of FLEXMOE_ROUTE_STATIC_SCRATCH_BYTES inside the library, one copy per GPU, held
+ * until the process ends; its address is looked up on the first call on each device.  Allocates
+ * nothing, frees nothing, does not synchronise.
+ *   Limit: units * E * 4 <= FLEXMOE_ROUTE_STATIC_SCRATCH_BYTES, where units = ceil(A / 256) for
+ *   A <= 65536, ceil(A / 512) up to A = 524288, at most 1024 beyond; e.g. any A with E <= 64, and
+ *   A <= 65536 with E = 256.  Larger problems return FLEXMOE_SCRATCH_LIMIT and launch nothing.
+ *   All calls on one GPU share the array: calls that overlap in time on one GPU (different
+ *   streams, or graphs replayed concurrently) race and must be serialised by the caller.  Nothing in
+ *   the array has to start at zero (every entry that is read is written first by the same call).
+ */
+#define FLEXMOE_ROUTE_STATIC_SCRATCH_BYTES (256 * 1024)
+int flexmoe_route_static(const int32_t* topk_idx, int N, int k, int E, int V,
+                         const int32_t* rep_off_host, const int32_t* rep_ids_host,
+                         int32_t* expert_count, int32_t* vexpert_count, int32_t* vexpert_off,
+                         int32_t* vexpert_owner, int32_t* dest, int32_t* src, void* stream);
 
 #ifdef __cplusplus
 }

@@ -18,12 +18,12 @@ LIB_PATH = os.path.join(_HERE, "libflexmoe.so")
 
 F32, BF16 = 0, 1
 RELU, GELU_ERF, GELU_TANH = 0, 1, 2
-OK, INVALID_ARG, BAD_PLACEMENT, WORKSPACE_TOO_SMALL, UNSUPPORTED, DEVICE_ERROR = range(6)
+OK, INVALID_ARG, BAD_PLACEMENT, WORKSPACE_TOO_SMALL, UNSUPPORTED, DEVICE_ERROR, SCRATCH_LIMIT = range(7)
 
 EXPORTS = ["flexmoe_status_str", "flexmoe_workspace_bytes", "flexmoe_gate_topk", "flexmoe_route",
            "flexmoe_permute", "flexmoe_expert_ffn_fwd", "flexmoe_expert_ffn_bwd", "flexmoe_combine",
            "flexmoe_gate_bwd", "flexmoe_expert_bias_grads", "flexmoe_expert_ffn_fwd_gather",
-           "flexmoe_expert_ffn_fwd_top1", "flexmoe_expert_ffn_bwd_top1",
+           "flexmoe_expert_ffn_fwd_top1", "flexmoe_expert_ffn_bwd_top1", "flexmoe_route_static",
            # host-side scheduler (include/flexmoe_scheduler.h; Python face in scheduler.py)
            "flexmoe_balance_ratio", "flexmoe_step_cost", "flexmoe_make_scheduling_plan", "flexmoe_schedule",
            "flexmoe_placement_table"]
@@ -56,6 +56,9 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.flexmoe_route.restype = c_int
     lib.flexmoe_route.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp,
                                   c_vp, c_sz, c_vp]
+    lib.flexmoe_route_static.restype = c_int
+    lib.flexmoe_route_static.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp,
+                                         c_vp]
     lib.flexmoe_permute.restype = c_int
     lib.flexmoe_permute.argtypes = [c_vp, c_vp, c_vp, c_int, c_int, c_int, c_int, c_vp, c_vp]
     lib.flexmoe_combine.restype = c_int
@@ -151,6 +154,18 @@ def flexmoe_route(topk_idx, E, rep_off_host, rep_ids_host, expert_count, vexpert
                                       _ptr(vexpert_off), _ptr(vexpert_owner), _ptr(dest), _ptr(src), _ptr(ws),
                                       ws.numel() * ws.element_size(), _stream())
     _check(st, "flexmoe_route")
+
+
+def flexmoe_route_static(topk_idx, E, rep_off_host, rep_ids_host, expert_count, vexpert_count, vexpert_off,
+                         vexpert_owner, dest, src):
+    N, k = topk_idx.shape
+    off, ids = _host_i32(rep_off_host), _host_i32(rep_ids_host)
+    V = int(ids.shape[0])
+    st = load_library().flexmoe_route_static(_ptr(topk_idx), N, k, E, V, off.ctypes.data_as(ctypes.c_void_p),
+                                             ids.ctypes.data_as(ctypes.c_void_p), _ptr(expert_count),
+                                             _ptr(vexpert_count), _ptr(vexpert_off), _ptr(vexpert_owner), _ptr(dest),
+                                             _ptr(src), _stream())
+    _check(st, "flexmoe_route_static")
 
 
 def flexmoe_permute(x, src, row_scale, k, xp):

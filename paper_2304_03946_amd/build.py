@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libflexmoe.so")
-SOURCES = ["api.hip", "gate.hip", "route.hip", "permute_combine.hip", "ffn_f32.hip", "ffn_bf16.hip", "gate_bwd.hip",
+SOURCES = ["api.hip", "gate.hip", "route.hip", "route_static.hip", "permute_combine.hip", "ffn_f32.hip", "ffn_bf16.hip", "gate_bwd.hip",
            "scheduler.cpp"]     # .cpp = host-only code
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -32,6 +32,7 @@ const char* flexmoe_status_str(int status) {
     case FLEXMOE_WORKSPACE_TOO_SMALL: return "workspace too small";
     case FLEXMOE_UNSUPPORTED: return "unsupported dtype or activation";
     case FLEXMOE_DEVICE_ERROR: return "device error";
+    case FLEXMOE_SCRATCH_LIMIT: return "problem exceeds the static scratch of the allocation-free entry point";
     default: return "unknown status";
   }
 }
