@@ -306,9 +306,14 @@ __global__ __launch_bounds__(WAVES * kWave) void gate_dma_kernel(const bf16_t* _
   const bf16_t* zsrc = (const bf16_t*)kGateZeroRow + (lane & 7) * 8;
   const unsigned lds_base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(gate_lds_t*)smem);
 
+  // Workgroups start their contraction at different K tiles and wrap around, so that the requests in flight on the
+  // chip are not all at the same column offset of their rows (measured: -7 % on 65536 tokens x 2048 features).
+  // The order of a token's sum then depends on its workgroup, i.e. on the token's index only: still reproducible.
+  const int kshift = (int)((blockIdx.x * 5u) % (unsigned)KT);
   auto issue = [&](int kt) {
     const unsigned st = lds_base + (kt % S) * kStage;
-    const int k0 = kt * kGateDK;
+    const int ktr = kt + kshift < KT ? kt + kshift : kt + kshift - KT;
+    const int k0 = ktr * kGateDK;
     const bool x_ok = k0 + lchunk * 8 < d;                    // whole 16-byte chunks: d is a multiple of 8
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
