@@ -40,6 +40,20 @@ def generate_tables() -> str:
     return out
 
 
+def build_probe(verbose: bool = True) -> str:
+    """The K-loop microbenchmark behind the ceilings quoted for the grouped GEMMs (csrc/probe/kloop_probe.hip):
+    a stand-alone executable next to the library; run it on the GPU machine as paper_2304_03946_amd/kloop_probe."""
+    out = os.path.join(PKG, "kloop_probe")
+    cmd = [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           os.path.join(CSRC, "probe", "kloop_probe.hip"), "-o", out]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for kloop_probe.hip:\n" + r.stderr)
+    if verbose:
+        print(f"built {out}")
+    return out
+
+
 def build_library(verbose: bool = True) -> str:
     """Compile every source and link the shared library; always rebuilds."""
     generate_tables()
@@ -56,3 +70,4 @@ def build_library(verbose: bool = True) -> str:
 
 if __name__ == "__main__":
     build_library()
+    build_probe()
