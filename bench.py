@@ -258,6 +258,7 @@ def run_workload(name, steps, warmup, with_stages=True, fused=False, variants=Tr
         out["stages"] = stages
         if cfg.backward:
             out["trainable_layer_extras"] = time_extras(r, steps)
+        out["token_cost_ns"] = r.L.profile_token_cost(r.w1, r.w2)      # Eq. 7: T_C per token from profiling
         counts = r.L.expert_count.cpu().numpy()
         vc = r.L.vexpert_count.cpu().numpy()
         out["loads"] = dict(hottest_expert_share=round(float(counts.max()) / cfg.A, 4),
@@ -387,7 +388,7 @@ def time_extras(r, steps):
     return out
 
 
-def scheduler_pass(name, G=64, S=4, reps=5):
+def scheduler_pass(name, G=64, S=4, reps=5, token_cost=1):
     """Host-side scheduler (Alg. 1: balance ratio, Policy Maker, Migrate) timed on an emulated cluster of the
     paper's size: G GPUs with S vExpert slots each, every expert owning a contiguous block of slots (the
     static expert-parallel placement), loads = G batches with the workload's expert skew."""
@@ -401,10 +402,12 @@ def scheduler_pass(name, G=64, S=4, reps=5):
     best = None
     for _ in range(reps):
         t0 = time.perf_counter()
-        ops, new_owner, before, after = sch.flexmoe_schedule(tokens, owner, G, 1, 1.0, 4 * V)
+        ops, new_owner, before, after = sch.flexmoe_schedule(tokens, owner, G, token_cost, 1.0, 4 * V)
         dt = time.perf_counter() - t0
         best = dt if best is None else min(best, dt)
-    return dict(cluster=f"{G} GPUs x {S} vExpert slots, {cfg.E} experts", primitives=int(len(ops)),
+    return dict(cluster=f"{G} GPUs x {S} vExpert slots, {cfg.E} experts", token_cost_ns=int(token_cost),
+                token_cost_source="HIP-event time of the expert FFN calls per routed token (MoELayer.profile_token_cost)",
+                primitives=int(len(ops)),
                 balance_ratio_before=round(before, 4), balance_ratio_after=round(after, 4),
                 us_per_pass=round(best * 1e6, 1))
 
@@ -568,7 +571,7 @@ def main():
             if "trainable_layer_extras" in o:
                 others[other]["trainable_layer_extras"] = o["trainable_layer_extras"]
         line["all_workloads"] = others
-    line["scheduler"] = scheduler_pass(name)
+    line["scheduler"] = scheduler_pass(name, token_cost=res.get("token_cost_ns", 1))
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(name)
     print(json.dumps(line))

@@ -89,6 +89,31 @@ class MoELayer:
         ev.record()
         return self._loads_host, ev
 
+    def profile_token_cost(self, w1, w2, reps: int = 3) -> int:
+        """T_C of Eq. 7 from profiling: nanoseconds of expert computation (forward, plus backward for a
+        training layer) per routed token, measured with HIP events around flexmoe_expert_ffn_fwd / _bwd on
+        the buckets the layer currently holds (call after `forward`, and after `backward` for a training
+        layer: xp, hpre, dyp must be filled).  The integer it returns is the `token_cost` (1 / TPS) the
+        scheduler entry points take; a sync_cost table in the same unit (ns) then weighs T_Sync against it."""
+        if self.A == 0:
+            return 1
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+
+        def once():
+            B.flexmoe_expert_ffn_fwd(self.xp, self.vexpert_off, self.vexpert_owner, w1, None, w2, None, self.act,
+                                     self.hpre, self.yp, self.ws)
+            if self.has_backward:
+                B.flexmoe_expert_ffn_bwd(self.dyp, self.xp, self.hpre, w1, w2, self.vexpert_off, self.vexpert_owner,
+                                         self.act, self.dxp, self.dw1, self.dw2, self.ws)
+        once()
+        ev[0].record()
+        for _ in range(reps):
+            once()
+        ev[1].record()
+        ev[1].synchronize()
+        ns = ev[0].elapsed_time(ev[1]) * 1e6 / reps
+        return max(1, int(round(ns / self.A)))
+
     def forward(self, x, wg, w1, w2, rep_off, rep_ids, b1=None, b2=None, keep_hpre=True):
         """keep_hpre=False (inference): the pre-activations are not stored; `backward` cannot follow."""
         self.gate(x, wg)

@@ -764,6 +764,16 @@ def test_scheduler_in_the_loop_keeps_the_layer_output(api):
     assert (before, after) == (r_before, r_after)
     assert len(ops) > 0 and after < before
 
+    # Eq. 7: the cost per token comes from profiling the expert computation; with a synchronisation table in
+    # the same unit the plan made with the measured cost is the oracle's plan for that cost
+    L.backward(dev["dy"], dev["w1"], dev["w2"])
+    cost = L.profile_token_cost(dev["w1"], dev["w2"])
+    assert isinstance(cost, int) and 1 <= cost < 10 ** 7
+    sync = [0, 0] + [40 * cost * g for g in range(2, G + 1)]
+    m_ops, m_owner, _, _ = sch.flexmoe_schedule(I, owner, G, cost, 1.0, 32, sync_cost=sync)
+    o_ops, o_owner, _, _ = SO.schedule(I.tolist(), owner.tolist(), G, cost, 1.0, 32, sync)
+    assert [tuple(o) for o in m_ops.tolist()] == o_ops and m_owner.tolist() == o_owner
+
     rep2 = sch.flexmoe_placement_table(new_owner, cfg.E)
     L.forward(dev["x"], dev["wg"], dev["w1"], dev["w2"], *rep2)
     torch.cuda.synchronize()
