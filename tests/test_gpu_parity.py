@@ -234,6 +234,9 @@ SMALL = {
     # tiles for 256 compute units) and a long contraction: the tiles left for the last round are cut along K
     # into four segments (fp32 partial tiles + reduce kernel)
     "split_tail": W.scaled(W.CONFIGS["swin"], N=66000, d=128, f=1024, E=8, V=12, max_rep=4, backward=False),
+    # the library's limits: 256 experts, 512 vExperts, 8 experts per token -- hundreds of buckets of a few dozen rows
+    # (every one a ragged tile, many experts with a handful of tokens, the bucket lookups at their widest)
+    "max_experts": W.scaled(W.CONFIGS["gpt_xl"], N=2500, d=128, f=256, E=256, V=512, k=8, max_rep=8, skew_s=1.0),
 }
 
 
