@@ -68,7 +68,8 @@ static int wgrad_seg_tiles(int A, int d, int f) {
 // tile sets (segments of experts that have more than one).
 static int wgrad_extra_segments(int A, int V, int seg_tiles) { return seg_tiles ? (A / DK + V) / seg_tiles : 0; }
 static int wgrad_partial_slots(int A, int V, int seg_tiles) { return seg_tiles ? 2 * ((A / DK + V) / seg_tiles) + 1 : 0; }
-static size_t wgrad_table_bytes() { return FLEXMOE_MAX_EXPERTS * sizeof(int4); }
+
+static int wgrad_seg_rows_max(int A, int d, int f, int E, int V) { return E + wgrad_extra_segments(A, V, wgrad_seg_tiles(A, d, f)); }
 
 static int max_row_tiles(int A, int V) { return A / BM + V; }
 
@@ -86,7 +87,7 @@ static size_t rows_split_bytes(int A, int V, int K, int NC) {
 static size_t wgrad_tail_bytes(int A, int d, int f, int V) {
   const int seg_tiles = wgrad_seg_tiles(A, d, f);
   if (!seg_tiles) return 0;
-  return align_up(wgrad_table_bytes() + (size_t)wgrad_partial_slots(A, V, seg_tiles) * d * f * sizeof(float), 256);
+  return align_up((size_t)wgrad_partial_slots(A, V, seg_tiles) * d * f * sizeof(float), 256);
 }
 
 size_t ffn_ws_bytes(int A, int d, int f, int E, int V, int dtype) {
@@ -95,8 +96,13 @@ size_t ffn_ws_bytes(int A, int d, int f, int E, int V, int dtype) {
   if (dtype == FLEXMOE_BF16) {
     need += 2 * wgrad_tail_bytes(A, d, f, V);      // one region per weight gradient
     need += rows_split_bytes(A, V, f, d);          // GEMM2 / dXp: partial tiles of the split last round
+    need += align_up(wgrad_plan_bytes(wgrad_seg_rows_max(A, d, f, E, V), E, V), 256);   // work list of the weight gradients
   }
   return need;
+}
+static void* wgrad_plan_ws(const FfnArgs& a, void* ws) {
+  return (char*)ws + 2 * align_up((size_t)a.A * a.f * sizeof(bf16_t), 256) + 2 * wgrad_tail_bytes(a.A, a.d, a.f, a.V) +
+         rows_split_bytes(a.A, a.V, a.f, a.d);
 }
 static void* rows_split_ws(const FfnArgs& a, void* ws) {
   return (char*)ws + 2 * align_up((size_t)a.A * a.f * sizeof(bf16_t), 256) + 2 * wgrad_tail_bytes(a.A, a.d, a.f, a.V);
@@ -160,28 +166,35 @@ static hipError_t launch_rows(const FfnArgs& a, const void* in, const void* w, c
 // One weight-gradient product's arguments and grid; `ws_tail` holds its job table and fp32 partial
 // tiles when the contraction is cut into segments (wgrad_tail_bytes each).
 static WgradDmaArgs wgrad_dma_args(const FfnArgs& a, const void* L, const void* R, int M, int NC, void* dw,
-                                   void* ws_tail, unsigned* grid) {
+                                   void* ws_tail, void* ws, unsigned* grid) {
   const int m_tiles = (M + BM - 1) / BM, n_tiles = (NC + BN - 1) / BN;
   const int seg_tiles = wgrad_seg_tiles(a.A, a.d, a.f);
-  int4* table = seg_tiles ? (int4*)ws_tail : nullptr;
-  float* partial = seg_tiles ? (float*)((char*)ws_tail + wgrad_table_bytes()) : nullptr;
-  const int seg_rows_max = a.E + wgrad_extra_segments(a.A, a.V, seg_tiles);
+  float* partial = seg_tiles ? (float*)ws_tail : nullptr;
+  const int seg_rows_max = wgrad_seg_rows_max(a.A, a.d, a.f, a.E, a.V);
   *grid = patched_grid(seg_rows_max * m_tiles, n_tiles);
   return WgradDmaArgs{(const bf16_t*)L, (const bf16_t*)R, a.voff, a.owner, a.E, a.V, M, NC, m_tiles, n_tiles,
-                      seg_tiles, seg_rows_max, partial, table, (bf16_t*)dw};
+                      seg_tiles, seg_rows_max, partial, wgrad_plan_at(wgrad_plan_ws(a, ws), seg_rows_max, a.E, a.V),
+                      (bf16_t*)dw};
+}
+
+// The work list both weight-gradient products of a backward call read (one small workgroup).
+static void launch_wgrad_plan(const FfnArgs& a, void* ws, hipStream_t s) {
+  const int seg_rows_max = wgrad_seg_rows_max(a.A, a.d, a.f, a.E, a.V);
+  hipLaunchKernelGGL(wgrad_plan_kernel, dim3(1), dim3(kGemmThreads), 0, s, a.voff, a.owner, a.E, a.V,
+                     wgrad_seg_tiles(a.A, a.d, a.f), seg_rows_max, wgrad_plan_at(wgrad_plan_ws(a, ws), seg_rows_max, a.E, a.V));
 }
 
 static void launch_wgrad_reduce(const FfnArgs& a, const WgradDmaArgs& g, hipStream_t s) {
   if (!g.seg_tiles) return;
   const int blocks = (int)std::min<size_t>(((size_t)g.M * g.NC / 4 + kGemmThreads - 1) / kGemmThreads, 2048);
-  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(blocks, a.E), dim3(kGemmThreads), 0, s, (const int4*)g.table, g.M, g.NC,
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(blocks, a.E), dim3(kGemmThreads), 0, s, (const int4*)g.plan.table, g.M, g.NC,
                      (const float*)g.partial, g.dw);
 }
 
 static hipError_t launch_wgrad(const FfnArgs& a, const void* L, const void* R, int M, int NC, void* dw, void* ws_tail,
-                               hipStream_t s) {
+                               void* ws, hipStream_t s) {
   unsigned grid;
-  const WgradDmaArgs g = wgrad_dma_args(a, L, R, M, NC, dw, ws_tail, &grid);
+  const WgradDmaArgs g = wgrad_dma_args(a, L, R, M, NC, dw, ws_tail, ws, &grid);
   hipLaunchKernelGGL(wgrad_gemm_dma_bf16, dim3(grid), dim3(kGemmThreads), 0, s, g);
   launch_wgrad_reduce(a, g, s);
   return hipGetLastError();
@@ -228,6 +241,7 @@ hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp
   bf16_t* dhpre = (bf16_t*)ws;
   bf16_t* h = (bf16_t*)((char*)ws + align_up((size_t)a.A * a.f * sizeof(bf16_t), 256));
   hipError_t err;
+  launch_wgrad_plan(a, ws, s);
   if (a.A > 0) {
     // dH = dYp . W2^T fused with act'(Hpre); W2_e is [f, d], contraction index d contiguous
     err = launch_rows<true, EPI_DH>(a, dyp, w2, nullptr, a.d, a.f, hpre, dhpre, h, s);
@@ -246,8 +260,8 @@ hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp
     unsigned grid2, grid1;
     RowsDmaArgs dx = rows_dma_args(a, dhpre, w1, nullptr, a.f, a.d, nullptr, dxp, nullptr, nullptr, 1);
     dx.scatter_rows = scatter_src;
-    const WgradDmaArgs g2 = wgrad_dma_args(a, h, dyp, a.f, a.d, dw2, ws_tail2, &grid2);
-    const WgradDmaArgs g1 = wgrad_dma_args(a, xp, dhpre, a.d, a.f, dw1, ws_tail1, &grid1);
+    const WgradDmaArgs g2 = wgrad_dma_args(a, h, dyp, a.f, a.d, dw2, ws_tail2, ws, &grid2);
+    const WgradDmaArgs g1 = wgrad_dma_args(a, xp, dhpre, a.d, a.f, dw1, ws_tail1, ws, &grid1);
     const unsigned n_dx = round8(patched_grid(dx.row_tiles_max, dx.col_tiles)), n_w2 = round8(grid2);
     hipLaunchKernelGGL(bwd_tail_dma_bf16, dim3(n_dx + n_w2 + grid1), dim3(kGemmThreads), 0, s, dx, n_dx, g2, n_w2, g1);
     launch_wgrad_reduce(a, g2, s);
@@ -260,9 +274,9 @@ hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp
                                        rows_split_ws(a, ws), scatter_src);
     if (err != hipSuccess) return err;
   }
-  err = launch_wgrad(a, h, dyp, a.f, a.d, dw2, ws_tail2, s);
+  err = launch_wgrad(a, h, dyp, a.f, a.d, dw2, ws_tail2, ws, s);
   if (err != hipSuccess) return err;
-  return launch_wgrad(a, xp, dhpre, a.d, a.f, dw1, ws_tail1, s);
+  return launch_wgrad(a, xp, dhpre, a.d, a.f, dw1, ws_tail1, ws, s);
 }
 
 }  // namespace flexmoe

@@ -10,29 +10,59 @@ namespace flexmoe {
 // into segments of seg_tiles K tiles that different workgroups contract (a hot expert would
 // otherwise be one long serial K loop): an expert with more than one segment leaves fp32 partial
 // tiles in the workspace, `slot` numbering them, which wgrad_reduce_kernel adds up in segment
-// order.  The whole list is a function of the bucket sizes only, so every workgroup re-derives it.
+// order.  The whole list is a function of the bucket sizes only.  It is built once per backward call
+// by wgrad_plan_kernel (one workgroup) and left in the workspace, where every workgroup of the two
+// weight-gradient products finds its job with one load (deriving the list in each of the thousands of
+// workgroups cost 4-5 us per output tile: 0.6 ms of the large layer's step).
 struct WgradJob {
   int e;        // expert, -1: no job
   int seg;      // segment of the expert's contraction
   int nseg;     // segments of this expert
   int slot;     // index of the expert's first partial tile set (meaningful when nseg > 1)
 };
-struct WgradShared {
+// Layout of the plan in the workspace (all int32 / int4, offsets in bytes from its 256-byte aligned start):
+//   jobs      [seg_rows_max] int4 {e, seg, nseg, slot} in work-list order (e = -1 past the end)
+//   table     [FLEXMOE_MAX_EXPERTS] int4 {expert, segments, first slot, 0} by load rank (for wgrad_reduce_kernel)
+//   boff      [E + 1]  int: expert e's non-empty buckets are entries boff[e] .. boff[e+1] of the two lists below
+//   bstart    [V]      int: first row of the bucket
+//   brows     [V]      int: rows of the bucket
+struct WgradPlan {
+  int4* jobs;
+  int4* table;
+  int* boff;
+  int* bstart;
+  int* brows;
+};
+__host__ __device__ inline size_t wgrad_plan_bytes(int seg_rows_max, int E, int V) {
+  return ((size_t)seg_rows_max + FLEXMOE_MAX_EXPERTS) * sizeof(int4) + ((size_t)E + 1 + 2 * (size_t)V) * sizeof(int);
+}
+__host__ __device__ inline WgradPlan wgrad_plan_at(void* base, int seg_rows_max, int E, int V) {
+  WgradPlan p;
+  p.jobs = (int4*)base;
+  p.table = p.jobs + seg_rows_max;
+  p.boff = (int*)(p.table + FLEXMOE_MAX_EXPERTS);
+  p.bstart = p.boff + E + 1;
+  p.brows = p.bstart + V;
+  return p;
+}
+
+struct WgradPlanShared {
   int cnt[FLEXMOE_MAX_VEXPERTS], own[FLEXMOE_MAX_VEXPERTS];
-  int load[FLEXMOE_MAX_EXPERTS], tiles[FLEXMOE_MAX_EXPERTS];
+  int load[FLEXMOE_MAX_EXPERTS], tiles[FLEXMOE_MAX_EXPERTS], nbuckets[FLEXMOE_MAX_EXPERTS];
   int rank_e[FLEXMOE_MAX_EXPERTS], rank_s[FLEXMOE_MAX_EXPERTS];
-  int job[4];
+  int boff[FLEXMOE_MAX_EXPERTS + 1];
+};
+// Buckets of the job's expert, copied from the plan into LDS by the workgroup that runs the job.
+struct WgradShared {
   int nb;
   int bstart[FLEXMOE_MAX_VEXPERTS], brows[FLEXMOE_MAX_VEXPERTS];
 };
 
-// `want` counts segments in work-list order (rank-major).  Also fills sh.bstart/brows/nb with the
-// expert's buckets.
-// `table` (optional, [E] entries of {expert, segments, first slot, 0} by load rank) is written by the
-// caller that passes it, for wgrad_reduce_kernel.
-__device__ __forceinline__ WgradJob wgrad_plan(const int32_t* __restrict__ voff, const int32_t* __restrict__ owner,
-                                               int E, int V, int seg_tiles, int want, WgradShared& sh,
-                                               int4* __restrict__ table) {
+// One workgroup of kGemmThreads threads; see the layout above.
+__global__ __launch_bounds__(kGemmThreads) void wgrad_plan_kernel(const int32_t* __restrict__ voff,
+                                                                  const int32_t* __restrict__ owner, int E, int V,
+                                                                  int seg_tiles, int seg_rows_max, WgradPlan plan) {
+  __shared__ WgradPlanShared sh;
   for (int v = threadIdx.x; v < V; v += kGemmThreads) {
     sh.cnt[v] = voff[v + 1] - voff[v];
     sh.own[v] = owner[v];
@@ -40,12 +70,13 @@ __device__ __forceinline__ WgradJob wgrad_plan(const int32_t* __restrict__ voff,
   for (int e = threadIdx.x; e < E; e += kGemmThreads) {
     sh.load[e] = 0;
     sh.tiles[e] = 0;
+    sh.nbuckets[e] = 0;
   }
-  if (threadIdx.x == 0) sh.job[0] = -1;
   __syncthreads();
   for (int v = threadIdx.x; v < V; v += kGemmThreads) {
-    atomicAdd(&sh.load[sh.own[v]], sh.cnt[v]);
+    atomicAdd(&sh.load[sh.own[v]], sh.cnt[v]);                       // integer sums: order does not matter
     atomicAdd(&sh.tiles[sh.own[v]], (sh.cnt[v] + DK - 1) / DK);
+    if (sh.cnt[v] > 0) atomicAdd(&sh.nbuckets[sh.own[v]], 1);
   }
   __syncthreads();
   for (int e = threadIdx.x; e < E; e += kGemmThreads) {
@@ -60,63 +91,88 @@ __device__ __forceinline__ WgradJob wgrad_plan(const int32_t* __restrict__ voff,
   }
   __syncthreads();
   if (threadIdx.x < kWave) {
-    // prefix over the ranks of the segment counts (and of the segment counts of split experts)
     const int lane = threadIdx.x;
     constexpr int kPer = FLEXMOE_MAX_EXPERTS / kWave;
-    int sum = 0, sum_split = 0;
+    // prefix over the ranks of the segment counts (and of the segment counts of split experts)
+    int sum = 0, sum_split = 0, sum_b = 0;
 #pragma unroll
     for (int q = 0; q < kPer; ++q) {
       const int r = lane * kPer + q;
       const int n = r < E ? sh.rank_s[r] : 0;
       sum += n;
       sum_split += n > 1 ? n : 0;
+      sum_b += r < E ? sh.nbuckets[r] : 0;                            // by expert id, for the bucket lists
     }
-    int incl = sum, incl_split = sum_split;
+    int incl = sum, incl_split = sum_split, incl_b = sum_b;
 #pragma unroll
     for (int o = 1; o < kWave; o <<= 1) {
-      const int up = __shfl_up(incl, o), up2 = __shfl_up(incl_split, o);
+      const int up = __shfl_up(incl, o), up2 = __shfl_up(incl_split, o), up3 = __shfl_up(incl_b, o);
       if (lane >= o) {
         incl += up;
         incl_split += up2;
+        incl_b += up3;
       }
     }
-    int start = incl - sum, slot = incl_split - sum_split;
+    int start = incl - sum, slot = incl_split - sum_split, bo = incl_b - sum_b;
 #pragma unroll
     for (int q = 0; q < kPer; ++q) {
       const int r = lane * kPer + q;
-      const int n = r < E ? sh.rank_s[r] : 0;
-      const bool hit = want >= start && want < start + n;
-      if (hit) {
-        sh.job[0] = sh.rank_e[r];
-        sh.job[1] = want - start;
-        sh.job[2] = n;
-        sh.job[3] = slot;
+      if (r < E) {
+        const int n = sh.rank_s[r];
+        plan.table[r] = make_int4(sh.rank_e[r], n, slot, 0);
+        for (int sg = 0; sg < n; ++sg)
+          if (start + sg < seg_rows_max) plan.jobs[start + sg] = make_int4(sh.rank_e[r], sg, n, slot);
+        start += n;
+        slot += n > 1 ? n : 0;
+        sh.boff[r] = bo;
+        plan.boff[r] = bo;
+        bo += sh.nbuckets[r];
       }
-      if (table && r < E) table[r] = make_int4(sh.rank_e[r], n, slot, 0);
-      start += n;
-      slot += n > 1 ? n : 0;
     }
+    const int total = __shfl(incl, kWave - 1), total_b = __shfl(incl_b, kWave - 1);
+    if (lane == 0) {
+      sh.boff[E] = total_b;
+      plan.boff[E] = total_b;
+    }
+    for (int w = total + lane; w < seg_rows_max; w += kWave) plan.jobs[w] = make_int4(-1, 0, 0, 0);
   }
   __syncthreads();
-  WgradJob job{sh.job[0], sh.job[1], sh.job[2], sh.job[3]};
-  if (job.e < 0) return job;                    // uniform
-  if (threadIdx.x < kWave) {                   // the expert's non-empty buckets, ascending vExpert id
-    const int lane = threadIdx.x;
+  // bucket lists: a wave per expert, the expert's non-empty buckets in ascending vExpert id
+  {
+    const int lane = threadIdx.x & (kWave - 1);
     const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    int nbw = 0;
-    for (int vb = 0; vb < V; vb += kWave) {
-      const int v = vb + lane;
-      const bool hit = v < V && sh.own[v] == job.e && sh.cnt[v] > 0;
-      const unsigned long long mask = __ballot(hit);
-      if (hit) {
-        const int pos = nbw + __popcll(mask & lt);
-        sh.bstart[pos] = voff[v];
-        sh.brows[pos] = sh.cnt[v];
+    for (int e = threadIdx.x / kWave; e < E; e += kGemmThreads / kWave) {
+      int pos0 = sh.boff[e];
+      for (int vb = 0; vb < V; vb += kWave) {
+        const int v = vb + lane;
+        const bool hit = v < V && sh.own[v] == e && sh.cnt[v] > 0;
+        const unsigned long long mask = __ballot(hit);
+        if (hit) {
+          const int pos = pos0 + __popcll(mask & lt);
+          plan.bstart[pos] = voff[v];
+          plan.brows[pos] = sh.cnt[v];
+        }
+        pos0 += __popcll(mask);
       }
-      nbw += __popcll(mask);
     }
-    if (lane == 0) sh.nb = nbw;
   }
+}
+
+// The job of work-list position `want` and the buckets of its expert (copied to sh); uniform over the workgroup.
+__device__ __forceinline__ WgradJob wgrad_fetch_job(const WgradPlan& plan, int want, WgradShared& sh) {
+  const int4 j = plan.jobs[want];
+  WgradJob job{j.x, j.y, j.z, j.w};
+  job.e = __builtin_amdgcn_readfirstlane(job.e);
+  job.seg = __builtin_amdgcn_readfirstlane(job.seg);
+  job.nseg = __builtin_amdgcn_readfirstlane(job.nseg);
+  job.slot = __builtin_amdgcn_readfirstlane(job.slot);
+  if (job.e < 0) return job;
+  const int b0 = plan.boff[job.e], nb = plan.boff[job.e + 1] - b0;
+  for (int b = threadIdx.x; b < nb; b += kGemmThreads) {
+    sh.bstart[b] = plan.bstart[b0 + b];
+    sh.brows[b] = plan.brows[b0 + b];
+  }
+  if (threadIdx.x == 0) sh.nb = nb;
   __syncthreads();
   return job;
 }
@@ -204,7 +260,7 @@ struct WgradDmaArgs {
   const int32_t* owner;
   int E, V, M, NC, m_tiles, n_tiles, seg_tiles, seg_rows_max;
   float* partial;
-  int4* table;
+  WgradPlan plan;
   bf16_t* dw;
 };
 
@@ -221,7 +277,7 @@ __device__ __forceinline__ void wgrad_dma_block(const WgradDmaArgs& p, unsigned 
   int grow, nt;
   if (!patched_tile(block, p.seg_rows_max * p.m_tiles, p.n_tiles, &grow, &nt)) return;
   const int mt = grow % m_tiles;
-  const WgradJob job = wgrad_plan(p.voff, p.owner, p.E, p.V, seg_tiles, grow / m_tiles, sh, block == 0 ? p.table : nullptr);
+  const WgradJob job = wgrad_fetch_job(p.plan, grow / m_tiles, sh);
   if (job.e < 0) return;
   const int nb = sh.nb;
 

@@ -43,10 +43,13 @@ def test_status_strings_and_workspace_size():
     binding, lib = _lib()
     assert binding.status_str(binding.OK) == "ok"
     assert "placement" in binding.status_str(binding.BAD_PLACEMENT)
-    # gpt_xl: workspace holds dHpre and act(Hpre), each A x f bf16, and 256 fp32 partial tiles of 256 x 256 for
-    # the split last round of the second forward product / dXp
+    # gpt_xl: workspace holds dHpre and act(Hpre), each A x f bf16, 256 fp32 partial tiles of 256 x 256 for
+    # the split last round of the second forward product / dXp, and the work list of the weight gradients
+    # (16 bytes per job and per slot of the 256-expert table, bucket offsets per expert, start and rows per
+    # vExpert), rounded up to 256 bytes
     ws = binding.flexmoe_workspace_bytes(65536, 2048, 8192, 64, 2, 96, binding.BF16)
-    assert ws == 2 * 131072 * 8192 * 2 + 256 * 256 * 256 * 4
+    plan = (64 + 256) * 16 + (64 + 1 + 2 * 96) * 4
+    assert ws == 2 * 131072 * 8192 * 2 + 256 * 256 * 256 * 4 + (plan + 255) // 256 * 256
     assert binding.flexmoe_workspace_bytes(16, 12, 64, 4, 1, 4, binding.BF16) == 0      # d not a multiple of 8
     assert binding.flexmoe_workspace_bytes(16, 64, 64, 4, 5, 4, binding.BF16) == 0      # k > E
 
