@@ -17,8 +17,8 @@
 //    (the result does not depend on scheduling).
 //
 // Two operand pipelines:
-//  * direct-to-LDS (rows_gemm_dma_bf16, wgrad_gemm_dma_bf16; used whenever K is a multiple of
-//    128, i.e. for every benchmark shape): global_load_lds_dwordx4 copies 32-wide K tiles
+//  * direct-to-LDS (rows_gemm_persist_bf16, bwd_tail_dma_bf16, wgrad_gemm_dma_bf16; used whenever K is a
+//    multiple of 128, i.e. for every benchmark shape): global_load_lds_dwordx4 copies 32-wide K tiles
 //    straight into one of four LDS stages (no register staging, no LDS store instructions); an
 //    operand whose contraction index is strided in memory is copied as stored and transposed on
 //    the way out of LDS by ds_read_tr16_b64.  The loads of the tile three steps ahead are
@@ -36,14 +36,20 @@
 // by the argument's bits (constant data in the code object, computed from the fp64 formulas when the
 // library is built; outside the table's range GELU equals ReLU to below bf16 resolution).
 //
+// The rows GEMMs that are launched on their own are persistent: 256 workgroups, one per compute unit,
+// each walking its share of the output tiles and issuing the next tile's first operand loads while the
+// current tile's K loop drains (ffn_bf16_persist.h).
+//
 // Layout of the sources: ffn_bf16_tile.h (tile mapping, fragments, activation tables, epilogues, the
-// register-staged kernel), ffn_bf16_dma.h (direct-to-LDS pipeline and its rows kernels),
-// ffn_bf16_wgrad.h (weight-gradient kernels, the shared backward launch); this file holds the host side.
+// register-staged kernel), ffn_bf16_dma.h (direct-to-LDS pipeline, one rows tile on it),
+// ffn_bf16_persist.h (persistent rows kernels and their row-tile table), ffn_bf16_wgrad.h
+// (weight-gradient kernels, the shared backward launch); this file holds the host side.
 #include <algorithm>
 
 #include "common.h"
 #include "ffn_bf16_tile.h"
 #include "ffn_bf16_dma.h"
+#include "ffn_bf16_persist.h"
 #include "ffn_bf16_wgrad.h"
 
 namespace flexmoe {
@@ -97,8 +103,19 @@ size_t ffn_ws_bytes(int A, int d, int f, int E, int V, int dtype) {
     need += 2 * wgrad_tail_bytes(A, d, f, V);      // one region per weight gradient
     need += rows_split_bytes(A, V, f, d);          // GEMM2 / dXp: partial tiles of the split last round
     need += align_up(wgrad_plan_bytes(wgrad_seg_rows_max(A, d, f, E, V), E, V), 256);   // work list of the weight gradients
+    need += align_up(rows_tab_bytes(max_row_tiles(A, V)), 256);                         // row tiles of the bucket list
   }
   return need;
+}
+static i32x4* rows_tab_ws(const FfnArgs& a, void* ws) {
+  return (i32x4*)((char*)ws + 2 * align_up((size_t)a.A * a.f * sizeof(bf16_t), 256) + 2 * wgrad_tail_bytes(a.A, a.d, a.f, a.V) +
+                  rows_split_bytes(a.A, a.V, a.f, a.d) +
+                  align_up(wgrad_plan_bytes(wgrad_seg_rows_max(a.A, a.d, a.f, a.E, a.V), a.E, a.V), 256));
+}
+// The row-tile table the persistent rows kernels of one call read.
+static void launch_rows_plan(const FfnArgs& a, void* ws, hipStream_t s) {
+  const int blocks = std::max(1, std::min(64, (max_row_tiles(a.A, a.V) + kGemmThreads - 1) / kGemmThreads));
+  hipLaunchKernelGGL(rows_plan_kernel, dim3(blocks), dim3(kGemmThreads), 0, s, a.voff, a.owner, a.V, rows_tab_ws(a, ws));
 }
 static void* wgrad_plan_ws(const FfnArgs& a, void* ws) {
   return (char*)ws + 2 * align_up((size_t)a.A * a.f * sizeof(bf16_t), 256) + 2 * wgrad_tail_bytes(a.A, a.d, a.f, a.V) +
@@ -118,24 +135,30 @@ static RowsDmaArgs rows_dma_args(const FfnArgs& a, const void* in, const void* w
 template <bool WT, int EPI, int ACT>
 static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w, const void* bias, int K, int NC,
                                 const void* hpre_in, void* out0, void* out1, hipStream_t s, const int32_t* gsrc, int gk,
-                                void* split_ws, const int32_t* scatter_rows) {
+                                void* split_ws, const int32_t* scatter_rows, const i32x4* row_tab) {
   const int col_tiles = (NC + BN - 1) / BN;
   const int row_tiles = max_row_tiles(a.A, a.V);
   const unsigned grid = patched_grid(row_tiles, col_tiles);
   if (K % 128 == 0) {
-    // K is a whole number of pipeline rounds: direct-to-LDS path
+    // K is a whole number of pipeline rounds: direct-to-LDS path, one persistent workgroup per compute unit
     RowsDmaArgs p = rows_dma_args(a, in, w, bias, K, NC, hpre_in, out0, out1, gsrc, gk);
     p.scatter_rows = scatter_rows;
+    const unsigned persist = std::min(grid, (unsigned)kComputeUnits);
     if (EPI == EPI_PLAIN && split_ws && rows_split_bytes(a.A, a.V, K, NC)) {
-      // the last, partly filled round of workgroups is cut along K: extra workgroups for the further
-      // segments behind the normal grid, then the sum of the partial tiles
+      // the last, partly filled round of tiles is cut along K, then the partial tiles are summed
       p.split_partial = (float*)split_ws;
       p.normal_grid = grid;
-      hipLaunchKernelGGL((rows_gemm_dma_bf16<WT, EPI, ACT>), dim3(grid + kSplitUnits), dim3(kGemmThreads), 0, s, p);
+      hipLaunchKernelGGL((rows_gemm_persist_bf16<WT, EPI, ACT, false>), dim3(persist), dim3(kGemmThreads), 0, s, p, row_tab);
       hipLaunchKernelGGL(rows_split_reduce_kernel, dim3(kSplitSlices, kSplitUnits / kSplitMax), dim3(kGemmThreads), 0, s, p);
       return hipGetLastError();
     }
-    hipLaunchKernelGGL((rows_gemm_dma_bf16<WT, EPI, ACT>), dim3(grid), dim3(kGemmThreads), 0, s, p);
+    if constexpr (!WT && EPI == EPI_FWD1) {
+      if (gsrc) {
+        hipLaunchKernelGGL((rows_gemm_persist_bf16<WT, EPI, ACT, true>), dim3(persist), dim3(kGemmThreads), 0, s, p, row_tab);
+        return hipGetLastError();
+      }
+    }
+    hipLaunchKernelGGL((rows_gemm_persist_bf16<WT, EPI, ACT, false>), dim3(persist), dim3(kGemmThreads), 0, s, p, row_tab);
     return hipGetLastError();
   }
   if (gsrc || scatter_rows) return hipErrorInvalidValue;   // gathered / scattered rows only on the direct-to-LDS path (host check upstream)
@@ -147,19 +170,20 @@ static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w,
 
 template <bool WT, int EPI>
 static hipError_t launch_rows(const FfnArgs& a, const void* in, const void* w, const void* bias, int K, int NC,
-                              const void* hpre_in, void* out0, void* out1, hipStream_t s,
+                              const void* hpre_in, void* out0, void* out1, void* ws, hipStream_t s,
                               const int32_t* gsrc = nullptr, int gk = 1, void* split_ws = nullptr,
                               const int32_t* scatter_rows = nullptr) {
+  const i32x4* tab = rows_tab_ws(a, ws);
   if (EPI == EPI_PLAIN)
     return launch_rows_t<WT, EPI, FLEXMOE_RELU>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, split_ws,
-                                                scatter_rows);
+                                                scatter_rows, tab);
   switch (a.act) {
     case FLEXMOE_RELU:
-      return launch_rows_t<WT, EPI, FLEXMOE_RELU>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, nullptr, nullptr);
+      return launch_rows_t<WT, EPI, FLEXMOE_RELU>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, nullptr, nullptr, tab);
     case FLEXMOE_GELU_ERF:
-      return launch_rows_t<WT, EPI, FLEXMOE_GELU_ERF>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, nullptr, nullptr);
+      return launch_rows_t<WT, EPI, FLEXMOE_GELU_ERF>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, nullptr, nullptr, tab);
     default:
-      return launch_rows_t<WT, EPI, FLEXMOE_GELU_TANH>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, nullptr, nullptr);
+      return launch_rows_t<WT, EPI, FLEXMOE_GELU_TANH>(a, in, w, bias, K, NC, hpre_in, out0, out1, s, gsrc, gk, nullptr, nullptr, tab);
   }
 }
 
@@ -203,10 +227,11 @@ static hipError_t launch_wgrad(const FfnArgs& a, const void* L, const void* R, i
 hipError_t launch_ffn_fwd_bf16(const FfnArgs& a, const void* xp, const void* w1, const void* b1, const void* w2,
                                const void* b2, void* hpre, void* yp, void* ws, hipStream_t s) {
   if (a.A == 0) return hipSuccess;
+  launch_rows_plan(a, ws, s);
   void* h = ws;
-  hipError_t err = launch_rows<false, EPI_FWD1>(a, xp, w1, b1, a.d, a.f, nullptr, hpre, h, s);
+  hipError_t err = launch_rows<false, EPI_FWD1>(a, xp, w1, b1, a.d, a.f, nullptr, hpre, h, ws, s);
   if (err != hipSuccess) return err;
-  return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, yp, nullptr, s, nullptr, 1, rows_split_ws(a, ws));
+  return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, yp, nullptr, ws, s, nullptr, 1, rows_split_ws(a, ws));
 }
 
 // Forward with the expert-wise layout transformation folded into GEMM1's row loads: bucket row p
@@ -215,10 +240,11 @@ hipError_t launch_ffn_fwd_gather_bf16(const FfnArgs& a, const void* x, const int
                                       const void* b1, const void* w2, const void* b2, void* hpre, void* yp, void* ws,
                                       hipStream_t s) {
   if (a.A == 0) return hipSuccess;
+  launch_rows_plan(a, ws, s);
   void* h = ws;
-  hipError_t err = launch_rows<false, EPI_FWD1>(a, x, w1, b1, a.d, a.f, nullptr, hpre, h, s, src, k);
+  hipError_t err = launch_rows<false, EPI_FWD1>(a, x, w1, b1, a.d, a.f, nullptr, hpre, h, ws, s, src, k);
   if (err != hipSuccess) return err;
-  return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, yp, nullptr, s, nullptr, 1, rows_split_ws(a, ws));
+  return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, yp, nullptr, ws, s, nullptr, 1, rows_split_ws(a, ws));
 }
 
 // The expert path of a top-1 layer without Xp and Yp: rows gathered through src on load (as above)
@@ -227,10 +253,11 @@ hipError_t launch_ffn_fwd_gather_bf16(const FfnArgs& a, const void* x, const int
 hipError_t launch_ffn_fwd_top1_bf16(const FfnArgs& a, const void* x, const int32_t* src, const void* w1, const void* b1,
                                     const void* w2, const void* b2, void* hpre, void* y, void* ws, hipStream_t s) {
   if (a.A == 0) return hipSuccess;
+  launch_rows_plan(a, ws, s);
   void* h = ws;
-  hipError_t err = launch_rows<false, EPI_FWD1>(a, x, w1, b1, a.d, a.f, nullptr, hpre, h, s, src, 1);
+  hipError_t err = launch_rows<false, EPI_FWD1>(a, x, w1, b1, a.d, a.f, nullptr, hpre, h, ws, s, src, 1);
   if (err != hipSuccess) return err;
-  return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, y, nullptr, s, nullptr, 1, rows_split_ws(a, ws), src);
+  return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, y, nullptr, ws, s, nullptr, 1, rows_split_ws(a, ws), src);
 }
 
 // scatter_src (top-1 layers, needs f % 128 == 0): bucket row p of dXp is stored as row scatter_src[p] of
@@ -243,8 +270,9 @@ hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp
   hipError_t err;
   launch_wgrad_plan(a, ws, s);
   if (a.A > 0) {
+    launch_rows_plan(a, ws, s);
     // dH = dYp . W2^T fused with act'(Hpre); W2_e is [f, d], contraction index d contiguous
-    err = launch_rows<true, EPI_DH>(a, dyp, w2, nullptr, a.d, a.f, hpre, dhpre, h, s);
+    err = launch_rows<true, EPI_DH>(a, dyp, w2, nullptr, a.d, a.f, hpre, dhpre, h, ws, s);
     if (err != hipSuccess) return err;
   }
   // dW2 = H^T . dYp, dW1 = Xp^T . dHpre: each with its own table and partial tiles
@@ -270,7 +298,7 @@ hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp
   }
   if (a.A > 0) {
     // dXp = dHpre . W1^T; W1_e is [d, f], contraction index f contiguous
-    err = launch_rows<true, EPI_PLAIN>(a, dhpre, w1, nullptr, a.f, a.d, nullptr, dxp, nullptr, s, nullptr, 1,
+    err = launch_rows<true, EPI_PLAIN>(a, dhpre, w1, nullptr, a.f, a.d, nullptr, dxp, nullptr, ws, s, nullptr, 1,
                                        rows_split_ws(a, ws), scatter_src);
     if (err != hipSuccess) return err;
   }

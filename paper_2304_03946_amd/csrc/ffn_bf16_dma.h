@@ -1,4 +1,4 @@
-// Direct-to-LDS pipeline (global_load_lds) and the rows kernels built on it, incl. the split last round.
+// Direct-to-LDS pipeline (global_load_lds), one output tile of a rows GEMM on it (used by the shared backward launch), the sum of the split last round.
 // Part of the bf16 expert-FFN kernels; included by ffn_bf16.hip only (one translation unit).
 #pragma once
 #include "common.h"
@@ -25,7 +25,8 @@ struct DmaSrc {
   uint32_t off[4];
   __device__ __forceinline__ void init(const bf16_t* b, size_t ld, int rows_valid) {
     base = b;
-    const int w = threadIdx.x >> 6, i = threadIdx.x & 63;
+    const int tid = opaque_tid();
+    const int w = tid >> 6, i = tid & 63;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int row = (w * 4 + q) * 16 + (i >> 2);
@@ -38,7 +39,8 @@ struct DmaSrc {
   __device__ __forceinline__ void init_gather(const bf16_t* b, size_t ld, const int32_t* __restrict__ rows, int k,
                                               int rows_valid) {
     base = b;
-    const int w = threadIdx.x >> 6, i = threadIdx.x & 63;
+    const int tid = opaque_tid();
+    const int w = tid >> 6, i = tid & 63;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int row = (w * 4 + q) * 16 + (i >> 2);
@@ -75,7 +77,8 @@ struct DmaSrcT {
   __device__ __forceinline__ void init(const bf16_t* b, size_t ld_, int cols_valid) {
     base = b;
     ld = ld_;
-    const int w = threadIdx.x >> 6, i = threadIdx.x & 63;
+    const int tid = opaque_tid();
+    const int w = tid >> 6, i = tid & 63;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int krow = (w * 4 + q) * 2 + (i >> 5);
@@ -163,10 +166,12 @@ __device__ __forceinline__ void dma_mma(f32x16 (&acc)[MB][NB], const DmaFrags& f
 // PRE: tile kt+3 exists (its second half is issued here).  POST: tile kt+4 exists.
 // NEXT: tile kt+1 exists; WAIT = how many younger tiles may still be in flight once this wave's
 // part of tile kt+1 has landed.
-template <bool TRA, bool TRB, bool PRE, bool POST, int WAIT, bool NEXT, typename Issue>
+// `issue` serves the first half of the step (PRE), `issue_post` the second (POST): the same object inside a
+// tile sequence, two different ones where the sequence of the workgroup's next output tile takes over.
+template <bool TRA, bool TRB, bool PRE, bool POST, int WAIT, bool NEXT, typename Issue, typename IssuePost>
 __device__ __forceinline__ void dma_step(lds_byte_t* prev, lds_byte_t* cur, const lds_byte_t* nxt,
-                                         f32x16 (&acc)[MB][NB], DmaFrags& f0, DmaFrags& f1, Issue& issue, int wm,
-                                         int wn) {
+                                         f32x16 (&acc)[MB][NB], DmaFrags& f0, DmaFrags& f1, Issue& issue,
+                                         IssuePost& issue_post, int wm, int wn) {
   dma_read_frags<TRA, TRB>(f1, cur, 1, wm, wn);
 #pragma unroll
   for (int i = 0; i < MB; ++i) {
@@ -184,7 +189,7 @@ __device__ __forceinline__ void dma_step(lds_byte_t* prev, lds_byte_t* cur, cons
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
   if (NEXT) dma_read_frags<TRA, TRB>(f0, nxt, 0, wm, wn);
-  if (POST) issue.begin();
+  if (POST) issue_post.begin();
 #pragma unroll
   for (int i = 0; i < MB; ++i) {
     __builtin_amdgcn_sched_barrier(0);
@@ -192,7 +197,7 @@ __device__ __forceinline__ void dma_step(lds_byte_t* prev, lds_byte_t* cur, cons
     for (int j = 0; j < NB; ++j)
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.b[j].v, f1.a[i].v, acc[i][j], 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
-    if (POST) issue.part(cur, i);
+    if (POST) issue_post.part(cur, i);
   }
 }
 
@@ -216,16 +221,69 @@ __device__ __forceinline__ void dma_pipeline(lds_byte_t* s0, lds_byte_t* s1, lds
   DmaFrags f0, f1;
   dma_read_frags<TRA, TRB>(f0, s0, 0, wm, wn);
   for (int kt = 0; kt < KT - 4; kt += 4) {
-    dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f0, f1, issue, wm, wn);
-    dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f0, f1, issue, wm, wn);
-    dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f0, f1, issue, wm, wn);
-    dma_step<TRA, TRB, true, true, 2, true>(s2, s3, s0, acc, f0, f1, issue, wm, wn);
+    dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f0, f1, issue, issue, wm, wn);
+    dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f0, f1, issue, issue, wm, wn);
+    dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f0, f1, issue, issue, wm, wn);
+    dma_step<TRA, TRB, true, true, 2, true>(s2, s3, s0, acc, f0, f1, issue, issue, wm, wn);
   }
-  dma_step<TRA, TRB, true, false, 2, true>(s3, s0, s1, acc, f0, f1, issue, wm, wn);
-  dma_step<TRA, TRB, false, false, 1, true>(s0, s1, s2, acc, f0, f1, issue, wm, wn);
-  dma_step<TRA, TRB, false, false, 0, true>(s1, s2, s3, acc, f0, f1, issue, wm, wn);
-  dma_step<TRA, TRB, false, false, 0, false>(s2, s3, s0, acc, f0, f1, issue, wm, wn);
+  dma_step<TRA, TRB, true, false, 2, true>(s3, s0, s1, acc, f0, f1, issue, issue, wm, wn);
+  dma_step<TRA, TRB, false, false, 1, true>(s0, s1, s2, acc, f0, f1, issue, issue, wm, wn);
+  dma_step<TRA, TRB, false, false, 0, true>(s1, s2, s3, acc, f0, f1, issue, issue, wm, wn);
+  dma_step<TRA, TRB, false, false, 0, false>(s2, s3, s0, acc, f0, f1, issue, issue, wm, wn);
   __syncthreads();                                     // all waves done with the last tile: LDS is free
+}
+
+// The K loop of a workgroup that goes on to another output tile afterwards (persistent kernels).
+// On entry K tiles 0, 1, 2 of `issue` have been issued into s0, s1, s2 (dma_prefetch3, or the previous
+// call of this function) and nothing of tile 3.  The last four steps, which have nothing left to fetch
+// for this output tile, issue K tiles 0, 1, 2 of `next`, the sequence of the workgroup's next output
+// tile, into the stages as they fall free: the pipeline never drains between output tiles, and stage s3
+// -- free for every wave once it is past the last step's barrier -- is where the epilogue puts its
+// patches.  There is one code path only (two, chosen by a branch, make the compiler shuffle the 256
+// accumulator registers where they join): a workgroup on its last tile passes a sequence whose loads
+// are valid but never used, and waits for them before it ends.  Global
+// stores of the previous epilogue may still be in flight on entry: they only make the hand-placed
+// wait counts conservative (a wait for "at most n operations in flight" covers every load that has n
+// younger loads, whatever else is in the queue).  after_barrier() runs once behind the first barrier,
+// when every wave has left the previous epilogue.
+template <typename Issue> __device__ __forceinline__ void dma_prefetch3(lds_byte_t* s0, lds_byte_t* s1, lds_byte_t* s2, Issue& issue) {
+  lds_byte_t* const stages[3] = {s0, s1, s2};
+#pragma unroll
+  for (int t = 0; t < 3; ++t) {
+    issue.begin();
+#pragma unroll
+    for (int q = 0; q < 8; ++q) issue.part(stages[t], q);
+    issue.end();
+  }
+}
+// make_next(next) builds the next tile's sequence; it is called behind the steady-state loop, so that the
+// sequence's registers are not live across it (spilled registers come back through the same in-order
+// queue as the operand tiles: every reload inside the K loop would wait for all tiles in flight).
+template <bool TRA, bool TRB, typename Issue, typename After, typename MakeNext>
+__device__ __forceinline__ void dma_pipeline_cont(lds_byte_t* s0, lds_byte_t* s1, lds_byte_t* s2, lds_byte_t* s3,
+                                                  f32x16 (&acc)[MB][NB], Issue& issue, int KT, Issue& next, int wm,
+                                                  int wn, After after_barrier, MakeNext make_next) {
+  __builtin_amdgcn_s_waitcnt(0x4F70);                  // vmcnt(16): tile 0 has landed
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  issue.begin();
+#pragma unroll
+  for (int q = 0; q < 4; ++q) issue.part(s3, q);       // tile 3: first half
+  after_barrier();
+  DmaFrags f0, f1;
+  dma_read_frags<TRA, TRB>(f0, s0, 0, wm, wn);
+  for (int kt = 0; kt < KT - 4; kt += 4) {
+    dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f0, f1, issue, issue, wm, wn);
+    dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f0, f1, issue, issue, wm, wn);
+    dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f0, f1, issue, issue, wm, wn);
+    dma_step<TRA, TRB, true, true, 2, true>(s2, s3, s0, acc, f0, f1, issue, issue, wm, wn);
+  }
+  make_next(next);
+  dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f0, f1, issue, next, wm, wn);
+  dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f0, f1, next, next, wm, wn);
+  dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f0, f1, next, next, wm, wn);
+  dma_step<TRA, TRB, true, false, 0, false>(s2, s3, s0, acc, f0, f1, next, next, wm, wn);
 }
 
 // Tile sequence of the rows kernels: K tile t of both operands starts at contraction index 32 t.
@@ -266,14 +324,14 @@ __device__ __forceinline__ void rows_dma_body(lds_byte_t* s0, lds_byte_t* s1, ld
     float* patch = (float*)s0 + wave * (32 * 64);
     float* patch_alt = (float*)s1 + wave * (32 * 64);
     epilogue_rounds<false>(
-        patch, patch_alt, acc, [](int, int) { return make_uint2(0, 0); },
-        [](int, int, float4 c, uint2) {
+        patch, patch_alt, acc, [](const EpiIdx&) { return make_uint2(0, 0); },
+        [](const EpiIdx&, float4 c, uint2) {
           return EpiOut{make_uint2(__float_as_uint(c.x), __float_as_uint(c.y)),
                         make_uint2(__float_as_uint(c.z), __float_as_uint(c.w))};
         },
-        [&](int row_w, int col_w, const EpiOut& o) {
-          const int lrow = (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31);
-          *(uint4*)(out + lrow * BN + wn * (NB * 32) + col_w) = make_uint4(o.a.x, o.a.y, o.b.x, o.b.y);
+        [&](const EpiIdx& x, const EpiOut& o) {
+          const int lrow = (wm + 2 * x.i) * 32 + (x.row_w & 31);
+          *(uint4*)(out + lrow * BN + wn * (NB * 32) + x.col_w) = make_uint4(o.a.x, o.a.y, o.b.x, o.b.y);
         });
     return;
   }
@@ -291,7 +349,7 @@ __device__ __forceinline__ void rows_dma_body(lds_byte_t* s0, lds_byte_t* s1, ld
                                                           out1, lut, smap);
 }
 
-// Arguments of one rows GEMM (device pointers; see rows_gemm_dma_bf16).
+// Arguments of one rows GEMM (device pointers; see rows_gemm_persist_bf16 and bwd_tail_dma_bf16).
 struct RowsDmaArgs {
   const bf16_t* in;
   const bf16_t* w;
@@ -348,18 +406,6 @@ __device__ __forceinline__ void rows_dma_block(const RowsDmaArgs& p, unsigned bl
     rows_dma_body<false, DmaSrcT, EPI, ACT>(s0, s1, s2, s3, t, p.in, w_src, p.bias, p.K, p.NC, p.hpre_in, p.out0,
                                             p.out1, lut, p.gsrc, p.gk, p.split_partial, p.scatter_rows);
   }
-}
-
-template <bool WT, int EPI, int ACT>
-__global__ __launch_bounds__(kGemmThreads) void rows_gemm_dma_bf16(const RowsDmaArgs p) {
-  __shared__ __align__(1024) unsigned char stage0[kDmaStageBytes];
-  __shared__ __align__(1024) unsigned char stage1[kDmaStageBytes];
-  __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
-  __shared__ __align__(1024) unsigned char stage3[kDmaStageBytes];
-  __shared__ __align__(1024) unsigned char lut_lds[epilogue_uses_lut<EPI, ACT>() ? kLutBytes : 16];
-  __shared__ int s_tile[8];
-  rows_dma_block<WT, EPI, ACT>(p, blockIdx.x, (lds_byte_t*)stage0, (lds_byte_t*)stage1, (lds_byte_t*)stage2,
-                               (lds_byte_t*)stage3, lut_lds, s_tile);
 }
 
 // Sum of the K segments of the split tail tiles (see lookup_row_tile): out = bf16(sum over

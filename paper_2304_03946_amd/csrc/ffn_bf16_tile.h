@@ -12,9 +12,23 @@ constexpr int kTileElems = BM * BK;                 // one operand tile in LDS (
 constexpr size_t kGemmLds = 2 * 2 * kTileElems * sizeof(bf16_t);   // 2 stages x (A + B) = 128 KB
 
 enum { EPI_FWD1 = 0, EPI_PLAIN = 1, EPI_DH = 2 };
+#ifndef FLEXMOE_EPI_AHEAD
+#define FLEXMOE_EPI_AHEAD 2      // rounds between the request and the use of an epilogue side input
+#endif
 #ifndef FLEXMOE_DMA_CPOL
 #define FLEXMOE_DMA_CPOL ""      // cache-policy modifiers of the direct-to-LDS loads
 #endif
+
+// threadIdx.x behind a compiler barrier: what is derived from it is computed where it is used.  The
+// persistent kernels use it for per-lane constants of code that runs once per output tile (operand
+// offsets, epilogue addressing): taken from threadIdx.x directly they are loop invariants, which the
+// compiler computes once, keeps across the K loop and, out of registers there, spills -- and a spilled
+// register comes back through the queue the operand tiles are in flight in.
+__device__ __forceinline__ int opaque_tid() {
+  int t = threadIdx.x;
+  asm volatile("" : "+v"(t));
+  return t;
+}
 
 union Frag8 {
   uint4 u;
@@ -234,14 +248,21 @@ template <int EPI, int ACT> constexpr bool epilogue_uses_lut() { return EPI != E
 // 64 consecutive columns of one row -> per-element epilogue in fp32 -> bf16 -> 8-byte stores that
 // fill whole 128-byte lines.  The K loop ends with a barrier, so the LDS tiles are free.
 // Per round, all eight 4-element pieces are first computed (compute(row in the wave's block
-// (0..127), column in the wave's block (multiple of 4), float4 accumulators, uint2 side input)
-// -> EpiOut, unconditional: straight-line code the scheduler can interleave) and then stored
-// (store(row, col, EpiOut), where the ragged-edge predicates live).
+// (0..127), column in the wave's block (multiple of 4), which 64-column half of the block that is,
+// float4 accumulators, uint2 side input) -> EpiOut, unconditional: straight-line code the scheduler
+// can interleave) and then stored (store(row, col, EpiOut), where the ragged-edge predicates live).
 // fetch(row, col) -> uint2: an optional per-element side input (the saved pre-activations of the
-// backward epilogue); the fetches of round n+1 are issued before round n is processed so that
-// their latency hides behind it.
+// backward epilogue).
 struct EpiOut {
   uint2 a, b;
+};
+// Which 4-element piece a callback of epilogue_rounds is asked about: 32-row block i (0..MB-1) and 64-column
+// half jh of the wave's 128 x 128 block, piece it (0..7) of the round -- compile-time constants once the
+// loops are unrolled -- and the same as lane-dependent coordinates inside the wave's block:
+// row_w = 32 i + 4 it + (lane / 16), col_w = 64 jh + 4 (lane % 16).
+struct EpiIdx {
+  int i, jh, it;
+  int row_w, col_w;
 };
 // 8-byte store with the non-temporal hint.  Used for the large outputs of the epilogues that carry an
 // activation (Hpre and H of the forward, dHpre and H of the backward) and for the weight gradients:
@@ -249,7 +270,7 @@ struct EpiOut {
 // Infinity Cache (measured: -4.5 % on the BERT-like layer's step, -2.4 % on the GPT-medium-like one,
 // -1 % on the GPT-XL-like one).  The plain epilogue's output (Yp, dXp) keeps the default policy: the
 // combine kernel reads it straight away, and streaming it out costs there what it gains here.
-__device__ __forceinline__ void store_nt8(bf16_t* p, uint2 v) {
+__device__ __forceinline__ void store_nt8(void* p, uint2 v) {
   typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
   u32x2_t v2;
   v2[0] = v.x;
@@ -259,18 +280,30 @@ __device__ __forceinline__ void store_nt8(bf16_t* p, uint2 v) {
 template <bool FETCH, typename Fetch, typename Compute, typename Store>
 __device__ __forceinline__ void epilogue_rounds(float* patch0, float* patch1, const f32x16 (&acc)[MB][NB], Fetch fetch,
                                                 Compute compute, Store store) {
-  const int lane = threadIdx.x & 63;
+  const int lane = opaque_tid() & 63;
   const int r = lane & 31, h = lane >> 5;
   const int rsub = lane >> 4, c = lane & 15;
   constexpr int kRounds = MB * (NB / 2);
-  uint2 side[2][8];
+  auto idx_of = [&](int round, int it) {
+    const int i = round / (NB / 2), jh = round % (NB / 2);
+    return EpiIdx{i, jh, it, i * 32 + it * 4 + rsub, jh * 64 + c * 4};
+  };
+  // Side inputs are requested kAhead rounds before they are used.  Loads and stores of a wave complete
+  // in issue order: a load issued behind a round's stores only returns once those stores are
+  // acknowledged, so a request made one round ahead puts a store round trip into every round.
+  constexpr int kAhead = FLEXMOE_EPI_AHEAD;
+  uint2 side[FETCH ? kAhead + 1 : 1][8];
+  auto fetch_round = [&](int round) {
+#pragma unroll
+    for (int it = 0; it < 8; ++it) side[round % (kAhead + 1)][it] = fetch(idx_of(round, it));
+  };
   if (FETCH) {
 #pragma unroll
-    for (int it = 0; it < 8; ++it) side[0][it] = fetch(it * 4 + rsub, c * 4);
+    for (int round = 0; round < kAhead; ++round) fetch_round(round);
   }
-  // Two patches per wave: round n+1's accumulators are written while round n is processed.  A
-  // wave's LDS instructions execute in issue order, so the reads that follow the writes need no
-  // wait, only a compiler barrier (the dependence runs across lanes, which the compiler cannot see).
+  // Two patches per wave (or one, used twice): round n+1's accumulators are written while round n is
+  // processed.  A wave's LDS instructions execute in issue order, so the reads that follow the writes
+  // need no wait, only a compiler barrier (the dependence runs across lanes, which the compiler cannot see).
   auto write_round = [&](int i, int jh, float* patch) {
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj)
@@ -283,35 +316,49 @@ __device__ __forceinline__ void epilogue_rounds(float* patch0, float* patch1, co
   };
   write_round(0, 0, patch0);
 #pragma unroll
-  for (int i = 0; i < MB; ++i) {
+  for (int round = 0; round < kRounds; ++round) {
+    float* patch = (round & 1) ? patch1 : patch0;
+    if (FETCH && round + kAhead < kRounds) fetch_round(round + kAhead);
+    asm volatile("" ::: "memory");
+    float4 v[8];
 #pragma unroll
-    for (int jh = 0; jh < NB / 2; ++jh) {
-      const int round = i * (NB / 2) + jh;
-      float* patch = (round & 1) ? patch1 : patch0;
-      if (FETCH && round + 1 < kRounds) {
-        const int ni = (round + 1) / (NB / 2), njh = (round + 1) % (NB / 2);
-#pragma unroll
-        for (int it = 0; it < 8; ++it) side[(round + 1) & 1][it] = fetch(ni * 32 + it * 4 + rsub, njh * 64 + c * 4);
-      }
-      asm volatile("" ::: "memory");
-      float4 v[8];
-#pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int row = it * 4 + rsub;
-        v[it] = *(const float4*)(patch + row * 64 + ((c ^ (row & 15)) << 2));
-      }
-      asm volatile("" ::: "memory");
-      if (round + 1 < kRounds) write_round((round + 1) / (NB / 2), (round + 1) % (NB / 2), (round & 1) ? patch0 : patch1);
-      asm volatile("" ::: "memory");
-      EpiOut o[8];
-#pragma unroll
-      for (int it = 0; it < 8; ++it)
-        o[it] = compute(i * 32 + it * 4 + rsub, jh * 64 + c * 4, v[it], FETCH ? side[round & 1][it] : make_uint2(0, 0));
-#pragma unroll
-      for (int it = 0; it < 8; ++it) store(i * 32 + it * 4 + rsub, jh * 64 + c * 4, o[it]);
+    for (int it = 0; it < 8; ++it) {
+      const int row = it * 4 + rsub;
+      v[it] = *(const float4*)(patch + row * 64 + ((c ^ (row & 15)) << 2));
     }
+    asm volatile("" ::: "memory");
+    if (round + 1 < kRounds) write_round((round + 1) / (NB / 2), (round + 1) % (NB / 2), (round & 1) ? patch0 : patch1);
+    asm volatile("" ::: "memory");
+    EpiOut o[8];
+#pragma unroll
+    for (int it = 0; it < 8; ++it)
+      o[it] = compute(idx_of(round, it), v[it], FETCH ? side[round % (kAhead + 1)][it] : make_uint2(0, 0));
+#pragma unroll
+    for (int it = 0; it < 8; ++it) store(idx_of(round, it), o[it]);
   }
 }
+
+// Addresses of the pieces of epilogue_rounds inside an output (or side input) tile whose rows are ld
+// elements of ELEM bytes apart: piece (i, jh, it) is at [uniform: first element of 32-row block i,
+// 64-column half jh of the wave's block] + [per lane, per it: byte offset of tile row wm*32 + 4 it +
+// lane/16, column 4 (lane%16)].  The eight lane offsets are computed once per tile and the uniform part
+// lives in scalar registers, so a store or load costs no address arithmetic.
+template <int ELEM> struct EpiAddr {
+  uint32_t vb[8];
+  int ld;
+  __device__ __forceinline__ void init(int wm, int ld_) {
+    ld = ld_;
+    const int lane = opaque_tid() & 63;
+    const int rsub = lane >> 4, c = lane & 15;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) vb[it] = (uint32_t)(((wm * 32 + it * 4 + rsub) * ld + c * 4) * ELEM);
+  }
+  // block_base: the wave's block of the tile (tile row 0, the wave's first column)
+  template <typename T> __device__ __forceinline__ T* at(T* block_base, const EpiIdx& x) const {
+    T* round_base = block_base + (size_t)(x.i * 64) * ld + x.jh * 64;
+    return (T*)((char*)round_base + vb[x.it]);
+  }
+};
 
 // One K tile of the software pipeline.  On entry LDS stage `cur` holds tile t and the registers
 // ra/rb hold tile t+1 (loaded during the previous step).  The tile is multiplied in four k
@@ -401,7 +448,9 @@ __device__ __forceinline__ void rows_mainloop(bf16_t* smem, f32x16 (&acc)[MB][NB
 // Epilogue of the rows kernels: bias, then plain store / pre-activation + activation / dH*act' + H.
 // LUT: the activation comes from the LDS copy `lut` of the activation table ({r, q} pairs, see
 // above); otherwise it is evaluated arithmetically.
-template <int EPI, int ACT, bool LUT, bool BIAS>
+// FULL: all 256 rows of the tile and all 128 columns of the wave's block exist (no store predicates).
+// SCATTER (plain epilogue): tile row r is stored as row smap[r] of out0.
+template <int EPI, int ACT, bool LUT, bool BIAS, bool FULL, bool SCATTER>
 __device__ __forceinline__ void rows_epilogue_t(float* lds, float* lds_alt, const f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ bias,
                                                 int NC, int row0, int rows_valid, int e, int n0,
                                                 const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
@@ -412,26 +461,34 @@ __device__ __forceinline__ void rows_epilogue_t(float* lds, float* lds_alt, cons
   float* patch = lds + wave * (32 * 64);
   float* patch_alt = lds_alt + wave * (32 * 64);
   const int col_base = n0 + wn * (NB * 32);
-  // tile-relative 32-bit offsets on top of uniform per-tile base pointers (scalar base + vector
-  // offset addressing instead of 64-bit vector address arithmetic per store)
+  // uniform per-tile base pointers (scalar registers) + per-lane 32-bit offsets
   const size_t tile_base = (size_t)row0 * NC + col_base;
   const bf16_t* hpre_t = hpre_in + tile_base;
   bf16_t* out0_t = out0 + tile_base;
   bf16_t* out1_t = out1 + tile_base;
   const bf16_t* bias_t = bias + (size_t)e * NC + col_base;
   const int cols_left = NC - col_base;
-  auto tile_row = [&](int row_w) { return (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31); };
-  auto fetch = [&](int row_w, int col_w) -> uint2 {
-    const int lrow = tile_row(row_w);
-    if (lrow < rows_valid && col_w < cols_left) return *(const uint2*)(hpre_t + (uint32_t)(lrow * NC + col_w));
+  EpiAddr<2> addr;
+  addr.init(wm, NC);
+  auto valid = [&](const EpiIdx& x) {
+    return FULL || ((wm + 2 * x.i) * 32 + (x.row_w & 31) < rows_valid && x.col_w < cols_left);
+  };
+  auto fetch = [&](const EpiIdx& x) -> uint2 {
+    if (valid(x)) return *(const uint2*)addr.at(hpre_t, x);
     return make_uint2(0, 0);
   };
-  auto compute = [&](int row_w, int col_w, float4 c, uint2 pre_in) -> EpiOut {
+  // the lane's bias values (two 64-column halves of the wave's block), read before any store is
+  // issued: a load behind stores returns only once they are acknowledged
+  float bvals[NB / 2][4];
+  if (BIAS) {
+    const int c4 = (opaque_tid() & 15) * 4;
+#pragma unroll
+    for (int jh = 0; jh < NB / 2; ++jh) unpack4(*(const uint2*)(bias_t + min(jh * 64 + c4, cols_left - 4)), bvals[jh]);
+  }
+  auto compute = [&](const EpiIdx& x, float4 c, uint2 pre_in) -> EpiOut {
     EpiOut o;
     if (BIAS) {
-      float b[4];
-      unpack4(*(const uint2*)(bias_t + min(col_w, cols_left - 4)), b);
-      c.x += b[0]; c.y += b[1]; c.z += b[2]; c.w += b[3];
+      c.x += bvals[x.jh][0]; c.y += bvals[x.jh][1]; c.z += bvals[x.jh][2]; c.w += bvals[x.jh][3];
     }
     if (EPI == EPI_PLAIN) {
       o.a = pack4(c.x, c.y, c.z, c.w);
@@ -457,18 +514,18 @@ __device__ __forceinline__ void rows_epilogue_t(float* lds, float* lds_alt, cons
     }
     return o;
   };
-  auto store = [&](int row_w, int col_w, const EpiOut& o) {
-    const int lrow = tile_row(row_w);
-    if (lrow < rows_valid && col_w < cols_left) {
-      const uint32_t off = (uint32_t)(lrow * NC + col_w);
-      if (EPI == EPI_PLAIN && smap) {
+  const bool store0 = EPI != EPI_FWD1 || out0 != nullptr;      // forward: the pre-activations are optional
+  auto store = [&](const EpiIdx& x, const EpiOut& o) {
+    if (valid(x)) {
+      if (SCATTER) {
         // scattered store: tile row lrow is row smap[lrow] of the output (reverse routing of a top-1 layer)
-        *(uint2*)(out0 + (size_t)smap[lrow] * NC + col_base + col_w) = o.a;
-      } else if (EPI != EPI_FWD1 || out0) {     // forward: the pre-activations are optional
-        if (EPI == EPI_PLAIN) *(uint2*)(out0_t + off) = o.a;
-        else store_nt8(out0_t + off, o.a);
+        const int lrow = (wm + 2 * x.i) * 32 + (x.row_w & 31);
+        *(uint2*)(out0 + (size_t)smap[lrow] * NC + col_base + x.col_w) = o.a;
+      } else if (store0) {
+        if (EPI == EPI_PLAIN) *(uint2*)addr.at(out0_t, x) = o.a;
+        else store_nt8(addr.at(out0_t, x), o.a);
       }
-      if (EPI != EPI_PLAIN) store_nt8(out1_t + off, o.b);
+      if (EPI != EPI_PLAIN) store_nt8(addr.at(out1_t, x), o.b);
     }
   };
   epilogue_rounds<EPI == EPI_DH>(patch, patch_alt, acc, fetch, compute, store);
@@ -480,8 +537,22 @@ __device__ __forceinline__ void rows_epilogue(float* lds, float* lds_alt, const 
                                               const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
                                               bf16_t* __restrict__ out1, const lds_byte_t* lut = nullptr,
                                               const lds_int_t* smap = nullptr) {
-  if (bias) rows_epilogue_t<EPI, ACT, LUT, true>(lds, lds_alt, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1, lut, smap);
-  else rows_epilogue_t<EPI, ACT, LUT, false>(lds, lds_alt, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1, lut, smap);
+  // the common case -- a whole tile, stored in place -- runs without store predicates
+  const int wn = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) & 1;
+  const bool full = rows_valid == BM && NC - n0 - wn * (NB * 32) >= NB * 32;
+#define FLEXMOE_EPI_CALL(BIAS, FULL, SCATTER) \
+  rows_epilogue_t<EPI, ACT, LUT, BIAS, FULL, SCATTER>(lds, lds_alt, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1, lut, smap)
+  if (EPI == EPI_PLAIN && smap) {
+    if (bias) FLEXMOE_EPI_CALL(true, false, true);
+    else FLEXMOE_EPI_CALL(false, false, true);
+  } else if (full) {
+    if (bias) FLEXMOE_EPI_CALL(true, true, false);
+    else FLEXMOE_EPI_CALL(false, true, false);
+  } else {
+    if (bias) FLEXMOE_EPI_CALL(true, false, false);
+    else FLEXMOE_EPI_CALL(false, false, false);
+  }
+#undef FLEXMOE_EPI_CALL
 }
 
 // One output tile of rows_gemm: main loop and epilogue.  FULL = all eight 32-row blocks hold rows.

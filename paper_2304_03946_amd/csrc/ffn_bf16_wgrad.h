@@ -313,32 +313,38 @@ __device__ __forceinline__ void wgrad_dma_block(const WgradDmaArgs& p, unsigned 
   float* patch = (float*)stage0 + wave * (32 * 64);
   float* patch_alt = (float*)stage1 + wave * (32 * 64);
   const int col_base = n0 + wn * (NB * 32);
-  auto tile_row = [&](int row_w) { return (wm + 2 * (row_w >> 5)) * 32 + (row_w & 31); };
+  // whole tiles (every benchmark shape: M and NC are multiples of 256) are stored without predicates
+  const bool full = mvalid == BM && nvalid == BN;
+  auto valid = [&](const EpiIdx& x) { return (wm + 2 * x.i) * 32 + (x.row_w & 31) < mvalid && col_base + x.col_w < NC; };
+  auto none = [](const EpiIdx&) { return make_uint2(0, 0); };
   if (job.nseg == 1) {
-    bf16_t* out = dw + (size_t)job.e * M * NC;
-    epilogue_rounds<false>(
-        patch, patch_alt, acc, [](int, int) { return make_uint2(0, 0); },
-        [](int, int, float4 c, uint2) { return EpiOut{pack4(c.x, c.y, c.z, c.w), make_uint2(0, 0)}; },
-        [&](int row_w, int col_w, const EpiOut& o) {
-          const int lrow = tile_row(row_w);
-          const int col = col_base + col_w;
-          if (lrow < mvalid && col < NC) store_nt8(out + (size_t)(m0 + lrow) * NC + col, o.a);   // written once
-        });
+    bf16_t* out = dw + (size_t)job.e * M * NC + (size_t)m0 * NC + col_base;      // the wave's block of the tile
+    EpiAddr<2> addr;
+    addr.init(wm, NC);
+    auto to_bf16 = [](const EpiIdx&, float4 c, uint2) { return EpiOut{pack4(c.x, c.y, c.z, c.w), make_uint2(0, 0)}; };
+    if (full)
+      epilogue_rounds<false>(patch, patch_alt, acc, none, to_bf16,
+                             [&](const EpiIdx& x, const EpiOut& o) { store_nt8(addr.at(out, x), o.a); });   // written once
+    else
+      epilogue_rounds<false>(patch, patch_alt, acc, none, to_bf16, [&](const EpiIdx& x, const EpiOut& o) {
+        if (valid(x)) store_nt8(addr.at(out, x), o.a);
+      });
   } else {
     // one of several segments: the fp32 tile goes to the workspace for wgrad_reduce_kernel
-    float* out = partial + (size_t)(job.slot + job.seg) * M * NC;
-    epilogue_rounds<false>(
-        patch, patch_alt, acc, [](int, int) { return make_uint2(0, 0); },
-        [](int, int, float4 c, uint2) {
-          return EpiOut{make_uint2(__float_as_uint(c.x), __float_as_uint(c.y)),
-                        make_uint2(__float_as_uint(c.z), __float_as_uint(c.w))};
-        },
-        [&](int row_w, int col_w, const EpiOut& o) {
-          const int lrow = tile_row(row_w);
-          const int col = col_base + col_w;
-          if (lrow < mvalid && col < NC)
-            *(uint4*)(out + (size_t)(m0 + lrow) * NC + col) = make_uint4(o.a.x, o.a.y, o.b.x, o.b.y);
-        });
+    float* out = partial + (size_t)(job.slot + job.seg) * M * NC + (size_t)m0 * NC + col_base;
+    EpiAddr<4> addr;
+    addr.init(wm, NC);
+    auto as_f32 = [](const EpiIdx&, float4 c, uint2) {
+      return EpiOut{make_uint2(__float_as_uint(c.x), __float_as_uint(c.y)), make_uint2(__float_as_uint(c.z), __float_as_uint(c.w))};
+    };
+    if (full)
+      epilogue_rounds<false>(patch, patch_alt, acc, none, as_f32, [&](const EpiIdx& x, const EpiOut& o) {
+        *(uint4*)addr.at(out, x) = make_uint4(o.a.x, o.a.y, o.b.x, o.b.y);
+      });
+    else
+      epilogue_rounds<false>(patch, patch_alt, acc, none, as_f32, [&](const EpiIdx& x, const EpiOut& o) {
+        if (valid(x)) *(uint4*)addr.at(out, x) = make_uint4(o.a.x, o.a.y, o.b.x, o.b.y);
+      });
   }
 }
 
