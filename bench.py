@@ -77,6 +77,8 @@ def stage_work(cfg):
 
 
 class Runner:
+    keep_h = True      # training layers: the forward pass keeps act(Hpre) for the backward pass (--recompute-h turns it off)
+
     def __init__(self, name, seed=None, fused=False):
         import torch
         from paper_2304_03946_amd import binding, layer, workloads as W
@@ -88,7 +90,7 @@ class Runner:
         up = layer.to_device
         self.x, self.w1, self.w2, self.dy = up(inp.x), up(inp.w1), up(inp.w2), up(inp.dy)
         self.wg_by_drift = {0: up(inp.wg)}
-        self.L = layer.MoELayer.for_config(cfg)
+        self.L = layer.MoELayer(cfg.N, cfg.d, cfg.f, cfg.E, cfg.k, cfg.V, cfg.dtype, cfg.act, cfg.backward, keep_h=Runner.keep_h)
         self.iter = 0
         self.drifting = name == "gpt_xl"
         # without a backward pass nothing reads Xp again: fold the permutation into the expert GEMM
@@ -135,14 +137,14 @@ class Runner:
             B.flexmoe_permute(self.x, L.src, None, cfg.k, L.xp); rec("permute")
             e0 = self._event(ffn_events)
             B.flexmoe_expert_ffn_fwd(L.xp, L.vexpert_off, L.vexpert_owner, self.w1, None, self.w2, None, cfg.act,
-                                     L.hpre, L.yp, L.ws); rec("ffn_fwd")
+                                     L.hpre, L.yp, L.ws, h=L.h); rec("ffn_fwd")      # training layers keep act(Hpre) for the backward pass
             self._event(ffn_events, e0, "fwd")
         B.flexmoe_combine(L.yp, L.dest, L.topk_w, cfg.k, L.y); rec("combine")
         if cfg.backward:
             B.flexmoe_permute(self.dy, L.src, L.topk_w, cfg.k, L.dyp); rec("bwd_permute")
             e0 = self._event(ffn_events)
             B.flexmoe_expert_ffn_bwd(L.dyp, L.xp, L.hpre, self.w1, self.w2, L.vexpert_off, L.vexpert_owner, cfg.act,
-                                     L.dxp, L.dw1, L.dw2, L.ws); rec("ffn_bwd")
+                                     L.dxp, L.dw1, L.dw2, L.ws, h=L.h); rec("ffn_bwd")
             self._event(ffn_events, e0, "bwd")
             B.flexmoe_combine(L.dxp, L.dest, None, cfg.k, L.dx); rec("bwd_combine")
         self.iter += 1
@@ -483,6 +485,9 @@ def main():
                          "pre-activations): profiles then hold the step's own launches only")
     ap.add_argument("--no-stages", action="store_true", help="skip the per-stage breakdown pass (profiled runs: the "
                     "kernel trace then holds warm-up + timed steps only)")
+    ap.add_argument("--recompute-h", action="store_true",
+                    help="training layers: do not keep act(Hpre) from the forward pass; the backward pass computes and "
+                         "stores it again (saves A*f elements of activation memory per layer, costs time)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device copy (calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -498,6 +503,7 @@ def main():
     steps = args.steps if args.steps is not None else (30 if big else 200)
     warmup = args.warmup if args.warmup is not None else (3 if big else 20)
 
+    Runner.keep_h = not args.recompute_h
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)

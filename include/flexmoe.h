@@ -110,12 +110,16 @@ int flexmoe_permute(const void* x, const int32_t* src, const float* row_scale,
  *   -> hpre [A,f] dtype (pre-activation, kept for the backward pass), yp [A,d] dtype.
  *   hpre may be NULL when no backward pass follows (inference): the pre-activations are then not
  *   stored, which halves what the first product writes; yp is the same, bit for bit.
+ *   h [A,f] dtype or NULL: where act(hpre), the second product's operand, is written.  NULL keeps it in
+ *   the workspace (gone after the call).  A caller that hands the same buffer to the backward pass saves
+ *   that pass computing and storing it again (the backward's first kernel then writes one [A,f] tensor
+ *   instead of two); the price is A*f more elements of saved activations per layer.  Same bits either way.
  * The activation is applied to hpre as stored (i.e. after rounding to dtype).
  */
 int flexmoe_expert_ffn_fwd(const void* xp, const int32_t* vexpert_off, const int32_t* vexpert_owner,
                            const void* w1, const void* b1, const void* w2, const void* b2,
                            int A, int d, int f, int E, int V, int act, int dtype,
-                           void* hpre, void* yp, void* ws, size_t ws_bytes, void* stream);
+                           void* hpre, void* h, void* yp, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Expert FFN backward (the backward half of T_C, Eq. 7) for upstream gradient dyp [A,d]:
@@ -125,8 +129,10 @@ int flexmoe_expert_ffn_fwd(const void* xp, const int32_t* vexpert_off, const int
  * The sum over an expert's vExperts is the on-chip image of the replica gradient
  * synchronisation (T_Sync, Eq. 9); it runs in ascending vExpert id with fp32 accumulation.
  * dw1/dw2 are overwritten (not accumulated); experts without tokens get zeros.
+ *   h [A,f] dtype or NULL: act(hpre) as a forward call left it in its `h` argument.  NULL: it is computed
+ *   again from hpre (into the workspace).  Same results, bit for bit.
  */
-int flexmoe_expert_ffn_bwd(const void* dyp, const void* xp, const void* hpre,
+int flexmoe_expert_ffn_bwd(const void* dyp, const void* xp, const void* hpre, const void* h,
                            const void* w1, const void* w2,
                            const int32_t* vexpert_off, const int32_t* vexpert_owner,
                            int A, int d, int f, int E, int V, int act, int dtype,
@@ -137,10 +143,10 @@ int flexmoe_expert_ffn_bwd(const void* dyp, const void* xp, const void* hpre,
  * row p of dXp is stored as row src[p] of dx, i.e. dx [N,d] is the expert-path gradient of the layer
  * input and flexmoe_combine(dxp, dest, NULL) is not needed (same bits).  dw1, dw2 as in
  * flexmoe_expert_ffn_bwd; the workspace afterwards serves flexmoe_expert_bias_grads in the same way.
- *   src [N] as written by flexmoe_route with k = 1.
+ *   src [N] as written by flexmoe_route with k = 1; h as in flexmoe_expert_ffn_bwd.
  * FLEXMOE_UNSUPPORTED unless dtype is bf16 and f is a multiple of 128.
  */
-int flexmoe_expert_ffn_bwd_top1(const void* dyp, const void* xp, const void* hpre,
+int flexmoe_expert_ffn_bwd_top1(const void* dyp, const void* xp, const void* hpre, const void* h,
                                 const void* w1, const void* w2,
                                 const int32_t* vexpert_off, const int32_t* vexpert_owner, const int32_t* src,
                                 int N, int d, int f, int E, int V, int act, int dtype,
@@ -160,7 +166,7 @@ int flexmoe_combine(const void* yp, const int32_t* dest, const float* topk_w,
  * first product is read as row src[p] / k of x while the tile is loaded (Section 4's layout
  * transformation folded into the expert computation).  Same results as the two calls, bit for bit.
  *   x [N,d], src [A] (A = N*k) as written by flexmoe_route; everything else as in
- *   flexmoe_expert_ffn_fwd (hpre may be NULL as well).  For forward-only use: the backward pass reads xp.
+ *   flexmoe_expert_ffn_fwd (hpre and h may be NULL as well).  For forward-only use: the backward pass reads xp.
  * FLEXMOE_UNSUPPORTED unless dtype is bf16, d is a multiple of 128 and N*d < 2^32: callers then
  * use the two separate calls.
  */
@@ -168,7 +174,7 @@ int flexmoe_expert_ffn_fwd_gather(const void* x, const int32_t* src, const int32
                                   const int32_t* vexpert_owner, const void* w1, const void* b1,
                                   const void* w2, const void* b2,
                                   int N, int k, int d, int f, int E, int V, int act, int dtype,
-                                  void* hpre, void* yp, void* ws, size_t ws_bytes, void* stream);
+                                  void* hpre, void* h, void* yp, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * The expert path of a top-1 layer (k = 1) in one call, without xp and yp: bucket row p is read as row
@@ -176,7 +182,7 @@ int flexmoe_expert_ffn_fwd_gather(const void* x, const int32_t* src, const int32
  * straight to y[src[p], :] (Section 4's layout transformation and the reverse routing of Eq. 4 folded
  * into the expert computation; with one expert per token the gate value is exactly 1).  Same y as
  * flexmoe_permute + flexmoe_expert_ffn_fwd + flexmoe_combine, bit for bit.
- *   x [N,d], src [N] as written by flexmoe_route with k = 1 -> hpre [N,f] (may be NULL), y [N,d].
+ *   x [N,d], src [N] as written by flexmoe_route with k = 1 -> hpre [N,f], h [N,f] (each may be NULL), y [N,d].
  * For forward-only use.  FLEXMOE_UNSUPPORTED unless dtype is bf16, d and f are multiples of 128 and
  * N*d < 2^32.
  */
@@ -184,7 +190,7 @@ int flexmoe_expert_ffn_fwd_top1(const void* x, const int32_t* src, const int32_t
                                 const int32_t* vexpert_owner, const void* w1, const void* b1,
                                 const void* w2, const void* b2,
                                 int N, int d, int f, int E, int V, int act, int dtype,
-                                void* hpre, void* y, void* ws, size_t ws_bytes, void* stream);
+                                void* hpre, void* h, void* y, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Backward of the gate path (Eq. 3-4; the logits are x . W_g, the top-k kept, softmax over the

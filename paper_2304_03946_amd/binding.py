@@ -64,15 +64,15 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.flexmoe_combine.restype = c_int
     lib.flexmoe_combine.argtypes = [c_vp, c_vp, c_vp, c_int, c_int, c_int, c_int, c_vp, c_vp]
     lib.flexmoe_expert_ffn_fwd.restype = c_int
-    lib.flexmoe_expert_ffn_fwd.argtypes = [c_vp] * 7 + [c_int] * 7 + [c_vp, c_vp, c_vp, c_sz, c_vp]
+    lib.flexmoe_expert_ffn_fwd.argtypes = [c_vp] * 7 + [c_int] * 7 + [c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.flexmoe_expert_ffn_bwd.restype = c_int
-    lib.flexmoe_expert_ffn_bwd.argtypes = [c_vp] * 7 + [c_int] * 7 + [c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    lib.flexmoe_expert_ffn_bwd.argtypes = [c_vp] * 8 + [c_int] * 7 + [c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.flexmoe_expert_ffn_fwd_gather.restype = c_int
-    lib.flexmoe_expert_ffn_fwd_gather.argtypes = [c_vp] * 8 + [c_int] * 8 + [c_vp, c_vp, c_vp, c_sz, c_vp]
+    lib.flexmoe_expert_ffn_fwd_gather.argtypes = [c_vp] * 8 + [c_int] * 8 + [c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.flexmoe_expert_ffn_fwd_top1.restype = c_int
-    lib.flexmoe_expert_ffn_fwd_top1.argtypes = [c_vp] * 8 + [c_int] * 7 + [c_vp, c_vp, c_vp, c_sz, c_vp]
+    lib.flexmoe_expert_ffn_fwd_top1.argtypes = [c_vp] * 8 + [c_int] * 7 + [c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.flexmoe_expert_ffn_bwd_top1.restype = c_int
-    lib.flexmoe_expert_ffn_bwd_top1.argtypes = [c_vp] * 8 + [c_int] * 7 + [c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    lib.flexmoe_expert_ffn_bwd_top1.argtypes = [c_vp] * 9 + [c_int] * 7 + [c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.flexmoe_gate_bwd.restype = c_int
     lib.flexmoe_gate_bwd.argtypes = [c_vp] * 10 + [c_int] * 6 + [c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.flexmoe_expert_bias_grads.restype = c_int
@@ -174,11 +174,11 @@ def flexmoe_permute(x, src, row_scale, k, xp):
     _check(st, "flexmoe_permute")
 
 
-def flexmoe_expert_ffn_bwd_top1(dyp, xp, hpre, w1, w2, vexpert_off, vexpert_owner, src, act, dx, dw1, dw2, ws):
+def flexmoe_expert_ffn_bwd_top1(dyp, xp, hpre, w1, w2, vexpert_off, vexpert_owner, src, act, dx, dw1, dw2, ws, h=None):
     N, d = xp.shape
     E, _, f = w1.shape
     V = vexpert_owner.shape[0]
-    st = load_library().flexmoe_expert_ffn_bwd_top1(_ptr(dyp), _ptr(xp), _ptr(hpre), _ptr(w1), _ptr(w2),
+    st = load_library().flexmoe_expert_ffn_bwd_top1(_ptr(dyp), _ptr(xp), _ptr(hpre), _ptr(h), _ptr(w1), _ptr(w2),
                                                     _ptr(vexpert_off), _ptr(vexpert_owner), _ptr(src), N, d, f, E, V,
                                                     act, dtype_code(xp), _ptr(dx), _ptr(dw1), _ptr(dw2), _ptr(ws),
                                                     ws.numel() * ws.element_size(), _stream())
@@ -191,32 +191,32 @@ def flexmoe_combine(yp, dest, topk_w, k, y):
     _check(st, "flexmoe_combine")
 
 
-def flexmoe_expert_ffn_fwd(xp, vexpert_off, vexpert_owner, w1, b1, w2, b2, act, hpre, yp, ws):
+def flexmoe_expert_ffn_fwd(xp, vexpert_off, vexpert_owner, w1, b1, w2, b2, act, hpre, yp, ws, h=None):
     A, d = xp.shape
     E, _, f = w1.shape
     V = vexpert_owner.shape[0]
     st = load_library().flexmoe_expert_ffn_fwd(_ptr(xp), _ptr(vexpert_off), _ptr(vexpert_owner), _ptr(w1), _ptr(b1),
                                                _ptr(w2), _ptr(b2), A, d, f, E, V, act, dtype_code(xp), _ptr(hpre),
-                                               _ptr(yp), _ptr(ws), ws.numel() * ws.element_size(), _stream())
+                                               _ptr(h), _ptr(yp), _ptr(ws), ws.numel() * ws.element_size(), _stream())
     _check(st, "flexmoe_expert_ffn_fwd")
 
 
-def flexmoe_expert_ffn_fwd_top1(x, src, vexpert_off, vexpert_owner, w1, b1, w2, b2, act, hpre, y, ws):
+def flexmoe_expert_ffn_fwd_top1(x, src, vexpert_off, vexpert_owner, w1, b1, w2, b2, act, hpre, y, ws, h=None):
     N, d = x.shape
     E, _, f = w1.shape
     V = vexpert_owner.shape[0]
     st = load_library().flexmoe_expert_ffn_fwd_top1(_ptr(x), _ptr(src), _ptr(vexpert_off), _ptr(vexpert_owner),
                                                     _ptr(w1), _ptr(b1), _ptr(w2), _ptr(b2), N, d, f, E, V, act,
-                                                    dtype_code(x), _ptr(hpre), _ptr(y), _ptr(ws),
+                                                    dtype_code(x), _ptr(hpre), _ptr(h), _ptr(y), _ptr(ws),
                                                     ws.numel() * ws.element_size(), _stream())
     _check(st, "flexmoe_expert_ffn_fwd_top1")
 
 
-def flexmoe_expert_ffn_bwd(dyp, xp, hpre, w1, w2, vexpert_off, vexpert_owner, act, dxp, dw1, dw2, ws):
+def flexmoe_expert_ffn_bwd(dyp, xp, hpre, w1, w2, vexpert_off, vexpert_owner, act, dxp, dw1, dw2, ws, h=None):
     A, d = xp.shape
     E, _, f = w1.shape
     V = vexpert_owner.shape[0]
-    st = load_library().flexmoe_expert_ffn_bwd(_ptr(dyp), _ptr(xp), _ptr(hpre), _ptr(w1), _ptr(w2), _ptr(vexpert_off),
+    st = load_library().flexmoe_expert_ffn_bwd(_ptr(dyp), _ptr(xp), _ptr(hpre), _ptr(h), _ptr(w1), _ptr(w2), _ptr(vexpert_off),
                                                _ptr(vexpert_owner), A, d, f, E, V, act, dtype_code(xp), _ptr(dxp),
                                                _ptr(dw1), _ptr(dw2), _ptr(ws), ws.numel() * ws.element_size(), _stream())
     _check(st, "flexmoe_expert_ffn_bwd")
@@ -243,12 +243,12 @@ def flexmoe_expert_bias_grads(dyp, vexpert_off, vexpert_owner, f, E, db1, db2, w
     _check(st, "flexmoe_expert_bias_grads")
 
 
-def flexmoe_expert_ffn_fwd_gather(x, src, k, vexpert_off, vexpert_owner, w1, b1, w2, b2, act, hpre, yp, ws):
+def flexmoe_expert_ffn_fwd_gather(x, src, k, vexpert_off, vexpert_owner, w1, b1, w2, b2, act, hpre, yp, ws, h=None):
     N, d = x.shape
     E, _, f = w1.shape
     V = vexpert_owner.shape[0]
     st = load_library().flexmoe_expert_ffn_fwd_gather(_ptr(x), _ptr(src), _ptr(vexpert_off), _ptr(vexpert_owner),
                                                       _ptr(w1), _ptr(b1), _ptr(w2), _ptr(b2), N, k, d, f, E, V, act,
-                                                      dtype_code(x), _ptr(hpre), _ptr(yp), _ptr(ws),
+                                                      dtype_code(x), _ptr(hpre), _ptr(h), _ptr(yp), _ptr(ws),
                                                       ws.numel() * ws.element_size(), _stream())
     _check(st, "flexmoe_expert_ffn_fwd_gather")

@@ -142,22 +142,22 @@ static int ffn_common(int A, int d, int f, int E, int V, int act, int dtype, con
 
 int flexmoe_expert_ffn_fwd(const void* xp, const int32_t* vexpert_off, const int32_t* vexpert_owner, const void* w1,
                            const void* b1, const void* w2, const void* b2, int A, int d, int f, int E, int V, int act,
-                           int dtype, void* hpre, void* yp, void* ws, size_t ws_bytes, void* stream) {
+                           int dtype, void* hpre, void* h, void* yp, void* ws, size_t ws_bytes, void* stream) {
   const int st = ffn_common(A, d, f, E, V, act, dtype, vexpert_off, vexpert_owner, ws, ws_bytes);
   if (st != FLEXMOE_OK) return st;
   if (!w1 || !w2 || !aligned16(w1) || !aligned16(w2) || !aligned16(b1) || !aligned16(b2)) return FLEXMOE_INVALID_ARG;
-  if (A > 0 && (!xp || !yp || !aligned16(xp) || !aligned16(hpre) || !aligned16(yp)))      // hpre may be NULL
+  if (A > 0 && (!xp || !yp || !aligned16(xp) || !aligned16(hpre) || !aligned16(h) || !aligned16(yp)))      // hpre, h may be NULL
     return FLEXMOE_INVALID_ARG;
   const FfnArgs a{A, d, f, E, V, act, vexpert_off, vexpert_owner};
   const hipStream_t s = (hipStream_t)stream;
-  return dev_status(dtype == FLEXMOE_BF16 ? launch_ffn_fwd_bf16(a, xp, w1, b1, w2, b2, hpre, yp, ws, s)
-                                          : launch_ffn_fwd_f32(a, xp, w1, b1, w2, b2, hpre, yp, ws, s));
+  return dev_status(dtype == FLEXMOE_BF16 ? launch_ffn_fwd_bf16(a, xp, w1, b1, w2, b2, hpre, h, yp, ws, s)
+                                          : launch_ffn_fwd_f32(a, xp, w1, b1, w2, b2, hpre, h, yp, ws, s));
 }
 
 int flexmoe_expert_ffn_fwd_gather(const void* x, const int32_t* src, const int32_t* vexpert_off,
                                   const int32_t* vexpert_owner, const void* w1, const void* b1, const void* w2,
                                   const void* b2, int N, int k, int d, int f, int E, int V, int act, int dtype,
-                                  void* hpre, void* yp, void* ws, size_t ws_bytes, void* stream) {
+                                  void* hpre, void* h, void* yp, void* ws, size_t ws_bytes, void* stream) {
   if (N < 0 || k < 1 || k > FLEXMOE_MAX_TOPK || (long long)N * k >= (1ll << 30)) return FLEXMOE_INVALID_ARG;
   const int A = N * k;
   const int st = ffn_common(A, d, f, E, V, act, dtype, vexpert_off, vexpert_owner, ws, ws_bytes);
@@ -165,29 +165,29 @@ int flexmoe_expert_ffn_fwd_gather(const void* x, const int32_t* src, const int32
   // gathered row loads exist on the bf16 direct-to-LDS path only; row offsets are 32-bit
   if (dtype != FLEXMOE_BF16 || (d % 128) || (long long)N * d >= (1ll << 32)) return FLEXMOE_UNSUPPORTED;
   if (!w1 || !w2 || !aligned16(w1) || !aligned16(w2) || !aligned16(b1) || !aligned16(b2)) return FLEXMOE_INVALID_ARG;
-  if (A > 0 && (!x || !src || !yp || !aligned16(x) || !aligned16(hpre) || !aligned16(yp)))    // hpre may be NULL
+  if (A > 0 && (!x || !src || !yp || !aligned16(x) || !aligned16(hpre) || !aligned16(h) || !aligned16(yp)))    // hpre, h may be NULL
     return FLEXMOE_INVALID_ARG;
   const FfnArgs a{A, d, f, E, V, act, vexpert_off, vexpert_owner};
-  return dev_status(launch_ffn_fwd_gather_bf16(a, x, src, k, w1, b1, w2, b2, hpre, yp, ws, (hipStream_t)stream));
+  return dev_status(launch_ffn_fwd_gather_bf16(a, x, src, k, w1, b1, w2, b2, hpre, h, yp, ws, (hipStream_t)stream));
 }
 
 int flexmoe_expert_ffn_fwd_top1(const void* x, const int32_t* src, const int32_t* vexpert_off,
                                 const int32_t* vexpert_owner, const void* w1, const void* b1, const void* w2,
                                 const void* b2, int N, int d, int f, int E, int V, int act, int dtype,
-                                void* hpre, void* y, void* ws, size_t ws_bytes, void* stream) {
+                                void* hpre, void* h, void* y, void* ws, size_t ws_bytes, void* stream) {
   if (N < 0 || N >= (1 << 30)) return FLEXMOE_INVALID_ARG;
   const int st = ffn_common(N, d, f, E, V, act, dtype, vexpert_off, vexpert_owner, ws, ws_bytes);
   if (st != FLEXMOE_OK) return st;
   // gathered loads and scattered stores exist on the bf16 direct-to-LDS path only; row offsets are 32-bit
   if (dtype != FLEXMOE_BF16 || (d % 128) || (f % 128) || (long long)N * d >= (1ll << 32)) return FLEXMOE_UNSUPPORTED;
   if (!w1 || !w2 || !aligned16(w1) || !aligned16(w2) || !aligned16(b1) || !aligned16(b2)) return FLEXMOE_INVALID_ARG;
-  if (N > 0 && (!x || !src || !y || !aligned16(x) || !aligned16(hpre) || !aligned16(y)))    // hpre may be NULL
+  if (N > 0 && (!x || !src || !y || !aligned16(x) || !aligned16(hpre) || !aligned16(h) || !aligned16(y)))    // hpre, h may be NULL
     return FLEXMOE_INVALID_ARG;
   const FfnArgs a{N, d, f, E, V, act, vexpert_off, vexpert_owner};
-  return dev_status(launch_ffn_fwd_top1_bf16(a, x, src, w1, b1, w2, b2, hpre, y, ws, (hipStream_t)stream));
+  return dev_status(launch_ffn_fwd_top1_bf16(a, x, src, w1, b1, w2, b2, hpre, h, y, ws, (hipStream_t)stream));
 }
 
-int flexmoe_expert_ffn_bwd(const void* dyp, const void* xp, const void* hpre, const void* w1, const void* w2,
+int flexmoe_expert_ffn_bwd(const void* dyp, const void* xp, const void* hpre, const void* h, const void* w1, const void* w2,
                            const int32_t* vexpert_off, const int32_t* vexpert_owner, int A, int d, int f, int E, int V,
                            int act, int dtype, void* dxp, void* dw1, void* dw2, void* ws, size_t ws_bytes,
                            void* stream) {
@@ -195,16 +195,16 @@ int flexmoe_expert_ffn_bwd(const void* dyp, const void* xp, const void* hpre, co
   if (st != FLEXMOE_OK) return st;
   if (!w1 || !w2 || !dw1 || !dw2 || !aligned16(w1) || !aligned16(w2) || !aligned16(dw1) || !aligned16(dw2))
     return FLEXMOE_INVALID_ARG;
-  if (A > 0 && (!dyp || !xp || !hpre || !dxp || !aligned16(dyp) || !aligned16(xp) || !aligned16(hpre) ||
-                !aligned16(dxp)))
+  if (A > 0 && (!dyp || !xp || !hpre || !dxp || !aligned16(dyp) || !aligned16(xp) || !aligned16(hpre) || !aligned16(h) ||
+                !aligned16(dxp)))      // h may be NULL
     return FLEXMOE_INVALID_ARG;
   const FfnArgs a{A, d, f, E, V, act, vexpert_off, vexpert_owner};
   const hipStream_t s = (hipStream_t)stream;
-  return dev_status(dtype == FLEXMOE_BF16 ? launch_ffn_bwd_bf16(a, dyp, xp, hpre, w1, w2, dxp, dw1, dw2, ws, s)
-                                          : launch_ffn_bwd_f32(a, dyp, xp, hpre, w1, w2, dxp, dw1, dw2, ws, s));
+  return dev_status(dtype == FLEXMOE_BF16 ? launch_ffn_bwd_bf16(a, dyp, xp, hpre, h, w1, w2, dxp, dw1, dw2, ws, s)
+                                          : launch_ffn_bwd_f32(a, dyp, xp, hpre, h, w1, w2, dxp, dw1, dw2, ws, s));
 }
 
-int flexmoe_expert_ffn_bwd_top1(const void* dyp, const void* xp, const void* hpre, const void* w1, const void* w2,
+int flexmoe_expert_ffn_bwd_top1(const void* dyp, const void* xp, const void* hpre, const void* h, const void* w1, const void* w2,
                                 const int32_t* vexpert_off, const int32_t* vexpert_owner, const int32_t* src,
                                 int N, int d, int f, int E, int V, int act, int dtype,
                                 void* dx, void* dw1, void* dw2, void* ws, size_t ws_bytes, void* stream) {
@@ -215,11 +215,11 @@ int flexmoe_expert_ffn_bwd_top1(const void* dyp, const void* xp, const void* hpr
   if (dtype != FLEXMOE_BF16 || (f % 128)) return FLEXMOE_UNSUPPORTED;
   if (!w1 || !w2 || !dw1 || !dw2 || !aligned16(w1) || !aligned16(w2) || !aligned16(dw1) || !aligned16(dw2))
     return FLEXMOE_INVALID_ARG;
-  if (N > 0 && (!dyp || !xp || !hpre || !dx || !src || !aligned16(dyp) || !aligned16(xp) || !aligned16(hpre) ||
-                !aligned16(dx)))
+  if (N > 0 && (!dyp || !xp || !hpre || !dx || !src || !aligned16(dyp) || !aligned16(xp) || !aligned16(hpre) || !aligned16(h) ||
+                !aligned16(dx)))      // h may be NULL
     return FLEXMOE_INVALID_ARG;
   const FfnArgs a{N, d, f, E, V, act, vexpert_off, vexpert_owner};
-  return dev_status(launch_ffn_bwd_bf16(a, dyp, xp, hpre, w1, w2, dx, dw1, dw2, ws, (hipStream_t)stream, src));
+  return dev_status(launch_ffn_bwd_bf16(a, dyp, xp, hpre, h, w1, w2, dx, dw1, dw2, ws, (hipStream_t)stream, src));
 }
 
 int flexmoe_gate_bwd(const void* wg, const int32_t* topk_idx, const float* topk_w, const void* dy, const void* yp,

@@ -164,14 +164,16 @@ struct FfnArgs {
   const int32_t* owner;
 };
 size_t ffn_ws_bytes(int A, int d, int f, int E, int V, int dtype);
+// h_keep / h_kept: act(Hpre) in a buffer of the caller's (written by the forward pass, read by the backward pass), or null
 hipError_t launch_ffn_fwd_bf16(const FfnArgs& a, const void* xp, const void* w1, const void* b1,
-                               const void* w2, const void* b2, void* hpre, void* yp, void* ws, hipStream_t s);
+                               const void* w2, const void* b2, void* hpre, void* h_keep, void* yp, void* ws, hipStream_t s);
 hipError_t launch_ffn_fwd_gather_bf16(const FfnArgs& a, const void* x, const int32_t* src, int k, const void* w1,
-                                      const void* b1, const void* w2, const void* b2, void* hpre, void* yp, void* ws,
-                                      hipStream_t s);
+                                      const void* b1, const void* w2, const void* b2, void* hpre, void* h_keep, void* yp,
+                                      void* ws, hipStream_t s);
 hipError_t launch_ffn_fwd_top1_bf16(const FfnArgs& a, const void* x, const int32_t* src, const void* w1, const void* b1,
-                                    const void* w2, const void* b2, void* hpre, void* y, void* ws, hipStream_t s);
-hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp, const void* hpre,
+                                    const void* w2, const void* b2, void* hpre, void* h_keep, void* y, void* ws,
+                                    hipStream_t s);
+hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp, const void* hpre, const void* h_kept,
                                const void* w1, const void* w2, void* dxp, void* dw1, void* dw2,
                                void* ws, hipStream_t s,
                                const int32_t* scatter_src = nullptr);
@@ -185,8 +187,8 @@ size_t bias_grads_ws_bytes(int A, int d, int f, int V, int dtype);
 hipError_t launch_bias_grads(const void* dyp, const int32_t* voff, const int32_t* owner, int A, int d, int f, int E,
                              int V, int dtype, void* db1, void* db2, void* ws, hipStream_t s);
 hipError_t launch_ffn_fwd_f32(const FfnArgs& a, const void* xp, const void* w1, const void* b1,
-                              const void* w2, const void* b2, void* hpre, void* yp, void* ws, hipStream_t s);
-hipError_t launch_ffn_bwd_f32(const FfnArgs& a, const void* dyp, const void* xp, const void* hpre,
+                              const void* w2, const void* b2, void* hpre, void* h_keep, void* yp, void* ws, hipStream_t s);
+hipError_t launch_ffn_bwd_f32(const FfnArgs& a, const void* dyp, const void* xp, const void* hpre, const void* h_kept,
                               const void* w1, const void* w2, void* dxp, void* dw1, void* dw2,
                               void* ws, hipStream_t s);
 

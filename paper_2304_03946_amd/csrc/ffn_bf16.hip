@@ -224,11 +224,13 @@ static hipError_t launch_wgrad(const FfnArgs& a, const void* L, const void* R, i
   return hipGetLastError();
 }
 
+// h_keep (all forward variants): where act(Hpre) goes -- the caller's buffer, kept for the backward pass -- or
+// null: the workspace.
 hipError_t launch_ffn_fwd_bf16(const FfnArgs& a, const void* xp, const void* w1, const void* b1, const void* w2,
-                               const void* b2, void* hpre, void* yp, void* ws, hipStream_t s) {
+                               const void* b2, void* hpre, void* h_keep, void* yp, void* ws, hipStream_t s) {
   if (a.A == 0) return hipSuccess;
   launch_rows_plan(a, ws, s);
-  void* h = ws;
+  void* h = h_keep ? h_keep : ws;
   hipError_t err = launch_rows<false, EPI_FWD1>(a, xp, w1, b1, a.d, a.f, nullptr, hpre, h, ws, s);
   if (err != hipSuccess) return err;
   return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, yp, nullptr, ws, s, nullptr, 1, rows_split_ws(a, ws));
@@ -237,11 +239,11 @@ hipError_t launch_ffn_fwd_bf16(const FfnArgs& a, const void* xp, const void* w1,
 // Forward with the expert-wise layout transformation folded into GEMM1's row loads: bucket row p
 // is row src[p] / k of x.  d must be a multiple of 128 (direct-to-LDS path).
 hipError_t launch_ffn_fwd_gather_bf16(const FfnArgs& a, const void* x, const int32_t* src, int k, const void* w1,
-                                      const void* b1, const void* w2, const void* b2, void* hpre, void* yp, void* ws,
-                                      hipStream_t s) {
+                                      const void* b1, const void* w2, const void* b2, void* hpre, void* h_keep, void* yp,
+                                      void* ws, hipStream_t s) {
   if (a.A == 0) return hipSuccess;
   launch_rows_plan(a, ws, s);
-  void* h = ws;
+  void* h = h_keep ? h_keep : ws;
   hipError_t err = launch_rows<false, EPI_FWD1>(a, x, w1, b1, a.d, a.f, nullptr, hpre, h, ws, s, src, k);
   if (err != hipSuccess) return err;
   return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, yp, nullptr, ws, s, nullptr, 1, rows_split_ws(a, ws));
@@ -251,10 +253,11 @@ hipError_t launch_ffn_fwd_gather_bf16(const FfnArgs& a, const void* x, const int
 // and the second product's rows stored straight to y[src[p], :] -- with one expert per token the gate
 // weight is exactly 1, so this is flexmoe_combine folded into the epilogue.  d and f multiples of 128.
 hipError_t launch_ffn_fwd_top1_bf16(const FfnArgs& a, const void* x, const int32_t* src, const void* w1, const void* b1,
-                                    const void* w2, const void* b2, void* hpre, void* y, void* ws, hipStream_t s) {
+                                    const void* w2, const void* b2, void* hpre, void* h_keep, void* y, void* ws,
+                                    hipStream_t s) {
   if (a.A == 0) return hipSuccess;
   launch_rows_plan(a, ws, s);
-  void* h = ws;
+  void* h = h_keep ? h_keep : ws;
   hipError_t err = launch_rows<false, EPI_FWD1>(a, x, w1, b1, a.d, a.f, nullptr, hpre, h, ws, s, src, 1);
   if (err != hipSuccess) return err;
   return launch_rows<false, EPI_PLAIN>(a, h, w2, b2, a.f, a.d, nullptr, y, nullptr, ws, s, nullptr, 1, rows_split_ws(a, ws), src);
@@ -262,17 +265,21 @@ hipError_t launch_ffn_fwd_top1_bf16(const FfnArgs& a, const void* x, const int32
 
 // scatter_src (top-1 layers, needs f % 128 == 0): bucket row p of dXp is stored as row scatter_src[p] of
 // `dxp`, which is then dX [N, d] itself -- the backward reverse routing folded into the epilogue.
-hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp, const void* hpre, const void* w1,
-                               const void* w2, void* dxp, void* dw1, void* dw2, void* ws, hipStream_t s,
+// h_kept: act(Hpre) as the forward pass left it in the caller's buffer, or null: it is computed again from
+// hpre by the dH kernel (into the workspace), which then stores two [A, f] tensors instead of one.
+hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp, const void* hpre, const void* h_kept,
+                               const void* w1, const void* w2, void* dxp, void* dw1, void* dw2, void* ws, hipStream_t s,
                                const int32_t* scatter_src) {
   bf16_t* dhpre = (bf16_t*)ws;
-  bf16_t* h = (bf16_t*)((char*)ws + align_up((size_t)a.A * a.f * sizeof(bf16_t), 256));
+  bf16_t* h_ws = (bf16_t*)((char*)ws + align_up((size_t)a.A * a.f * sizeof(bf16_t), 256));
+  const bf16_t* h = h_kept ? (const bf16_t*)h_kept : h_ws;
   hipError_t err;
   launch_wgrad_plan(a, ws, s);
   if (a.A > 0) {
     launch_rows_plan(a, ws, s);
     // dH = dYp . W2^T fused with act'(Hpre); W2_e is [f, d], contraction index d contiguous
-    err = launch_rows<true, EPI_DH>(a, dyp, w2, nullptr, a.d, a.f, hpre, dhpre, h, ws, s);
+    err = h_kept ? launch_rows<true, EPI_DHQ>(a, dyp, w2, nullptr, a.d, a.f, hpre, dhpre, nullptr, ws, s)
+                 : launch_rows<true, EPI_DH>(a, dyp, w2, nullptr, a.d, a.f, hpre, dhpre, h_ws, ws, s);
     if (err != hipSuccess) return err;
   }
   // dW2 = H^T . dYp, dW1 = Xp^T . dHpre: each with its own table and partial tiles

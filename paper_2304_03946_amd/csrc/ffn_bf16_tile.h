@@ -11,7 +11,7 @@ constexpr int MB = 4, NB = 4;                       // 32x32 MFMA tiles per wave
 constexpr int kTileElems = BM * BK;                 // one operand tile in LDS (elements)
 constexpr size_t kGemmLds = 2 * 2 * kTileElems * sizeof(bf16_t);   // 2 stages x (A + B) = 128 KB
 
-enum { EPI_FWD1 = 0, EPI_PLAIN = 1, EPI_DH = 2 };
+enum { EPI_FWD1 = 0, EPI_PLAIN = 1, EPI_DH = 2, EPI_DHQ = 3 };      // DHQ: dH * act'(Hpre) only (H was kept by the forward)
 #ifndef FLEXMOE_EPI_AHEAD
 #define FLEXMOE_EPI_AHEAD 2      // rounds between the request and the use of an epilogue side input
 #endif
@@ -237,6 +237,10 @@ __device__ __forceinline__ void lut_act_both(const lds_byte_t* lut, uint32_t zu,
   const f32x2_t rq = *(const __attribute__((address_space(3))) f32x2_t*)(lut + lut_offset(zu));
   *a = relu_bits(zu) + rq[0];
   *da = (int32_t)zu < 0 ? -rq[1] : 1.f + rq[1];
+}
+__device__ __forceinline__ float lut_act_d(const lds_byte_t* lut, uint32_t zu) {
+  const float q = *(const __attribute__((address_space(3))) float*)(lut + lut_offset(zu) + 4);
+  return (int32_t)zu < 0 ? -q : 1.f + q;
 }
 template <int EPI, int ACT> constexpr bool epilogue_uses_lut() { return EPI != EPI_PLAIN && ACT != FLEXMOE_RELU; }
 
@@ -501,6 +505,16 @@ __device__ __forceinline__ void rows_epilogue_t(float* lds, float* lds_alt, cons
 #pragma unroll
       for (int q = 0; q < 4; ++q) a[q] = LUT ? lut_act(lut, __float_as_uint(z[q])) : act_fast<ACT>(z[q]);
       o.b = pack4(a[0], a[1], a[2], a[3]);
+    } else if (EPI == EPI_DHQ) {
+      float z[4], a, d[4];
+      unpack4(pre_in, z);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (LUT) d[q] = lut_act_d(lut, __float_as_uint(z[q]));
+        else act_both<ACT>(z[q], &a, &d[q]);
+      }
+      o.a = pack4(c.x * d[0], c.y * d[1], c.z * d[2], c.w * d[3]);
+      o.b = make_uint2(0, 0);
     } else {
       float z[4], a[4], d[4];
       unpack4(pre_in, z);
@@ -525,10 +539,10 @@ __device__ __forceinline__ void rows_epilogue_t(float* lds, float* lds_alt, cons
         if (EPI == EPI_PLAIN) *(uint2*)addr.at(out0_t, x) = o.a;
         else store_nt8(addr.at(out0_t, x), o.a);
       }
-      if (EPI != EPI_PLAIN) store_nt8(addr.at(out1_t, x), o.b);
+      if (EPI == EPI_FWD1 || EPI == EPI_DH) store_nt8(addr.at(out1_t, x), o.b);
     }
   };
-  epilogue_rounds<EPI == EPI_DH>(patch, patch_alt, acc, fetch, compute, store);
+  epilogue_rounds<EPI == EPI_DH || EPI == EPI_DHQ>(patch, patch_alt, acc, fetch, compute, store);
 }
 
 template <int EPI, int ACT, bool LUT = false>

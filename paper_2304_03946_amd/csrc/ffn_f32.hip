@@ -70,9 +70,9 @@ __global__ __launch_bounds__(kF32Threads) void wgrad_f32(const float* __restrict
 static dim3 elems_grid(size_t n) { return dim3((unsigned)((n + kF32Threads - 1) / kF32Threads)); }
 
 hipError_t launch_ffn_fwd_f32(const FfnArgs& a, const void* xp, const void* w1, const void* b1, const void* w2,
-                              const void* b2, void* hpre, void* yp, void* ws, hipStream_t s) {
+                              const void* b2, void* hpre, void* h_keep, void* yp, void* ws, hipStream_t s) {
   if (a.A == 0) return hipSuccess;
-  float* h = (float*)ws;
+  float* h = h_keep ? (float*)h_keep : (float*)ws;
   hipLaunchKernelGGL((rows_gemm_f32<false, EPI_FWD1>), elems_grid((size_t)a.A * a.f), dim3(kF32Threads), 0, s,
                      (const float*)xp, (const float*)w1, (const float*)b1, a.voff, a.owner, a.V, a.A, a.d, a.f, a.act,
                      (const float*)nullptr, (float*)hpre, h);
@@ -82,10 +82,13 @@ hipError_t launch_ffn_fwd_f32(const FfnArgs& a, const void* xp, const void* w1, 
   return hipGetLastError();
 }
 
-hipError_t launch_ffn_bwd_f32(const FfnArgs& a, const void* dyp, const void* xp, const void* hpre, const void* w1,
-                              const void* w2, void* dxp, void* dw1, void* dw2, void* ws, hipStream_t s) {
+// h_kept is accepted for symmetry with the bf16 path; this reference-grade path computes act(Hpre) again all the same
+// and takes the weight gradient's operand from wherever the caller says.
+hipError_t launch_ffn_bwd_f32(const FfnArgs& a, const void* dyp, const void* xp, const void* hpre, const void* h_kept,
+                              const void* w1, const void* w2, void* dxp, void* dw1, void* dw2, void* ws, hipStream_t s) {
   float* dhpre = (float*)ws;
   float* h = dhpre + (size_t)a.A * a.f;
+  const float* h_src = h_kept ? (const float*)h_kept : h;
   if (a.A > 0) {
     // dH = dYp . W2^T (W2_e is [f, d]: contraction over its second index), fused with act'
     hipLaunchKernelGGL((rows_gemm_f32<true, EPI_DH>), elems_grid((size_t)a.A * a.f), dim3(kF32Threads), 0, s,
@@ -96,7 +99,7 @@ hipError_t launch_ffn_bwd_f32(const FfnArgs& a, const void* dyp, const void* xp,
                        (const float*)dhpre, (const float*)w1, (const float*)nullptr, a.voff, a.owner, a.V, a.A, a.f,
                        a.d, a.act, (const float*)nullptr, (float*)dxp, (float*)nullptr);
   }
-  hipLaunchKernelGGL(wgrad_f32, dim3(elems_grid((size_t)a.f * a.d).x, a.E), dim3(kF32Threads), 0, s, (const float*)h,
+  hipLaunchKernelGGL(wgrad_f32, dim3(elems_grid((size_t)a.f * a.d).x, a.E), dim3(kF32Threads), 0, s, h_src,
                      (const float*)dyp, a.voff, a.owner, a.V, a.f, a.d, (float*)dw2);
   hipLaunchKernelGGL(wgrad_f32, dim3(elems_grid((size_t)a.d * a.f).x, a.E), dim3(kF32Threads), 0, s, (const float*)xp,
                      (const float*)dhpre, a.voff, a.owner, a.V, a.d, a.f, (float*)dw1);

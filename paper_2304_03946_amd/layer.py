@@ -31,7 +31,10 @@ def to_host_f32(t: torch.Tensor) -> np.ndarray:
 
 
 class MoELayer:
-    def __init__(self, N, d, f, E, k, V, dtype, act, backward=False, device="cuda"):
+    def __init__(self, N, d, f, E, k, V, dtype, act, backward=False, device="cuda", keep_h=None):
+        """keep_h (training layers; default on): the forward pass leaves act(Hpre) in a buffer of the layer's
+        and the backward pass reads it there instead of computing and storing it again -- A*f more elements
+        of saved activations for a shorter backward pass."""
         self.N, self.d, self.f, self.E, self.k, self.V = N, d, f, E, k, V
         self.A = N * k
         self.act = act
@@ -57,6 +60,9 @@ class MoELayer:
             raise ValueError("unsupported layer shape")
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
         self.has_backward = backward
+        self.h = None
+        if backward and (keep_h is None or keep_h):
+            self.h = torch.empty((A, f), dtype=tdt, device=dev)
         if backward:
             self.dyp = torch.empty((A, d), dtype=tdt, device=dev)
             self.dxp = torch.empty((A, d), dtype=tdt, device=dev)
@@ -101,10 +107,10 @@ class MoELayer:
 
         def once():
             B.flexmoe_expert_ffn_fwd(self.xp, self.vexpert_off, self.vexpert_owner, w1, None, w2, None, self.act,
-                                     self.hpre, self.yp, self.ws)
+                                     self.hpre, self.yp, self.ws, h=self.h)
             if self.has_backward:
                 B.flexmoe_expert_ffn_bwd(self.dyp, self.xp, self.hpre, w1, w2, self.vexpert_off, self.vexpert_owner,
-                                         self.act, self.dxp, self.dw1, self.dw2, self.ws)
+                                         self.act, self.dxp, self.dw1, self.dw2, self.ws, h=self.h)
         once()
         ev[0].record()
         for _ in range(reps):
@@ -120,7 +126,7 @@ class MoELayer:
         self.route(rep_off, rep_ids)
         B.flexmoe_permute(x, self.src, None, self.k, self.xp)
         B.flexmoe_expert_ffn_fwd(self.xp, self.vexpert_off, self.vexpert_owner, w1, b1, w2, b2, self.act,
-                                 self.hpre if keep_hpre else None, self.yp, self.ws)
+                                 self.hpre if keep_hpre else None, self.yp, self.ws, h=self.h)
         B.flexmoe_combine(self.yp, self.dest, self.topk_w, self.k, self.y)
         return self.y
 
@@ -150,9 +156,10 @@ class MoELayer:
         return self.y
 
     def backward(self, dy, w1, w2):
+        """After `forward` (the one pass that fills xp, hpre and, with keep_h, h)."""
         B.flexmoe_permute(dy, self.src, self.topk_w, self.k, self.dyp)
         B.flexmoe_expert_ffn_bwd(self.dyp, self.xp, self.hpre, w1, w2, self.vexpert_off, self.vexpert_owner,
-                                 self.act, self.dxp, self.dw1, self.dw2, self.ws)
+                                 self.act, self.dxp, self.dw1, self.dw2, self.ws, h=self.h)
         B.flexmoe_combine(self.dxp, self.dest, None, self.k, self.dx)
         return self.dx, self.dw1, self.dw2
 
@@ -160,7 +167,7 @@ class MoELayer:
         """`backward` for a top-1 layer: dX comes straight out of the expert backward (no dXp, no combine)."""
         B.flexmoe_permute(dy, self.src, self.topk_w, self.k, self.dyp)
         B.flexmoe_expert_ffn_bwd_top1(self.dyp, self.xp, self.hpre, w1, w2, self.vexpert_off, self.vexpert_owner,
-                                      self.src, self.act, self.dx, self.dw1, self.dw2, self.ws)
+                                      self.src, self.act, self.dx, self.dw1, self.dw2, self.ws, h=self.h)
         return self.dx, self.dw1, self.dw2
 
     def backward_full(self, dy, wg, w1, w2):
@@ -174,7 +181,7 @@ class MoELayer:
             self.dwg = torch.empty((self.d, self.E), dtype=tdt, device=dev)
         B.flexmoe_permute(dy, self.src, self.topk_w, self.k, self.dyp)
         B.flexmoe_expert_ffn_bwd(self.dyp, self.xp, self.hpre, w1, w2, self.vexpert_off, self.vexpert_owner,
-                                 self.act, self.dxp, self.dw1, self.dw2, self.ws)
+                                 self.act, self.dxp, self.dw1, self.dw2, self.ws, h=self.h)
         B.flexmoe_expert_bias_grads(self.dyp, self.vexpert_off, self.vexpert_owner, self.f, self.E, self.db1,
                                     self.db2, self.ws)
         B.flexmoe_combine(self.dxp, self.dest, None, self.k, self.dx)

@@ -73,13 +73,13 @@ def test_argument_validation_needs_no_device():
     bf16, relu = binding.BF16, binding.RELU
     # dtype / activation outside the enums
     assert lib.flexmoe_gate_topk(one, one, 4, 64, 4, 1, 7, one, one, one, 1 << 20, null) == binding.UNSUPPORTED
-    assert lib.flexmoe_expert_ffn_fwd(one, one, one, one, null, one, null, 4, 64, 64, 4, 4, 9, bf16, one, one, one,
+    assert lib.flexmoe_expert_ffn_fwd(one, one, one, one, null, one, null, 4, 64, 64, 4, 4, 9, bf16, one, null, one, one,
                                       1 << 20, null) == binding.UNSUPPORTED
     # k > E, d not a multiple of 8, V < E
     assert lib.flexmoe_gate_topk(one, one, 4, 64, 4, 5, bf16, one, one, one, 1 << 20, null) == binding.INVALID_ARG
     assert lib.flexmoe_permute(one, one, null, 4, 1, 12, bf16, one, null) == binding.INVALID_ARG
     assert lib.flexmoe_combine(one, one, null, 4, 1, 12, bf16, one, null) == binding.INVALID_ARG
-    assert lib.flexmoe_expert_ffn_bwd(one, one, one, one, one, one, one, 4, 64, 64, 4, 3, relu, bf16, one, one, one,
+    assert lib.flexmoe_expert_ffn_bwd(one, one, one, null, one, one, one, one, 4, 64, 64, 4, 3, relu, bf16, one, one, one,
                                       one, 1 << 20, null) == binding.INVALID_ARG
     # null outputs
     assert lib.flexmoe_gate_bwd(one, one, one, one, one, one, one, one, one, one, 4, 64, 4, 2, 4, bf16, null, one,
@@ -87,23 +87,26 @@ def test_argument_validation_needs_no_device():
     assert lib.flexmoe_gate_bwd(one, one, one, one, one, one, one, one, one, one, 4, 64, 4, 2, 4, bf16, one, one,
                                 null, one, 1 << 20, null) == binding.INVALID_ARG
     # workspace too small
-    assert lib.flexmoe_expert_ffn_fwd(one, one, one, one, null, one, null, 64, 64, 64, 4, 4, relu, bf16, one, one,
+    assert lib.flexmoe_expert_ffn_fwd(one, one, one, one, null, one, null, 64, 64, 64, 4, 4, relu, bf16, one, one, one,
                                       one, 256, null) == binding.WORKSPACE_TOO_SMALL
+    # a misaligned buffer for the kept activations
+    assert lib.flexmoe_expert_ffn_fwd(one, one, one, one, null, one, null, 64, 64, 64, 4, 4, relu, bf16, one,
+                                      ctypes.c_void_p(24), one, one, 1 << 20, null) == binding.INVALID_ARG
     assert lib.flexmoe_expert_bias_grads(one, one, one, 64, 64, 64, 4, 4, bf16, one, one, one, 256,
                                          null) == binding.WORKSPACE_TOO_SMALL
     assert lib.flexmoe_gate_bwd(one, one, one, one, one, one, one, one, one, one, 64, 64, 4, 2, 4, bf16, one, one,
                                 one, one, 16, null) == binding.WORKSPACE_TOO_SMALL
     # the gathered forward exists for bf16 with d a multiple of 128 only
     assert lib.flexmoe_expert_ffn_fwd_gather(one, one, one, one, one, null, one, null, 64, 1, 64, 64, 4, 4, relu,
-                                             bf16, one, one, one, 1 << 20, null) == binding.UNSUPPORTED
+                                             bf16, one, null, one, one, 1 << 20, null) == binding.UNSUPPORTED
     assert lib.flexmoe_expert_ffn_fwd_gather(one, one, one, one, one, null, one, null, 64, 1, 128, 64, 4, 4, relu,
-                                             binding.F32, one, one, one, 1 << 20, null) == binding.UNSUPPORTED
+                                             binding.F32, one, null, one, one, 1 << 20, null) == binding.UNSUPPORTED
     # the top-1 forward needs d and f multiples of 128
     assert lib.flexmoe_expert_ffn_fwd_top1(one, one, one, one, one, null, one, null, 64, 128, 64, 4, 4, relu, bf16, one,
-                                           one, one, 1 << 20, null) == binding.UNSUPPORTED
+                                           null, one, one, 1 << 20, null) == binding.UNSUPPORTED
     assert lib.flexmoe_expert_ffn_fwd_top1(one, one, one, one, one, null, one, null, 64, 128, 128, 4, 4, relu, bf16, one,
-                                           null, one, 1 << 20, null) == binding.INVALID_ARG
-    assert lib.flexmoe_expert_ffn_bwd_top1(one, one, one, one, one, one, one, one, 64, 128, 64, 4, 4, relu, bf16, one,
+                                           null, null, one, 1 << 20, null) == binding.INVALID_ARG
+    assert lib.flexmoe_expert_ffn_bwd_top1(one, one, one, null, one, one, one, one, one, 64, 128, 64, 4, 4, relu, bf16, one,
                                            one, one, one, 1 << 20, null) == binding.UNSUPPORTED
     # a placement table that leaves an expert without a vExpert (host arrays: these are read)
     off = (ctypes.c_int32 * 3)(0, 2, 2)

@@ -509,6 +509,44 @@ def test_top1_backward_equals_the_staged_backward(api, name):
     assert not bool(L.dxp.any()), "the fused backward must not touch dxp"
 
 
+@pytest.mark.parametrize("name", ["gpt_small", "gpt_dma", "gpt_dma_seg", "swin_small", "tiny_f32", "gelu_tanh"])
+def test_backward_with_kept_activations_equals_the_recomputing_backward(api, name):
+    """The forward pass may leave act(Hpre) in a buffer of the caller's, and the backward pass then skips
+    computing and storing it: the kept tensor is what the recomputing backward derives from hpre, and dX, dW1,
+    dW2 are the same bits (direct-to-LDS and register-staged paths, shared and separate backward launches,
+    the top-1 calls, fp32)."""
+    binding, layer_mod = api
+    if name == "tiny_f32":
+        cfg = W.scaled(W.CONFIGS["tiny"], N=301, E=5, V=8, k=2, backward=True, max_rep=3)
+    elif name == "gelu_tanh":
+        cfg = W.scaled(SMALL["gpt_dma"], act=W.ACT_GELU_TANH)
+    else:
+        cfg = SMALL[name]
+    cfg = W.scaled(cfg, backward=True)
+    inp = W.make_layer_inputs(cfg)
+    dev = upload(layer_mod, inp)
+    rep = W.placement_from_loads(W.prior_loads(cfg), cfg.V, cfg.max_rep, shuffle_seed=4)
+    grads = {}
+    for keep in (False, True):
+        L = layer_mod.MoELayer(cfg.N, cfg.d, cfg.f, cfg.E, cfg.k, cfg.V, cfg.dtype, cfg.act, backward=True, keep_h=keep)
+        assert (L.h is not None) == keep
+        L.forward(dev["x"], dev["wg"], dev["w1"], dev["w2"], *rep)
+        top1 = keep and L.k == 1 and L.dtype_code == binding.BF16 and L.f % 128 == 0
+        (L.backward_top1 if top1 else L.backward)(dev["dy"], dev["w1"], dev["w2"])
+        torch.cuda.synchronize()
+        grads[keep] = {n: getattr(L, n).clone() for n in ("y", "dx", "dw1", "dw2")}
+        if keep:
+            kept = L.h.clone()
+        else:
+            # the recomputing backward leaves act(Hpre) behind dHpre in its workspace
+            esz = L.hpre.element_size()
+            off = (L.A * L.f * esz + 255) // 256 * 256 if L.dtype_code == binding.BF16 else L.A * L.f * esz
+            recomputed = L.ws[off:off + L.A * L.f * esz].view(L.hpre.dtype).view(L.A, L.f).clone()
+    assert torch.equal(kept, recomputed), "act(Hpre): kept by the forward pass vs computed again by the backward pass"
+    for n in grads[True]:
+        assert torch.equal(grads[True][n], grads[False][n]), n
+
+
 def test_gathered_forward_refuses_what_it_cannot_do(api):
     binding, layer_mod = api
     cfg = SMALL["bert_small"]                       # d = 328: not a multiple of 128
