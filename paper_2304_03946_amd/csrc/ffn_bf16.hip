@@ -219,7 +219,10 @@ static hipError_t launch_wgrad(const FfnArgs& a, const void* L, const void* R, i
                                void* ws, hipStream_t s) {
   unsigned grid;
   const WgradDmaArgs g = wgrad_dma_args(a, L, R, M, NC, dw, ws_tail, ws, &grid);
-  hipLaunchKernelGGL(wgrad_gemm_dma_bf16, dim3(grid), dim3(kGemmThreads), 0, s, g);
+  if (M % BM == 0 && NC % BN == 0)      // whole output tiles: one persistent workgroup per compute unit
+    hipLaunchKernelGGL(wgrad_gemm_persist_bf16, dim3(std::min(grid, (unsigned)kComputeUnits)), dim3(kGemmThreads), 0, s, g);
+  else
+    hipLaunchKernelGGL(wgrad_gemm_dma_bf16, dim3(grid), dim3(kGemmThreads), 0, s, g);
   launch_wgrad_reduce(a, g, s);
   return hipGetLastError();
 }

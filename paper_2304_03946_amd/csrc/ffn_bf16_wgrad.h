@@ -26,15 +26,19 @@ struct WgradJob {
 //   boff      [E + 1]  int: expert e's non-empty buckets are entries boff[e] .. boff[e+1] of the two lists below
 //   bstart    [V]      int: first row of the bucket
 //   brows     [V]      int: rows of the bucket
+//   etiles    [E]      int: 32-token K tiles of the expert (sum over its buckets of ceil(rows / 32))
+//   njobs     [1]      int: entries of `jobs` in use
 struct WgradPlan {
   int4* jobs;
   int4* table;
   int* boff;
   int* bstart;
   int* brows;
+  int* etiles;
+  int* njobs;
 };
 __host__ __device__ inline size_t wgrad_plan_bytes(int seg_rows_max, int E, int V) {
-  return ((size_t)seg_rows_max + FLEXMOE_MAX_EXPERTS) * sizeof(int4) + ((size_t)E + 1 + 2 * (size_t)V) * sizeof(int);
+  return ((size_t)seg_rows_max + FLEXMOE_MAX_EXPERTS) * sizeof(int4) + (2 * (size_t)E + 2 + 2 * (size_t)V) * sizeof(int);
 }
 __host__ __device__ inline WgradPlan wgrad_plan_at(void* base, int seg_rows_max, int E, int V) {
   WgradPlan p;
@@ -43,6 +47,8 @@ __host__ __device__ inline WgradPlan wgrad_plan_at(void* base, int seg_rows_max,
   p.boff = (int*)(p.table + FLEXMOE_MAX_EXPERTS);
   p.bstart = p.boff + E + 1;
   p.brows = p.bstart + V;
+  p.etiles = p.brows + V;
+  p.njobs = p.etiles + E;
   return p;
 }
 
@@ -133,7 +139,9 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_plan_kernel(const int32_t*
     if (lane == 0) {
       sh.boff[E] = total_b;
       plan.boff[E] = total_b;
+      plan.njobs[0] = min(total, seg_rows_max);
     }
+    for (int e = lane; e < E; e += kWave) plan.etiles[e] = sh.tiles[e];
     for (int w = total + lane; w < seg_rows_max; w += kWave) plan.jobs[w] = make_int4(-1, 0, 0, 0);
   }
   __syncthreads();
@@ -356,6 +364,173 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_dma_bf16(const WgradD
   __shared__ __align__(1024) unsigned char stage3[kDmaStageBytes];
   __shared__ WgradShared sh;
   wgrad_dma_block(p, blockIdx.x, stage0, stage1, stage2, stage3, sh);
+}
+
+// =============================================================================================
+// wgrad_gemm_persist: the same product on one workgroup per compute unit that walks the output tiles
+// (see rows_gemm_persist_bf16 for why): workgroup b takes positions b, b + G, .. of the patched grid
+// over (job, m tile) x (n tile), finds each tile's job in the plan with scalar loads, and issues the first
+// K tiles of its next output tile while the current K loop drains.  For output matrices that are a whole
+// number of 256 x 256 tiles (every benchmark shape; the host falls back to wgrad_gemm_dma_bf16 otherwise),
+// so the per-lane load offsets are the same for every tile and only scalars change from tile to tile.
+// An expert without tokens contracts four all-zero K tiles (the pipeline's minimum) and stores zeros.
+// =============================================================================================
+typedef const int __attribute__((address_space(4)))* ConstIntPtr;
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+typedef const i32x4_t __attribute__((address_space(4)))* ConstInt4Ptr;
+
+struct WgradIssueV {
+  DmaSrcTok l_src, r_src;           // per-lane offsets: the same for every tile of the launch
+  ConstIntPtr bstart, brows;        // the expert's bucket list in the plan
+  int M, NC, nb, T;
+  int bi, issued;
+  const bf16_t* lbase;              // L + m0, R + n0: first column of the tile in token row 0
+  const bf16_t* rbase;
+  const bf16_t* lp;                 // token row 0 of the next K tile, first column of the tile
+  const bf16_t* rp;
+  int rows_left;                    // rows of bucket bi from that row on
+  __device__ __forceinline__ void seek(int bucket, int koff) {
+    bi = bucket;
+    int start = 0;
+    rows_left = 0;
+    if (nb > 0) {
+      start = bstart[bi];
+      rows_left = brows[bi] - koff;
+    }
+    lp = lbase + ((size_t)start + koff) * M;
+    rp = rbase + ((size_t)start + koff) * NC;
+  }
+  __device__ __forceinline__ void begin() {}
+  __device__ __forceinline__ void part(lds_byte_t* stage, int q) const {
+    const int kv = issued < T ? rows_left : 0;
+    if (q < 4) l_src.part(stage, lp, kv, q);
+    else r_src.part(stage + kDmaTileBytes, rp, kv, q - 4);
+  }
+  __device__ __forceinline__ void end() {
+    ++issued;
+    if (issued < T) {
+      rows_left -= DK;
+      lp += (size_t)DK * M;
+      rp += (size_t)DK * NC;
+      if (rows_left <= 0) seek(min(bi + 1, nb - 1), 0);
+    }
+  }
+};
+
+__global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_persist_bf16(const WgradDmaArgs p) {
+  __shared__ __align__(1024) unsigned char stage0[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage1[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
+  __shared__ __align__(1024) unsigned char stage3[kDmaStageBytes];
+  lds_byte_t* const s0 = (lds_byte_t*)stage0;
+  lds_byte_t* const s1 = (lds_byte_t*)stage1;
+  lds_byte_t* const s2 = (lds_byte_t*)stage2;
+  lds_byte_t* const s3 = (lds_byte_t*)stage3;
+  const ConstInt4Ptr jobs = (ConstInt4Ptr)p.plan.jobs;
+  const ConstIntPtr boff = (ConstIntPtr)p.plan.boff, bstart = (ConstIntPtr)p.plan.bstart;
+  const ConstIntPtr brows = (ConstIntPtr)p.plan.brows, etiles = (ConstIntPtr)p.plan.etiles;
+  const int M = p.M, NC = p.NC, m_tiles = p.m_tiles, n_tiles = p.n_tiles, seg_tiles = p.seg_tiles;
+  const int grid_rows = ((ConstIntPtr)p.plan.njobs)[0] * m_tiles;
+  const unsigned total = patched_grid(grid_rows, n_tiles);
+  const unsigned G = gridDim.x;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+
+  struct Tile {
+    int e, seg, nseg, slot, m0, n0, KT;
+  };
+  // the first position from idx on (steps of G) that holds a tile
+  auto find = [&](unsigned* idx, int* grow, int* nt) {
+    for (; *idx < total; *idx += G)
+      if (patched_tile(*idx, grid_rows, n_tiles, grow, nt)) return true;
+    return false;
+  };
+  // tile -> its description and its K-tile sequence (scalars only)
+  auto describe = [&](int grow, int nt, Tile* t, WgradIssueV* is) {
+    const i32x4_t job = jobs[grow / m_tiles];
+    t->e = job[0];
+    t->seg = job[1];
+    t->nseg = job[2];
+    t->slot = job[3];
+    t->m0 = (grow % m_tiles) * BM;
+    t->n0 = nt * BN;
+    const int b0 = boff[t->e], nb = boff[t->e + 1] - b0, Te = etiles[t->e];
+    // this job's K tiles [lo, hi) of the expert's sequence, and the bucket / offset where they start
+    const int lo = t->nseg > 1 ? t->seg * seg_tiles : 0;
+    const int hi = t->nseg > 1 ? min(Te, lo + seg_tiles) : Te;
+    int bi = 0, skip = lo;
+    while (bi < nb - 1 && skip >= (brows[b0 + bi] + DK - 1) / DK) {
+      skip -= (brows[b0 + bi] + DK - 1) / DK;
+      ++bi;
+    }
+    const int T = hi - lo;
+    t->KT = max(4, (T + 3) & ~3);               // padded with all-zero tiles
+    is->bstart = bstart + b0;
+    is->brows = brows + b0;
+    is->nb = nb;
+    is->T = T;
+    is->issued = 0;
+    is->lbase = p.L + t->m0;
+    is->rbase = p.R + t->n0;
+    is->seek(bi, skip * DK);
+  };
+
+  unsigned idx = blockIdx.x;
+  int grow, nt;
+  if (!find(&idx, &grow, &nt)) return;
+  WgradIssueV issue;
+  issue.l_src.init(M, BM);
+  issue.r_src.init(NC, BN);
+  issue.M = M;
+  issue.NC = NC;
+  Tile t;
+  describe(grow, nt, &t, &issue);
+  dma_prefetch3(s0, s1, s2, issue);
+  float* const patch = (float*)stage3 + wave * (32 * 64);      // wave-private; stage 3 is the one the next tile has not touched yet
+
+  for (;;) {
+    f32x16 acc[MB][NB];
+    zero_acc(acc);
+    unsigned nidx = idx + G;
+    int ngrow, nnt;
+    const bool has_next = find(&nidx, &ngrow, &nnt);
+    // (none: this tile's first K tiles once more, waited for below and never used)
+    WgradIssueV next = issue;
+    Tile tn;
+    describe(has_next ? ngrow : grow, has_next ? nnt : nt, &tn, &next);
+    dma_pipeline_cont<true, true>(s0, s1, s2, s3, acc, issue, t.KT, next, wm, wn, []() {}, [](WgradIssueV&) {});
+
+    const int col_base = t.n0 + wn * (NB * 32);
+    auto none = [](const EpiIdx&) { return make_uint2(0, 0); };
+    if (t.nseg == 1) {
+      bf16_t* out = p.dw + (size_t)t.e * M * NC + (size_t)t.m0 * NC + col_base;      // the wave's block of the tile
+      EpiAddr<2> addr;
+      addr.init(wm, NC);
+      epilogue_rounds<false>(
+          patch, patch, acc, none,
+          [](const EpiIdx&, float4 c, uint2) { return EpiOut{pack4(c.x, c.y, c.z, c.w), make_uint2(0, 0)}; },
+          [&](const EpiIdx& x, const EpiOut& o) { store_nt8(addr.at(out, x), o.a); });      // written once
+    } else {
+      // one of several segments: the fp32 tile goes to the workspace for wgrad_reduce_kernel
+      float* out = p.partial + (size_t)(t.slot + t.seg) * M * NC + (size_t)t.m0 * NC + col_base;
+      EpiAddr<4> addr;
+      addr.init(wm, NC);
+      epilogue_rounds<false>(
+          patch, patch, acc, none,
+          [](const EpiIdx&, float4 c, uint2) {
+            return EpiOut{make_uint2(__float_as_uint(c.x), __float_as_uint(c.y)),
+                          make_uint2(__float_as_uint(c.z), __float_as_uint(c.w))};
+          },
+          [&](const EpiIdx& x, const EpiOut& o) { *(uint4*)addr.at(out, x) = make_uint4(o.a.x, o.a.y, o.b.x, o.b.y); });
+    }
+    if (!has_next) break;
+    t = tn;
+    issue = next;
+    idx = nidx;
+    grow = ngrow;
+    nt = nnt;
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): nothing may still be landing in LDS when the workgroup ends
 }
 
 // The three GEMMs of the backward pass that only depend on the dH kernel -- dXp = dHpre . W1^T,
