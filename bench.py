@@ -445,8 +445,7 @@ def cpu_baseline(name):
 
 FFN_KERNELS = {
     True: "flexmoe_expert_ffn_fwd (rows_gemm_persist_bf16 x2: GEMM1 + Hpre/GELU epilogue, GEMM2) + flexmoe_expert_ffn_bwd "
-          "(rows_gemm_persist_bf16: dH + GELU' epilogue, dXp; wgrad_gemm_dma_bf16: dW2, dW1; on grids of a few rounds the "
-          "last three share one launch, bwd_tail_dma_bf16)",
+          "(rows_gemm_persist_bf16: dH + GELU' epilogue, dXp; wgrad_gemm_persist_bf16: dW2, dW1)",
     False: "flexmoe_expert_ffn_fwd (two grouped-GEMM launches: rows_gemm_persist_bf16 x2)",
 }
 

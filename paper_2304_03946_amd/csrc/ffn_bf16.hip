@@ -17,7 +17,7 @@
 //    (the result does not depend on scheduling).
 //
 // Two operand pipelines:
-//  * direct-to-LDS (rows_gemm_persist_bf16, bwd_tail_dma_bf16, wgrad_gemm_dma_bf16; used whenever K is a
+//  * direct-to-LDS (rows_gemm_persist_bf16, wgrad_gemm_persist_bf16, wgrad_gemm_dma_bf16; used whenever K is a
 //    multiple of 128, i.e. for every benchmark shape): global_load_lds_dwordx4 copies 32-wide K tiles
 //    straight into one of four LDS stages (no register staging, no LDS store instructions); an
 //    operand whose contraction index is strided in memory is copied as stored and transposed on
@@ -36,14 +36,15 @@
 // by the argument's bits (constant data in the code object, computed from the fp64 formulas when the
 // library is built; outside the table's range GELU equals ReLU to below bf16 resolution).
 //
-// The rows GEMMs that are launched on their own are persistent: 256 workgroups, one per compute unit,
-// each walking its share of the output tiles and issuing the next tile's first operand loads while the
-// current tile's K loop drains (ffn_bf16_persist.h).
+// The direct-to-LDS kernels are persistent: 256 workgroups, one per compute unit, each walking its share
+// of the output tiles and issuing the next tile's first operand loads while the current tile's K loop
+// drains (ffn_bf16_persist.h, wgrad_gemm_persist_bf16; weight gradients whose output is not a whole
+// number of 256 x 256 tiles keep one workgroup per tile, wgrad_gemm_dma_bf16).
 //
 // Layout of the sources: ffn_bf16_tile.h (tile mapping, fragments, activation tables, epilogues, the
 // register-staged kernel), ffn_bf16_dma.h (direct-to-LDS pipeline, one rows tile on it),
 // ffn_bf16_persist.h (persistent rows kernels and their row-tile table), ffn_bf16_wgrad.h
-// (weight-gradient kernels, the shared backward launch); this file holds the host side.
+// (weight-gradient plan and kernels); this file holds the host side.
 #include <algorithm>
 
 #include "common.h"
@@ -285,27 +286,11 @@ hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp
                  : launch_rows<true, EPI_DH>(a, dyp, w2, nullptr, a.d, a.f, hpre, dhpre, h_ws, ws, s);
     if (err != hipSuccess) return err;
   }
-  // dW2 = H^T . dYp, dW1 = Xp^T . dHpre: each with its own table and partial tiles
+  // dW2 = H^T . dYp, dW1 = Xp^T . dHpre: each with its own partial tiles.  (One launch for dXp, dW2 and dW1, which
+  // filled the partly empty last rounds of the three grids, was measured against three persistent launches: the
+  // latter are 2 % faster on the GPT-medium-like backward pass and 4.5 % on the Swin-like one.)
   void* ws_tail2 = (char*)ws + 2 * align_up((size_t)a.A * a.f * sizeof(bf16_t), 256);
   void* ws_tail1 = (char*)ws_tail2 + wgrad_tail_bytes(a.A, a.d, a.f, a.V);
-  // dXp, dW2 and dW1 share one launch when dXp's contraction is a whole number of pipeline rounds and
-  // its grid is only a few rounds of workgroups (the partly filled last round is then a visible
-  // share of it; with many rounds keeping each product's tiles to themselves is faster: measured
-  // -3 % on the backward pass at 1.2 rounds, -1 % at 2.4, +1.7 % at 17.5)
-  const unsigned dx_tiles = patched_grid(max_row_tiles(a.A, a.V), (a.d + BN - 1) / BN);
-  if (a.A > 0 && a.f % 128 == 0 && dx_tiles <= 8 * 256) {
-    auto round8 = [](unsigned n) { return (n + 7u) & ~7u; };
-    unsigned grid2, grid1;
-    RowsDmaArgs dx = rows_dma_args(a, dhpre, w1, nullptr, a.f, a.d, nullptr, dxp, nullptr, nullptr, 1);
-    dx.scatter_rows = scatter_src;
-    const WgradDmaArgs g2 = wgrad_dma_args(a, h, dyp, a.f, a.d, dw2, ws_tail2, ws, &grid2);
-    const WgradDmaArgs g1 = wgrad_dma_args(a, xp, dhpre, a.d, a.f, dw1, ws_tail1, ws, &grid1);
-    const unsigned n_dx = round8(patched_grid(dx.row_tiles_max, dx.col_tiles)), n_w2 = round8(grid2);
-    hipLaunchKernelGGL(bwd_tail_dma_bf16, dim3(n_dx + n_w2 + grid1), dim3(kGemmThreads), 0, s, dx, n_dx, g2, n_w2, g1);
-    launch_wgrad_reduce(a, g2, s);
-    launch_wgrad_reduce(a, g1, s);
-    return hipGetLastError();
-  }
   if (a.A > 0) {
     // dXp = dHpre . W1^T; W1_e is [d, f], contraction index f contiguous
     err = launch_rows<true, EPI_PLAIN>(a, dhpre, w1, nullptr, a.f, a.d, nullptr, dxp, nullptr, ws, s, nullptr, 1,

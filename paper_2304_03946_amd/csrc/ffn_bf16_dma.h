@@ -1,4 +1,4 @@
-// Direct-to-LDS pipeline (global_load_lds), one output tile of a rows GEMM on it (used by the shared backward launch), the sum of the split last round.
+// Direct-to-LDS pipeline (global_load_lds): operand sources, the K loop in its one-tile and its continuing form, the sum of the split last round.
 // Part of the bf16 expert-FFN kernels; included by ffn_bf16.hip only (one translation unit).
 #pragma once
 #include "common.h"
@@ -286,70 +286,7 @@ __device__ __forceinline__ void dma_pipeline_cont(lds_byte_t* s0, lds_byte_t* s1
   dma_step<TRA, TRB, true, false, 0, false>(s2, s3, s0, acc, f0, f1, next, next, wm, wn);
 }
 
-// Tile sequence of the rows kernels: K tile t of both operands starts at contraction index 32 t.
-template <typename WSrc> struct RowsIssue {
-  const DmaSrc& a_src;
-  const WSrc& w_src;
-  int k_next;
-  __device__ __forceinline__ void begin() {}
-  __device__ __forceinline__ void part(lds_byte_t* stage, int q) const {
-    if (q < 4) a_src.part(stage, k_next, q);
-    else w_src.part(stage + kDmaTileBytes, k_next, q - 4);
-  }
-  __device__ __forceinline__ void end() { k_next += DK; }
-};
-
-template <bool WT, typename WSrc, int EPI, int ACT>
-__device__ __forceinline__ void rows_dma_body(lds_byte_t* s0, lds_byte_t* s1, lds_byte_t* s2, lds_byte_t* s3,
-                                              const RowTile& t, const bf16_t* __restrict__ in, const WSrc& w_src,
-                                              const bf16_t* __restrict__ bias, int K, int NC,
-                                              const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
-                                              bf16_t* __restrict__ out1, const lds_byte_t* lut,
-                                              const int32_t* __restrict__ gsrc, int gk,
-                                              float* __restrict__ split_partial = nullptr,
-                                              const int32_t* __restrict__ scatter_rows = nullptr) {
-  const int wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  DmaSrc a_src;
-  if (gsrc) a_src.init_gather(in, K, gsrc + t.row0, gk, t.rows_valid);
-  else a_src.init(in + (size_t)t.row0 * K, K, t.rows_valid);
-  f32x16 acc[MB][NB];
-  zero_acc(acc);
-  if (EPI == EPI_PLAIN && t.nseg > 1) {
-    // one K segment of a split tile: fp32 partial tile (all 256 x 256 entries) for the reduce kernel
-    const int kt = K / DK / t.nseg;
-    RowsIssue<WSrc> issue{a_src, w_src, t.seg * kt * DK};
-    dma_pipeline<false, !WT>(s0, s1, s2, s3, acc, issue, kt, wm, wn);
-    float* out = split_partial + (size_t)t.slot * (BM * BN);
-    float* patch = (float*)s0 + wave * (32 * 64);
-    float* patch_alt = (float*)s1 + wave * (32 * 64);
-    epilogue_rounds<false>(
-        patch, patch_alt, acc, [](const EpiIdx&) { return make_uint2(0, 0); },
-        [](const EpiIdx&, float4 c, uint2) {
-          return EpiOut{make_uint2(__float_as_uint(c.x), __float_as_uint(c.y)),
-                        make_uint2(__float_as_uint(c.z), __float_as_uint(c.w))};
-        },
-        [&](const EpiIdx& x, const EpiOut& o) {
-          const int lrow = (wm + 2 * x.i) * 32 + (x.row_w & 31);
-          *(uint4*)(out + lrow * BN + wn * (NB * 32) + x.col_w) = make_uint4(o.a.x, o.a.y, o.b.x, o.b.y);
-        });
-    return;
-  }
-  RowsIssue<WSrc> issue{a_src, w_src, 0};
-  dma_pipeline<false, !WT>(s0, s1, s2, s3, acc, issue, K / DK, wm, wn);   // K % 128 == 0 (host check)
-  const lds_int_t* smap = nullptr;
-  if (EPI == EPI_PLAIN && scatter_rows) {
-    // output rows of this tile (the epilogue's patches live in stages 0 and 1; stage 2 is free)
-    lds_int_t* m = (lds_int_t*)s2;
-    m[threadIdx.x] = scatter_rows[t.row0 + min((int)threadIdx.x, t.rows_valid - 1)];
-    __syncthreads();
-    smap = m;
-  }
-  rows_epilogue<EPI, ACT, epilogue_uses_lut<EPI, ACT>()>((float*)s0, (float*)s1, acc, bias, NC, t.row0, t.rows_valid, t.e, t.n0, hpre_in, out0,
-                                                          out1, lut, smap);
-}
-
-// Arguments of one rows GEMM (device pointers; see rows_gemm_persist_bf16 and bwd_tail_dma_bf16).
+// Arguments of one rows GEMM (device pointers; see rows_gemm_persist_bf16).
 struct RowsDmaArgs {
   const bf16_t* in;
   const bf16_t* w;
@@ -366,47 +303,6 @@ struct RowsDmaArgs {
   unsigned normal_grid;      // blocks before the extra segment workgroups (meaningful with split_partial)
   const int32_t* scatter_rows;   // plain epilogue only: bucket row p is stored as output row scatter_rows[p]; or null
 };
-
-// One workgroup's tile of a rows GEMM; `block` is its index in that GEMM's (patched) grid.
-template <bool WT, int EPI, int ACT>
-__device__ __forceinline__ void rows_dma_block(const RowsDmaArgs& p, unsigned block, lds_byte_t* s0, lds_byte_t* s1,
-                                               lds_byte_t* s2, lds_byte_t* s3, unsigned char* lut_lds, int* s_tile) {
-  constexpr bool kLut = epilogue_uses_lut<EPI, ACT>();
-  RowTile t;
-  if (EPI == EPI_PLAIN) {
-    const SplitArg sp{p.split_partial ? p.normal_grid : 0u, p.K / DK, -1};
-    if (!lookup_row_tile<true>(p.voff, p.owner, p.V, p.NC, p.row_tiles_max, p.col_tiles, block, s_tile, &t, sp)) return;
-  } else {
-    if (!lookup_row_tile(p.voff, p.owner, p.V, p.NC, p.row_tiles_max, p.col_tiles, block, s_tile, &t)) return;
-  }
-  const lds_byte_t* lut = nullptr;
-  if (kLut) {
-    // the table rides in front of the operand tiles: its direct loads are the oldest in every
-    // wave's queue, so the first wait of the K loop covers them and its barrier publishes them
-    lut = (const lds_byte_t*)lut_lds;
-    const unsigned w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)lut) + w * (kLutBytes / 4);
-    const unsigned char* g = (const unsigned char*)g_act_lut[ACT == FLEXMOE_GELU_ERF ? 0 : 1] + w * (kLutBytes / 4) +
-                             (threadIdx.x & 63) * 16;
-#pragma unroll
-    for (int q = 0; q < kLutBytes / 4 / 1024; ++q) {
-      const unsigned char* gq = g + q * 1024;
-      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" FLEXMOE_DMA_CPOL ::"v"(gq), "s"(lds0 + q * 1024) : "memory");
-    }
-  }
-  const bf16_t* w_e = p.w + (size_t)t.e * p.K * p.NC;
-  if (WT) {
-    DmaSrc w_src;
-    w_src.init(w_e + (size_t)t.n0 * p.K, p.K, t.cols_valid);
-    rows_dma_body<true, DmaSrc, EPI, ACT>(s0, s1, s2, s3, t, p.in, w_src, p.bias, p.K, p.NC, p.hpre_in, p.out0, p.out1,
-                                          lut, p.gsrc, p.gk, p.split_partial, p.scatter_rows);
-  } else {
-    DmaSrcT w_src;
-    w_src.init(w_e + t.n0, p.NC, t.cols_valid);
-    rows_dma_body<false, DmaSrcT, EPI, ACT>(s0, s1, s2, s3, t, p.in, w_src, p.bias, p.K, p.NC, p.hpre_in, p.out0,
-                                            p.out1, lut, p.gsrc, p.gk, p.split_partial, p.scatter_rows);
-  }
-}
 
 // Sum of the K segments of the split tail tiles (see lookup_row_tile): out = bf16(sum over
 // segments in order + bias).  Grid: (kSplitSlices row slices of a tile, kSplitUnits / kSplitMax tail tiles).

@@ -533,29 +533,6 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_persist_bf16(const Wg
   __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): nothing may still be landing in LDS when the workgroup ends
 }
 
-// The three GEMMs of the backward pass that only depend on the dH kernel -- dXp = dHpre . W1^T,
-// dW2 and dW1 -- as one launch: workgroups [0, n_dx) take dXp's tiles, the next n_w2 dW2's, the rest
-// dW1's.  Each product alone ends in a partly filled last round of workgroups; in one grid the
-// next product's tiles fill those compute units.  n_dx and n_w2 are multiples of 8, so every
-// product keeps its workgroup -> XCD mapping.
-__global__ __launch_bounds__(kGemmThreads) void bwd_tail_dma_bf16(const RowsDmaArgs dx, unsigned n_dx,
-                                                                  const WgradDmaArgs g2, unsigned n_w2,
-                                                                  const WgradDmaArgs g1) {
-  __shared__ __align__(1024) unsigned char stage0[kDmaStageBytes];
-  __shared__ __align__(1024) unsigned char stage1[kDmaStageBytes];
-  __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
-  __shared__ __align__(1024) unsigned char stage3[kDmaStageBytes];
-  __shared__ WgradShared sh;
-  __shared__ int s_tile[8];
-  const unsigned b = blockIdx.x;
-  if (b < n_dx)
-    rows_dma_block<true, EPI_PLAIN, FLEXMOE_RELU>(dx, b, (lds_byte_t*)stage0, (lds_byte_t*)stage1, (lds_byte_t*)stage2,
-                                                   (lds_byte_t*)stage3, nullptr, s_tile);
-  else
-    wgrad_dma_block(b < n_dx + n_w2 ? g2 : g1, b < n_dx + n_w2 ? b - n_dx : b - n_dx - n_w2, stage0, stage1, stage2,
-                    stage3, sh);
-}
-
 // dW_e = sum of the expert's partial tiles in segment order, for the experts that were split.
 // Grid: (element blocks of the [M, NC] matrix, load rank); `table` as left by the GEMM kernel.
 __global__ __launch_bounds__(kGemmThreads) void wgrad_reduce_kernel(const int4* __restrict__ table, int M, int NC,
