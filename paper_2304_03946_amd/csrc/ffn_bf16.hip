@@ -202,11 +202,14 @@ static WgradDmaArgs wgrad_dma_args(const FfnArgs& a, const void* L, const void* 
                       (bf16_t*)dw};
 }
 
-// The work list both weight-gradient products of a backward call read (one small workgroup).
-static void launch_wgrad_plan(const FfnArgs& a, void* ws, hipStream_t s) {
+// The work list both weight-gradient products of a backward call read and (with tokens) the row-tile table
+// of its rows products: one small launch.
+static void launch_bwd_plan(const FfnArgs& a, void* ws, hipStream_t s) {
   const int seg_rows_max = wgrad_seg_rows_max(a.A, a.d, a.f, a.E, a.V);
-  hipLaunchKernelGGL(wgrad_plan_kernel, dim3(1), dim3(kGemmThreads), 0, s, a.voff, a.owner, a.E, a.V,
-                     wgrad_seg_tiles(a.A, a.d, a.f), seg_rows_max, wgrad_plan_at(wgrad_plan_ws(a, ws), seg_rows_max, a.E, a.V));
+  const int row_blocks = a.A > 0 ? std::max(1, std::min(64, (max_row_tiles(a.A, a.V) + kGemmThreads - 1) / kGemmThreads)) : 0;
+  hipLaunchKernelGGL(ffn_bwd_plan_kernel, dim3(1 + row_blocks), dim3(kGemmThreads), 0, s, a.voff, a.owner, a.E, a.V,
+                     wgrad_seg_tiles(a.A, a.d, a.f), seg_rows_max,
+                     wgrad_plan_at(wgrad_plan_ws(a, ws), seg_rows_max, a.E, a.V), rows_tab_ws(a, ws));
 }
 
 static void launch_wgrad_reduce(const FfnArgs& a, const WgradDmaArgs& g, hipStream_t s) {
@@ -278,9 +281,8 @@ hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp
   bf16_t* h_ws = (bf16_t*)((char*)ws + align_up((size_t)a.A * a.f * sizeof(bf16_t), 256));
   const bf16_t* h = h_kept ? (const bf16_t*)h_kept : h_ws;
   hipError_t err;
-  launch_wgrad_plan(a, ws, s);
+  launch_bwd_plan(a, ws, s);
   if (a.A > 0) {
-    launch_rows_plan(a, ws, s);
     // dH = dYp . W2^T fused with act'(Hpre); W2_e is [f, d], contraction index d contiguous
     err = h_kept ? launch_rows<true, EPI_DHQ>(a, dyp, w2, nullptr, a.d, a.f, hpre, dhpre, nullptr, ws, s)
                  : launch_rows<true, EPI_DH>(a, dyp, w2, nullptr, a.d, a.f, hpre, dhpre, h_ws, ws, s);

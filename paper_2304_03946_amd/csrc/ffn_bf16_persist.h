@@ -28,9 +28,9 @@ typedef const i32x4 __attribute__((address_space(4)))* RowTabPtr;
 // tab[0] = {row tiles of the bucket list, 0, 0, 0}; tab[1 + t] = {first row, rows, expert, 0} of row tile t.
 __host__ __device__ inline size_t rows_tab_bytes(int row_tiles_max) { return ((size_t)row_tiles_max + 1) * sizeof(i32x4); }
 
-__global__ __launch_bounds__(kGemmThreads) void rows_plan_kernel(const int32_t* __restrict__ voff,
-                                                                 const int32_t* __restrict__ owner, int V,
-                                                                 i32x4* __restrict__ tab) {
+// Workgroup `block` of `nblocks` that fill the table (each derives the bucket prefix again and writes its share of the rows).
+__device__ __forceinline__ void rows_plan_block(const int32_t* __restrict__ voff, const int32_t* __restrict__ owner, int V,
+                                                i32x4* __restrict__ tab, int block, int nblocks) {
   __shared__ int cum[FLEXMOE_MAX_VEXPERTS + 1];      // cum[v] = row tiles before bucket v
   __shared__ int wsum[kGemmThreads / kWave];
   // two buckets per thread, inclusive scan over the workgroup
@@ -54,8 +54,8 @@ __global__ __launch_bounds__(kGemmThreads) void rows_plan_kernel(const int32_t* 
   if (2 * t + 2 <= V) cum[2 * t + 2] = excl + c0 + c1;
   __syncthreads();
   const int rows_act = cum[V];
-  if (blockIdx.x == 0 && t == 0) tab[0] = i32x4{rows_act, 0, 0, 0};
-  for (int rt = blockIdx.x * kGemmThreads + t; rt < rows_act; rt += gridDim.x * kGemmThreads) {
+  if (block == 0 && t == 0) tab[0] = i32x4{rows_act, 0, 0, 0};
+  for (int rt = block * kGemmThreads + t; rt < rows_act; rt += nblocks * kGemmThreads) {
     int lo = 0, hi = V;                              // last v with cum[v] <= rt (empty buckets share a value: take the last)
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
@@ -65,6 +65,12 @@ __global__ __launch_bounds__(kGemmThreads) void rows_plan_kernel(const int32_t* 
     const int row0 = voff[lo] + (rt - cum[lo]) * BM;
     tab[1 + rt] = i32x4{row0, min(BM, voff[lo + 1] - row0), owner[lo], 0};
   }
+}
+
+__global__ __launch_bounds__(kGemmThreads) void rows_plan_kernel(const int32_t* __restrict__ voff,
+                                                                 const int32_t* __restrict__ owner, int V,
+                                                                 i32x4* __restrict__ tab) {
+  rows_plan_block(voff, owner, V, tab, blockIdx.x, gridDim.x);
 }
 
 // The walk of one product's tiles (all values uniform over the launch).

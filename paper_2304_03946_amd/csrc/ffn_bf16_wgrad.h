@@ -3,6 +3,7 @@
 #pragma once
 #include "common.h"
 #include "ffn_bf16_dma.h"
+#include "ffn_bf16_persist.h"
 namespace flexmoe {
 // Work list of the weight-gradient kernels.  Experts are taken by descending load (ties by
 // ascending id: the long contractions start first).  An expert's contraction runs over its
@@ -65,9 +66,8 @@ struct WgradShared {
 };
 
 // One workgroup of kGemmThreads threads; see the layout above.
-__global__ __launch_bounds__(kGemmThreads) void wgrad_plan_kernel(const int32_t* __restrict__ voff,
-                                                                  const int32_t* __restrict__ owner, int E, int V,
-                                                                  int seg_tiles, int seg_rows_max, WgradPlan plan) {
+__device__ __forceinline__ void wgrad_plan_block(const int32_t* __restrict__ voff, const int32_t* __restrict__ owner, int E,
+                                                 int V, int seg_tiles, int seg_rows_max, const WgradPlan& plan) {
   __shared__ WgradPlanShared sh;
   for (int v = threadIdx.x; v < V; v += kGemmThreads) {
     sh.cnt[v] = voff[v + 1] - voff[v];
@@ -164,6 +164,16 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_plan_kernel(const int32_t*
       }
     }
   }
+}
+
+// Everything the kernels of a backward call look up, in one launch: workgroup 0 writes the work list of the
+// weight gradients, the others (if any) the row-tile table of the rows products (see rows_plan_block).
+__global__ __launch_bounds__(kGemmThreads) void ffn_bwd_plan_kernel(const int32_t* __restrict__ voff,
+                                                                    const int32_t* __restrict__ owner, int E, int V,
+                                                                    int seg_tiles, int seg_rows_max, WgradPlan plan,
+                                                                    i32x4* __restrict__ row_tab) {
+  if (blockIdx.x == 0) wgrad_plan_block(voff, owner, E, V, seg_tiles, seg_rows_max, plan);
+  else rows_plan_block(voff, owner, V, row_tab, blockIdx.x - 1, gridDim.x - 1);
 }
 
 // The job of work-list position `want` and the buckets of its expert (copied to sh); uniform over the workgroup.
