@@ -204,6 +204,81 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 template <int PATTERN>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void loop_256x128(const LoopArgs p) { loop_body<2, 3, PATTERN>(p); }
 
+// ---- E: the same 256 x 256 tile and LDS stages with eight waves (two per SIMD) ----------------------------------
+// Wave w covers rows (wm + 2 i) * 32, i < 4, and two 32-column blocks: 128 x 64 outputs = 128 accumulator registers,
+// so two waves fit a SIMD and one can issue while the other waits.  Contiguous loads, four per wave and K tile.
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void loop_256x256_8waves(const LoopArgs p) {
+  constexpr int kStage = 32768, STAGES = 4;
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[STAGES * kStage];
+  for (int i = threadIdx.x; i < STAGES * kStage / 4; i += 512) ((uint32_t*)lds)[i] = 0x3e003e00u;
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = (wave >> 1) & 1, wn = wave & 1, hh = wave >> 2;
+  const int r = lane & 31, h = lane >> 5;
+  const int x = blockIdx.x % 8, j = blockIdx.x / 8;
+  const unsigned char* gp = p.g + ((size_t)x * (32 / p.share) + (j % 32) / p.share) * p.window + threadIdx.x * 16;
+  size_t goff = ((size_t)(j % p.share) * 65536) % p.window;
+  if (goff + kStage > p.window) goff = 0;
+  f32x16 acc[4][2];
+  for (int i = 0; i < 4; ++i) for (int c = 0; c < 2; ++c) for (int q = 0; q < 16; ++q) acc[i][c][q] = 0.f;
+  bf16x8 a0[4], b0[2], a1[4], b1[2];
+  auto frags = [&](bf16x8 (&a)[4], bf16x8 (&b)[2], const lds_byte_t* st, int ks) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a[i] = *(const __attribute__((address_space(3))) bf16x8*)(st + dma_off((wm + 2 * i) * 32 + r, 2 * ks + h));
+#pragma unroll
+    for (int c = 0; c < 2; ++c) b[c] = *(const __attribute__((address_space(3))) bf16x8*)(st + 16384 + dma_off((wn * 4 + hh * 2 + c) * 32 + r, 2 * ks + h));
+  };
+  const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_byte_t*)lds);
+  const unsigned wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  auto issue = [&](int stage, int q) {
+    const unsigned char* src = gp + goff + q * 8192;
+    DMA(src, lds0 + stage * kStage + q * 8192 + wv * 1024);
+  };
+  auto advance = [&]() {
+    goff += kStage;
+    if (goff + kStage > p.window) goff = 0;
+  };
+  for (int t = 0; t < STAGES - 1; ++t) {
+    for (int q = 0; q < 4; ++q) issue(t, q);
+    advance();
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  lds_barrier();
+  frags(a0, b0, (const lds_byte_t*)lds, 0);
+  int cur = 0;
+  for (int it = 0; it < p.iters; ++it) {
+    const lds_byte_t* st = (const lds_byte_t*)lds + cur * kStage;
+    const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
+    const int fill_stage = cur == 0 ? STAGES - 1 : cur - 1;
+    frags(a1, b1, st, 1);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int c = 0; c < 2; ++c) acc[i][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0[c], a0[i], acc[i][c], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      issue(fill_stage, i);
+    }
+    advance();
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0x0F78);      // vmcnt(8): the next tile has landed, two younger (four loads each) in flight
+    lds_barrier();
+    frags(a0, b0, (const lds_byte_t*)lds + nxt * kStage, 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int c = 0; c < 2; ++c) acc[i][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1[c], a1[i], acc[i][c], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    cur = nxt;
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  __syncthreads();
+  float s = 0.f;
+  for (int i = 0; i < 4; ++i) for (int c = 0; c < 2; ++c) for (int q = 0; q < 16; ++q) s += acc[i][c][q];
+  if (s == 123.456f) p.out[threadIdx.x] = s;
+}
+
 // ---- host ---------------------------------------------------------------------------------------------------
 template <typename Launch>
 static int timed(const char* name, double flops, Launch launch) {
@@ -256,6 +331,11 @@ int main() {
     if (timed(name, 256.0 * 4 * li * 32 * 32768.0, [&](int w) { LoopArgs q = pr; if (w) q.iters = w; hipLaunchKernelGGL(loop_256x256<2>, dim3(256), dim3(256), 0, 0, q); })) return 1;
     snprintf(name, sizeof name, "D  K loop, 256 x 128 tiles, two workgroups per compute unit, contiguous loads, %s", tag);
     if (timed(name, 512.0 * 4 * li * 16 * 32768.0, [&](int w) { LoopArgs q = pr; if (w) q.iters = w; hipLaunchKernelGGL(loop_256x128<0>, dim3(512), dim3(256), 0, 0, q); })) return 1;
+    for (int share : {32, 4}) {
+      LoopArgs pe{out, g, li, share, gbytes / (8 * (32 / share))};
+      snprintf(name, sizeof name, "E  K loop, 256 x 256 tile on eight waves, contiguous loads, L2 miss share 1/%d, %s", share, tag);
+      if (timed(name, 256.0 * 4 * li * 32 * 32768.0, [&](int w) { LoopArgs q = pe; if (w) q.iters = w; hipLaunchKernelGGL(loop_256x256_8waves, dim3(256), dim3(512), 0, 0, q); })) return 1;
+    }
     snprintf(name, sizeof name, "D  K loop, 256 x 128 tiles, two workgroups per compute unit, row-major operands, %s", tag);
     if (timed(name, 512.0 * 4 * li * 16 * 32768.0, [&](int w) { LoopArgs q = pr; if (w) q.iters = w; hipLaunchKernelGGL(loop_256x128<1>, dim3(512), dim3(256), 0, 0, q); })) return 1;
   }
