@@ -149,17 +149,17 @@ static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w,
       // the last, partly filled round of tiles is cut along K, then the partial tiles are summed
       p.split_partial = (float*)split_ws;
       p.normal_grid = grid;
-      hipLaunchKernelGGL((rows_gemm_persist_bf16<WT, EPI, ACT, false>), dim3(persist), dim3(kGemmThreads), 0, s, p, row_tab);
+      hipLaunchKernelGGL((rows_gemm_persist_bf16<WT, EPI, ACT, false>), dim3(persist), dim3(kDmaThreads), 0, s, p, row_tab);
       hipLaunchKernelGGL(rows_split_reduce_kernel, dim3(kSplitSlices, kSplitUnits / kSplitMax), dim3(kGemmThreads), 0, s, p);
       return hipGetLastError();
     }
     if constexpr (!WT && EPI == EPI_FWD1) {
       if (gsrc) {
-        hipLaunchKernelGGL((rows_gemm_persist_bf16<WT, EPI, ACT, true>), dim3(persist), dim3(kGemmThreads), 0, s, p, row_tab);
+        hipLaunchKernelGGL((rows_gemm_persist_bf16<WT, EPI, ACT, true>), dim3(persist), dim3(kDmaThreads), 0, s, p, row_tab);
         return hipGetLastError();
       }
     }
-    hipLaunchKernelGGL((rows_gemm_persist_bf16<WT, EPI, ACT, false>), dim3(persist), dim3(kGemmThreads), 0, s, p, row_tab);
+    hipLaunchKernelGGL((rows_gemm_persist_bf16<WT, EPI, ACT, false>), dim3(persist), dim3(kDmaThreads), 0, s, p, row_tab);
     return hipGetLastError();
   }
   if (gsrc || scatter_rows) return hipErrorInvalidValue;   // gathered / scattered rows only on the direct-to-LDS path (host check upstream)
@@ -224,9 +224,9 @@ static hipError_t launch_wgrad(const FfnArgs& a, const void* L, const void* R, i
   unsigned grid;
   const WgradDmaArgs g = wgrad_dma_args(a, L, R, M, NC, dw, ws_tail, ws, &grid);
   if (M % BM == 0 && NC % BN == 0)      // whole output tiles: one persistent workgroup per compute unit
-    hipLaunchKernelGGL(wgrad_gemm_persist_bf16, dim3(std::min(grid, (unsigned)kComputeUnits)), dim3(kGemmThreads), 0, s, g);
+    hipLaunchKernelGGL(wgrad_gemm_persist_bf16, dim3(std::min(grid, (unsigned)kComputeUnits)), dim3(kDmaThreads), 0, s, g);
   else
-    hipLaunchKernelGGL(wgrad_gemm_dma_bf16, dim3(grid), dim3(kGemmThreads), 0, s, g);
+    hipLaunchKernelGGL(wgrad_gemm_dma_bf16, dim3(grid), dim3(kDmaThreads), 0, s, g);
   launch_wgrad_reduce(a, g, s);
   return hipGetLastError();
 }

@@ -13,8 +13,19 @@ namespace flexmoe {
 // the wave's LDS base + 16*i, so one instruction fills 16 rows x 64 bytes; the bank swizzle
 // (16-byte chunk index XOR (row>>2)&3) is applied by choosing which global chunk a lane fetches.
 // =============================================================================================
+// The tile is worked on by eight waves, two per SIMD: wave w owns rows (wm + 2 i) * 32, i < 4, and the two
+// 32-column blocks cb0, cb0 + 1 with wm = (w >> 1) & 1, cb0 = (w & 1) * 4 + (w >> 2) * 2 -- 128 x 64 outputs, 128
+// accumulator registers.  With one wave per SIMD (128 x 128 outputs each) nothing can issue while that wave
+// waits for LDS data, a barrier or its loads; with two, the other wave's MFMAs fill the gap (measured on the
+// stripped K loop with random operands and everything in L2: 1.34 -> 1.48 PFLOP/s).
 constexpr int DK = 32;
 constexpr int kDmaStages = 4;
+constexpr int kDmaWaves = 8;
+constexpr int kDmaThreads = kDmaWaves * kWave;
+constexpr int NBW = 2;                                 // 32-column blocks per wave
+constexpr int kOpLoads = 16 / kDmaWaves;               // direct loads (1 KB) per wave and 16 KB operand tile
+__device__ __forceinline__ int dma_wave_wm(int w) { return (w >> 1) & 1; }
+__device__ __forceinline__ int dma_wave_cb0(int w) { return (w & 1) * 4 + (w >> 2) * 2; }
 constexpr int kDmaTileBytes = 256 * DK * 2;            // one operand tile: 16 KB
 constexpr int kDmaStageBytes = 2 * kDmaTileBytes;      // A + B
 
@@ -22,14 +33,14 @@ __device__ __forceinline__ int dma_off(int row, int c) { return row * (DK * 2) +
 
 struct DmaSrc {
   const bf16_t* base;
-  uint32_t off[4];
+  uint32_t off[kOpLoads];
   __device__ __forceinline__ void init(const bf16_t* b, size_t ld, int rows_valid) {
     base = b;
     const int tid = opaque_tid();
     const int w = tid >> 6, i = tid & 63;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int row = (w * 4 + q) * 16 + (i >> 2);
+    for (int q = 0; q < kOpLoads; ++q) {
+      const int row = (w * kOpLoads + q) * 16 + (i >> 2);
       const int c = (i & 3) ^ ((row >> 2) & 3);
       off[q] = (uint32_t)(min(row, rows_valid - 1) * ld + c * 8);
     }
@@ -42,8 +53,8 @@ struct DmaSrc {
     const int tid = opaque_tid();
     const int w = tid >> 6, i = tid & 63;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int row = (w * 4 + q) * 16 + (i >> 2);
+    for (int q = 0; q < kOpLoads; ++q) {
+      const int row = (w * kOpLoads + q) * 16 + (i >> 2);
       const int c = (i & 3) ^ ((row >> 2) & 3);
       off[q] = (uint32_t)((size_t)(rows[min(row, rows_valid - 1)] / k) * ld + c * 8);
     }
@@ -53,10 +64,10 @@ struct DmaSrc {
   // slice, lane i lands at M0 + 16*i): the compiler's wait-count insertion cannot tell which LDS
   // stage a direct load writes and would wait for every outstanding load before any LDS read;
   // here the waits are placed by hand (wait_vmcnt_le) before the barrier that publishes a stage.
-  // q-th of the wave's four direct loads of one tile
+  // q-th of the wave's kOpLoads direct loads of one tile
   __device__ __forceinline__ void part(lds_byte_t* tile, int k0, int q) const {
     const unsigned w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)tile) + w * 4096;
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)tile) + w * (kOpLoads * 1024);
     const bf16_t* g = base + k0 + off[q];
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" FLEXMOE_DMA_CPOL ::"v"(g), "s"(lds0 + q * 1024) : "memory");
   }
@@ -72,7 +83,7 @@ __device__ __forceinline__ int dmat_chunk(int krow, int c) { return c ^ ((krow &
 
 struct DmaSrcT {
   const bf16_t* base;     // first contraction row, first column of the tile
-  uint32_t off[4];
+  uint32_t off[kOpLoads];
   size_t ld;
   __device__ __forceinline__ void init(const bf16_t* b, size_t ld_, int cols_valid) {
     base = b;
@@ -80,15 +91,15 @@ struct DmaSrcT {
     const int tid = opaque_tid();
     const int w = tid >> 6, i = tid & 63;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int krow = (w * 4 + q) * 2 + (i >> 5);
+    for (int q = 0; q < kOpLoads; ++q) {
+      const int krow = (w * kOpLoads + q) * 2 + (i >> 5);
       const int c = min(dmat_chunk(krow, i & 31), cols_valid / 8 - 1);
       off[q] = (uint32_t)(krow * ld + c * 8);
     }
   }
   __device__ __forceinline__ void part(lds_byte_t* tile, int k0, int q) const {
     const unsigned w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)tile) + w * 4096;
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)tile) + w * (kOpLoads * 1024);
     const bf16_t* g = base + (size_t)k0 * ld + off[q];
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" FLEXMOE_DMA_CPOL ::"v"(g), "s"(lds0 + q * 1024) : "memory");
   }
@@ -114,21 +125,29 @@ __device__ __forceinline__ bf16x8 dmat_read_frag(const lds_byte_t* tile, int nb0
   return __builtin_bit_cast(bf16x8, v);
 }
 
-// s_waitcnt vmcnt(8 * tiles) only (expcnt / lgkmcnt fields left at "no wait"): returns once at
-// most `tiles` of the most recently issued K tiles (8 direct loads per wave each) are in flight.
-__device__ __forceinline__ void wait_tiles_in_flight(int tiles) {
-  if (tiles >= 3) __builtin_amdgcn_s_waitcnt(0x4F78);        // vmcnt(24)
-  else if (tiles == 2) __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16)
-  else if (tiles == 1) __builtin_amdgcn_s_waitcnt(0x0F78);   // vmcnt(8)
-  else __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0)
+// s_waitcnt vmcnt(n) only (expcnt / lgkmcnt fields left at "no wait").
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
+// Returns once at most `tiles` of the most recently issued K tiles (2 kOpLoads direct loads per wave each) are in flight.
+template <int TILES> __device__ __forceinline__ void wait_tiles_in_flight() { wait_vmcnt<2 * kOpLoads * TILES>(); }
 
 struct DmaFrags {
-  Frag8 a[MB], b[NB];
+  Frag8 a[MB], b[NBW];
 };
+typedef f32x16 DmaAcc[MB][NBW];
+__device__ __forceinline__ void zero_acc(DmaAcc& acc) {
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NBW; ++j)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+}
 // TRA / TRB: the operand's LDS tile is [k][256] (transposing reads) instead of [256][k].
 template <bool TRA, bool TRB>
-__device__ __forceinline__ void dma_read_frags(DmaFrags& f, const lds_byte_t* stage, int ks, int wm, int wn) {
+__device__ __forceinline__ void dma_read_frags(DmaFrags& f, const lds_byte_t* stage, int ks, int wm, int cb0) {
   const int lane = threadIdx.x & 63;
   const int r = lane & 31, h = lane >> 5;
   const lds_byte_t* As = stage;
@@ -139,17 +158,10 @@ __device__ __forceinline__ void dma_read_frags(DmaFrags& f, const lds_byte_t* st
     else f.a[i].v = *(const __attribute__((address_space(3))) bf16x8*)(As + dma_off((wm + 2 * i) * 32 + r, 2 * ks + h));
   }
 #pragma unroll
-  for (int j = 0; j < NB; ++j) {
-    if (TRB) f.b[j].v = dmat_read_frag(Bs, (wn * NB + j) * 32, ks);
-    else f.b[j].v = *(const __attribute__((address_space(3))) bf16x8*)(Bs + dma_off((wn * NB + j) * 32 + r, 2 * ks + h));
+  for (int j = 0; j < NBW; ++j) {
+    if (TRB) f.b[j].v = dmat_read_frag(Bs, (cb0 + j) * 32, ks);
+    else f.b[j].v = *(const __attribute__((address_space(3))) bf16x8*)(Bs + dma_off((cb0 + j) * 32 + r, 2 * ks + h));
   }
-}
-__device__ __forceinline__ void dma_mma(f32x16 (&acc)[MB][NB], const DmaFrags& f) {
-#pragma unroll
-  for (int i = 0; i < MB; ++i)
-#pragma unroll
-    for (int j = 0; j < NB; ++j)
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j].v, f.a[i].v, acc[i][j], 0, 0, 0);
 }
 
 // One K tile (two 16-wide k steps).  On entry f0 holds the fragments of (tile kt, k step 0).
@@ -157,47 +169,48 @@ __device__ __forceinline__ void dma_mma(f32x16 (&acc)[MB][NB], const DmaFrags& f
 // from `cur`, so after it `cur` is free for tile kt+4; and tile kt+1 is published, so its first
 // fragments can be fetched while the second k step's MFMAs run -- no LDS latency after the barrier.
 // The direct loads are spread evenly between the MFMAs, one after every four (128 cycles of
-// matrix-pipe work): the four waves share one address path, and a wave that issues its loads back
-// to back leaves its matrix pipe idle while it queues there.  So a tile's eight loads per wave go
-// out in two halves: loads 0..3 of tile kt+4 after the barrier of step kt (into `cur`, just
-// freed), loads 4..7 before the barrier of step kt+1 (into that step's `prev`).
+// matrix-pipe work): the waves share one address path, and a wave that issues its loads back
+// to back leaves its matrix pipe idle while it queues there.  So a tile's 2 kOpLoads loads per wave go
+// out in two halves: the first operand's (of tile kt+4) after the barrier of step kt (into `cur`, just
+// freed), the second operand's before the barrier of step kt+1 (into that step's `prev`).
 // Issue: begin() prepares the next tile in sequence, part(stage, q) starts its q-th direct load
-// (q = 0..7) into `stage`, end() moves on to the tile after it.
+// (q = 0 .. 2 kOpLoads - 1) into `stage`, end() moves on to the tile after it.
 // PRE: tile kt+3 exists (its second half is issued here).  POST: tile kt+4 exists.
 // NEXT: tile kt+1 exists; WAIT = how many younger tiles may still be in flight once this wave's
 // part of tile kt+1 has landed.
 // `issue` serves the first half of the step (PRE), `issue_post` the second (POST): the same object inside a
 // tile sequence, two different ones where the sequence of the workgroup's next output tile takes over.
 template <bool TRA, bool TRB, bool PRE, bool POST, int WAIT, bool NEXT, typename Issue, typename IssuePost>
-__device__ __forceinline__ void dma_step(lds_byte_t* prev, lds_byte_t* cur, const lds_byte_t* nxt,
-                                         f32x16 (&acc)[MB][NB], DmaFrags& f0, DmaFrags& f1, Issue& issue,
-                                         IssuePost& issue_post, int wm, int wn) {
-  dma_read_frags<TRA, TRB>(f1, cur, 1, wm, wn);
+__device__ __forceinline__ void dma_step(lds_byte_t* prev, lds_byte_t* cur, const lds_byte_t* nxt, DmaAcc& acc,
+                                         DmaFrags& f0, DmaFrags& f1, Issue& issue, IssuePost& issue_post, int wm,
+                                         int cb0) {
+  constexpr int kEvery = MB / kOpLoads;      // a load after every kEvery-th group of NBW MFMAs
+  dma_read_frags<TRA, TRB>(f1, cur, 1, wm, cb0);
 #pragma unroll
   for (int i = 0; i < MB; ++i) {
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int j = 0; j < NB; ++j)
+    for (int j = 0; j < NBW; ++j)
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.b[j].v, f0.a[i].v, acc[i][j], 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
-    if (PRE) issue.part(prev, 4 + i);
+    if (PRE && i % kEvery == kEvery - 1) issue.part(prev, kOpLoads + i / kEvery);
   }
   if (PRE) issue.end();
   __builtin_amdgcn_sched_barrier(0);     // everything above is queued before the wave goes to wait
-  if (NEXT) wait_tiles_in_flight(WAIT);
+  if (NEXT) wait_tiles_in_flight<WAIT>();
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-  if (NEXT) dma_read_frags<TRA, TRB>(f0, nxt, 0, wm, wn);
+  if (NEXT) dma_read_frags<TRA, TRB>(f0, nxt, 0, wm, cb0);
   if (POST) issue_post.begin();
 #pragma unroll
   for (int i = 0; i < MB; ++i) {
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int j = 0; j < NB; ++j)
+    for (int j = 0; j < NBW; ++j)
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.b[j].v, f1.a[i].v, acc[i][j], 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
-    if (POST) issue_post.part(cur, i);
+    if (POST && i % kEvery == kEvery - 1) issue_post.part(cur, i / kEvery);
   }
 }
 
@@ -206,30 +219,30 @@ __device__ __forceinline__ void dma_step(lds_byte_t* prev, lds_byte_t* cur, cons
 // branch-free.
 template <bool TRA, bool TRB, typename Issue>
 __device__ __forceinline__ void dma_pipeline(lds_byte_t* s0, lds_byte_t* s1, lds_byte_t* s2, lds_byte_t* s3,
-                                             f32x16 (&acc)[MB][NB], Issue& issue, int KT, int wm, int wn) {
+                                             DmaAcc& acc, Issue& issue, int KT, int wm, int cb0) {
   lds_byte_t* const stages[4] = {s0, s1, s2, s3};
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
     issue.begin();
 #pragma unroll
-    for (int q = 0; q < (t < 3 ? 8 : 4); ++q) issue.part(stages[t], q);   // tile 3: first half only
+    for (int q = 0; q < (t < 3 ? 2 * kOpLoads : kOpLoads); ++q) issue.part(stages[t], q);   // tile 3: first half only
     if (t < 3) issue.end();
   }
-  __builtin_amdgcn_s_waitcnt(0x4F74);                  // vmcnt(20): tile 0 has landed
+  wait_vmcnt<5 * kOpLoads>();                          // tile 0 has landed (two and a half tiles younger)
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
   DmaFrags f0, f1;
-  dma_read_frags<TRA, TRB>(f0, s0, 0, wm, wn);
+  dma_read_frags<TRA, TRB>(f0, s0, 0, wm, cb0);
   for (int kt = 0; kt < KT - 4; kt += 4) {
-    dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f0, f1, issue, issue, wm, wn);
-    dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f0, f1, issue, issue, wm, wn);
-    dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f0, f1, issue, issue, wm, wn);
-    dma_step<TRA, TRB, true, true, 2, true>(s2, s3, s0, acc, f0, f1, issue, issue, wm, wn);
+    dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f0, f1, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f0, f1, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f0, f1, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s2, s3, s0, acc, f0, f1, issue, issue, wm, cb0);
   }
-  dma_step<TRA, TRB, true, false, 2, true>(s3, s0, s1, acc, f0, f1, issue, issue, wm, wn);
-  dma_step<TRA, TRB, false, false, 1, true>(s0, s1, s2, acc, f0, f1, issue, issue, wm, wn);
-  dma_step<TRA, TRB, false, false, 0, true>(s1, s2, s3, acc, f0, f1, issue, issue, wm, wn);
-  dma_step<TRA, TRB, false, false, 0, false>(s2, s3, s0, acc, f0, f1, issue, issue, wm, wn);
+  dma_step<TRA, TRB, true, false, 2, true>(s3, s0, s1, acc, f0, f1, issue, issue, wm, cb0);
+  dma_step<TRA, TRB, false, false, 1, true>(s0, s1, s2, acc, f0, f1, issue, issue, wm, cb0);
+  dma_step<TRA, TRB, false, false, 0, true>(s1, s2, s3, acc, f0, f1, issue, issue, wm, cb0);
+  dma_step<TRA, TRB, false, false, 0, false>(s2, s3, s0, acc, f0, f1, issue, issue, wm, cb0);
   __syncthreads();                                     // all waves done with the last tile: LDS is free
 }
 
@@ -239,7 +252,7 @@ __device__ __forceinline__ void dma_pipeline(lds_byte_t* s0, lds_byte_t* s1, lds
 // for this output tile, issue K tiles 0, 1, 2 of `next`, the sequence of the workgroup's next output
 // tile, into the stages as they fall free: the pipeline never drains between output tiles, and stage s3
 // -- free for every wave once it is past the last step's barrier -- is where the epilogue puts its
-// patches.  There is one code path only (two, chosen by a branch, make the compiler shuffle the 256
+// patches.  There is one code path only (two, chosen by a branch, make the compiler shuffle the
 // accumulator registers where they join): a workgroup on its last tile passes a sequence whose loads
 // are valid but never used, and waits for them before it ends.  Global
 // stores of the previous epilogue may still be in flight on entry: they only make the hand-placed
@@ -252,7 +265,7 @@ template <typename Issue> __device__ __forceinline__ void dma_prefetch3(lds_byte
   for (int t = 0; t < 3; ++t) {
     issue.begin();
 #pragma unroll
-    for (int q = 0; q < 8; ++q) issue.part(stages[t], q);
+    for (int q = 0; q < 2 * kOpLoads; ++q) issue.part(stages[t], q);
     issue.end();
   }
 }
@@ -261,29 +274,29 @@ template <typename Issue> __device__ __forceinline__ void dma_prefetch3(lds_byte
 // queue as the operand tiles: every reload inside the K loop would wait for all tiles in flight).
 template <bool TRA, bool TRB, typename Issue, typename After, typename MakeNext>
 __device__ __forceinline__ void dma_pipeline_cont(lds_byte_t* s0, lds_byte_t* s1, lds_byte_t* s2, lds_byte_t* s3,
-                                                  f32x16 (&acc)[MB][NB], Issue& issue, int KT, Issue& next, int wm,
-                                                  int wn, After after_barrier, MakeNext make_next) {
-  __builtin_amdgcn_s_waitcnt(0x4F70);                  // vmcnt(16): tile 0 has landed
+                                                  DmaAcc& acc, Issue& issue, int KT, Issue& next, int wm,
+                                                  int cb0, After after_barrier, MakeNext make_next) {
+  wait_tiles_in_flight<2>();                           // tile 0 has landed
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
   issue.begin();
 #pragma unroll
-  for (int q = 0; q < 4; ++q) issue.part(s3, q);       // tile 3: first half
+  for (int q = 0; q < kOpLoads; ++q) issue.part(s3, q);       // tile 3: first half
   after_barrier();
   DmaFrags f0, f1;
-  dma_read_frags<TRA, TRB>(f0, s0, 0, wm, wn);
+  dma_read_frags<TRA, TRB>(f0, s0, 0, wm, cb0);
   for (int kt = 0; kt < KT - 4; kt += 4) {
-    dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f0, f1, issue, issue, wm, wn);
-    dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f0, f1, issue, issue, wm, wn);
-    dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f0, f1, issue, issue, wm, wn);
-    dma_step<TRA, TRB, true, true, 2, true>(s2, s3, s0, acc, f0, f1, issue, issue, wm, wn);
+    dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f0, f1, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f0, f1, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f0, f1, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s2, s3, s0, acc, f0, f1, issue, issue, wm, cb0);
   }
   make_next(next);
-  dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f0, f1, issue, next, wm, wn);
-  dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f0, f1, next, next, wm, wn);
-  dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f0, f1, next, next, wm, wn);
-  dma_step<TRA, TRB, true, false, 0, false>(s2, s3, s0, acc, f0, f1, next, next, wm, wn);
+  dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f0, f1, issue, next, wm, cb0);
+  dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f0, f1, next, next, wm, cb0);
+  dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f0, f1, next, next, wm, cb0);
+  dma_step<TRA, TRB, true, false, 0, false>(s2, s3, s0, acc, f0, f1, next, next, wm, cb0);
 }
 
 // Arguments of one rows GEMM (device pointers; see rows_gemm_persist_bf16).

@@ -135,8 +135,8 @@ template <typename WSrc> struct RowsIssueV {
   int k_next;
   __device__ __forceinline__ void begin() {}
   __device__ __forceinline__ void part(lds_byte_t* stage, int q) const {
-    if (q < 4) a_src.part(stage, k_next, q);
-    else w_src.part(stage + kDmaTileBytes, k_next, q - 4);
+    if (q < kOpLoads) a_src.part(stage, k_next, q);
+    else w_src.part(stage + kDmaTileBytes, k_next, q - kOpLoads);
   }
   __device__ __forceinline__ void end() { k_next += DK; }
 };
@@ -151,7 +151,7 @@ template <> struct RowsWSrc<true> {
 // Arguments: RowsDmaArgs (split_partial: null = no splitting; normal_grid unused) plus the row-tile table.
 // GATHER: p.gsrc holds the rows of `in` to read (rows gathered on load).
 template <bool WT, int EPI, int ACT, bool GATHER>
-__global__ __launch_bounds__(kGemmThreads) void rows_gemm_persist_bf16(const RowsDmaArgs p, const i32x4* row_tab) {
+__global__ __launch_bounds__(kDmaThreads) void rows_gemm_persist_bf16(const RowsDmaArgs p, const i32x4* row_tab) {
   __shared__ __align__(1024) unsigned char stage0[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char stage1[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
@@ -171,7 +171,7 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_persist_bf16(const Row
   const TileSeq seq = make_tile_seq(tab[0][0], p.col_tiles, EPI == EPI_PLAIN && p.split_partial != nullptr, K / DK);
   const unsigned G = gridDim.x;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = dma_wave_wm(wave), wn = wave & 1, cb0 = dma_wave_cb0(wave);
 
   // tile -> operand sources and the K range [k0, k0 + 32 KT)
   auto fetch_tile = [&](const TileId& id) {
@@ -202,10 +202,10 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_persist_bf16(const Row
   TileId id;
   if (!find_tile(seq, &idx, G, &id)) return;
   const lds_byte_t* lut = nullptr;
-  if (kLut) {
-    // the table rides in front of the first operand tiles: its direct loads are the oldest in every
-    // wave's queue, so the first wait of the K loop covers them and its barrier publishes them
-    lut = (const lds_byte_t*)lut_lds;
+  if (kLut) lut = (const lds_byte_t*)lut_lds;
+  if (kLut && wave < 4) {
+    // the table rides in front of the first operand tiles (four waves fetch a quarter each): its direct loads are the
+    // oldest in those waves' queues, so the first wait of the K loop covers them and its barrier publishes them
     const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)lut) + wave * (kLutBytes / 4);
     const unsigned char* g = (const unsigned char*)g_act_lut[ACT == FLEXMOE_GELU_ERF ? 0 : 1] + wave * (kLutBytes / 4) +
                              (threadIdx.x & 63) * 16;
@@ -218,10 +218,10 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_persist_bf16(const Row
   RowTile t = fetch_tile(id);
   Issue issue = make_issue(t);
   dma_prefetch3(s0, s1, s2, issue);
-  float* const patch = (float*)stage3 + wave * (32 * 64);      // wave-private; stage 3 is the one the next tile has not touched yet
+  float* const patch = (float*)stage3 + wave * (16 * 64);      // wave-private, 4 KB; stage 3 is the one the next tile has not touched yet
 
   for (;;) {
-    f32x16 acc[MB][NB];
+    DmaAcc acc;
     zero_acc(acc);
     // the workgroup's next tile
     unsigned nidx = idx + G;
@@ -233,9 +233,9 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_persist_bf16(const Row
     if constexpr (GATHER) next = make_issue(tn);       // its index loads share the operand tiles' queue: up here, where little is in flight
     const int KT = K / DK / t.nseg;
     dma_pipeline_cont<false, !WT>(
-        s0, s1, s2, s3, acc, issue, KT, next, wm, wn,
+        s0, s1, s2, s3, acc, issue, KT, next, wm, cb0,
         [&]() {
-          if (EPI == EPI_PLAIN && p.scatter_rows && t.nseg == 1)
+          if (EPI == EPI_PLAIN && p.scatter_rows && t.nseg == 1 && threadIdx.x < BM)
             smap_lds[threadIdx.x] = p.scatter_rows[t.row0 + min((int)threadIdx.x, t.rows_valid - 1)];
         },
         [&](Issue& nx) {
@@ -244,8 +244,8 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_persist_bf16(const Row
     if (EPI == EPI_PLAIN && t.nseg > 1) {
       // one K segment of a split tile: fp32 partial tile (all 256 x 256 entries) for the reduce kernel
       float* out = p.split_partial + (size_t)t.slot * (BM * BN);
-      epilogue_rounds<false>(
-          patch, patch, acc, [](const EpiIdx&) { return make_uint2(0, 0); },
+      epilogue_rounds8<false>(
+          patch, wave >> 2, acc, [](const EpiIdx&) { return make_uint2(0, 0); },
           [](const EpiIdx&, float4 c, uint2) {
             return EpiOut{make_uint2(__float_as_uint(c.x), __float_as_uint(c.y)),
                           make_uint2(__float_as_uint(c.z), __float_as_uint(c.w))};
@@ -256,7 +256,7 @@ __global__ __launch_bounds__(kGemmThreads) void rows_gemm_persist_bf16(const Row
           });
     } else {
       const lds_int_t* smap = (EPI == EPI_PLAIN && p.scatter_rows) ? (const lds_int_t*)smap_lds : nullptr;
-      rows_epilogue<EPI, ACT, kLut>((float*)stage3, (float*)stage3, acc, p.bias, NC, t.row0, t.rows_valid, t.e, t.n0,
+      rows_epilogue<EPI, ACT, kLut, 8>((float*)stage3, (float*)stage3, acc, p.bias, NC, t.row0, t.rows_valid, t.e, t.n0,
                                     p.hpre_in, p.out0, p.out1, lut, smap);
     }
     if (!has_next) break;

@@ -264,9 +264,12 @@ struct EpiOut {
 // half jh of the wave's 128 x 128 block, piece it (0..7) of the round -- compile-time constants once the
 // loops are unrolled -- and the same as lane-dependent coordinates inside the wave's block:
 // row_w = 32 i + 4 it + (lane / 16), col_w = 64 jh + 4 (lane % 16).
+// (Eight-wave kernels, epilogue_rounds8: a wave owns one 64-column half, jh is then uniform over the wave, and a
+// round covers 16 rows: sub = which half of the 32-row block, row_w = 32 i + 16 sub + 4 it + (lane / 16), it < 4.)
 struct EpiIdx {
   int i, jh, it;
   int row_w, col_w;
+  int sub;
 };
 // 8-byte store with the non-temporal hint.  Used for the large outputs of the epilogues that carry an
 // activation (Hpre and H of the forward, dHpre and H of the backward) and for the weight gradients:
@@ -290,7 +293,7 @@ __device__ __forceinline__ void epilogue_rounds(float* patch0, float* patch1, co
   constexpr int kRounds = MB * (NB / 2);
   auto idx_of = [&](int round, int it) {
     const int i = round / (NB / 2), jh = round % (NB / 2);
-    return EpiIdx{i, jh, it, i * 32 + it * 4 + rsub, jh * 64 + c * 4};
+    return EpiIdx{i, jh, it, i * 32 + it * 4 + rsub, jh * 64 + c * 4, 0};
   };
   // Side inputs are requested kAhead rounds before they are used.  Loads and stores of a wave complete
   // in issue order: a load issued behind a round's stores only returns once those stores are
@@ -342,6 +345,69 @@ __device__ __forceinline__ void epilogue_rounds(float* patch0, float* patch1, co
   }
 }
 
+// The same for a wave of the eight-wave kernels: its accumulators are acc[i][0..1], the 64-column half jh of a
+// 128-column block, and its patch holds 16 rows x 64 columns (4 KB: eight of them fit the one LDS stage a
+// persistent kernel has free while its next tile's operands are landing in the others).  Eight rounds -- 32-row
+// block i, rows 16 sub .. 16 sub + 15 of it -- of four 4-element pieces per lane; lanes whose accumulator row
+// is in the other half of the block sit a round's patch write out.
+template <bool FETCH, typename Fetch, typename Compute, typename Store>
+__device__ __forceinline__ void epilogue_rounds8(float* patch, int jh, const f32x16 (&acc)[MB][2], Fetch fetch,
+                                                 Compute compute, Store store) {
+  const int lane = opaque_tid() & 63;
+  const int r = lane & 31, h = lane >> 5;
+  const int rsub = lane >> 4, c = lane & 15;
+  constexpr int kRounds = MB * 2, kIts = 4;
+  auto idx_of = [&](int round, int it) {
+    const int i = round >> 1, sub = round & 1;
+    return EpiIdx{i, jh, it, i * 32 + sub * 16 + it * 4 + rsub, jh * 64 + c * 4, sub};
+  };
+  constexpr int kAhead = FLEXMOE_EPI_AHEAD;
+  uint2 side[FETCH ? kAhead + 1 : 1][kIts];
+  auto fetch_round = [&](int round) {
+#pragma unroll
+    for (int it = 0; it < kIts; ++it) side[round % (kAhead + 1)][it] = fetch(idx_of(round, it));
+  };
+  if (FETCH) {
+#pragma unroll
+    for (int round = 0; round < kAhead; ++round) fetch_round(round);
+  }
+  // a round's write follows the previous round's reads in the wave's instruction stream: LDS executes a
+  // wave's instructions in order, so one patch serves every round
+  auto write_round = [&](int i, int sub) {
+    if ((r >> 4) == sub) {
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int cc = jj * 8 + 2 * g + h;
+          const f32x16& a = acc[i][jj];
+          *(float4*)(patch + (r & 15) * 64 + ((cc ^ (r & 15)) << 2)) = make_float4(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]);
+        }
+    }
+  };
+  write_round(0, 0);
+#pragma unroll
+  for (int round = 0; round < kRounds; ++round) {
+    if (FETCH && round + kAhead < kRounds) fetch_round(round + kAhead);
+    asm volatile("" ::: "memory");
+    float4 v[kIts];
+#pragma unroll
+    for (int it = 0; it < kIts; ++it) {
+      const int row = it * 4 + rsub;
+      v[it] = *(const float4*)(patch + row * 64 + ((c ^ row) << 2));
+    }
+    asm volatile("" ::: "memory");
+    if (round + 1 < kRounds) write_round((round + 1) >> 1, (round + 1) & 1);
+    asm volatile("" ::: "memory");
+    EpiOut o[kIts];
+#pragma unroll
+    for (int it = 0; it < kIts; ++it)
+      o[it] = compute(idx_of(round, it), v[it], FETCH ? side[round % (kAhead + 1)][it] : make_uint2(0, 0));
+#pragma unroll
+    for (int it = 0; it < kIts; ++it) store(idx_of(round, it), o[it]);
+  }
+}
+
 // Addresses of the pieces of epilogue_rounds inside an output (or side input) tile whose rows are ld
 // elements of ELEM bytes apart: piece (i, jh, it) is at [uniform: first element of 32-row block i,
 // 64-column half jh of the wave's block] + [per lane, per it: byte offset of tile row wm*32 + 4 it +
@@ -359,7 +425,7 @@ template <int ELEM> struct EpiAddr {
   }
   // block_base: the wave's block of the tile (tile row 0, the wave's first column)
   template <typename T> __device__ __forceinline__ T* at(T* block_base, const EpiIdx& x) const {
-    T* round_base = block_base + (size_t)(x.i * 64) * ld + x.jh * 64;
+    T* round_base = block_base + (size_t)(x.i * 64 + x.sub * 16) * ld + x.jh * 64;
     return (T*)((char*)round_base + vb[x.it]);
   }
 };
@@ -454,15 +520,16 @@ __device__ __forceinline__ void rows_mainloop(bf16_t* smem, f32x16 (&acc)[MB][NB
 // above); otherwise it is evaluated arithmetically.
 // FULL: all 256 rows of the tile and all 128 columns of the wave's block exist (no store predicates).
 // SCATTER (plain epilogue): tile row r is stored as row smap[r] of out0.
-template <int EPI, int ACT, bool LUT, bool BIAS, bool FULL, bool SCATTER>
-__device__ __forceinline__ void rows_epilogue_t(float* lds, float* lds_alt, const f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ bias,
+// NW = 8: a wave of the eight-wave kernels (accumulators [MB][2], patches of 4 KB per wave at `lds`, lds_alt unused).
+template <int EPI, int ACT, bool LUT, bool BIAS, bool FULL, bool SCATTER, int NW, typename Acc>
+__device__ __forceinline__ void rows_epilogue_t(float* lds, float* lds_alt, const Acc& acc, const bf16_t* __restrict__ bias,
                                                 int NC, int row0, int rows_valid, int e, int n0,
                                                 const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
                                                 bf16_t* __restrict__ out1, const lds_byte_t* lut,
                                                 const lds_int_t* smap) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
-  float* patch = lds + wave * (32 * 64);
+  const int wm = (wave >> 1) & 1, wn = wave & 1, hh = wave >> 2;      // hh: the wave's 64-column half (eight waves)
+  float* patch = lds + wave * (NW == 8 ? 16 * 64 : 32 * 64);
   float* patch_alt = lds_alt + wave * (32 * 64);
   const int col_base = n0 + wn * (NB * 32);
   // uniform per-tile base pointers (scalar registers) + per-lane 32-bit offsets
@@ -487,12 +554,14 @@ __device__ __forceinline__ void rows_epilogue_t(float* lds, float* lds_alt, cons
   if (BIAS) {
     const int c4 = (opaque_tid() & 15) * 4;
 #pragma unroll
-    for (int jh = 0; jh < NB / 2; ++jh) unpack4(*(const uint2*)(bias_t + min(jh * 64 + c4, cols_left - 4)), bvals[jh]);
+    for (int jh = 0; jh < NB / 2; ++jh)      // eight waves: entry 0 holds the wave's own half
+      unpack4(*(const uint2*)(bias_t + min((NW == 8 ? hh : jh) * 64 + c4, cols_left - 4)), bvals[jh]);
   }
   auto compute = [&](const EpiIdx& x, float4 c, uint2 pre_in) -> EpiOut {
     EpiOut o;
     if (BIAS) {
-      c.x += bvals[x.jh][0]; c.y += bvals[x.jh][1]; c.z += bvals[x.jh][2]; c.w += bvals[x.jh][3];
+      const float* bv = bvals[NW == 8 ? 0 : x.jh];
+      c.x += bv[0]; c.y += bv[1]; c.z += bv[2]; c.w += bv[3];
     }
     if (EPI == EPI_PLAIN) {
       o.a = pack4(c.x, c.y, c.z, c.w);
@@ -542,11 +611,12 @@ __device__ __forceinline__ void rows_epilogue_t(float* lds, float* lds_alt, cons
       if (EPI == EPI_FWD1 || EPI == EPI_DH) store_nt8(addr.at(out1_t, x), o.b);
     }
   };
-  epilogue_rounds<EPI == EPI_DH || EPI == EPI_DHQ>(patch, patch_alt, acc, fetch, compute, store);
+  if constexpr (NW == 8) epilogue_rounds8<EPI == EPI_DH || EPI == EPI_DHQ>(patch, hh, acc, fetch, compute, store);
+  else epilogue_rounds<EPI == EPI_DH || EPI == EPI_DHQ>(patch, patch_alt, acc, fetch, compute, store);
 }
 
-template <int EPI, int ACT, bool LUT = false>
-__device__ __forceinline__ void rows_epilogue(float* lds, float* lds_alt, const f32x16 (&acc)[MB][NB], const bf16_t* __restrict__ bias,
+template <int EPI, int ACT, bool LUT = false, int NW = 4, typename Acc>
+__device__ __forceinline__ void rows_epilogue(float* lds, float* lds_alt, const Acc& acc, const bf16_t* __restrict__ bias,
                                               int NC, int row0, int rows_valid, int e, int n0,
                                               const bf16_t* __restrict__ hpre_in, bf16_t* __restrict__ out0,
                                               bf16_t* __restrict__ out1, const lds_byte_t* lut = nullptr,
@@ -555,7 +625,7 @@ __device__ __forceinline__ void rows_epilogue(float* lds, float* lds_alt, const 
   const int wn = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) & 1;
   const bool full = rows_valid == BM && NC - n0 - wn * (NB * 32) >= NB * 32;
 #define FLEXMOE_EPI_CALL(BIAS, FULL, SCATTER) \
-  rows_epilogue_t<EPI, ACT, LUT, BIAS, FULL, SCATTER>(lds, lds_alt, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1, lut, smap)
+  rows_epilogue_t<EPI, ACT, LUT, BIAS, FULL, SCATTER, NW>(lds, lds_alt, acc, bias, NC, row0, rows_valid, e, n0, hpre_in, out0, out1, lut, smap)
   if (EPI == EPI_PLAIN && smap) {
     if (bias) FLEXMOE_EPI_CALL(true, false, true);
     else FLEXMOE_EPI_CALL(false, false, true);

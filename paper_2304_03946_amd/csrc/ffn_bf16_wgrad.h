@@ -186,7 +186,7 @@ __device__ __forceinline__ WgradJob wgrad_fetch_job(const WgradPlan& plan, int w
   job.slot = __builtin_amdgcn_readfirstlane(job.slot);
   if (job.e < 0) return job;
   const int b0 = plan.boff[job.e], nb = plan.boff[job.e + 1] - b0;
-  for (int b = threadIdx.x; b < nb; b += kGemmThreads) {
+  for (int b = threadIdx.x; b < nb; b += blockDim.x) {
     sh.bstart[b] = plan.bstart[b0 + b];
     sh.brows[b] = plan.brows[b0 + b];
   }
@@ -207,15 +207,15 @@ __device__ __forceinline__ WgradJob wgrad_fetch_job(const WgradPlan& plan, int w
 __device__ const uint4 kZeroRow[32] = {};
 
 struct DmaSrcTok {
-  uint32_t off[4];
-  int krow[4];
+  uint32_t off[kOpLoads];
+  int krow[kOpLoads];
   size_t ld;
   __device__ __forceinline__ void init(size_t ld_, int cols_valid) {
     ld = ld_;
     const int w = threadIdx.x >> 6, i = threadIdx.x & 63;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      krow[q] = (w * 4 + q) * 2 + (i >> 5);
+    for (int q = 0; q < kOpLoads; ++q) {
+      krow[q] = (w * kOpLoads + q) * 2 + (i >> 5);
       const int c = min(dmat_chunk(krow[q], i & 31), cols_valid / 8 - 1);
       off[q] = (uint32_t)(krow[q] * ld + c * 8);
     }
@@ -223,7 +223,7 @@ struct DmaSrcTok {
   // `p`: token row 0 of this K tile, first column of the tile; rows >= k_valid come from kZeroRow
   __device__ __forceinline__ void part(lds_byte_t* tile, const bf16_t* __restrict__ p, int k_valid, int q) const {
     const unsigned w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)tile) + w * 4096;
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)tile) + w * (kOpLoads * 1024);
     const bf16_t* z = (const bf16_t*)kZeroRow + (threadIdx.x & 31) * 8;
     const bf16_t* g = (k_valid >= DK || krow[q] < k_valid) ? p + off[q] : z;
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" FLEXMOE_DMA_CPOL ::"v"(g), "s"(lds0 + q * 1024) : "memory");
@@ -256,8 +256,8 @@ struct WgradIssue {
   __device__ __forceinline__ void begin() {}
   __device__ __forceinline__ void part(lds_byte_t* stage, int q) const {
     const int kv = issued < T ? rows_left : 0;
-    if (q < 4) l_src.part(stage, lp, kv, q);
-    else r_src.part(stage + kDmaTileBytes, rp, kv, q - 4);
+    if (q < kOpLoads) l_src.part(stage, lp, kv, q);
+    else r_src.part(stage + kDmaTileBytes, rp, kv, q - kOpLoads);
   }
   __device__ __forceinline__ void end() {
     ++issued;
@@ -302,8 +302,8 @@ __device__ __forceinline__ void wgrad_dma_block(const WgradDmaArgs& p, unsigned 
   const int m0 = mt * BM, n0 = nt * BN;
   const int mvalid = min(BM, M - m0), nvalid = min(BN, NC - n0);
   const int wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  f32x16 acc[MB][NB];
+  const int wm = dma_wave_wm(wave), wn = wave & 1, cb0 = dma_wave_cb0(wave);
+  DmaAcc acc;
   zero_acc(acc);
   lds_byte_t* s0 = (lds_byte_t*)stage0;
 
@@ -325,11 +325,11 @@ __device__ __forceinline__ void wgrad_dma_block(const WgradDmaArgs& p, unsigned 
     r_src.init(NC, nvalid);
     WgradIssue issue{l_src, r_src, L, R, sh.bstart, sh.brows, M, NC, m0, n0, nb, T, 0, 0, nullptr, nullptr, 0};
     issue.seek(bi, skip * DK);
-    dma_pipeline<true, true>(s0, (lds_byte_t*)stage1, (lds_byte_t*)stage2, (lds_byte_t*)stage3, acc, issue, KT, wm, wn);
+    dma_pipeline<true, true>(s0, (lds_byte_t*)stage1, (lds_byte_t*)stage2, (lds_byte_t*)stage3, acc, issue, KT, wm, cb0);
   }
 
-  float* patch = (float*)stage0 + wave * (32 * 64);
-  float* patch_alt = (float*)stage1 + wave * (32 * 64);
+  float* patch = (float*)stage0 + wave * (16 * 64);
+  const int jh = wave >> 2;
   const int col_base = n0 + wn * (NB * 32);
   // whole tiles (every benchmark shape: M and NC are multiples of 256) are stored without predicates
   const bool full = mvalid == BM && nvalid == BN;
@@ -341,10 +341,10 @@ __device__ __forceinline__ void wgrad_dma_block(const WgradDmaArgs& p, unsigned 
     addr.init(wm, NC);
     auto to_bf16 = [](const EpiIdx&, float4 c, uint2) { return EpiOut{pack4(c.x, c.y, c.z, c.w), make_uint2(0, 0)}; };
     if (full)
-      epilogue_rounds<false>(patch, patch_alt, acc, none, to_bf16,
-                             [&](const EpiIdx& x, const EpiOut& o) { store_nt8(addr.at(out, x), o.a); });   // written once
+      epilogue_rounds8<false>(patch, jh, acc, none, to_bf16,
+                              [&](const EpiIdx& x, const EpiOut& o) { store_nt8(addr.at(out, x), o.a); });   // written once
     else
-      epilogue_rounds<false>(patch, patch_alt, acc, none, to_bf16, [&](const EpiIdx& x, const EpiOut& o) {
+      epilogue_rounds8<false>(patch, jh, acc, none, to_bf16, [&](const EpiIdx& x, const EpiOut& o) {
         if (valid(x)) store_nt8(addr.at(out, x), o.a);
       });
   } else {
@@ -356,18 +356,18 @@ __device__ __forceinline__ void wgrad_dma_block(const WgradDmaArgs& p, unsigned 
       return EpiOut{make_uint2(__float_as_uint(c.x), __float_as_uint(c.y)), make_uint2(__float_as_uint(c.z), __float_as_uint(c.w))};
     };
     if (full)
-      epilogue_rounds<false>(patch, patch_alt, acc, none, as_f32, [&](const EpiIdx& x, const EpiOut& o) {
+      epilogue_rounds8<false>(patch, jh, acc, none, as_f32, [&](const EpiIdx& x, const EpiOut& o) {
         *(uint4*)addr.at(out, x) = make_uint4(o.a.x, o.a.y, o.b.x, o.b.y);
       });
     else
-      epilogue_rounds<false>(patch, patch_alt, acc, none, as_f32, [&](const EpiIdx& x, const EpiOut& o) {
+      epilogue_rounds8<false>(patch, jh, acc, none, as_f32, [&](const EpiIdx& x, const EpiOut& o) {
         if (valid(x)) *(uint4*)addr.at(out, x) = make_uint4(o.a.x, o.a.y, o.b.x, o.b.y);
       });
   }
 }
 
 
-__global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_dma_bf16(const WgradDmaArgs p) {
+__global__ __launch_bounds__(kDmaThreads) void wgrad_gemm_dma_bf16(const WgradDmaArgs p) {
   __shared__ __align__(1024) unsigned char stage0[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char stage1[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
@@ -413,8 +413,8 @@ struct WgradIssueV {
   __device__ __forceinline__ void begin() {}
   __device__ __forceinline__ void part(lds_byte_t* stage, int q) const {
     const int kv = issued < T ? rows_left : 0;
-    if (q < 4) l_src.part(stage, lp, kv, q);
-    else r_src.part(stage + kDmaTileBytes, rp, kv, q - 4);
+    if (q < kOpLoads) l_src.part(stage, lp, kv, q);
+    else r_src.part(stage + kDmaTileBytes, rp, kv, q - kOpLoads);
   }
   __device__ __forceinline__ void end() {
     ++issued;
@@ -427,7 +427,7 @@ struct WgradIssueV {
   }
 };
 
-__global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_persist_bf16(const WgradDmaArgs p) {
+__global__ __launch_bounds__(kDmaThreads) void wgrad_gemm_persist_bf16(const WgradDmaArgs p) {
   __shared__ __align__(1024) unsigned char stage0[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char stage1[kDmaStageBytes];
   __shared__ __align__(1024) unsigned char stage2[kDmaStageBytes];
@@ -444,7 +444,7 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_persist_bf16(const Wg
   const unsigned total = patched_grid(grid_rows, n_tiles);
   const unsigned G = gridDim.x;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = dma_wave_wm(wave), wn = wave & 1, cb0 = dma_wave_cb0(wave);
 
   struct Tile {
     int e, seg, nseg, slot, m0, n0, KT;
@@ -496,10 +496,10 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_persist_bf16(const Wg
   Tile t;
   describe(grow, nt, &t, &issue);
   dma_prefetch3(s0, s1, s2, issue);
-  float* const patch = (float*)stage3 + wave * (32 * 64);      // wave-private; stage 3 is the one the next tile has not touched yet
+  float* const patch = (float*)stage3 + wave * (16 * 64);      // wave-private, 4 KB; stage 3 is the one the next tile has not touched yet
 
   for (;;) {
-    f32x16 acc[MB][NB];
+    DmaAcc acc;
     zero_acc(acc);
     unsigned nidx = idx + G;
     int ngrow, nnt;
@@ -508,7 +508,7 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_persist_bf16(const Wg
     WgradIssueV next = issue;
     Tile tn;
     describe(has_next ? ngrow : grow, has_next ? nnt : nt, &tn, &next);
-    dma_pipeline_cont<true, true>(s0, s1, s2, s3, acc, issue, t.KT, next, wm, wn, []() {}, [](WgradIssueV&) {});
+    dma_pipeline_cont<true, true>(s0, s1, s2, s3, acc, issue, t.KT, next, wm, cb0, []() {}, [](WgradIssueV&) {});
 
     const int col_base = t.n0 + wn * (NB * 32);
     auto none = [](const EpiIdx&) { return make_uint2(0, 0); };
@@ -516,8 +516,8 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_persist_bf16(const Wg
       bf16_t* out = p.dw + (size_t)t.e * M * NC + (size_t)t.m0 * NC + col_base;      // the wave's block of the tile
       EpiAddr<2> addr;
       addr.init(wm, NC);
-      epilogue_rounds<false>(
-          patch, patch, acc, none,
+      epilogue_rounds8<false>(
+          patch, wave >> 2, acc, none,
           [](const EpiIdx&, float4 c, uint2) { return EpiOut{pack4(c.x, c.y, c.z, c.w), make_uint2(0, 0)}; },
           [&](const EpiIdx& x, const EpiOut& o) { store_nt8(addr.at(out, x), o.a); });      // written once
     } else {
@@ -525,8 +525,8 @@ __global__ __launch_bounds__(kGemmThreads) void wgrad_gemm_persist_bf16(const Wg
       float* out = p.partial + (size_t)(t.slot + t.seg) * M * NC + (size_t)t.m0 * NC + col_base;
       EpiAddr<4> addr;
       addr.init(wm, NC);
-      epilogue_rounds<false>(
-          patch, patch, acc, none,
+      epilogue_rounds8<false>(
+          patch, wave >> 2, acc, none,
           [](const EpiIdx&, float4 c, uint2) {
             return EpiOut{make_uint2(__float_as_uint(c.x), __float_as_uint(c.y)),
                           make_uint2(__float_as_uint(c.z), __float_as_uint(c.w))};
