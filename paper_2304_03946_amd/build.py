@@ -54,6 +54,24 @@ def build_probe(verbose: bool = True) -> str:
     return out
 
 
+def build_phases_library(verbose: bool = True) -> str:
+    """A second library with per-tile phase timers in the persistent GEMM kernels (-DFLEXMOE_TILE_PHASES), for
+    paper_2304_03946_amd/tile_phases.py; not loaded by anything else.  Needs the objects of build_library()."""
+    out = os.path.join(PKG, "libflexmoe_phases.so")
+    obj = os.path.join(CSRC, "ffn_bf16_phases.o")
+    r = subprocess.run([HIPCC, *FLAGS, "-DFLEXMOE_TILE_PHASES", "-c", os.path.join(CSRC, "ffn_bf16.hip"), "-o", obj],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for ffn_bf16.hip (phases):\n" + r.stderr)
+    objs = [obj if s == "ffn_bf16.hip" else os.path.join(CSRC, os.path.splitext(s)[0] + ".o") for s in SOURCES]
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n" + r.stderr)
+    if verbose:
+        print(f"built {out}")
+    return out
+
+
 def build_library(verbose: bool = True) -> str:
     """Compile every source and link the shared library; always rebuilds."""
     generate_tables()
@@ -71,3 +89,4 @@ def build_library(verbose: bool = True) -> str:
 if __name__ == "__main__":
     build_library()
     build_probe()
+    build_phases_library()

@@ -190,15 +190,16 @@ static hipError_t launch_rows(const FfnArgs& a, const void* in, const void* w, c
 
 // One weight-gradient product's arguments and grid; `ws_tail` holds its job table and fp32 partial
 // tiles when the contraction is cut into segments (wgrad_tail_bytes each).
+// product: 0 = dW2 (M = f, NC = d), 1 = dW1 (M = d, NC = f): which of the plan's two work lists it reads.
 static WgradDmaArgs wgrad_dma_args(const FfnArgs& a, const void* L, const void* R, int M, int NC, void* dw,
-                                   void* ws_tail, void* ws, unsigned* grid) {
+                                   void* ws_tail, void* ws, unsigned* grid, int product) {
   const int m_tiles = (M + BM - 1) / BM, n_tiles = (NC + BN - 1) / BN;
   const int seg_tiles = wgrad_seg_tiles(a.A, a.d, a.f);
   float* partial = seg_tiles ? (float*)ws_tail : nullptr;
   const int seg_rows_max = wgrad_seg_rows_max(a.A, a.d, a.f, a.E, a.V);
   *grid = patched_grid(seg_rows_max * m_tiles, n_tiles);
   return WgradDmaArgs{(const bf16_t*)L, (const bf16_t*)R, a.voff, a.owner, a.E, a.V, M, NC, m_tiles, n_tiles,
-                      seg_tiles, seg_rows_max, partial, wgrad_plan_at(wgrad_plan_ws(a, ws), seg_rows_max, a.E, a.V),
+                      seg_tiles, seg_rows_max, partial, wgrad_plan_at(wgrad_plan_ws(a, ws), seg_rows_max, a.E, a.V, product),
                       (bf16_t*)dw};
 }
 
@@ -207,9 +208,14 @@ static WgradDmaArgs wgrad_dma_args(const FfnArgs& a, const void* L, const void* 
 static void launch_bwd_plan(const FfnArgs& a, void* ws, hipStream_t s) {
   const int seg_rows_max = wgrad_seg_rows_max(a.A, a.d, a.f, a.E, a.V);
   const int row_blocks = a.A > 0 ? std::max(1, std::min(64, (max_row_tiles(a.A, a.V) + kGemmThreads - 1) / kGemmThreads)) : 0;
+  const int f_tiles = (a.f + BM - 1) / BM, d_tiles = (a.d + BM - 1) / BM;
+  const bool whole = a.f % BM == 0 && a.d % BN == 0;
   hipLaunchKernelGGL(ffn_bwd_plan_kernel, dim3(1 + row_blocks), dim3(kGemmThreads), 0, s, a.voff, a.owner, a.E, a.V,
                      wgrad_seg_tiles(a.A, a.d, a.f), seg_rows_max,
-                     wgrad_plan_at(wgrad_plan_ws(a, ws), seg_rows_max, a.E, a.V), rows_tab_ws(a, ws));
+                     wgrad_plan_at(wgrad_plan_ws(a, ws), seg_rows_max, a.E, a.V, 0),
+                     // (only the persistent kernels skip the holes that balancing leaves in a list)
+                     whole ? wgrad_balance_geometry(f_tiles, d_tiles) : WgradBalance{1, 1},
+                     whole ? wgrad_balance_geometry(d_tiles, f_tiles) : WgradBalance{1, 1}, rows_tab_ws(a, ws));
 }
 
 static void launch_wgrad_reduce(const FfnArgs& a, const WgradDmaArgs& g, hipStream_t s) {
@@ -220,9 +226,9 @@ static void launch_wgrad_reduce(const FfnArgs& a, const WgradDmaArgs& g, hipStre
 }
 
 static hipError_t launch_wgrad(const FfnArgs& a, const void* L, const void* R, int M, int NC, void* dw, void* ws_tail,
-                               void* ws, hipStream_t s) {
+                               void* ws, hipStream_t s, int product) {
   unsigned grid;
-  const WgradDmaArgs g = wgrad_dma_args(a, L, R, M, NC, dw, ws_tail, ws, &grid);
+  const WgradDmaArgs g = wgrad_dma_args(a, L, R, M, NC, dw, ws_tail, ws, &grid, product);
   if (M % BM == 0 && NC % BN == 0)      // whole output tiles: one persistent workgroup per compute unit
     hipLaunchKernelGGL(wgrad_gemm_persist_bf16, dim3(std::min(grid, (unsigned)kComputeUnits)), dim3(kDmaThreads), 0, s, g);
   else
@@ -299,9 +305,17 @@ hipError_t launch_ffn_bwd_bf16(const FfnArgs& a, const void* dyp, const void* xp
                                        rows_split_ws(a, ws), scatter_src);
     if (err != hipSuccess) return err;
   }
-  err = launch_wgrad(a, h, dyp, a.f, a.d, dw2, ws_tail2, ws, s);
+  err = launch_wgrad(a, h, dyp, a.f, a.d, dw2, ws_tail2, ws, s, 0);
   if (err != hipSuccess) return err;
-  return launch_wgrad(a, xp, dhpre, a.d, a.f, dw1, ws_tail1, ws, s);
+  return launch_wgrad(a, xp, dhpre, a.d, a.f, dw1, ws_tail1, ws, s, 1);
 }
 
 }  // namespace flexmoe
+
+#ifdef FLEXMOE_TILE_PHASES
+// Profiling build only: copies the per-workgroup phase counters of the persistent GEMM kernels (5 x 256 x 4 uint64,
+// see TilePhases) to host memory.
+extern "C" int flexmoe_debug_tile_phases(unsigned long long* host_out) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(flexmoe::g_tile_phases), sizeof(flexmoe::g_tile_phases));
+}
+#endif

@@ -129,6 +129,34 @@ __device__ __forceinline__ bool find_tile(const TileSeq& q, unsigned* idx, unsig
   return false;
 }
 
+// Profiling build only (-DFLEXMOE_TILE_PHASES, paper_2304_03946_amd/tile_phases.py): per workgroup, the 100 MHz
+// clock ticks spent from a tile's start to its first barrier ("top": the previous epilogue's stragglers, the wait
+// for the first K tile), in the K loop and in the epilogue, and the tiles done; one set per kind of rows product.
+#ifdef FLEXMOE_TILE_PHASES
+__device__ unsigned long long g_tile_phases[5][256][4];      // [GEMM1, GEMM2, dH, dXp, weight gradient][workgroup][top, K loop, epilogue, tiles]
+struct TilePhases {
+  unsigned long long top = 0, kloop = 0, epi = 0, n = 0, c0 = 0, c1 = 0, c2 = 0;
+  __device__ __forceinline__ void start() { c0 = c1 = wall_clock64(); }
+  __device__ __forceinline__ void first_barrier() { c1 = wall_clock64(); }
+  __device__ __forceinline__ void k_done() { c2 = wall_clock64(); }
+  __device__ __forceinline__ void tile_done(int kind, bool last) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    const unsigned long long c3 = wall_clock64();
+    top += c1 - c0; kloop += c2 - c1; epi += c3 - c2; n += 1;
+    if (last && threadIdx.x == 0) {
+      g_tile_phases[kind][blockIdx.x][0] = top; g_tile_phases[kind][blockIdx.x][1] = kloop;
+      g_tile_phases[kind][blockIdx.x][2] = epi; g_tile_phases[kind][blockIdx.x][3] = n;
+    }
+  }
+};
+#else
+struct TilePhases {
+  __device__ __forceinline__ void start() {}
+  __device__ __forceinline__ void first_barrier() {}
+  __device__ __forceinline__ void k_done() {}
+  __device__ __forceinline__ void tile_done(int, bool) {}
+};
+#endif
 template <typename WSrc> struct RowsIssueV {
   DmaSrc a_src;
   WSrc w_src;
@@ -220,7 +248,9 @@ __global__ __launch_bounds__(kDmaThreads) void rows_gemm_persist_bf16(const Rows
   dma_prefetch3(s0, s1, s2, issue);
   float* const patch = (float*)stage3 + wave * (16 * 64);      // wave-private, 4 KB; stage 3 is the one the next tile has not touched yet
 
+  TilePhases phases;
   for (;;) {
+    phases.start();
     DmaAcc acc;
     zero_acc(acc);
     // the workgroup's next tile
@@ -235,12 +265,14 @@ __global__ __launch_bounds__(kDmaThreads) void rows_gemm_persist_bf16(const Rows
     dma_pipeline_cont<false, !WT>(
         s0, s1, s2, s3, acc, issue, KT, next, wm, cb0,
         [&]() {
+          phases.first_barrier();
           if (EPI == EPI_PLAIN && p.scatter_rows && t.nseg == 1 && threadIdx.x < BM)
             smap_lds[threadIdx.x] = p.scatter_rows[t.row0 + min((int)threadIdx.x, t.rows_valid - 1)];
         },
         [&](Issue& nx) {
           if constexpr (!GATHER) nx = make_issue(tn);
         });
+    phases.k_done();
     if (EPI == EPI_PLAIN && t.nseg > 1) {
       // one K segment of a split tile: fp32 partial tile (all 256 x 256 entries) for the reduce kernel
       float* out = p.split_partial + (size_t)t.slot * (BM * BN);
@@ -259,6 +291,7 @@ __global__ __launch_bounds__(kDmaThreads) void rows_gemm_persist_bf16(const Rows
       rows_epilogue<EPI, ACT, kLut, 8>((float*)stage3, (float*)stage3, acc, p.bias, NC, t.row0, t.rows_valid, t.e, t.n0,
                                     p.hpre_in, p.out0, p.out1, lut, smap);
     }
+    phases.tile_done((WT ? 2 : 0) + (EPI == EPI_PLAIN ? 1 : 0), !has_next);
     if (!has_next) break;
     t = tn;
     issue = next;

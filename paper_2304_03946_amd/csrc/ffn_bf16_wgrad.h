@@ -21,16 +21,27 @@ struct WgradJob {
   int nseg;     // segments of this expert
   int slot;     // index of the expert's first partial tile set (meaningful when nseg > 1)
 };
+// The work list exists twice, once per weight-gradient product, because the order of the jobs is also what spreads
+// them over the XCDs: position j of the list owns grid rows j * m_tiles .. of the patched tile grid, whose patches
+// go to the XCDs round-robin.  When a job's tiles fill fewer than eight patches (mid-size layers: two patches per
+// job, or several jobs per patch), a list in descending load would hand the heaviest job of every round to the
+// same XCDs (measured on the GPT-medium-like layer: two XCDs busy for 400 us, the others for 200-250).  So the jobs
+// are dealt out heaviest first, each to the bin with the least work so far (balance_jobs; a bin = an XCD group, or,
+// where several jobs share a patch, one of the patch's job slots: its workgroups are a fixed part of the XCD's
+// compute units); a bin that holds a heavy job then gets fewer jobs, and the positions it leaves unused are holes
+// (e = -1) that the kernels skip.
+// `groups` and `per_slot` describe the product's geometry (wgrad_balance_geometry).
 // Layout of the plan in the workspace (all int32 / int4, offsets in bytes from its 256-byte aligned start):
-//   jobs      [seg_rows_max] int4 {e, seg, nseg, slot} in work-list order (e = -1 past the end)
+//   jobs      2 x [2 seg_rows_max] int4 {e, seg, nseg, slot} by list position (e = -1: no job): dW2's list, dW1's list
 //   table     [FLEXMOE_MAX_EXPERTS] int4 {expert, segments, first slot, 0} by load rank (for wgrad_reduce_kernel)
 //   boff      [E + 1]  int: expert e's non-empty buckets are entries boff[e] .. boff[e+1] of the two lists below
 //   bstart    [V]      int: first row of the bucket
 //   brows     [V]      int: rows of the bucket
 //   etiles    [E]      int: 32-token K tiles of the expert (sum over its buckets of ceil(rows / 32))
-//   njobs     [1]      int: entries of `jobs` in use
+//   njobs     [2]      int: positions of dW2's / dW1's list in use
 struct WgradPlan {
-  int4* jobs;
+  int4* jobs;             // the list of the product at hand (wgrad_plan_at's `product`: 0 = dW2, 1 = dW1)
+  int4* jobs_other;
   int4* table;
   int* boff;
   int* bstart;
@@ -39,35 +50,92 @@ struct WgradPlan {
   int* njobs;
 };
 __host__ __device__ inline size_t wgrad_plan_bytes(int seg_rows_max, int E, int V) {
-  return ((size_t)seg_rows_max + FLEXMOE_MAX_EXPERTS) * sizeof(int4) + (2 * (size_t)E + 2 + 2 * (size_t)V) * sizeof(int);
+  return (4 * (size_t)seg_rows_max + FLEXMOE_MAX_EXPERTS) * sizeof(int4) + (2 * (size_t)E + 4 + 2 * (size_t)V) * sizeof(int);
 }
-__host__ __device__ inline WgradPlan wgrad_plan_at(void* base, int seg_rows_max, int E, int V) {
+__host__ __device__ inline WgradPlan wgrad_plan_at(void* base, int seg_rows_max, int E, int V, int product = 0) {
   WgradPlan p;
-  p.jobs = (int4*)base;
-  p.table = p.jobs + seg_rows_max;
+  p.jobs = (int4*)base + (product ? 2 * seg_rows_max : 0);
+  p.jobs_other = (int4*)base + (product ? 0 : 2 * seg_rows_max);
+  p.table = (int4*)base + 4 * seg_rows_max;
   p.boff = (int*)(p.table + FLEXMOE_MAX_EXPERTS);
   p.bstart = p.boff + E + 1;
   p.brows = p.bstart + V;
   p.etiles = p.brows + V;
-  p.njobs = p.etiles + E;
+  p.njobs = p.etiles + E + (product ? 1 : 0);
   return p;
 }
+
+// How the positions of a product's work list map to XCDs: `groups` XCD groups take turns, `per_slot` consecutive
+// jobs per turn.  groups = 1: nothing to balance (a job covers all XCDs evenly, or the geometry is irregular).
+struct WgradBalance {
+  int groups, per_slot;
+};
+__host__ __device__ inline WgradBalance wgrad_balance_geometry(int m_tiles, int n_tiles) {
+  const int pw = patch_width(n_tiles), ph = kPatch / pw, npc = (n_tiles + pw - 1) / pw;
+  if (pw * ph != kPatch) return WgradBalance{1, 1};
+  if (m_tiles % ph == 0) {
+    const int pj = (m_tiles / ph) * npc;                 // patches per job
+    if (pj < kXcds && kXcds % pj == 0) return WgradBalance{kXcds / pj, 1};
+    return WgradBalance{1, 1};
+  }
+  if (ph % m_tiles == 0 && npc == 1) return WgradBalance{kXcds, ph / m_tiles};      // several jobs per patch
+  return WgradBalance{1, 1};
+}
+constexpr int kPlanJobsLds = 1024;      // work lists up to this length are balanced (longer ones keep load order)
+constexpr int kBalanceBins = 64;        // ... if the geometry has at most this many bins and jobs x bins <= kBalanceWork
+constexpr int kBalanceWork = 16384;     // (one thread deals the jobs out)
 
 struct WgradPlanShared {
   int cnt[FLEXMOE_MAX_VEXPERTS], own[FLEXMOE_MAX_VEXPERTS];
   int load[FLEXMOE_MAX_EXPERTS], tiles[FLEXMOE_MAX_EXPERTS], nbuckets[FLEXMOE_MAX_EXPERTS];
   int rank_e[FLEXMOE_MAX_EXPERTS], rank_s[FLEXMOE_MAX_EXPERTS];
   int boff[FLEXMOE_MAX_EXPERTS + 1];
+  int4 jobs[kPlanJobsLds];
+  int njobs;
+  int bal_load[2][kBalanceBins], bal_count[2][kBalanceBins];
 };
+// One thread: deals the work list (in load order in LDS) out to dst as described above; dst holds -1 everywhere on
+// entry.  Returns the positions in use.  A group's list may grow to twice the even share of positions, so that
+// 2 seg_rows_max positions always suffice.
+__device__ inline int balance_jobs(WgradPlanShared& sh, int which, WgradBalance geo, int seg_tiles, int positions,
+                                   int4* __restrict__ dst) {
+  const int J = sh.njobs, nb = geo.groups * geo.per_slot;      // position p belongs to bin p % nb
+  const int rounds_max = positions / nb;                       // what fits the list
+  if (geo.groups <= 1 || nb > kBalanceBins || J * nb > kBalanceWork || rounds_max * nb < J) {
+    for (int j = 0; j < J; ++j) dst[j] = sh.jobs[j];
+    return J;
+  }
+  int* load = sh.bal_load[which];
+  int* count = sh.bal_count[which];
+  for (int c = 0; c < nb; ++c) load[c] = count[c] = 0;
+  // jobs per bin at most: twice the even share (once, twice and three times measured the same to 0.5 %)
+  const int limit = min(2 * ((J + nb - 1) / nb), rounds_max);
+  int rounds = 0;
+  for (int j = 0; j < J; ++j) {
+    int c = -1;
+    for (int q = 0; q < nb; ++q)
+      if (count[q] < limit && (c < 0 || load[q] < load[c])) c = q;
+    const int4 job = sh.jobs[j];
+    const int Te = sh.tiles[job.x];
+    const int len = job.z > 1 ? min(seg_tiles, Te - job.y * seg_tiles) : Te;
+    load[c] += max(4, (len + 3) & ~3) + 6;               // K tiles of the job + its fixed cost per output tile
+    dst[count[c] * nb + c] = job;
+    count[c] += 1;
+    rounds = max(rounds, count[c]);
+  }
+  return rounds * nb;
+}
+
 // Buckets of the job's expert, copied from the plan into LDS by the workgroup that runs the job.
 struct WgradShared {
   int nb;
   int bstart[FLEXMOE_MAX_VEXPERTS], brows[FLEXMOE_MAX_VEXPERTS];
 };
 
-// One workgroup of kGemmThreads threads; see the layout above.
+// plan: made for product 0 (plan.jobs = dW2's list, plan.jobs_other = dW1's); geo0 / geo1: the two products' geometry.
 __device__ __forceinline__ void wgrad_plan_block(const int32_t* __restrict__ voff, const int32_t* __restrict__ owner, int E,
-                                                 int V, int seg_tiles, int seg_rows_max, const WgradPlan& plan) {
+                                                 int V, int seg_tiles, int seg_rows_max, const WgradPlan& plan,
+                                                 WgradBalance geo0, WgradBalance geo1) {
   __shared__ WgradPlanShared sh;
   for (int v = threadIdx.x; v < V; v += kGemmThreads) {
     sh.cnt[v] = voff[v + 1] - voff[v];
@@ -127,7 +195,15 @@ __device__ __forceinline__ void wgrad_plan_block(const int32_t* __restrict__ vof
         const int n = sh.rank_s[r];
         plan.table[r] = make_int4(sh.rank_e[r], n, slot, 0);
         for (int sg = 0; sg < n; ++sg)
-          if (start + sg < seg_rows_max) plan.jobs[start + sg] = make_int4(sh.rank_e[r], sg, n, slot);
+          if (start + sg < seg_rows_max) {
+            const int4 job = make_int4(sh.rank_e[r], sg, n, slot);
+            if (seg_rows_max <= kPlanJobsLds) {
+              sh.jobs[start + sg] = job;
+            } else {
+              plan.jobs[start + sg] = job;
+              plan.jobs_other[start + sg] = job;
+            }
+          }
         start += n;
         slot += n > 1 ? n : 0;
         sh.boff[r] = bo;
@@ -139,12 +215,29 @@ __device__ __forceinline__ void wgrad_plan_block(const int32_t* __restrict__ vof
     if (lane == 0) {
       sh.boff[E] = total_b;
       plan.boff[E] = total_b;
-      plan.njobs[0] = min(total, seg_rows_max);
+      sh.njobs = min(total, seg_rows_max);
+      if (seg_rows_max > kPlanJobsLds) plan.njobs[0] = plan.njobs[1] = sh.njobs;
     }
     for (int e = lane; e < E; e += kWave) plan.etiles[e] = sh.tiles[e];
-    for (int w = total + lane; w < seg_rows_max; w += kWave) plan.jobs[w] = make_int4(-1, 0, 0, 0);
   }
-  __syncthreads();
+  // the two products' lists, dealt out so that their XCD groups get equal work (one thread of waves 1 and 2 each;
+  // the bucket lists below are written meanwhile)
+  if (seg_rows_max <= kPlanJobsLds) {
+    for (int w = threadIdx.x; w < 2 * seg_rows_max; w += kGemmThreads) {
+      plan.jobs[w] = make_int4(-1, 0, 0, 0);
+      plan.jobs_other[w] = make_int4(-1, 0, 0, 0);
+    }
+    __threadfence_block();
+    __syncthreads();
+    if (threadIdx.x == kWave) plan.njobs[0] = balance_jobs(sh, 0, geo0, seg_tiles, 2 * seg_rows_max, plan.jobs);
+    if (threadIdx.x == 2 * kWave) plan.njobs[1] = balance_jobs(sh, 1, geo1, seg_tiles, 2 * seg_rows_max, plan.jobs_other);
+  } else {
+    __syncthreads();
+    for (int w = sh.njobs + threadIdx.x; w < 2 * seg_rows_max; w += kGemmThreads) {
+      plan.jobs[w] = make_int4(-1, 0, 0, 0);
+      plan.jobs_other[w] = make_int4(-1, 0, 0, 0);
+    }
+  }
   // bucket lists: a wave per expert, the expert's non-empty buckets in ascending vExpert id
   {
     const int lane = threadIdx.x & (kWave - 1);
@@ -171,8 +264,9 @@ __device__ __forceinline__ void wgrad_plan_block(const int32_t* __restrict__ vof
 __global__ __launch_bounds__(kGemmThreads) void ffn_bwd_plan_kernel(const int32_t* __restrict__ voff,
                                                                     const int32_t* __restrict__ owner, int E, int V,
                                                                     int seg_tiles, int seg_rows_max, WgradPlan plan,
+                                                                    WgradBalance geo0, WgradBalance geo1,
                                                                     i32x4* __restrict__ row_tab) {
-  if (blockIdx.x == 0) wgrad_plan_block(voff, owner, E, V, seg_tiles, seg_rows_max, plan);
+  if (blockIdx.x == 0) wgrad_plan_block(voff, owner, E, V, seg_tiles, seg_rows_max, plan, geo0, geo1);
   else rows_plan_block(voff, owner, V, row_tab, blockIdx.x - 1, gridDim.x - 1);
 }
 
@@ -449,10 +543,10 @@ __global__ __launch_bounds__(kDmaThreads) void wgrad_gemm_persist_bf16(const Wgr
   struct Tile {
     int e, seg, nseg, slot, m0, n0, KT;
   };
-  // the first position from idx on (steps of G) that holds a tile
+  // the first position from idx on (steps of G) that holds a tile of a job (the list has holes: e = -1)
   auto find = [&](unsigned* idx, int* grow, int* nt) {
     for (; *idx < total; *idx += G)
-      if (patched_tile(*idx, grid_rows, n_tiles, grow, nt)) return true;
+      if (patched_tile(*idx, grid_rows, n_tiles, grow, nt) && jobs[*grow / m_tiles][0] >= 0) return true;
     return false;
   };
   // tile -> its description and its K-tile sequence (scalars only)
@@ -498,7 +592,9 @@ __global__ __launch_bounds__(kDmaThreads) void wgrad_gemm_persist_bf16(const Wgr
   dma_prefetch3(s0, s1, s2, issue);
   float* const patch = (float*)stage3 + wave * (16 * 64);      // wave-private, 4 KB; stage 3 is the one the next tile has not touched yet
 
+  TilePhases phases;
   for (;;) {
+    phases.start();
     DmaAcc acc;
     zero_acc(acc);
     unsigned nidx = idx + G;
@@ -508,7 +604,9 @@ __global__ __launch_bounds__(kDmaThreads) void wgrad_gemm_persist_bf16(const Wgr
     WgradIssueV next = issue;
     Tile tn;
     describe(has_next ? ngrow : grow, has_next ? nnt : nt, &tn, &next);
-    dma_pipeline_cont<true, true>(s0, s1, s2, s3, acc, issue, t.KT, next, wm, cb0, []() {}, [](WgradIssueV&) {});
+    dma_pipeline_cont<true, true>(s0, s1, s2, s3, acc, issue, t.KT, next, wm, cb0, [&]() { phases.first_barrier(); },
+                                  [](WgradIssueV&) {});
+    phases.k_done();
 
     const int col_base = t.n0 + wn * (NB * 32);
     auto none = [](const EpiIdx&) { return make_uint2(0, 0); };
@@ -533,6 +631,7 @@ __global__ __launch_bounds__(kDmaThreads) void wgrad_gemm_persist_bf16(const Wgr
           },
           [&](const EpiIdx& x, const EpiOut& o) { *(uint4*)addr.at(out, x) = make_uint4(o.a.x, o.a.y, o.b.x, o.b.y); });
     }
+    phases.tile_done(4, !has_next);
     if (!has_next) break;
     t = tn;
     issue = next;

@@ -49,7 +49,7 @@ def test_status_strings_and_workspace_size():
     # rows per vExpert, the job count) and the table of 256-row tiles of the bucket list (16 bytes each, at most A / 256 + V of them, and a
     # header), each rounded up to 256 bytes
     ws = binding.flexmoe_workspace_bytes(65536, 2048, 8192, 64, 2, 96, binding.BF16)
-    plan = (64 + 256) * 16 + (2 * 64 + 2 + 2 * 96) * 4
+    plan = (4 * 64 + 256) * 16 + (2 * 64 + 4 + 2 * 96) * 4      # one work list (with room for holes) and one length per weight-gradient product
     tiles = (131072 // 256 + 96 + 1) * 16
     assert ws == 2 * 131072 * 8192 * 2 + 256 * 256 * 256 * 4 + (plan + 255) // 256 * 256 + (tiles + 255) // 256 * 256
     assert binding.flexmoe_workspace_bytes(16, 12, 64, 4, 1, 4, binding.BF16) == 0      # d not a multiple of 8
