@@ -150,7 +150,7 @@ static hipError_t launch_rows_t(const FfnArgs& a, const void* in, const void* w,
       p.split_partial = (float*)split_ws;
       p.normal_grid = grid;
       hipLaunchKernelGGL((rows_gemm_persist_bf16<WT, EPI, ACT, false>), dim3(persist), dim3(kDmaThreads), 0, s, p, row_tab);
-      hipLaunchKernelGGL(rows_split_reduce_kernel, dim3(kSplitSlices, kSplitUnits / kSplitMax), dim3(kGemmThreads), 0, s, p);
+      hipLaunchKernelGGL(rows_split_reduce_kernel, dim3(kSplitSlices, kSplitUnits / 2), dim3(kGemmThreads), 0, s, p);      // up to 128 tail tiles (two segments each)
       return hipGetLastError();
     }
     if constexpr (!WT && EPI == EPI_FWD1) {

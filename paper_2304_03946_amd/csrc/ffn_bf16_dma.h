@@ -318,7 +318,7 @@ struct RowsDmaArgs {
 };
 
 // Sum of the K segments of the split tail tiles (see lookup_row_tile): out = bf16(sum over
-// segments in order + bias).  Grid: (kSplitSlices row slices of a tile, kSplitUnits / kSplitMax tail tiles).
+// segments in order + bias).  Grid: (kSplitSlices row slices of a tile, kSplitUnits / 2 tail tiles at most).
 constexpr int kSplitSlices = 16;
 __global__ __launch_bounds__(kGemmThreads) void rows_split_reduce_kernel(const RowsDmaArgs p) {
   __shared__ int s_tile[8];

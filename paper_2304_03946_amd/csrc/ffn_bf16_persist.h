@@ -94,8 +94,9 @@ __device__ __forceinline__ TileSeq make_tile_seq(int rows_act, int col_tiles, bo
     const int full = rows_act * col_tiles / kSplitUnits;
     const int r_split = full * kSplitUnits / col_tiles;
     const int tail_tiles = (rows_act - r_split) * col_tiles;
-    if (full >= 1 && tail_tiles > 0 && kSplitMax * tail_tiles <= kSplitUnits && k_tiles % (4 * kSplitMax) == 0) {
-      q.S = kSplitMax;
+    const int S = split_factor(full, tail_tiles, k_tiles);
+    if (S > 1) {
+      q.S = S;
       q.r_split = r_split;
       q.tail_tiles = tail_tiles;
     }

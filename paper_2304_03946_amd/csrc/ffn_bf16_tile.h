@@ -669,7 +669,7 @@ struct RowTile {
 // contraction).  With T valid tiles on 256 compute units, the tiles of the row tiles from
 // r_split = floor(floor(T / 256) * 256 / col_tiles) on are the ones left for that last round; when
 // they fill at most a quarter of the chip, each is contracted by S = 4 workgroups (K segments of equal
-// length, a whole number of pipeline rounds each): segment 0 by the tile's own workgroup, segments
+// length, a whole number of pipeline rounds each; S = 2 when they fill up to half of it): segment 0 by the tile's own workgroup, segments
 // 1..S-1 by extra workgroups appended to the grid (block >= normal_grid).  Every segment leaves an
 // fp32 partial tile; rows_split_reduce_kernel adds them in segment order (fixed order: results do
 // not depend on scheduling).  The plan is a function of the bucket sizes: every workgroup derives
@@ -677,6 +677,14 @@ struct RowTile {
 constexpr int kSplitMax = 4;
 constexpr int kSplitUnits = 256;                      // compute units a round of workgroups fills
 constexpr int kSplitMaxSlots = kSplitUnits;           // tail tiles x S <= 256
+// In how many K segments the tail tiles are contracted: four when they then still fit one round of workgroups, else
+// two, else one (no splitting); a segment is a whole number of pipeline rounds (four K tiles).
+__host__ __device__ inline int split_factor(int full_rounds, int tail_tiles, int k_tiles) {
+  if (full_rounds < 1 || tail_tiles <= 0) return 1;
+  if (4 * tail_tiles <= kSplitUnits && k_tiles % 16 == 0) return 4;
+  if (2 * tail_tiles <= kSplitUnits && k_tiles % 8 == 0) return 2;
+  return 1;
+}
 struct SplitArg {
   unsigned normal_grid;      // blocks of the unsplit grid; 0 = no splitting
   int k_tiles;               // K / 32
@@ -718,10 +726,9 @@ __device__ __forceinline__ bool lookup_row_tile(const int32_t* __restrict__ voff
       const int full = rows_act * col_tiles / kSplitUnits;
       const int r_split = full * kSplitUnits / col_tiles;
       const int tail_tiles = (rows_act - r_split) * col_tiles;
-      // four segments or none: cutting in two (tails of 65 to 128 tiles) measured no faster than not
-      // cutting, the fp32 round trip of the partial tiles eats what the shorter last round gains
-      const int S = (full >= 1 && tail_tiles > 0 && kSplitMax * tail_tiles <= kSplitUnits &&
-                     sp.k_tiles % (4 * kSplitMax) == 0) ? kSplitMax : 1;
+      // (cutting in two pays since the kernels are persistent: -3.6 % on the GPT-medium-like step, whose second
+      // forward product has 2.3 rounds of tiles; with one workgroup per tile it had measured no gain)
+      const int S = split_factor(full, tail_tiles, sp.k_tiles);
       if (sp.tail_tile < 0 && block < sp.normal_grid) {
         if (!patched_tile(block, row_tiles_max, col_tiles, &rt, &ct)) rt = -1;
         if (S > 1 && rt >= r_split && rt < rows_act) {
