@@ -76,10 +76,12 @@ struct DmaSrc {
 // Operand stored [K, ld] with the output index contiguous (the forward weights W_e [K, NC]): the
 // 32 x 256 tile is copied to LDS as it lies in memory, one k-row = 512 bytes = 32 chunks, two
 // k-rows per direct-load instruction, and transposed on the way out of LDS by ds_read_tr16_b64.
-// Chunk index XOR (k & 3) << 2 keeps those transposing reads free of bank conflicts.  Columns
+// Chunk index XOR (k & 3) << 2 XOR (k & 8) >> 2 keeps those transposing reads free of bank conflicts: a
+// group of 16 lanes reads 32 bytes of four consecutive k-rows (512 bytes apart: 64 bytes apart after the first
+// term), and the neighbouring group the same columns eight k-rows further (32 bytes aside by the second).  Columns
 // past cols_valid are clamped to the last valid 8-column chunk.
 typedef short s16x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ int dmat_chunk(int krow, int c) { return c ^ ((krow & 3) << 2); }
+__device__ __forceinline__ int dmat_chunk(int krow, int c) { return c ^ ((krow & 3) << 2) ^ ((krow & 8) >> 2); }
 
 struct DmaSrcT {
   const bf16_t* base;     // first contraction row, first column of the tile
@@ -105,25 +107,31 @@ struct DmaSrcT {
   }
 };
 
-// MFMA fragment (8 consecutive k of output column nb0 + lane%32, k = 16*ks + 8*(lane/32) ..) from
-// a [32 k][256 n] tile.  ds_read_tr16_b64 works on groups of 16 lanes: lanes 4m..4m+3 of a group
+// MFMA fragment (v_mfma_f32_16x16x32_bf16: 8 consecutive k of output column n0 + lane % 16, k = 8 (lane / 16) ..)
+// from a [32 k][256 n] tile.  ds_read_tr16_b64 works on groups of 16 lanes: lanes 4m..4m+3 of a group
 // address 16 consecutive elements of row m (4 each) and lane i of the group receives column i of
-// those four rows.  So lane L (group g = L/16, i = L%16) points at row k' + i/4, columns
-// nb0 + 16*(g%2) + 4*(i%4), with k' = 16*ks + 8*(g/2) (+4 for the second read).
-__device__ __forceinline__ bf16x8 dmat_read_frag(const lds_byte_t* tile, int nb0, int ks) {
-  const int L = threadIdx.x & 63;
+// those four rows.  So lane L (group g = L/16, i = L%16) points at row k = 8 g + i/4 (+4 for the second read),
+// columns n0 + 4 (i%4): byte k * 512 + 16 dmat_chunk(k, col / 8) + 2 (col % 8) of the tile.  With n0 = 16 m that is
+//   [k * 512 + 8 (i & 1) + 16 ((i & 3) >> 1) + 32 x(k)]  XOR  32 (m & 7),  + 256 (m >> 3),
+// x(k) = 2 (k & 3) ^ ((k >> 3) & 1): a lane constant, a constant of the fragment XORed in, a constant added.
+// The kernels keep only the lane constant in a register and form each fragment's address where it is read
+// (kept per fragment, a dozen address registers would push the accumulators' neighbours into scratch).
+__device__ __forceinline__ uint32_t dmat_lane(int L) {
   const int g = L >> 4, i = L & 15;
-  const int col = nb0 + 16 * (g & 1) + 4 * (i & 3);
-  const int k_lo = 16 * ks + 8 * (g >> 1) + (i >> 2);
-  const int k_hi = k_lo + 4;
-  const int a_lo = k_lo * 512 + (dmat_chunk(k_lo, col >> 3) << 4) + ((col & 7) << 1);
-  const int a_hi = k_hi * 512 + (dmat_chunk(k_hi, col >> 3) << 4) + ((col & 7) << 1);
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(tile + a_lo));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(tile + a_hi));
+  const int k = 8 * g + (i >> 2);
+  const int x = (((i >> 2) & 3) << 1) ^ (g & 1);
+  return (uint32_t)(k * 512 + 8 * (i & 1) + 16 * ((i & 3) >> 1) + (x << 5));
+}
+__device__ __forceinline__ bf16x8 dmat_read_frag(const lds_byte_t* at) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)at);
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(at + 4 * 512));
   typedef short s16x8 __attribute__((ext_vector_type(8)));
   const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, v);
 }
+// The same for a [256][32 k] tile (dma_off): lane L reads the 16 bytes of row n0 + L % 16, chunk L / 16; n0 = 16 m
+// only adds 1024 m.
+__device__ __forceinline__ uint32_t dma_lane(int L) { return (uint32_t)dma_off(L & 15, L >> 4); }
 
 // s_waitcnt vmcnt(n) only (expcnt / lgkmcnt fields left at "no wait").
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
@@ -133,10 +141,12 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // Returns once at most `tiles` of the most recently issued K tiles (2 kOpLoads direct loads per wave each) are in flight.
 template <int TILES> __device__ __forceinline__ void wait_tiles_in_flight() { wait_vmcnt<2 * kOpLoads * TILES>(); }
 
-struct DmaFrags {
-  Frag8 a[MB], b[NBW];
-};
-typedef f32x16 DmaAcc[MB][NBW];
+// The matrix instruction is v_mfma_f32_16x16x32_bf16: on real operands the chip holds a higher clock with it than
+// with the 32 x 32 x 16 form (half the accumulator traffic per flop; the instruction alone: 2.1 against 1.85 PFLOP/s).
+// A wave's 128 x 64 block is 8 x 4 of its 16 x 16 tiles.  Called as (column fragment, row fragment), lane L of a
+// tile holds row L % 16 and the four consecutive columns 4 (L / 16) ..: acc[i][j][2 si + sj] is the tile of rows
+// 16 si .., columns 16 sj .. of the wave's 32-row block i and 32-column block j.
+typedef f32x16 DmaAcc[MB][NBW];      // [i][j], elements 4 (2 si + sj) .. + 3: one 16 x 16 tile each
 __device__ __forceinline__ void zero_acc(DmaAcc& acc) {
 #pragma unroll
   for (int i = 0; i < MB; ++i)
@@ -145,30 +155,63 @@ __device__ __forceinline__ void zero_acc(DmaAcc& acc) {
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 }
+// A K tile is multiplied in two halves: row blocks 0, 1 of the wave (a0: four 16-row fragments), then 2, 3 (a1),
+// each against all four 16-column fragments b, which are read once per tile.
+struct DmaFrags {
+  Frag8 a0[4], a1[4], b[4];
+  uint32_t la, lb;      // lane parts of the fragment addresses inside a stage (first / second operand)
+};
 // TRA / TRB: the operand's LDS tile is [k][256] (transposing reads) instead of [256][k].
-template <bool TRA, bool TRB>
-__device__ __forceinline__ void dma_read_frags(DmaFrags& f, const lds_byte_t* stage, int ks, int wm, int cb0) {
-  const int lane = threadIdx.x & 63;
-  const int r = lane & 31, h = lane >> 5;
-  const lds_byte_t* As = stage;
-  const lds_byte_t* Bs = stage + kDmaTileBytes;
+template <bool TRA, bool TRB> __device__ __forceinline__ void dma_lane_init(DmaFrags& f, int wm, int cb0) {
+  const int L = opaque_tid() & 63;
+  f.la = TRA ? dmat_lane(L) ^ (uint32_t)(wm << 6) : dma_lane(L) + wm * 2048;
+  f.lb = kDmaTileBytes + (TRB ? (dmat_lane(L) ^ (uint32_t)(((2 * cb0) & 4) << 5)) + (cb0 >> 2) * 256 : dma_lane(L) + cb0 * 2048);
+}
+// The four row fragments of half `half` (row blocks i = 2 half, 2 half + 1 of the wave, rows 16 si .. of each;
+// 16-row unit m = 2 wm + 4 i + si, la carries the wave's wm).
+template <bool TR> __device__ __forceinline__ void dma_read_rows(Frag8 (&a)[4], const lds_byte_t* stage, uint32_t la, int half) {
 #pragma unroll
-  for (int i = 0; i < MB; ++i) {
-    if (TRA) f.a[i].v = dmat_read_frag(As, (wm + 2 * i) * 32, ks);
-    else f.a[i].v = *(const __attribute__((address_space(3))) bf16x8*)(As + dma_off((wm + 2 * i) * 32 + r, 2 * ks + h));
+  for (int p = 0; p < 4; ++p) {
+    const int i = 2 * half + (p >> 1), si = p & 1;
+    if (TR) a[p].v = dmat_read_frag(stage + ((la ^ (uint32_t)((4 * (i & 1) + si) << 5)) + (i >> 1) * 256));
+    else a[p].v = *(const __attribute__((address_space(3))) bf16x8*)(stage + (la + i * 4096 + si * 1024));
   }
+}
+// Column fragment q (columns 32 (cb0 + q / 2) + 16 (q % 2) ..) of the second operand's tile (lb carries cb0 and
+// the tile's place in the stage).
+template <bool TR> __device__ __forceinline__ void dma_read_col(Frag8& b, const lds_byte_t* stage, uint32_t lb, int q) {
+  if (TR) b.v = dmat_read_frag(stage + (lb ^ (uint32_t)(q << 5)));
+  else b.v = *(const __attribute__((address_space(3))) bf16x8*)(stage + (lb + (q >> 1) * 2048 + (q & 1) * 1024));
+}
+// Everything the first half of a tile's step needs (the K loop's entry).
+template <bool TRA, bool TRB>
+__device__ __forceinline__ void dma_read_first(DmaFrags& f, const lds_byte_t* stage, int wm, int cb0) {
+  dma_lane_init<TRA, TRB>(f, wm, cb0);
+  dma_read_rows<TRA>(f.a0, stage, f.la, 0);
 #pragma unroll
-  for (int j = 0; j < NBW; ++j) {
-    if (TRB) f.b[j].v = dmat_read_frag(Bs, (cb0 + j) * 32, ks);
-    else f.b[j].v = *(const __attribute__((address_space(3))) bf16x8*)(Bs + dma_off((cb0 + j) * 32 + r, 2 * ks + h));
+  for (int q = 0; q < 4; ++q) dma_read_col<TRB>(f.b[q], stage, f.lb, q);
+}
+// The 16 matrix instructions of column fragment q against the four row fragments of half `half`.
+__device__ __forceinline__ void dma_mfma_group(DmaAcc& acc, const Frag8 (&a)[4], const Frag8& b, int half, int q) {
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    f32x16& t = acc[2 * half + (p >> 1)][q >> 1];
+    const int e = 4 * (2 * (p & 1) + (q & 1));
+    f32x4 c = {t[e], t[e + 1], t[e + 2], t[e + 3]};
+    c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b.v, a[p].v, c, 0, 0, 0);
+    t[e] = c[0];
+    t[e + 1] = c[1];
+    t[e + 2] = c[2];
+    t[e + 3] = c[3];
   }
 }
 
-// One K tile (two 16-wide k steps).  On entry f0 holds the fragments of (tile kt, k step 0).
-// The barrier sits between the two k steps: before it the wave has fetched everything it needs
+// One K tile.  On entry f.a0 and f.b hold the fragments of tile kt's first half.
+// The barrier sits between the two halves: before it the wave has fetched everything it needs
 // from `cur`, so after it `cur` is free for tile kt+4; and tile kt+1 is published, so its first
-// fragments can be fetched while the second k step's MFMAs run -- no LDS latency after the barrier.
-// The direct loads are spread evenly between the MFMAs, one after every four (128 cycles of
+// fragments can be fetched while the second half's MFMAs run -- no LDS latency after the barrier: the row
+// fragments at once (a0 is free), each column fragment as soon as the second half is done with the current one.
+// The direct loads are spread evenly between the MFMAs, one after every eight (128 cycles of
 // matrix-pipe work): the waves share one address path, and a wave that issues its loads back
 // to back leaves its matrix pipe idle while it queues there.  So a tile's 2 kOpLoads loads per wave go
 // out in two halves: the first operand's (of tile kt+4) after the barrier of step kt (into `cur`, just
@@ -182,18 +225,18 @@ __device__ __forceinline__ void dma_read_frags(DmaFrags& f, const lds_byte_t* st
 // tile sequence, two different ones where the sequence of the workgroup's next output tile takes over.
 template <bool TRA, bool TRB, bool PRE, bool POST, int WAIT, bool NEXT, typename Issue, typename IssuePost>
 __device__ __forceinline__ void dma_step(lds_byte_t* prev, lds_byte_t* cur, const lds_byte_t* nxt, DmaAcc& acc,
-                                         DmaFrags& f0, DmaFrags& f1, Issue& issue, IssuePost& issue_post, int wm,
-                                         int cb0) {
-  constexpr int kEvery = MB / kOpLoads;      // a load after every kEvery-th group of NBW MFMAs
-  dma_read_frags<TRA, TRB>(f1, cur, 1, wm, cb0);
+                                         DmaFrags& f, Issue& issue, IssuePost& issue_post, int wm, int cb0) {
+  constexpr int kEvery = 4 / kOpLoads;      // a load after every kEvery-th group of four MFMAs
+  // (behind an empty asm: each fragment address is derived from these where it is used, not once for the whole loop)
+  asm volatile("" : "+v"(f.la), "+v"(f.lb));
+  const uint32_t la = f.la, lb = f.lb;
+  dma_read_rows<TRA>(f.a1, cur, la, 1);
 #pragma unroll
-  for (int i = 0; i < MB; ++i) {
+  for (int q = 0; q < 4; ++q) {
     __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < NBW; ++j)
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.b[j].v, f0.a[i].v, acc[i][j], 0, 0, 0);
+    dma_mfma_group(acc, f.a0, f.b[q], 0, q);
     __builtin_amdgcn_sched_barrier(0);
-    if (PRE && i % kEvery == kEvery - 1) issue.part(prev, kOpLoads + i / kEvery);
+    if (PRE && q % kEvery == kEvery - 1) issue.part(prev, kOpLoads + q / kEvery);
   }
   if (PRE) issue.end();
   __builtin_amdgcn_sched_barrier(0);     // everything above is queued before the wave goes to wait
@@ -201,16 +244,15 @@ __device__ __forceinline__ void dma_step(lds_byte_t* prev, lds_byte_t* cur, cons
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-  if (NEXT) dma_read_frags<TRA, TRB>(f0, nxt, 0, wm, cb0);
+  if (NEXT) dma_read_rows<TRA>(f.a0, nxt, la, 0);
   if (POST) issue_post.begin();
 #pragma unroll
-  for (int i = 0; i < MB; ++i) {
+  for (int q = 0; q < 4; ++q) {
     __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < NBW; ++j)
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.b[j].v, f1.a[i].v, acc[i][j], 0, 0, 0);
+    dma_mfma_group(acc, f.a1, f.b[q], 1, q);
+    if (NEXT) dma_read_col<TRB>(f.b[q], nxt, lb, q);
     __builtin_amdgcn_sched_barrier(0);
-    if (POST && i % kEvery == kEvery - 1) issue_post.part(cur, i / kEvery);
+    if (POST && q % kEvery == kEvery - 1) issue_post.part(cur, q / kEvery);
   }
 }
 
@@ -231,18 +273,18 @@ __device__ __forceinline__ void dma_pipeline(lds_byte_t* s0, lds_byte_t* s1, lds
   wait_vmcnt<5 * kOpLoads>();                          // tile 0 has landed (two and a half tiles younger)
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-  DmaFrags f0, f1;
-  dma_read_frags<TRA, TRB>(f0, s0, 0, wm, cb0);
+  DmaFrags f;
+  dma_read_first<TRA, TRB>(f, s0, wm, cb0);
   for (int kt = 0; kt < KT - 4; kt += 4) {
-    dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f0, f1, issue, issue, wm, cb0);
-    dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f0, f1, issue, issue, wm, cb0);
-    dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f0, f1, issue, issue, wm, cb0);
-    dma_step<TRA, TRB, true, true, 2, true>(s2, s3, s0, acc, f0, f1, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s2, s3, s0, acc, f, issue, issue, wm, cb0);
   }
-  dma_step<TRA, TRB, true, false, 2, true>(s3, s0, s1, acc, f0, f1, issue, issue, wm, cb0);
-  dma_step<TRA, TRB, false, false, 1, true>(s0, s1, s2, acc, f0, f1, issue, issue, wm, cb0);
-  dma_step<TRA, TRB, false, false, 0, true>(s1, s2, s3, acc, f0, f1, issue, issue, wm, cb0);
-  dma_step<TRA, TRB, false, false, 0, false>(s2, s3, s0, acc, f0, f1, issue, issue, wm, cb0);
+  dma_step<TRA, TRB, true, false, 2, true>(s3, s0, s1, acc, f, issue, issue, wm, cb0);
+  dma_step<TRA, TRB, false, false, 1, true>(s0, s1, s2, acc, f, issue, issue, wm, cb0);
+  dma_step<TRA, TRB, false, false, 0, true>(s1, s2, s3, acc, f, issue, issue, wm, cb0);
+  dma_step<TRA, TRB, false, false, 0, false>(s2, s3, s0, acc, f, issue, issue, wm, cb0);
   __syncthreads();                                     // all waves done with the last tile: LDS is free
 }
 
@@ -284,19 +326,20 @@ __device__ __forceinline__ void dma_pipeline_cont(lds_byte_t* s0, lds_byte_t* s1
 #pragma unroll
   for (int q = 0; q < kOpLoads; ++q) issue.part(s3, q);       // tile 3: first half
   after_barrier();
-  DmaFrags f0, f1;
-  dma_read_frags<TRA, TRB>(f0, s0, 0, wm, cb0);
+  DmaFrags f;
+  dma_read_first<TRA, TRB>(f, s0, wm, cb0);
   for (int kt = 0; kt < KT - 4; kt += 4) {
-    dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f0, f1, issue, issue, wm, cb0);
-    dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f0, f1, issue, issue, wm, cb0);
-    dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f0, f1, issue, issue, wm, cb0);
-    dma_step<TRA, TRB, true, true, 2, true>(s2, s3, s0, acc, f0, f1, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s2, s3, s0, acc, f, issue, issue, wm, cb0);
   }
   make_next(next);
-  dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f0, f1, issue, next, wm, cb0);
-  dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f0, f1, next, next, wm, cb0);
-  dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f0, f1, next, next, wm, cb0);
-  dma_step<TRA, TRB, true, false, 0, false>(s2, s3, s0, acc, f0, f1, next, next, wm, cb0);
+  dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f, issue, next, wm, cb0);
+  dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f, next, next, wm, cb0);
+  dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f, next, next, wm, cb0);
+  dma_step<TRA, TRB, true, false, 0, false>(s2, s3, s0, acc, f, next, next, wm, cb0);
+  __builtin_amdgcn_sched_barrier(0);      // the epilogue's preparations stay behind the last MFMAs (registers)
 }
 
 // Arguments of one rows GEMM (device pointers; see rows_gemm_persist_bf16).

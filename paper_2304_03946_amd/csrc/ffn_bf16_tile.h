@@ -348,13 +348,12 @@ __device__ __forceinline__ void epilogue_rounds(float* patch0, float* patch1, co
 // The same for a wave of the eight-wave kernels: its accumulators are acc[i][0..1], the 64-column half jh of a
 // 128-column block, and its patch holds 16 rows x 64 columns (4 KB: eight of them fit the one LDS stage a
 // persistent kernel has free while its next tile's operands are landing in the others).  Eight rounds -- 32-row
-// block i, rows 16 sub .. 16 sub + 15 of it -- of four 4-element pieces per lane; lanes whose accumulator row
-// is in the other half of the block sit a round's patch write out.
+// block i, rows 16 sub .. 16 sub + 15 of it: the four 16 x 16 accumulator tiles of those rows -- of four
+// 4-element pieces per lane.
 template <bool FETCH, typename Fetch, typename Compute, typename Store>
 __device__ __forceinline__ void epilogue_rounds8(float* patch, int jh, const f32x16 (&acc)[MB][2], Fetch fetch,
                                                  Compute compute, Store store) {
   const int lane = opaque_tid() & 63;
-  const int r = lane & 31, h = lane >> 5;
   const int rsub = lane >> 4, c = lane & 15;
   constexpr int kRounds = MB * 2, kIts = 4;
   auto idx_of = [&](int round, int it) {
@@ -373,17 +372,18 @@ __device__ __forceinline__ void epilogue_rounds8(float* patch, int jh, const f32
   }
   // a round's write follows the previous round's reads in the wave's instruction stream: LDS executes a
   // wave's instructions in order, so one patch serves every round
+  // (accumulator tile: elements 4 (2 sub + sj) .. of acc[i][jj]; the lane's row is lane % 16 of the round's 16, its four columns start at
+  // 32 jj + 16 sj + 4 (lane / 16) of the wave's 64)
   auto write_round = [&](int i, int sub) {
-    if ((r >> 4) == sub) {
 #pragma unroll
-      for (int jj = 0; jj < 2; ++jj)
+    for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int cc = jj * 8 + 2 * g + h;
-          const f32x16& a = acc[i][jj];
-          *(float4*)(patch + (r & 15) * 64 + ((cc ^ (r & 15)) << 2)) = make_float4(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]);
-        }
-    }
+      for (int sj = 0; sj < 2; ++sj) {
+        const int cc = jj * 8 + sj * 4 + rsub;
+        const f32x16& a = acc[i][jj];
+        const int e = 4 * (2 * sub + sj);
+        *(float4*)(patch + c * 64 + ((cc ^ c) << 2)) = make_float4(a[e], a[e + 1], a[e + 2], a[e + 3]);
+      }
   };
   write_round(0, 0);
 #pragma unroll
