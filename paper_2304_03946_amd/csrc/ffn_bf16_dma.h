@@ -42,7 +42,7 @@ struct DmaSrc {
     for (int q = 0; q < kOpLoads; ++q) {
       const int row = (w * kOpLoads + q) * 16 + (i >> 2);
       const int c = (i & 3) ^ ((row >> 2) & 3);
-      off[q] = (uint32_t)(min(row, rows_valid - 1) * ld + c * 8);
+      off[q] = (uint32_t)(min(row, rows_valid - 1) * ld + c * 8) * 2;      // bytes
     }
   }
   // The same tile with its rows gathered: tile row r is row rows[r] / k of the matrix at b (the
@@ -56,7 +56,7 @@ struct DmaSrc {
     for (int q = 0; q < kOpLoads; ++q) {
       const int row = (w * kOpLoads + q) * 16 + (i >> 2);
       const int c = (i & 3) ^ ((row >> 2) & 3);
-      off[q] = (uint32_t)((size_t)(rows[min(row, rows_valid - 1)] / k) * ld + c * 8);
+      off[q] = (uint32_t)(((size_t)(rows[min(row, rows_valid - 1)] / k) * ld + c * 8) * 2);      // bytes: the matrix is below 4 GB (host check)
     }
   }
   // Fills the 16 KB LDS tile at `tile` with K columns k0..k0+31 of the operand's 256 rows.
@@ -68,8 +68,10 @@ struct DmaSrc {
   __device__ __forceinline__ void part(lds_byte_t* tile, int k0, int q) const {
     const unsigned w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)tile) + w * (kOpLoads * 1024);
-    const bf16_t* g = base + k0 + off[q];
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" FLEXMOE_DMA_CPOL ::"v"(g), "s"(lds0 + q * 1024) : "memory");
+    // (uniform base in scalar registers + the lane's 32-bit byte offset: half the address registers of a 64-bit
+    // pointer per lane, and no 64-bit add per load)
+    const bf16_t* g = base + k0;
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" FLEXMOE_DMA_CPOL ::"v"(off[q]), "s"(g), "s"(lds0 + q * 1024) : "memory");
   }
 };
 
@@ -96,14 +98,14 @@ struct DmaSrcT {
     for (int q = 0; q < kOpLoads; ++q) {
       const int krow = (w * kOpLoads + q) * 2 + (i >> 5);
       const int c = min(dmat_chunk(krow, i & 31), cols_valid / 8 - 1);
-      off[q] = (uint32_t)(krow * ld + c * 8);
+      off[q] = (uint32_t)(krow * ld + c * 8) * 2;      // bytes
     }
   }
   __device__ __forceinline__ void part(lds_byte_t* tile, int k0, int q) const {
     const unsigned w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)tile) + w * (kOpLoads * 1024);
-    const bf16_t* g = base + (size_t)k0 * ld + off[q];
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" FLEXMOE_DMA_CPOL ::"v"(g), "s"(lds0 + q * 1024) : "memory");
+    const bf16_t* g = base + (size_t)k0 * ld;
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" FLEXMOE_DMA_CPOL ::"v"(off[q]), "s"(g), "s"(lds0 + q * 1024) : "memory");
   }
 };
 

@@ -10,6 +10,8 @@
 //   C  the loop with the access pattern of a row-major operand (row pitch 16 KB, 64 bytes of 16 rows per load: half
 //      lines), 4 x 8 tiles per XCD sharing rows as the real kernels do; and the same bytes as whole lines
 //   D  256 x 128 tiles, two workgroups per compute unit (three stages of 24 KB each), contiguous and row-major
+//   E  the 256 x 256 tile on eight waves (two per SIMD, 128 x 64 accumulator blocks)
+//   F  E with v_mfma_f32_16x16x32_bf16 and the fragment schedule the kernels use with it
 // Build: paper_2304_03946_amd/build.py builds it next to the library; run: paper_2304_03946_amd/kloop_probe
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -279,6 +281,95 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   if (s == 123.456f) p.out[threadIdx.x] = s;
 }
 
+// ---- F: E on v_mfma_f32_16x16x32_bf16 ---------------------------------------------------------------------------
+// The wave's 128 x 64 block as 8 x 4 tiles of 16 x 16.  A K tile in two halves: row blocks 0, 1 (a0: four 16-row
+// fragments), then 2, 3 (a1), each against four 16-column fragments b that are read once per tile and replaced by the
+// next tile's one by one as the second half is done with them.
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void loop_256x256_8waves_16(const LoopArgs p) {
+  constexpr int kStage = 32768, STAGES = 4;
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[STAGES * kStage];
+  for (int i = threadIdx.x; i < STAGES * kStage / 4; i += 512) ((uint32_t*)lds)[i] = 0x3e003e00u;
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = (wave >> 1) & 1, wn = wave & 1, hh = wave >> 2;
+  const int x = blockIdx.x % 8, j = blockIdx.x / 8;
+  const unsigned char* gp = p.g + ((size_t)x * (32 / p.share) + (j % 32) / p.share) * p.window + threadIdx.x * 16;
+  size_t goff = ((size_t)(j % p.share) * 65536) % p.window;
+  if (goff + kStage > p.window) goff = 0;
+  f32x16 acc[4][2];
+  for (int i = 0; i < 4; ++i) for (int c = 0; c < 2; ++c) for (int q = 0; q < 16; ++q) acc[i][c][q] = 0.f;
+  bf16x8 a0[4], a1[4], b[4];
+  const int la = dma_off(lane & 15, lane >> 4) + wm * 2048, lb = 16384 + dma_off(lane & 15, lane >> 4) + (wn * 4 + hh * 2) * 2048;
+  auto rows = [&](bf16x8 (&a)[4], const lds_byte_t* st, int half) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      a[q] = *(const __attribute__((address_space(3))) bf16x8*)(st + la + (2 * half + (q >> 1)) * 4096 + (q & 1) * 1024);
+  };
+  auto col = [&](const lds_byte_t* st, int q) {
+    b[q] = *(const __attribute__((address_space(3))) bf16x8*)(st + lb + (q >> 1) * 2048 + (q & 1) * 1024);
+  };
+  auto group = [&](const bf16x8 (&a)[4], int half, int q) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      f32x16& t = acc[2 * half + (r >> 1)][q >> 1];
+      const int e = 4 * (2 * (r & 1) + (q & 1));
+      f32x4 c = {t[e], t[e + 1], t[e + 2], t[e + 3]};
+      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[q], a[r], c, 0, 0, 0);
+      t[e] = c[0]; t[e + 1] = c[1]; t[e + 2] = c[2]; t[e + 3] = c[3];
+    }
+  };
+  const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_byte_t*)lds);
+  const unsigned wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  auto issue = [&](int stage, int q) {
+    const unsigned char* src = gp + goff + q * 8192;
+    DMA(src, lds0 + stage * kStage + q * 8192 + wv * 1024);
+  };
+  auto advance = [&]() {
+    goff += kStage;
+    if (goff + kStage > p.window) goff = 0;
+  };
+  for (int t = 0; t < STAGES - 1; ++t) {
+    for (int q = 0; q < 4; ++q) issue(t, q);
+    advance();
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  lds_barrier();
+  rows(a0, (const lds_byte_t*)lds, 0);
+  for (int q = 0; q < 4; ++q) col((const lds_byte_t*)lds, q);
+  int cur = 0;
+  for (int it = 0; it < p.iters; ++it) {
+    const lds_byte_t* st = (const lds_byte_t*)lds + cur * kStage;
+    const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
+    const int fill_stage = cur == 0 ? STAGES - 1 : cur - 1;
+    rows(a1, st, 1);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      __builtin_amdgcn_sched_barrier(0);
+      group(a0, 0, q);
+      __builtin_amdgcn_sched_barrier(0);
+      issue(fill_stage, q);
+    }
+    advance();
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0x0F78);      // vmcnt(8): the next tile has landed, two younger (four loads each) in flight
+    lds_barrier();
+    const lds_byte_t* sn = (const lds_byte_t*)lds + nxt * kStage;
+    rows(a0, sn, 0);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      __builtin_amdgcn_sched_barrier(0);
+      group(a1, 1, q);
+      col(sn, q);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    cur = nxt;
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  __syncthreads();
+  float s = 0.f;
+  for (int i = 0; i < 4; ++i) for (int c = 0; c < 2; ++c) for (int q = 0; q < 16; ++q) s += acc[i][c][q];
+  if (s == 123.456f) p.out[threadIdx.x] = s;
+}
+
 // ---- host ---------------------------------------------------------------------------------------------------
 template <typename Launch>
 static int timed(const char* name, double flops, Launch launch) {
@@ -335,6 +426,11 @@ int main() {
       LoopArgs pe{out, g, li, share, gbytes / (8 * (32 / share))};
       snprintf(name, sizeof name, "E  K loop, 256 x 256 tile on eight waves, contiguous loads, L2 miss share 1/%d, %s", share, tag);
       if (timed(name, 256.0 * 4 * li * 32 * 32768.0, [&](int w) { LoopArgs q = pe; if (w) q.iters = w; hipLaunchKernelGGL(loop_256x256_8waves, dim3(256), dim3(512), 0, 0, q); })) return 1;
+    }
+    for (int share : {32, 4}) {
+      LoopArgs pe{out, g, li, share, gbytes / (8 * (32 / share))};
+      snprintf(name, sizeof name, "F  K loop, eight waves, 16x16x32 instruction, contiguous loads, L2 miss share 1/%d, %s", share, tag);
+      if (timed(name, 256.0 * 4 * li * 32 * 32768.0, [&](int w) { LoopArgs q = pe; if (w) q.iters = w; hipLaunchKernelGGL(loop_256x256_8waves_16, dim3(256), dim3(512), 0, 0, q); })) return 1;
     }
     snprintf(name, sizeof name, "D  K loop, 256 x 128 tiles, two workgroups per compute unit, row-major operands, %s", tag);
     if (timed(name, 512.0 * 4 * li * 16 * 32768.0, [&](int w) { LoopArgs q = pr; if (w) q.iters = w; hipLaunchKernelGGL(loop_256x128<1>, dim3(512), dim3(256), 0, 0, q); })) return 1;
