@@ -11,7 +11,7 @@ namespace flexmoe {
 // Four LDS stages of a 32-wide K tile (2 x 16 KB each): while tile t is multiplied, tiles
 // t+1..t+3 are landed or in flight and tile t+4 is issued half-way through the step.  A direct load writes lane i's 16 bytes at
 // the wave's LDS base + 16*i, so one instruction fills 16 rows x 64 bytes; the bank swizzle
-// (16-byte chunk index XOR (row>>2)&3) is applied by choosing which global chunk a lane fetches.
+// (16-byte chunk index XOR (row>>1)&3) is applied by choosing which global chunk a lane fetches.
 // =============================================================================================
 // The tile is worked on by eight waves, two per SIMD: wave w owns rows (wm + 2 i) * 32, i < 4, and the two
 // 32-column blocks cb0, cb0 + 1 with wm = (w >> 1) & 1, cb0 = (w & 1) * 4 + (w >> 2) * 2 -- 128 x 64 outputs, 128
@@ -29,7 +29,11 @@ __device__ __forceinline__ int dma_wave_cb0(int w) { return (w & 1) * 4 + (w >> 
 constexpr int kDmaTileBytes = 256 * DK * 2;            // one operand tile: 16 KB
 constexpr int kDmaStageBytes = 2 * kDmaTileBytes;      // A + B
 
-__device__ __forceinline__ int dma_off(int row, int c) { return row * (DK * 2) + ((c ^ ((row >> 2) & 3)) << 4); }
+// (Measured with ds_read_b128 alone: lane L reading row L % 16, chunk L / 16 -- the fragment of the 16 x 16 x 32
+// instruction -- runs at 118 bytes per clock and compute unit with (row >> 2) & 3, at 180 with (row >> 1) & 3, which is
+// what a conflict-free read reaches.)
+__device__ __forceinline__ int dma_swz(int row) { return (row >> 1) & 3; }
+__device__ __forceinline__ int dma_off(int row, int c) { return row * (DK * 2) + ((c ^ dma_swz(row)) << 4); }
 
 struct DmaSrc {
   const bf16_t* base;
@@ -41,7 +45,7 @@ struct DmaSrc {
 #pragma unroll
     for (int q = 0; q < kOpLoads; ++q) {
       const int row = (w * kOpLoads + q) * 16 + (i >> 2);
-      const int c = (i & 3) ^ ((row >> 2) & 3);
+      const int c = (i & 3) ^ dma_swz(row);
       off[q] = (uint32_t)(min(row, rows_valid - 1) * ld + c * 8) * 2;      // bytes
     }
   }
@@ -55,7 +59,7 @@ struct DmaSrc {
 #pragma unroll
     for (int q = 0; q < kOpLoads; ++q) {
       const int row = (w * kOpLoads + q) * 16 + (i >> 2);
-      const int c = (i & 3) ^ ((row >> 2) & 3);
+      const int c = (i & 3) ^ dma_swz(row);
       off[q] = (uint32_t)(((size_t)(rows[min(row, rows_valid - 1)] / k) * ld + c * 8) * 2);      // bytes: the matrix is below 4 GB (host check)
     }
   }

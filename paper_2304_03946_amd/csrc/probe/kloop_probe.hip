@@ -11,7 +11,10 @@
 //      lines), 4 x 8 tiles per XCD sharing rows as the real kernels do; and the same bytes as whole lines
 //   D  256 x 128 tiles, two workgroups per compute unit (three stages of 24 KB each), contiguous and row-major
 //   E  the 256 x 256 tile on eight waves (two per SIMD, 128 x 64 accumulator blocks)
-//   F  E with v_mfma_f32_16x16x32_bf16 and the fragment schedule the kernels use with it
+//   F  E with v_mfma_f32_16x16x32_bf16 and the fragment schedule the kernels use with it; and, to price the loop's
+//      parts, the same loop without its barrier, without its direct loads (after the first three tiles: the stages keep
+//      what they hold), without its LDS reads (fragments stay what they are), and without any of them.  These
+//      variants compute nothing meaningful; every LDS and global address stays what it is in the full loop.
 // Build: paper_2304_03946_amd/build.py builds it next to the library; run: paper_2304_03946_amd/kloop_probe
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -32,6 +35,8 @@ typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
 #define DMA(p, ldsaddr) asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(p), "s"(ldsaddr) : "memory")
 
 __device__ __forceinline__ int dma_off(int row, int c) { return row * 64 + ((c ^ ((row >> 2) & 3)) << 4); }
+// the swizzle that keeps the 16 x 16 x 32 instruction's fragment reads (row = lane % 16, chunk = lane / 16) free of bank conflicts
+__device__ __forceinline__ int dma_off16(int row, int c) { return row * 64 + ((c ^ ((row >> 1) & 3)) << 4); }
 __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
@@ -285,6 +290,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // The wave's 128 x 64 block as 8 x 4 tiles of 16 x 16.  A K tile in two halves: row blocks 0, 1 (a0: four 16-row
 // fragments), then 2, 3 (a1), each against four 16-column fragments b that are read once per tile and replaced by the
 // next tile's one by one as the second half is done with them.
+template <bool BARRIER, bool LOADS, bool READS>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void loop_256x256_8waves_16(const LoopArgs p) {
   constexpr int kStage = 32768, STAGES = 4;
   __shared__ __attribute__((aligned(1024))) unsigned char lds[STAGES * kStage];
@@ -298,7 +304,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   f32x16 acc[4][2];
   for (int i = 0; i < 4; ++i) for (int c = 0; c < 2; ++c) for (int q = 0; q < 16; ++q) acc[i][c][q] = 0.f;
   bf16x8 a0[4], a1[4], b[4];
-  const int la = dma_off(lane & 15, lane >> 4) + wm * 2048, lb = 16384 + dma_off(lane & 15, lane >> 4) + (wn * 4 + hh * 2) * 2048;
+  const int la = dma_off16(lane & 15, lane >> 4) + wm * 2048, lb = 16384 + dma_off16(lane & 15, lane >> 4) + (wn * 4 + hh * 2) * 2048;
   auto rows = [&](bf16x8 (&a)[4], const lds_byte_t* st, int half) {
 #pragma unroll
     for (int q = 0; q < 4; ++q)
@@ -340,25 +346,25 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const lds_byte_t* st = (const lds_byte_t*)lds + cur * kStage;
     const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
     const int fill_stage = cur == 0 ? STAGES - 1 : cur - 1;
-    rows(a1, st, 1);
+    if (READS || it == 0) rows(a1, st, 1);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       __builtin_amdgcn_sched_barrier(0);
       group(a0, 0, q);
       __builtin_amdgcn_sched_barrier(0);
-      issue(fill_stage, q);
+      if (LOADS) issue(fill_stage, q);
     }
     advance();
     __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(0x0F78);      // vmcnt(8): the next tile has landed, two younger (four loads each) in flight
-    lds_barrier();
+    if (LOADS) __builtin_amdgcn_s_waitcnt(0x0F78);      // vmcnt(8): the next tile has landed, two younger (four loads each) in flight
+    if (BARRIER) lds_barrier();
     const lds_byte_t* sn = (const lds_byte_t*)lds + nxt * kStage;
-    rows(a0, sn, 0);
+    if (READS) rows(a0, sn, 0);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       __builtin_amdgcn_sched_barrier(0);
       group(a1, 1, q);
-      col(sn, q);
+      if (READS) col(sn, q);
       __builtin_amdgcn_sched_barrier(0);
     }
     cur = nxt;
@@ -429,8 +435,15 @@ int main() {
     }
     for (int share : {32, 4}) {
       LoopArgs pe{out, g, li, share, gbytes / (8 * (32 / share))};
-      snprintf(name, sizeof name, "F  K loop, eight waves, 16x16x32 instruction, contiguous loads, L2 miss share 1/%d, %s", share, tag);
-      if (timed(name, 256.0 * 4 * li * 32 * 32768.0, [&](int w) { LoopArgs q = pe; if (w) q.iters = w; hipLaunchKernelGGL(loop_256x256_8waves_16, dim3(256), dim3(512), 0, 0, q); })) return 1;
+      auto variant = [&](const char* what, auto kernel) {
+        snprintf(name, sizeof name, "F  K loop, eight waves, 16x16x32 instruction, L2 miss share 1/%d, %s, %s", share, what, tag);
+        return timed(name, 256.0 * 4 * li * 32 * 32768.0, [&](int w) { LoopArgs q = pe; if (w) q.iters = w; hipLaunchKernelGGL(kernel, dim3(256), dim3(512), 0, 0, q); });
+      };
+      if (variant("whole loop", loop_256x256_8waves_16<true, true, true>)) return 1;
+      if (variant("no barrier", loop_256x256_8waves_16<false, true, true>)) return 1;
+      if (variant("no direct loads", loop_256x256_8waves_16<true, false, true>)) return 1;
+      if (variant("no LDS reads", loop_256x256_8waves_16<true, true, false>)) return 1;
+      if (variant("MFMA and loop control only", loop_256x256_8waves_16<false, false, false>)) return 1;
     }
     snprintf(name, sizeof name, "D  K loop, 256 x 128 tiles, two workgroups per compute unit, row-major operands, %s", tag);
     if (timed(name, 512.0 * 4 * li * 16 * 32768.0, [&](int w) { LoopArgs q = pr; if (w) q.iters = w; hipLaunchKernelGGL(loop_256x128<1>, dim3(512), dim3(256), 0, 0, q); })) return 1;
