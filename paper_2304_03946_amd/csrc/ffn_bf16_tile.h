@@ -40,12 +40,13 @@ __device__ __forceinline__ int lds_off(int row, int chunk) { return row * BK + (
 
 // ---- workgroup id -> tile, XCD aware ---------------------------------------------------------
 // Workgroups are dealt round-robin to the 8 XCDs (id % 8), each with its own L2, and an XCD runs
-// its workgroups in ascending id.  The rows x cols tile grid is cut into patches of ph x pw tiles
-// (about 32 = one per CU of an XCD; pw divides cols whenever a divisor in 5..8 exists, so patches
-// are full and every XCD gets the same work); the j-th workgroup of XCD x gets tile j % (ph*pw) of
-// patch (j / (ph*pw)) * 8 + x.  The workgroups that run together on one XCD then share ph row
-// operands and pw column operands in its L2, and the 8 patches in flight on the 8 XCDs are
-// neighbours in the grid, so what they share is fetched from HBM once.
+// its workgroups in ascending id.  The rows x cols tile grid is cut into column strips pw tiles wide
+// (pw divides cols whenever a divisor in 5..8 exists) and every strip, walked row by row, into patches
+// of 32 consecutive tiles (one per CU of an XCD: 32 / pw rows of the strip; where pw does not divide 32
+// a patch starts and ends inside a row); the j-th workgroup of XCD x gets tile j % 32 of patch
+// (j / 32) * 8 + x, patches numbered strip by strip within a row of patches.  The workgroups that run
+// together on one XCD then share about 32 / pw row operands and pw column operands in its L2, and the 8
+// patches in flight on the 8 XCDs are neighbours in the grid, so what they share is fetched from HBM once.
 constexpr int kXcds = 8, kPatch = 32;
 __host__ __device__ inline int patch_width(int cols) {
   if (cols <= 8) return cols;
@@ -54,18 +55,19 @@ __host__ __device__ inline int patch_width(int cols) {
   return 8;
 }
 __host__ __device__ inline unsigned patched_grid(int rows, int cols) {
-  const int pw = patch_width(cols), ph = kPatch / pw;
-  const int np = ((rows + ph - 1) / ph) * ((cols + pw - 1) / pw);
-  return (unsigned)((np + kXcds - 1) / kXcds * kXcds) * (ph * pw);
+  const int pw = patch_width(cols);
+  const int np = ((rows * pw + kPatch - 1) / kPatch) * ((cols + pw - 1) / pw);
+  return (unsigned)((np + kXcds - 1) / kXcds * kXcds) * kPatch;
 }
 // returns false when the workgroup falls into the padding of the patch grid
 __device__ __forceinline__ bool patched_tile(unsigned b, int rows, int cols, int* r, int* c) {
-  const int pw = patch_width(cols), ph = kPatch / pw, psize = ph * pw;
+  const int pw = patch_width(cols);
   const int npc = (cols + pw - 1) / pw;
   const unsigned x = b % kXcds, j = b / kXcds;
-  const unsigned P = (j / psize) * kXcds + x, q = j % psize;
-  *r = (int)(P / npc) * ph + (int)(q / pw);
-  *c = (int)(P % npc) * pw + (int)(q % pw);
+  const unsigned P = (j / kPatch) * kXcds + x, q = j % kPatch;
+  const unsigned t = (P / npc) * kPatch + q;      // position in the strip's row-by-row walk
+  *r = (int)(t / pw);
+  *c = (int)(P % npc) * pw + (int)(t % pw);
   return *r < rows && *c < cols;
 }
 

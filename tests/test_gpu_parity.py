@@ -234,6 +234,12 @@ SMALL = {
     # tiles for 256 compute units) and a long contraction: the tiles left for the last round are cut along K
     # into four segments (fp32 partial tiles + reduce kernel)
     "split_tail": W.scaled(W.CONFIGS["swin"], N=66000, d=128, f=1024, E=8, V=12, max_rep=4, backward=False),
+    # three and six column tiles: patches of the tile grid that start and end inside a row of their column strip
+    # (32 is no multiple of the strip's width), in all four rows products and both weight gradients
+    "strip_patches": W.scaled(W.CONFIGS["bert"], N=2600, d=768, f=1536, E=6, V=9, max_rep=2, backward=True),
+    # whole 256 x 256 weight-gradient tiles with two patches per job (d = 512, f = 1024) and skewed loads: the
+    # work lists are dealt out over the XCD groups by load, with holes the persistent kernel skips
+    "wgrad_balance": W.scaled(W.CONFIGS["gpt_m"], N=2500, d=512, f=1024, E=8, V=13, max_rep=4),
     # the library's limits: 256 experts, 512 vExperts, 8 experts per token -- hundreds of buckets of a few dozen rows
     # (every one a ragged tile, many experts with a handful of tokens, the bucket lookups at their widest)
     "max_experts": W.scaled(W.CONFIGS["gpt_xl"], N=2500, d=128, f=256, E=256, V=512, k=8, max_rep=8, skew_s=1.0),
@@ -344,7 +350,7 @@ def test_full_backward_fp32(api):
     run_full_backward(api, cfg, inp, *W.placement_from_loads([5, 4, 3, 2, 1], cfg.V, 3, shuffle_seed=3), b1=b1, b2=b2)
 
 
-@pytest.mark.parametrize("name", ["gpt_small", "swin_small", "xl_small", "gpt_dma", "gpt_dma_seg"])
+@pytest.mark.parametrize("name", ["gpt_small", "swin_small", "xl_small", "gpt_dma", "gpt_dma_seg", "strip_patches", "wgrad_balance"])
 def test_full_backward_reduced_configs(api, name):
     cfg = SMALL[name]
     inp = W.make_layer_inputs(cfg)
