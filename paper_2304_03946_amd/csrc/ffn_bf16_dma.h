@@ -148,7 +148,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 template <int TILES> __device__ __forceinline__ void wait_tiles_in_flight() { wait_vmcnt<2 * kOpLoads * TILES>(); }
 
 // The matrix instruction is v_mfma_f32_16x16x32_bf16: on real operands the chip holds a higher clock with it than
-// with the 32 x 32 x 16 form (half the accumulator traffic per flop; the instruction alone: 2.1 against 1.85 PFLOP/s).
+// with the 32 x 32 x 16 form (half the accumulator traffic per flop; the instruction alone: 2.13 against 1.94 PFLOP/s).
 // A wave's 128 x 64 block is 8 x 4 of its 16 x 16 tiles.  Called as (column fragment, row fragment), lane L of a
 // tile holds row L % 16 and the four consecutive columns 4 (L / 16) ..: acc[i][j][2 si + sj] is the tile of rows
 // 16 si .., columns 16 sj .. of the wave's 32-row block i and 32-column block j.
