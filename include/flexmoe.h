@@ -167,7 +167,7 @@ int flexmoe_combine(const void* yp, const int32_t* dest, const float* topk_w,
  * transformation folded into the expert computation).  Same results as the two calls, bit for bit.
  *   x [N,d], src [A] (A = N*k) as written by flexmoe_route; everything else as in
  *   flexmoe_expert_ffn_fwd (hpre and h may be NULL as well).  For forward-only use: the backward pass reads xp.
- * FLEXMOE_UNSUPPORTED unless dtype is bf16, d is a multiple of 128 and N*d < 2^31: callers then
+ * FLEXMOE_UNSUPPORTED unless dtype is bf16, d is a multiple of 128 and N*d < 2^30: callers then
  * use the two separate calls.
  */
 int flexmoe_expert_ffn_fwd_gather(const void* x, const int32_t* src, const int32_t* vexpert_off,
@@ -184,7 +184,7 @@ int flexmoe_expert_ffn_fwd_gather(const void* x, const int32_t* src, const int32
  * flexmoe_permute + flexmoe_expert_ffn_fwd + flexmoe_combine, bit for bit.
  *   x [N,d], src [N] as written by flexmoe_route with k = 1 -> hpre [N,f], h [N,f] (each may be NULL), y [N,d].
  * For forward-only use.  FLEXMOE_UNSUPPORTED unless dtype is bf16, d and f are multiples of 128 and
- * N*d < 2^31.
+ * N*d < 2^30.
  */
 int flexmoe_expert_ffn_fwd_top1(const void* x, const int32_t* src, const int32_t* vexpert_off,
                                 const int32_t* vexpert_owner, const void* w1, const void* b1,

@@ -162,8 +162,8 @@ int flexmoe_expert_ffn_fwd_gather(const void* x, const int32_t* src, const int32
   const int A = N * k;
   const int st = ffn_common(A, d, f, E, V, act, dtype, vexpert_off, vexpert_owner, ws, ws_bytes);
   if (st != FLEXMOE_OK) return st;
-  // gathered row loads exist on the bf16 direct-to-LDS path only; row offsets are 32-bit byte counts
-  if (dtype != FLEXMOE_BF16 || (d % 128) || (long long)N * d >= (1ll << 31)) return FLEXMOE_UNSUPPORTED;
+  // gathered row loads exist on the bf16 direct-to-LDS path only; row offsets are 32-bit byte counts kept below 2^31
+  if (dtype != FLEXMOE_BF16 || (d % 128) || (long long)N * d >= (1ll << 30)) return FLEXMOE_UNSUPPORTED;
   if (!w1 || !w2 || !aligned16(w1) || !aligned16(w2) || !aligned16(b1) || !aligned16(b2)) return FLEXMOE_INVALID_ARG;
   if (A > 0 && (!x || !src || !yp || !aligned16(x) || !aligned16(hpre) || !aligned16(h) || !aligned16(yp)))    // hpre, h may be NULL
     return FLEXMOE_INVALID_ARG;
@@ -178,8 +178,8 @@ int flexmoe_expert_ffn_fwd_top1(const void* x, const int32_t* src, const int32_t
   if (N < 0 || N >= (1 << 30)) return FLEXMOE_INVALID_ARG;
   const int st = ffn_common(N, d, f, E, V, act, dtype, vexpert_off, vexpert_owner, ws, ws_bytes);
   if (st != FLEXMOE_OK) return st;
-  // gathered loads and scattered stores exist on the bf16 direct-to-LDS path only; row offsets are 32-bit byte counts
-  if (dtype != FLEXMOE_BF16 || (d % 128) || (f % 128) || (long long)N * d >= (1ll << 31)) return FLEXMOE_UNSUPPORTED;
+  // gathered loads and scattered stores exist on the bf16 direct-to-LDS path only; row offsets are 32-bit byte counts kept below 2^31
+  if (dtype != FLEXMOE_BF16 || (d % 128) || (f % 128) || (long long)N * d >= (1ll << 30)) return FLEXMOE_UNSUPPORTED;
   if (!w1 || !w2 || !aligned16(w1) || !aligned16(w2) || !aligned16(b1) || !aligned16(b2)) return FLEXMOE_INVALID_ARG;
   if (N > 0 && (!x || !src || !y || !aligned16(x) || !aligned16(hpre) || !aligned16(h) || !aligned16(y)))    // hpre, h may be NULL
     return FLEXMOE_INVALID_ARG;

@@ -60,7 +60,7 @@ struct DmaSrc {
     for (int q = 0; q < kOpLoads; ++q) {
       const int row = (w * kOpLoads + q) * 16 + (i >> 2);
       const int c = (i & 3) ^ dma_swz(row);
-      off[q] = (uint32_t)(((size_t)(rows[min(row, rows_valid - 1)] / k) * ld + c * 8) * 2);      // bytes: the matrix is below 4 GB (host check)
+      off[q] = (uint32_t)(((size_t)(rows[min(row, rows_valid - 1)] / k) * ld + c * 8) * 2);      // bytes: the matrix is below 2 GB (host check)
     }
   }
   // Fills the 16 KB LDS tile at `tile` with K columns k0..k0+31 of the operand's 256 rows.

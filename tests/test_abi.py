@@ -101,8 +101,8 @@ def test_argument_validation_needs_no_device():
                                              bf16, one, null, one, one, 1 << 20, null) == binding.UNSUPPORTED
     assert lib.flexmoe_expert_ffn_fwd_gather(one, one, one, one, one, null, one, null, 64, 1, 128, 64, 4, 4, relu,
                                              binding.F32, one, null, one, one, 1 << 20, null) == binding.UNSUPPORTED
-    # ... and addresses the gathered rows with 32-bit byte offsets: N * d below 2^31
-    assert lib.flexmoe_expert_ffn_fwd_gather(one, one, one, one, one, null, one, null, 1 << 23, 1, 256, 128, 4, 4, relu,
+    # ... and addresses the gathered rows with 32-bit byte offsets below 2^31: N * d below 2^30
+    assert lib.flexmoe_expert_ffn_fwd_gather(one, one, one, one, one, null, one, null, 1 << 22, 1, 256, 128, 4, 4, relu,
                                              bf16, one, null, one, one, 1 << 40, null) == binding.UNSUPPORTED
     # the top-1 forward needs d and f multiples of 128
     assert lib.flexmoe_expert_ffn_fwd_top1(one, one, one, one, one, null, one, null, 64, 128, 64, 4, 4, relu, bf16, one,
