@@ -175,13 +175,10 @@ template <bool TRA, bool TRB> __device__ __forceinline__ void dma_lane_init(DmaF
 }
 // The four row fragments of half `half` (row blocks i = 2 half, 2 half + 1 of the wave, rows 16 si .. of each;
 // 16-row unit m = 2 wm + 4 i + si, la carries the wave's wm).
-// NBLK (ragged tiles): how many of the wave's four row blocks the tile's rows reach at all; the others are neither
-// read nor multiplied (a compile-time count: the K loop of such a tile is a copy of its own, not a branch per group).
-template <bool TR, int NBLK = 4> __device__ __forceinline__ void dma_read_rows(Frag8 (&a)[4], const lds_byte_t* stage, uint32_t la, int half) {
+template <bool TR> __device__ __forceinline__ void dma_read_rows(Frag8 (&a)[4], const lds_byte_t* stage, uint32_t la, int half) {
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
     const int i = 2 * half + (p >> 1), si = p & 1;
-    if (i >= NBLK) continue;
     if (TR) a[p].v = dmat_read_frag(stage + ((la ^ (uint32_t)((4 * (i & 1) + si) << 5)) + (i >> 1) * 256));
     else a[p].v = *(const __attribute__((address_space(3))) bf16x8*)(stage + (la + i * 4096 + si * 1024));
   }
@@ -204,13 +201,11 @@ __device__ __forceinline__ void dma_read_first(DmaFrags& f, const lds_byte_t* st
 // PRIO: the wave runs its four instructions at raised priority (the SIMD's other wave then gets its loads and LDS
 // reads in behind them instead of between them).  Measured on the GPT-XL-like layer: backward products -0.4 ... -0.7 %,
 // forward products (one operand read with transposing loads) +0.3 %, so only the former ask for it.
-template <bool PRIO, int NBLK = 4>
+template <bool PRIO>
 __device__ __forceinline__ void dma_mfma_group(DmaAcc& acc, const Frag8 (&a)[4], const Frag8& b, int half, int q) {
-  if (2 * half >= NBLK) return;
   if (PRIO) __builtin_amdgcn_s_setprio(1);
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
-    if (2 * half + (p >> 1) >= NBLK) continue;
     f32x16& t = acc[2 * half + (p >> 1)][q >> 1];
     const int e = 4 * (2 * (p & 1) + (q & 1));
     f32x4 c = {t[e], t[e + 1], t[e + 2], t[e + 3]};
@@ -240,18 +235,18 @@ __device__ __forceinline__ void dma_mfma_group(DmaAcc& acc, const Frag8 (&a)[4],
 // part of tile kt+1 has landed.
 // `issue` serves the first half of the step (PRE), `issue_post` the second (POST): the same object inside a
 // tile sequence, two different ones where the sequence of the workgroup's next output tile takes over.
-template <bool TRA, bool TRB, bool PRE, bool POST, int WAIT, bool NEXT, int NBLK = 4, typename Issue, typename IssuePost>
+template <bool TRA, bool TRB, bool PRE, bool POST, int WAIT, bool NEXT, typename Issue, typename IssuePost>
 __device__ __forceinline__ void dma_step(lds_byte_t* prev, lds_byte_t* cur, const lds_byte_t* nxt, DmaAcc& acc,
                                          DmaFrags& f, Issue& issue, IssuePost& issue_post, int wm, int cb0) {
   constexpr int kEvery = 4 / kOpLoads;      // a load after every kEvery-th group of four MFMAs
   // (behind an empty asm: each fragment address is derived from these where it is used, not once for the whole loop)
   asm volatile("" : "+v"(f.la), "+v"(f.lb));
   const uint32_t la = f.la, lb = f.lb;
-  dma_read_rows<TRA, NBLK>(f.a1, cur, la, 1);
+  dma_read_rows<TRA>(f.a1, cur, la, 1);
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     __builtin_amdgcn_sched_barrier(0);
-    dma_mfma_group<TRA == TRB, NBLK>(acc, f.a0, f.b[q], 0, q);
+    dma_mfma_group<TRA == TRB>(acc, f.a0, f.b[q], 0, q);
     __builtin_amdgcn_sched_barrier(0);
     if (PRE && q % kEvery == kEvery - 1) issue.part(prev, kOpLoads + q / kEvery);
   }
@@ -261,12 +256,12 @@ __device__ __forceinline__ void dma_step(lds_byte_t* prev, lds_byte_t* cur, cons
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-  if (NEXT) dma_read_rows<TRA, NBLK>(f.a0, nxt, la, 0);
+  if (NEXT) dma_read_rows<TRA>(f.a0, nxt, la, 0);
   if (POST) issue_post.begin();
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     __builtin_amdgcn_sched_barrier(0);
-    dma_mfma_group<TRA == TRB, NBLK>(acc, f.a1, f.b[q], 1, q);
+    dma_mfma_group<TRA == TRB>(acc, f.a1, f.b[q], 1, q);
     if (NEXT) dma_read_col<TRB>(f.b[q], nxt, lb, q);
     __builtin_amdgcn_sched_barrier(0);
     if (POST && q % kEvery == kEvery - 1) issue_post.part(cur, q / kEvery);
@@ -331,7 +326,7 @@ template <typename Issue> __device__ __forceinline__ void dma_prefetch3(lds_byte
 // make_next(next) builds the next tile's sequence; it is called behind the steady-state loop, so that the
 // sequence's registers are not live across it (spilled registers come back through the same in-order
 // queue as the operand tiles: every reload inside the K loop would wait for all tiles in flight).
-template <bool TRA, bool TRB, int NBLK = 4, typename Issue, typename After, typename MakeNext>
+template <bool TRA, bool TRB, typename Issue, typename After, typename MakeNext>
 __device__ __forceinline__ void dma_pipeline_cont(lds_byte_t* s0, lds_byte_t* s1, lds_byte_t* s2, lds_byte_t* s3,
                                                   DmaAcc& acc, Issue& issue, int KT, Issue& next, int wm,
                                                   int cb0, After after_barrier, MakeNext make_next) {
@@ -346,16 +341,16 @@ __device__ __forceinline__ void dma_pipeline_cont(lds_byte_t* s0, lds_byte_t* s1
   DmaFrags f;
   dma_read_first<TRA, TRB>(f, s0, wm, cb0);
   for (int kt = 0; kt < KT - 4; kt += 4) {
-    dma_step<TRA, TRB, true, true, 2, true, NBLK>(s3, s0, s1, acc, f, issue, issue, wm, cb0);
-    dma_step<TRA, TRB, true, true, 2, true, NBLK>(s0, s1, s2, acc, f, issue, issue, wm, cb0);
-    dma_step<TRA, TRB, true, true, 2, true, NBLK>(s1, s2, s3, acc, f, issue, issue, wm, cb0);
-    dma_step<TRA, TRB, true, true, 2, true, NBLK>(s2, s3, s0, acc, f, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f, issue, issue, wm, cb0);
+    dma_step<TRA, TRB, true, true, 2, true>(s2, s3, s0, acc, f, issue, issue, wm, cb0);
   }
   make_next(next);
-  dma_step<TRA, TRB, true, true, 2, true, NBLK>(s3, s0, s1, acc, f, issue, next, wm, cb0);
-  dma_step<TRA, TRB, true, true, 2, true, NBLK>(s0, s1, s2, acc, f, next, next, wm, cb0);
-  dma_step<TRA, TRB, true, true, 2, true, NBLK>(s1, s2, s3, acc, f, next, next, wm, cb0);
-  dma_step<TRA, TRB, true, false, 0, false, NBLK>(s2, s3, s0, acc, f, next, next, wm, cb0);
+  dma_step<TRA, TRB, true, true, 2, true>(s3, s0, s1, acc, f, issue, next, wm, cb0);
+  dma_step<TRA, TRB, true, true, 2, true>(s0, s1, s2, acc, f, next, next, wm, cb0);
+  dma_step<TRA, TRB, true, true, 2, true>(s1, s2, s3, acc, f, next, next, wm, cb0);
+  dma_step<TRA, TRB, true, false, 0, false>(s2, s3, s0, acc, f, next, next, wm, cb0);
   __builtin_amdgcn_sched_barrier(0);      // the epilogue's preparations stay behind the last MFMAs (registers)
 }
 

@@ -5,7 +5,6 @@
 #include "common.h"
 #include "ffn_bf16_tile.h"
 #include "ffn_bf16_dma.h"
-#include <type_traits>
 namespace flexmoe {
 // =============================================================================================
 // Why: with 128 KB of LDS stages and 256 accumulator registers per lane a compute unit holds one
@@ -253,6 +252,8 @@ __global__ __launch_bounds__(kDmaThreads) void rows_gemm_persist_bf16(const Rows
   TilePhases phases;
   for (;;) {
     phases.start();
+    DmaAcc acc;
+    zero_acc(acc);
     // the workgroup's next tile
     unsigned nidx = idx + G;
     TileId nid;
@@ -262,15 +263,7 @@ __global__ __launch_bounds__(kDmaThreads) void rows_gemm_persist_bf16(const Rows
     Issue next;
     if constexpr (GATHER) next = make_issue(tn);       // its index loads share the operand tiles' queue: up here, where little is in flight
     const int KT = K / DK / t.nseg;
-    // The tile's K loop and epilogue exist twice: for tiles whose rows reach into the wave's third 32-row block
-    // ((wm + 2 i) * 32, i = 2), and for ragged ones that end before it, which neither read nor multiply the wave's
-    // blocks 2 and 3.  (Two copies of straight-line code that meet where no accumulator is live: branches around the
-    // MFMA groups of one copy make the accumulators move at every join.)
-    auto tile_body = [&](auto blocks) {
-    constexpr int NBLK = decltype(blocks)::value;
-    DmaAcc acc;
-    zero_acc(acc);
-    dma_pipeline_cont<false, !WT, NBLK>(
+    dma_pipeline_cont<false, !WT>(
         s0, s1, s2, s3, acc, issue, KT, next, wm, cb0,
         [&]() {
           phases.first_barrier();
@@ -299,9 +292,6 @@ __global__ __launch_bounds__(kDmaThreads) void rows_gemm_persist_bf16(const Rows
       rows_epilogue<EPI, ACT, kLut, 8>((float*)stage3, (float*)stage3, acc, p.bias, NC, t.row0, t.rows_valid, t.e, t.n0,
                                     p.hpre_in, p.out0, p.out1, lut, smap);
     }
-    };
-    if (t.rows_valid <= (4 + wm) * 32) tile_body(std::integral_constant<int, 2>{});
-    else tile_body(std::integral_constant<int, 4>{});
     phases.tile_done((WT ? 2 : 0) + (EPI == EPI_PLAIN ? 1 : 0), !has_next);
     if (!has_next) break;
     t = tn;
